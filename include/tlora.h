@@ -1,0 +1,126 @@
+/* tlora.h -- C ABI of the fused multi-LoRA linear layer for AMD MI355X (gfx950).
+ *
+ * Many fine-tuning jobs share one frozen base weight W; job j owns a low-rank adapter
+ * (A_j: d_in x r_j, B_j: r_j x d_out, scale_j) that applies to its own contiguous segment of
+ * the token batch (paper Sec. 2: W + dW with dW = A.B; Sec. 3.2: jobs fused on a shared backbone
+ * keep independent forward/backward semantics; Sec. 3.3: fused batched LoRA kernel -- tokens of
+ * adapter i go through A_i into a compact |X_i| x r_i intermediate and straight on through B_i
+ * into the output, the dense A_i.B_i is never formed).
+ *
+ *   forward :  Y[seg j]  = X[seg j].W   + scale_j * (X[seg j].A_j).B_j
+ *   backward:  dX[seg j] = dY[seg j].W^T + scale_j * (dY[seg j].B_j^T).A_j^T
+ *              dA_j      = scale_j * X[seg j]^T . (dY[seg j].B_j^T)
+ *              dB_j      = scale_j * (X[seg j].A_j)^T . dY[seg j]          (W is frozen: no dW)
+ *
+ * General conventions
+ *   - All matrices are dense row-major.  seg j = rows offsets[j] .. offsets[j+1]-1.
+ *   - HOST pointers: the problem struct, ranks, offsets, scales and the arrays of per-job
+ *     pointers.  DEVICE pointers: X, W, every A_j / B_j, Y, dY, dX, every dA_j / dB_j and the
+ *     workspace.  The caller owns every buffer; the library allocates no device memory, keeps no
+ *     pointer after a call returns and never writes W, X, A_j, B_j or dY.
+ *   - dtype TLORA_BF16: X, W, A_j, B_j, Y, dY, dX hold bf16; accumulation is fp32; Y / dX are rounded
+ *     to nearest-even once on store.  dtype TLORA_F32: those tensors hold fp32.  dA_j, dB_j are fp32
+ *     for both dtypes.  Gradients are overwritten, not accumulated.
+ *   - X, W, Y, dY, dX must be 16-byte aligned and d_in, d_out multiples of 8.  A_j, B_j, dA_j, dB_j
+ *     need only element alignment (ranks such as 1 or 3 are legal).  The workspace must be 256-byte
+ *     aligned.
+ *   - Legal degenerate inputs: T_j = 0 (dA_j = dB_j = 0), r_j = 0 (rows of that job get the
+ *     backbone product only; its A/B/dA/dB pointers are ignored and may be NULL), T = 0 (X, Y, dY, dX
+ *     may be NULL; the forward launches nothing, the backward zero-fills dA_j / dB_j).  T must be below 2^31 and r_j at most TLORA_MAX_RANK.
+ *   - Calls are asynchronous on `hip_stream` (a hipStream_t; NULL = the default stream).  Host
+ *     arrays may be reused as soon as the call returns.  Two calls that share a workspace must be
+ *     ordered on one stream.
+ *   - Every entry point returns a tlora_status_t (0 = ok, negative = error).  On error nothing has
+ *     been launched.  The results are independent of the internal tiling and are bit-identical from
+ *     run to run (no floating-point atomics).
+ */
+#ifndef TLORA_H
+#define TLORA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TLORA_MAX_RANK 1024
+
+typedef enum { TLORA_F32 = 0, TLORA_BF16 = 1 } tlora_dtype_t;
+
+typedef enum {
+  TLORA_OK = 0,
+  TLORA_EINVAL = -1,      /* bad sizes: J < 1, d not a multiple of 8, offsets not non-decreasing from 0, ... */
+  TLORA_ENULL = -2,       /* a required pointer is NULL                                                   */
+  TLORA_EDTYPE = -3,      /* dtype is neither TLORA_F32 nor TLORA_BF16                                    */
+  TLORA_EWORKSPACE = -4,  /* workspace NULL, misaligned or smaller than tlora_workspace_bytes()           */
+  TLORA_EARCH = -5,       /* the current device is not gfx950                                             */
+  TLORA_EHIP = -6,        /* a HIP runtime call failed                                                    */
+  TLORA_EALIGN = -7       /* X / W / Y / dY / dX not 16-byte aligned                                      */
+} tlora_status_t;
+
+/* Problem statement of one fused layer call (Sec. 3.2 / 3.3: shared frozen backbone, per-job adapters
+ * on per-job token segments). */
+typedef struct {
+  int32_t dtype;            /* tlora_dtype_t of X, W, A_j, B_j, Y, dY, dX                          */
+  int32_t num_jobs;         /* J >= 1                                                              */
+  int32_t d_in, d_out;      /* multiples of 8                                                      */
+  const int32_t* ranks;     /* HOST [J]   r_j in [0, TLORA_MAX_RANK]                               */
+  const int64_t* offsets;   /* HOST [J+1] offsets[0] = 0, non-decreasing, T = offsets[J] < 2^31    */
+  const float* scales;      /* HOST [J]   scale_j                                                  */
+  const void* X;            /* DEVICE [T, d_in]                                                    */
+  const void* W;            /* DEVICE [d_in, d_out], never written                                 */
+  const void* const* A;     /* HOST array of J DEVICE pointers, A_j [d_in, r_j]                    */
+  const void* const* B;     /* HOST array of J DEVICE pointers, B_j [r_j, d_out]                   */
+} tlora_problem_t;
+
+/* Bytes of device workspace that tlora_fwd / tlora_bwd need for this problem (depends only on
+ * dtype, J, d_in, d_out, ranks, offsets).  It grows with sum_j T_j * r_j and with r_j * (d_in + d_out);
+ * no d_in x d_out per-job buffer is ever used (Sec. 3.3: the merged adapter weight is not
+ * materialised).  Returns 0 if the problem is invalid. */
+size_t tlora_workspace_bytes(const tlora_problem_t* p);
+
+/* Forward (Sec. 3.3).  Y: DEVICE [T, d_out], overwritten.  The workspace afterwards holds the
+ * intermediates S_j = X_j.A_j, which a following tlora_bwd on the same problem, workspace and
+ * stream may reuse (TLORA_BWD_REUSE_S). */
+int tlora_fwd(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_bytes, void* hip_stream);
+
+/* flags for tlora_bwd */
+#define TLORA_BWD_REUSE_S 1   /* the workspace still holds S_j from tlora_fwd of this same problem */
+
+/* Backward (derivatives of L = sum(dY * Y); Sec. 3.2 fixes only that each job's backward is
+ * independent and that W gets no gradient).
+ *   dY: DEVICE [T, d_out].   dX: DEVICE [T, d_in], overwritten; NULL skips it.
+ *   dA: HOST array of J DEVICE pointers to fp32 [d_in, r_j];  dB: likewise fp32 [r_j, d_out].
+ *   Both arrays may be NULL together to skip the adapter gradients. */
+int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* dA, void* const* dB,
+              int flags, void* workspace, size_t ws_bytes, void* hip_stream);
+
+/* Integer bookkeeping of the nano-batch plan (Sec. 3.3, nano-batches = partition of the combined
+ * batch along the token dimension), for bit-exact checks.  All outputs are HOST arrays and each may
+ * be NULL.  Per job: rpad[J] (rank rounded up to the 8-element granule), soff[J+1] (element
+ * offset of job j's rows in the packed intermediate: sum_{i<j} T_i * rpad_i).  Per row tile of
+ * the backbone GEMM (uniform tiles of `*tile_rows` rows over the concatenated batch; a tile may
+ * hold rows of several jobs): tile_row0, tile_nrows, tile_job_first, tile_job_last (first / last
+ * job with a row in the tile).  *n_tiles: in = capacity of the tile arrays, out = number of tiles
+ * (the call fails with TLORA_EINVAL if the capacity is too small, after storing the count). */
+int tlora_plan_dump(const tlora_problem_t* p, int32_t* rpad, int64_t* soff, int32_t* tile_rows,
+                    int64_t* tile_row0, int32_t* tile_nrows, int32_t* tile_job_first,
+                    int32_t* tile_job_last, int64_t* n_tiles);
+
+/* Tuning knobs (process-wide, for experiments and for the tiling-independence tests).
+ *   "shrink_rows"  : token rows per work unit of the shrink kernels        (64 | 128)
+ *   "grad_tokens"  : minimum tokens per work unit of the dA / dB kernels   (multiple of 64)
+ * Returns TLORA_EINVAL for an unknown name or an illegal value. */
+int tlora_set_option(const char* name, int64_t value);
+
+/* Static description of an error code. */
+const char* tlora_strerror(int status);
+
+/* Library version string. */
+const char* tlora_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TLORA_H */

@@ -1,0 +1,553 @@
+// Host side of the C ABI: argument validation, the nano-batch plan (integer bookkeeping), workspace
+// layout and the launch sequence of the forward and backward passes.
+#include <hip/hip_runtime.h>
+#include <string.h>
+
+#include <algorithm>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "../../include/tlora.h"
+#include "tlora_internal.h"
+#include "tlora_kernels.h"
+
+namespace tlora {
+namespace {
+
+struct Options {
+  int shrink_rows = 64;
+  int grad_tokens = 512;
+};
+Options g_opt;
+std::mutex g_mu;
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---- the plan ---------------------------------------------------------------------------------------
+struct Plan {
+  int J = 0, T = 0, d_in = 0, d_out = 0, dtype = 0;
+  int max_rpad = 0;
+  int grad_mb = 1;
+  std::vector<JobDev> jobs;
+  std::vector<TileJobs> tile_jobs;
+  std::vector<ShrinkUnit> shrink_units;
+  std::vector<GradUnit> gradB_units, gradA_units;      // dB: columns over d_out;  dA: columns over d_in
+  std::vector<GradGroup> gradB_groups, gradA_groups;
+  int64_t s_elems = 0;                                  // elements of the packed S (= dS) buffer
+  int64_t atp_elems = 0, ap_elems = 0, bp_elems = 0;
+  // workspace byte offsets
+  size_t off_tables = 0, off_S = 0, off_dS = 0, off_Sb = 0, off_dSb = 0, off_atp = 0, off_ap = 0, off_bp = 0,
+         off_partial = 0, total = 0;
+  size_t tables_bytes = 0;
+  // offsets of each table inside the table blob
+  size_t tb_jobs = 0, tb_tiles = 0, tb_shrink = 0, tb_gBu = 0, tb_gBg = 0, tb_gAu = 0, tb_gAg = 0, tb_f32 = 0;
+  size_t f32_reserved = 0;
+};
+
+int validate(const tlora_problem_t* p) {
+  if (!p) return TLORA_ENULL;
+  if (p->dtype != TLORA_F32 && p->dtype != TLORA_BF16) return TLORA_EDTYPE;
+  if (p->num_jobs < 1 || p->d_in < 8 || p->d_out < 8 || (p->d_in % 8) || (p->d_out % 8)) return TLORA_EINVAL;
+  if (!p->ranks || !p->offsets || !p->scales) return TLORA_ENULL;
+  if (p->offsets[0] != 0) return TLORA_EINVAL;
+  for (int j = 0; j < p->num_jobs; ++j) {
+    if (p->offsets[j + 1] < p->offsets[j]) return TLORA_EINVAL;
+    if (p->ranks[j] < 0 || p->ranks[j] > TLORA_MAX_RANK) return TLORA_EINVAL;
+  }
+  if (p->offsets[p->num_jobs] >= (int64_t)1 << 31) return TLORA_EINVAL;
+  return TLORA_OK;
+}
+
+void build_grad_units(const Plan& pl, int D, std::vector<GradUnit>& units, std::vector<GradGroup>& groups) {
+  const int mb = pl.grad_mb;
+  const int prow = kGradRanks * mb;
+  const int ncb = (D + kGradCols - 1) / kGradCols;
+  for (int j = 0; j < pl.J; ++j) {
+    const JobDev& jb = pl.jobs[j];
+    if (jb.rank == 0) continue;
+    const int Tj = jb.row1 - jb.row0;
+    // rank-aware token chunking: a chunk reads chunk*256*2 bytes and writes prow*256*4, so keep
+    // chunk >= 16 * rank rows; otherwise as many chunks as the token count allows.
+    int chunk = std::max(g_opt.grad_tokens, 16 * std::min(jb.rpad, prow));
+    chunk = (chunk + 63) / 64 * 64;
+    const int nchunks = Tj > 0 ? (Tj + chunk - 1) / chunk : 0;
+    const int npb = (jb.rpad + prow - 1) / prow;
+    for (int pb = 0; pb < npb; ++pb)
+      for (int cb = 0; cb < ncb; ++cb) {
+        GradGroup g{};
+        g.job = j;  g.cb = cb;  g.pb = pb;  g.unit0 = (int)units.size();  g.nunits = nchunks;
+        for (int c = 0; c < nchunks; ++c) {
+          GradUnit u{};
+          u.job = j;  u.t0 = jb.row0 + c * chunk;  u.t1 = std::min(jb.row1, u.t0 + chunk);  u.cb = cb;  u.pb = pb;
+          units.push_back(u);
+        }
+        groups.push_back(g);
+      }
+  }
+}
+
+int build_plan(const tlora_problem_t* p, Plan& pl) {
+  const int rc = validate(p);
+  if (rc != TLORA_OK) return rc;
+  pl.J = p->num_jobs;  pl.T = (int)p->offsets[p->num_jobs];  pl.d_in = p->d_in;  pl.d_out = p->d_out;
+  pl.dtype = p->dtype;
+  pl.jobs.resize(pl.J);
+  int64_t soff = 0, atp = 0, ap = 0, bp = 0;
+  for (int j = 0; j < pl.J; ++j) {
+    JobDev& jb = pl.jobs[j];
+    memset(&jb, 0, sizeof(jb));
+    jb.row0 = (int32_t)p->offsets[j];  jb.row1 = (int32_t)p->offsets[j + 1];
+    jb.rank = p->ranks[j];
+    jb.rpad = (jb.rank + kRankGranule - 1) / kRankGranule * kRankGranule;
+    jb.scale = p->scales[j];
+    jb.soff = soff;  jb.atp_off = atp;  jb.ap_off = ap;  jb.bp_off = bp;
+    soff += (int64_t)(jb.row1 - jb.row0) * jb.rpad;
+    atp += (int64_t)jb.rpad * pl.d_in;  ap += (int64_t)jb.rpad * pl.d_in;  bp += (int64_t)jb.rpad * pl.d_out;
+    pl.max_rpad = std::max(pl.max_rpad, jb.rpad);
+  }
+  pl.s_elems = soff;  pl.atp_elems = atp;  pl.ap_elems = ap;  pl.bp_elems = bp;
+  pl.grad_mb = pl.max_rpad > kGradRanks ? 2 : 1;
+
+  // row tiles of the backbone GEMM (nano-batches of the concatenated batch, Sec. 3.3)
+  const int tiles_m = (pl.T + kGemmBM - 1) / kGemmBM;
+  pl.tile_jobs.resize(tiles_m);
+  {
+    int j = 0;
+    for (int tm = 0; tm < tiles_m; ++tm) {
+      const int r0 = tm * kGemmBM, r1 = std::min(pl.T, r0 + kGemmBM);
+      while (pl.jobs[j].row1 <= r0) ++j;             // first job with a row at or after r0
+      int last = j;
+      for (int k = j; k < pl.J && pl.jobs[k].row0 < r1; ++k)
+        if (pl.jobs[k].row1 > pl.jobs[k].row0) last = k;
+      pl.tile_jobs[tm].first = j;  pl.tile_jobs[tm].last = last;
+    }
+  }
+  if (pl.dtype == TLORA_BF16) {
+    for (int j = 0; j < pl.J; ++j) {
+      const JobDev& jb = pl.jobs[j];
+      if (jb.rpad == 0) continue;
+      const int npb = (jb.rpad + kShrinkCols - 1) / kShrinkCols;
+      for (int t0 = jb.row0; t0 < jb.row1; t0 += g_opt.shrink_rows)
+        for (int pb = 0; pb < npb; ++pb) {
+          ShrinkUnit u;
+          u.job = j;  u.t0 = t0;  u.nrows = std::min(g_opt.shrink_rows, jb.row1 - t0);  u.pb = pb;
+          pl.shrink_units.push_back(u);
+        }
+    }
+    build_grad_units(pl, pl.d_out, pl.gradB_units, pl.gradB_groups);
+    build_grad_units(pl, pl.d_in, pl.gradA_units, pl.gradA_groups);
+  }
+
+  // table blob
+  size_t o = 0;
+  auto place = [&](size_t bytes) { const size_t at = o;  o = align_up(o + bytes, 256);  return at; };
+  pl.tb_jobs = place(sizeof(JobDev) * pl.jobs.size());
+  pl.tb_tiles = place(sizeof(TileJobs) * pl.tile_jobs.size());
+  pl.tb_shrink = place(sizeof(ShrinkUnit) * pl.shrink_units.size());
+  pl.tb_gBu = place(sizeof(GradUnit) * pl.gradB_units.size());
+  pl.tb_gBg = place(sizeof(GradGroup) * pl.gradB_groups.size());
+  pl.tb_gAu = place(sizeof(GradUnit) * pl.gradA_units.size());
+  pl.tb_gAg = place(sizeof(GradGroup) * pl.gradA_groups.size());
+  if (pl.dtype == TLORA_F32) {
+    // the fp32 path needs at most 3 J + 1 products per launch, two launches per pass
+    const size_t max_units = 2 * (size_t)(3 * pl.J + 1);
+    size_t max_tiles = 0;
+    auto tiles_of = [](int64_t m, int64_t n) { return (size_t)(((m + 63) / 64) * ((n + 63) / 64)); };
+    max_tiles += 2 * tiles_of(pl.T, std::max(pl.d_in, pl.d_out));
+    for (int j = 0; j < pl.J; ++j) {
+      const JobDev& jb = pl.jobs[j];
+      const int Tj = jb.row1 - jb.row0;
+      max_tiles += 2 * tiles_of(Tj, jb.rank) + tiles_of(Tj, std::max(pl.d_in, pl.d_out)) +
+                   tiles_of(pl.d_in, jb.rank) + tiles_of(jb.rank, pl.d_out);
+    }
+    pl.f32_reserved = align_up(sizeof(F32Unit) * max_units, 256) + align_up(sizeof(F32Tile) * max_tiles, 256) + 4 * 256;
+    pl.tb_f32 = place(pl.f32_reserved);
+  }
+  pl.tables_bytes = o;
+
+  // workspace layout
+  size_t w = 0;
+  auto wplace = [&](size_t bytes) { const size_t at = w;  w = align_up(w + bytes, 256);  return at; };
+  pl.off_tables = wplace(pl.tables_bytes);
+  pl.off_S = wplace(sizeof(float) * (size_t)pl.s_elems);
+  pl.off_dS = wplace(sizeof(float) * (size_t)pl.s_elems);
+  if (pl.dtype == TLORA_BF16) {
+    pl.off_Sb = wplace(2 * (size_t)pl.s_elems);
+    pl.off_dSb = wplace(2 * (size_t)pl.s_elems);
+    pl.off_atp = wplace(2 * (size_t)pl.atp_elems);
+    pl.off_ap = wplace(2 * (size_t)pl.ap_elems);
+    pl.off_bp = wplace(2 * (size_t)pl.bp_elems);
+    const size_t tile_bytes = sizeof(float) * (size_t)pl.grad_mb * kGradRanks * kGradCols;
+    pl.off_partial = wplace(tile_bytes * std::max(pl.gradB_units.size(), pl.gradA_units.size()));
+  }
+  pl.total = std::max<size_t>(w, 256);
+  return TLORA_OK;
+}
+
+// ---- pinned staging for the table upload ----------------------------------------------------------------
+// A small ring of pinned host buffers; a slot is reused only after the copy that read it has finished.
+struct Slot {
+  void* host = nullptr;
+  size_t cap = 0;
+  hipEvent_t ev = nullptr;
+  bool busy = false;
+};
+constexpr int kSlots = 16;
+Slot g_slots[kSlots];
+int g_next_slot = 0;
+
+int upload_tables(const std::vector<uint8_t>& blob, void* dst, hipStream_t st) {
+  Slot& s = g_slots[g_next_slot];
+  g_next_slot = (g_next_slot + 1) % kSlots;
+  if (s.busy) {
+    if (hipEventSynchronize(s.ev) != hipSuccess) return TLORA_EHIP;
+    s.busy = false;
+  }
+  if (s.cap < blob.size()) {
+    if (s.host) (void)hipHostFree(s.host);
+    s.host = nullptr;  s.cap = 0;
+    const size_t cap = align_up(blob.size() * 2, 4096);
+    if (hipHostMalloc(&s.host, cap, hipHostMallocDefault) != hipSuccess) return TLORA_EHIP;
+    s.cap = cap;
+  }
+  if (!s.ev && hipEventCreateWithFlags(&s.ev, hipEventDisableTiming) != hipSuccess) return TLORA_EHIP;
+  memcpy(s.host, blob.data(), blob.size());
+  if (hipMemcpyAsync(dst, s.host, blob.size(), hipMemcpyHostToDevice, st) != hipSuccess) return TLORA_EHIP;
+  if (hipEventRecord(s.ev, st) != hipSuccess) return TLORA_EHIP;
+  s.busy = true;
+  return TLORA_OK;
+}
+
+int check_arch() {
+  static int cached = 1;   // 1 = unknown
+  if (cached != 1) return cached;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return TLORA_EHIP;
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return TLORA_EHIP;
+  cached = strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? TLORA_OK : TLORA_EARCH;
+  return cached;
+}
+
+inline bool misaligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) != 0; }
+
+template <class T>
+void put(std::vector<uint8_t>& blob, size_t at, const std::vector<T>& v) {
+  if (!v.empty()) memcpy(blob.data() + at, v.data(), sizeof(T) * v.size());
+}
+
+std::vector<uint8_t> make_blob(const Plan& pl) {
+  std::vector<uint8_t> blob(pl.tables_bytes, 0);
+  put(blob, pl.tb_jobs, pl.jobs);
+  put(blob, pl.tb_tiles, pl.tile_jobs);
+  put(blob, pl.tb_shrink, pl.shrink_units);
+  put(blob, pl.tb_gBu, pl.gradB_units);
+  put(blob, pl.tb_gBg, pl.gradB_groups);
+  put(blob, pl.tb_gAu, pl.gradA_units);
+  put(blob, pl.tb_gAg, pl.gradA_groups);
+  return blob;
+}
+
+// fp32 path: append the tiles of one product
+void f32_add(std::vector<F32Unit>& units, std::vector<F32Tile>& tiles, const F32Unit& u) {
+  if (u.M <= 0 || u.N <= 0) return;
+  const int id = (int)units.size();
+  units.push_back(u);
+  for (int tm = 0; tm < (u.M + 63) / 64; ++tm)
+    for (int tn = 0; tn < (u.N + 63) / 64; ++tn) tiles.push_back(F32Tile{id, tm, tn, 0});
+}
+F32Unit f32_unit(const float* A, int64_t a_rs, int64_t a_cs, const float* B, int64_t b_rs, int64_t b_cs, float* C,
+                 int64_t c_rs, int M, int N, int K, float alpha, bool accumulate) {
+  F32Unit u{};
+  u.A = A;  u.B = B;  u.C = C;  u.M = M;  u.N = N;  u.K = K;  u.accumulate = accumulate ? 1 : 0;
+  u.a_rs = a_rs;  u.a_cs = a_cs;  u.b_rs = b_rs;  u.b_cs = b_cs;  u.c_rs = c_rs;  u.alpha = alpha;
+  return u;
+}
+
+// Write the two launches' unit/tile tables into the blob's fp32 area and return their device addresses.
+struct F32Launch {
+  size_t units_at[2], tiles_at[2];
+  int ntiles[2];
+};
+int f32_place(const Plan& pl, std::vector<uint8_t>& blob, std::vector<F32Unit> units[2], std::vector<F32Tile> tiles[2],
+              F32Launch& L) {
+  size_t o = pl.tb_f32;
+  for (int i = 0; i < 2; ++i) {
+    // tile indices are per launch: rebase nothing, each launch has its own unit array
+    L.units_at[i] = o;
+    o = align_up(o + sizeof(F32Unit) * units[i].size(), 256);
+    L.tiles_at[i] = o;
+    o = align_up(o + sizeof(F32Tile) * tiles[i].size(), 256);
+    L.ntiles[i] = (int)tiles[i].size();
+  }
+  if (o > pl.tb_f32 + pl.f32_reserved) return TLORA_EWORKSPACE;
+  for (int i = 0; i < 2; ++i) {
+    put(blob, L.units_at[i], units[i]);
+    put(blob, L.tiles_at[i], tiles[i]);
+  }
+  return TLORA_OK;
+}
+
+int common_checks(const tlora_problem_t* p, Plan& pl, void* ws, size_t ws_bytes) {
+  int rc = build_plan(p, pl);
+  if (rc != TLORA_OK) return rc;
+  if ((pl.T > 0 && !p->X) || !p->W || !p->A || !p->B) return TLORA_ENULL;
+  for (int j = 0; j < pl.J; ++j)
+    if (pl.jobs[j].rank > 0 && (!p->A[j] || !p->B[j])) return TLORA_ENULL;
+  if (misaligned16(p->X) || misaligned16(p->W)) return TLORA_EALIGN;
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255) || ws_bytes < pl.total) return TLORA_EWORKSPACE;
+  for (int j = 0; j < pl.J; ++j) {
+    pl.jobs[j].A = p->A[j];
+    pl.jobs[j].B = p->B[j];
+  }
+  return TLORA_OK;
+}
+
+}  // namespace
+}  // namespace tlora
+
+using namespace tlora;
+
+extern "C" {
+
+size_t tlora_workspace_bytes(const tlora_problem_t* p) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  Plan pl;
+  if (build_plan(p, pl) != TLORA_OK) return 0;
+  return pl.total;
+}
+
+int tlora_fwd(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_bytes, void* hip_stream) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  Plan pl;
+  int rc = common_checks(p, pl, workspace, ws_bytes);
+  if (rc != TLORA_OK) return rc;
+  if (pl.T > 0 && !Y) return TLORA_ENULL;
+  if (misaligned16(Y)) return TLORA_EALIGN;
+  rc = check_arch();
+  if (rc != TLORA_OK) return rc;
+  if (pl.T == 0) return TLORA_OK;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  uint8_t* ws = static_cast<uint8_t*>(workspace);
+  uint8_t* tb = ws + pl.off_tables;
+  std::vector<uint8_t> blob = make_blob(pl);
+  const JobDev* jobs = reinterpret_cast<const JobDev*>(tb + pl.tb_jobs);
+  float* S = reinterpret_cast<float*>(ws + pl.off_S);
+
+  if (pl.dtype == TLORA_F32) {
+    const float* X = static_cast<const float*>(p->X);
+    const float* W = static_cast<const float*>(p->W);
+    float* Yf = static_cast<float*>(Y);
+    std::vector<F32Unit> units[2];
+    std::vector<F32Tile> tiles[2];
+    f32_add(units[0], tiles[0], f32_unit(X, pl.d_in, 1, W, pl.d_out, 1, Yf, pl.d_out, pl.T, pl.d_out, pl.d_in, 1.f, false));
+    for (int j = 0; j < pl.J; ++j) {
+      const JobDev& jb = pl.jobs[j];
+      const int Tj = jb.row1 - jb.row0;
+      if (jb.rank == 0 || Tj == 0) continue;
+      const float* Xj = X + (int64_t)jb.row0 * pl.d_in;
+      float* Sj = S + jb.soff;
+      f32_add(units[0], tiles[0], f32_unit(Xj, pl.d_in, 1, static_cast<const float*>(jb.A), jb.rank, 1, Sj, jb.rpad,
+                                           Tj, jb.rank, pl.d_in, 1.f, false));
+      f32_add(units[1], tiles[1], f32_unit(Sj, jb.rpad, 1, static_cast<const float*>(jb.B), pl.d_out, 1,
+                                           Yf + (int64_t)jb.row0 * pl.d_out, pl.d_out, Tj, pl.d_out, jb.rank, jb.scale,
+                                           true));
+    }
+    F32Launch L;
+    rc = f32_place(pl, blob, units, tiles, L);
+    if (rc != TLORA_OK) return rc;
+    rc = upload_tables(blob, tb, st);
+    if (rc != TLORA_OK) return rc;
+    for (int i = 0; i < 2; ++i)
+      launch_f32_units(reinterpret_cast<const F32Unit*>(tb + L.units_at[i]),
+                       reinterpret_cast<const F32Tile*>(tb + L.tiles_at[i]), L.ntiles[i], st);
+    return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+  }
+
+  rc = upload_tables(blob, tb, st);
+  if (rc != TLORA_OK) return rc;
+  uint16_t* Sb = reinterpret_cast<uint16_t*>(ws + pl.off_Sb);
+  uint16_t* atp = reinterpret_cast<uint16_t*>(ws + pl.off_atp);
+  uint16_t* ap = reinterpret_cast<uint16_t*>(ws + pl.off_ap);
+  uint16_t* bp = reinterpret_cast<uint16_t*>(ws + pl.off_bp);
+  launch_pack_adapters(jobs, pl.J, pl.d_in, pl.d_out, pl.max_rpad, atp, ap, bp, st);
+  launch_shrink(jobs, reinterpret_cast<const ShrinkUnit*>(tb + pl.tb_shrink), (int)pl.shrink_units.size(),
+                g_opt.shrink_rows, static_cast<const uint16_t*>(p->X), pl.d_in, atp, true, S, Sb, st);
+  launch_seg_gemm(true, jobs, reinterpret_cast<const TileJobs*>(tb + pl.tb_tiles), static_cast<const uint16_t*>(p->X),
+                  static_cast<const uint16_t*>(p->W), Sb, bp, static_cast<uint16_t*>(Y), pl.T, pl.d_in, pl.d_out, st);
+  return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+}
+
+int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* dA, void* const* dB, int flags,
+              void* workspace, size_t ws_bytes, void* hip_stream) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  Plan pl;
+  int rc = common_checks(p, pl, workspace, ws_bytes);
+  if (rc != TLORA_OK) return rc;
+  if (pl.T > 0 && !dY) return TLORA_ENULL;
+  if ((dA == nullptr) != (dB == nullptr)) return TLORA_ENULL;
+  if (misaligned16(dY) || (dX && misaligned16(dX))) return TLORA_EALIGN;
+  const bool want_grads = dA != nullptr;
+  if (want_grads)
+    for (int j = 0; j < pl.J; ++j) {
+      if (pl.jobs[j].rank > 0 && (!dA[j] || !dB[j])) return TLORA_ENULL;
+      pl.jobs[j].dA = dA[j];
+      pl.jobs[j].dB = dB[j];
+    }
+  if (flags & ~TLORA_BWD_REUSE_S) return TLORA_EINVAL;
+  rc = check_arch();
+  if (rc != TLORA_OK) return rc;
+  const bool reuse_S = (flags & TLORA_BWD_REUSE_S) != 0;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  uint8_t* ws = static_cast<uint8_t*>(workspace);
+  uint8_t* tb = ws + pl.off_tables;
+  std::vector<uint8_t> blob = make_blob(pl);
+  const JobDev* jobs = reinterpret_cast<const JobDev*>(tb + pl.tb_jobs);
+  float* S = reinterpret_cast<float*>(ws + pl.off_S);
+  float* dS = reinterpret_cast<float*>(ws + pl.off_dS);
+
+  if (pl.dtype == TLORA_F32) {
+    const float* X = static_cast<const float*>(p->X);
+    const float* W = static_cast<const float*>(p->W);
+    const float* dYf = static_cast<const float*>(dY);
+    float* dXf = static_cast<float*>(dX);
+    std::vector<F32Unit> units[2];
+    std::vector<F32Tile> tiles[2];
+    if (dXf)   // dX = dY . W^T : B(k = o, n = i) = W[i, o]
+      f32_add(units[0], tiles[0], f32_unit(dYf, pl.d_out, 1, W, 1, pl.d_out, dXf, pl.d_in, pl.T, pl.d_in, pl.d_out, 1.f, false));
+    for (int j = 0; j < pl.J; ++j) {
+      const JobDev& jb = pl.jobs[j];
+      const int Tj = jb.row1 - jb.row0;
+      if (jb.rank == 0) continue;
+      const float* Aj = static_cast<const float*>(jb.A);
+      const float* Bj = static_cast<const float*>(jb.B);
+      const float* Xj = X + (int64_t)jb.row0 * pl.d_in;
+      const float* dYj = dYf + (int64_t)jb.row0 * pl.d_out;
+      float* Sj = S + jb.soff;
+      float* dSj = dS + jb.soff;
+      // dS_j = dY_j . B_j^T : B(k = o, n = p) = B_j[p, o]
+      f32_add(units[0], tiles[0], f32_unit(dYj, pl.d_out, 1, Bj, 1, pl.d_out, dSj, jb.rpad, Tj, jb.rank, pl.d_out, 1.f, false));
+      if (!reuse_S && want_grads)
+        f32_add(units[0], tiles[0], f32_unit(Xj, pl.d_in, 1, Aj, jb.rank, 1, Sj, jb.rpad, Tj, jb.rank, pl.d_in, 1.f, false));
+      if (dXf)   // dX_j += s_j dS_j . A_j^T : B(k = p, n = i) = A_j[i, p]
+        f32_add(units[1], tiles[1], f32_unit(dSj, jb.rpad, 1, Aj, 1, jb.rank, dXf + (int64_t)jb.row0 * pl.d_in, pl.d_in,
+                                             Tj, pl.d_in, jb.rank, jb.scale, true));
+      if (want_grads) {
+        // dA_j = s_j X_j^T . dS_j : A(m = i, k = t) = X_j[t, i]
+        f32_add(units[1], tiles[1], f32_unit(Xj, 1, pl.d_in, dSj, jb.rpad, 1, static_cast<float*>(jb.dA), jb.rank,
+                                             pl.d_in, jb.rank, Tj, jb.scale, false));
+        // dB_j = s_j S_j^T . dY_j : A(m = p, k = t) = S_j[t, p]
+        f32_add(units[1], tiles[1], f32_unit(Sj, 1, jb.rpad, dYj, pl.d_out, 1, static_cast<float*>(jb.dB), pl.d_out,
+                                             jb.rank, pl.d_out, Tj, jb.scale, false));
+      }
+    }
+    F32Launch L;
+    rc = f32_place(pl, blob, units, tiles, L);
+    if (rc != TLORA_OK) return rc;
+    rc = upload_tables(blob, tb, st);
+    if (rc != TLORA_OK) return rc;
+    for (int i = 0; i < 2; ++i)
+      launch_f32_units(reinterpret_cast<const F32Unit*>(tb + L.units_at[i]),
+                       reinterpret_cast<const F32Tile*>(tb + L.tiles_at[i]), L.ntiles[i], st);
+    return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+  }
+
+  rc = upload_tables(blob, tb, st);
+  if (rc != TLORA_OK) return rc;
+  uint16_t* Sb = reinterpret_cast<uint16_t*>(ws + pl.off_Sb);
+  uint16_t* dSb = reinterpret_cast<uint16_t*>(ws + pl.off_dSb);
+  uint16_t* atp = reinterpret_cast<uint16_t*>(ws + pl.off_atp);
+  uint16_t* ap = reinterpret_cast<uint16_t*>(ws + pl.off_ap);
+  uint16_t* bp = reinterpret_cast<uint16_t*>(ws + pl.off_bp);
+  float* partial = reinterpret_cast<float*>(ws + pl.off_partial);
+  const ShrinkUnit* su = reinterpret_cast<const ShrinkUnit*>(tb + pl.tb_shrink);
+  const uint16_t* Xb = static_cast<const uint16_t*>(p->X);
+  const uint16_t* dYb = static_cast<const uint16_t*>(dY);
+
+  launch_pack_adapters(jobs, pl.J, pl.d_in, pl.d_out, pl.max_rpad, atp, ap, bp, st);
+  if (pl.T > 0) {
+    if (want_grads && !reuse_S)
+      launch_shrink(jobs, su, (int)pl.shrink_units.size(), g_opt.shrink_rows, Xb, pl.d_in, atp, true, S, Sb, st);
+    launch_shrink(jobs, su, (int)pl.shrink_units.size(), g_opt.shrink_rows, dYb, pl.d_out, bp, false, dS, dSb, st);
+    if (dX)
+      launch_seg_gemm(false, jobs, reinterpret_cast<const TileJobs*>(tb + pl.tb_tiles), dYb,
+                      static_cast<const uint16_t*>(p->W), dSb, ap, static_cast<uint16_t*>(dX), pl.T, pl.d_out, pl.d_in,
+                      st);
+  }
+  if (want_grads) {
+    launch_rank_grad(pl.grad_mb, jobs, reinterpret_cast<const GradUnit*>(tb + pl.tb_gBu), (int)pl.gradB_units.size(), S,
+                     dYb, pl.d_out, partial, st);
+    launch_grad_reduce(pl.grad_mb, jobs, reinterpret_cast<const GradGroup*>(tb + pl.tb_gBg),
+                       (int)pl.gradB_groups.size(), partial, pl.d_out, false, st);
+    launch_rank_grad(pl.grad_mb, jobs, reinterpret_cast<const GradUnit*>(tb + pl.tb_gAu), (int)pl.gradA_units.size(), dS,
+                     Xb, pl.d_in, partial, st);
+    launch_grad_reduce(pl.grad_mb, jobs, reinterpret_cast<const GradGroup*>(tb + pl.tb_gAg),
+                       (int)pl.gradA_groups.size(), partial, pl.d_in, true, st);
+  }
+  return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+}
+
+int tlora_plan_dump(const tlora_problem_t* p, int32_t* rpad, int64_t* soff, int32_t* tile_rows, int64_t* tile_row0,
+                    int32_t* tile_nrows, int32_t* tile_job_first, int32_t* tile_job_last, int64_t* n_tiles) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  Plan pl;
+  const int rc = build_plan(p, pl);
+  if (rc != TLORA_OK) return rc;
+  for (int j = 0; j < pl.J; ++j) {
+    if (rpad) rpad[j] = pl.jobs[j].rpad;
+    if (soff) soff[j] = pl.jobs[j].soff;
+  }
+  if (soff) soff[pl.J] = pl.s_elems;
+  if (tile_rows) *tile_rows = kGemmBM;
+  const int64_t nt = (int64_t)pl.tile_jobs.size();
+  if (n_tiles) {
+    const int64_t cap = *n_tiles;
+    *n_tiles = nt;
+    if (cap < nt && (tile_row0 || tile_nrows || tile_job_first || tile_job_last)) return TLORA_EINVAL;
+  } else if (tile_row0 || tile_nrows || tile_job_first || tile_job_last) {
+    return TLORA_ENULL;
+  }
+  for (int64_t t = 0; t < nt; ++t) {
+    if (tile_row0) tile_row0[t] = t * kGemmBM;
+    if (tile_nrows) tile_nrows[t] = (int32_t)std::min<int64_t>(kGemmBM, pl.T - t * kGemmBM);
+    if (tile_job_first) tile_job_first[t] = pl.tile_jobs[t].first;
+    if (tile_job_last) tile_job_last[t] = pl.tile_jobs[t].last;
+  }
+  return TLORA_OK;
+}
+
+int tlora_set_option(const char* name, int64_t value) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  if (!name) return TLORA_ENULL;
+  const std::string n(name);
+  if (n == "shrink_rows") {
+    if (value != 64 && value != 128) return TLORA_EINVAL;
+    g_opt.shrink_rows = (int)value;
+    return TLORA_OK;
+  }
+  if (n == "grad_tokens") {
+    if (value < 64 || value % 64 || value > (1 << 20)) return TLORA_EINVAL;
+    g_opt.grad_tokens = (int)value;
+    return TLORA_OK;
+  }
+  return TLORA_EINVAL;
+}
+
+const char* tlora_strerror(int status) {
+  switch (status) {
+    case TLORA_OK: return "ok";
+    case TLORA_EINVAL: return "invalid problem size, offsets, rank or option";
+    case TLORA_ENULL: return "a required pointer is null";
+    case TLORA_EDTYPE: return "unsupported dtype";
+    case TLORA_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case TLORA_EARCH: return "the current device is not gfx950";
+    case TLORA_EHIP: return "a HIP runtime call failed";
+    case TLORA_EALIGN: return "X, W, Y, dY or dX is not 16-byte aligned";
+    default: return "unknown status";
+  }
+}
+
+const char* tlora_version(void) { return "tlora-gfx950 0.1"; }
+
+}  // extern "C"

@@ -1,0 +1,81 @@
+// Internal tables shared by the host planner and the gfx950 kernels (plain PODs, copied to the
+// head of the caller's workspace once per call).
+#pragma once
+#include <stddef.h>
+#include <stdint.h>
+
+namespace tlora {
+
+constexpr int kRankGranule = 8;     // ranks are padded to 8 elements = one 16-byte bf16 chunk
+constexpr int kGemmBM = 256;        // backbone GEMM macro tile (token rows x output columns)
+constexpr int kGemmBN = 256;
+constexpr int kGemmBK = 64;
+constexpr int kShrinkCols = 64;     // rank columns per shrink work unit
+constexpr int kGradCols = 256;      // feature columns per dA/dB work unit (one wave row: 32 lanes x 8)
+constexpr int kGradRanks = 32;      // rank rows per MFMA block of the dA/dB kernel
+
+// One job's view of the problem (Sec. 3.2: one adapter branch per job on the shared backbone).
+struct JobDev {
+  int32_t row0, row1;      // token segment [row0, row1) of the concatenated batch
+  int32_t rank, rpad;      // r_j and r_j rounded up to kRankGranule
+  float scale;
+  int32_t pad_;
+  int64_t soff;            // element offset of the job's [T_j, rpad] block in S / dS / Sb / dSb
+  int64_t atp_off;         // element offset of A_j^T packed [rpad, d_in]  (bf16)
+  int64_t ap_off;          // element offset of A_j   packed [d_in, rpad]  (bf16)
+  int64_t bp_off;          // element offset of B_j   packed [rpad, d_out] (bf16)
+  const void* A;           // caller's A_j [d_in, r_j]
+  const void* B;           // caller's B_j [r_j, d_out]
+  void* dA;                // caller's dA_j (fp32) or null
+  void* dB;                // caller's dB_j (fp32) or null
+};
+
+// Row tile of the backbone GEMM: first and last job with a row inside the tile.
+struct TileJobs {
+  int32_t first, last;
+};
+
+// Work unit of the shrink kernels (S_j = X_j.A_j and dS_j = dY_j.B_j^T): a block of token rows of
+// one job times a block of kShrinkCols padded rank columns.
+struct ShrinkUnit {
+  int32_t job;
+  int32_t t0;              // first global token row
+  int32_t nrows;           // rows in this unit (<= shrink_rows)
+  int32_t pb;              // rank-column block
+};
+
+// Work unit of the dA/dB kernels: tokens [t0, t1) of one job x kGradCols feature columns x a block
+// of rank rows; writes one partial tile that the reduce pass sums in unit order.
+struct GradUnit {
+  int32_t job;
+  int32_t t0, t1;
+  int32_t cb;              // feature-column block
+  int32_t pb;              // rank block (of kGradRanks * MB rows)
+  int32_t pad_;
+};
+
+// One output tile of dA_j / dB_j: the run of partial tiles that sum to it.
+struct GradGroup {
+  int32_t job;
+  int32_t cb, pb;
+  int32_t unit0;           // first partial tile
+  int32_t nunits;          // number of partial tiles (token chunks)
+  int32_t pad_;
+};
+
+// fp32 path: one strided matrix product  C (+)= alpha * A.B  (used for the fp32 configuration).
+struct F32Unit {
+  const float* A;
+  const float* B;
+  float* C;
+  int32_t M, N, K;
+  int32_t accumulate;
+  int64_t a_rs, a_cs, b_rs, b_cs, c_rs;
+  float alpha;
+  int32_t pad_;
+};
+struct F32Tile {
+  int32_t unit, tm, tn, pad_;
+};
+
+}  // namespace tlora

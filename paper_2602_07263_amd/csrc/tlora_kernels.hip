@@ -1,0 +1,623 @@
+// gfx950 (CDNA4) kernels of the fused multi-LoRA linear layer.
+//
+// Wavefront = 64 lanes.  The contractions run on v_mfma_f32_32x32x16_bf16: lane l feeds row/column
+// (l % 32) of its operand with the 8 consecutive k-values 8*(l/32) .. +7, and owns, of the 32x32 fp32
+// result, column (l % 32) and rows 8*(i/4) + 4*(l/32) + (i%4) for accumulator register i.  All
+// kernels put the weight-side operand first, so a lane ends up with 4 consecutive output features of
+// one token and stores them with one 8- or 16-byte access.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tlora_kernels.h"
+
+namespace tlora {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+__device__ __forceinline__ u32x4 ldg16(const void* p) { return *reinterpret_cast<const u32x4*>(p); }
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  bf16x2 v = {(__bf16)lo, (__bf16)hi};   // round-to-nearest-even
+  return __builtin_bit_cast(uint32_t, v);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// LDS tile layouts.
+//  "row tile": R rows x 64 bf16 (128 B per row), k contiguous.  The 16-byte chunk c of row r sits at
+//  chunk slot c ^ ((r >> 1) & 7): 16 consecutive rows read at one logical chunk hit 16 distinct
+//  16-byte bank groups.
+//  "kn tile": 64 k-rows x 256 bf16 (512 B per row), n contiguous (W as stored for the forward).  The
+//  16-byte chunk c of k-row k sits at slot c ^ ((k & 3) << 2): the four k-rows one transposing read
+//  touches land in four distinct 64-byte bank groups.
+// ---------------------------------------------------------------------------------------------------
+__device__ __forceinline__ int row_tile_off(int r, int c) { return r * 128 + ((c ^ ((r >> 1) & 7)) << 4); }
+__device__ __forceinline__ int kn_tile_off(int k, int c) { return k * 512 + ((c ^ ((k & 3) << 2)) << 4); }
+
+// MFMA operand fragment of a row tile: rows rb .. rb+31, k-step kk (16 k-values).
+__device__ __forceinline__ bf16x8 frag_row_tile(const uint8_t* tile, int rb, int kk, int lane) {
+  const int r = rb + (lane & 31);
+  const int c = kk * 2 + (lane >> 5);
+  return as_bf16x8(*reinterpret_cast<const u32x4*>(tile + row_tile_off(r, c)));
+}
+// MFMA operand fragment of a kn tile: columns nb .. nb+31, k-step kk, through the transposing LDS read
+// (ds_read_b64_tr_b16: inside each group of 16 lanes, lane i receives element (i % 4) of the 8-byte
+// rows addressed by lanes 4e + i/4, e = 0..3 -- i.e. 4 consecutive k for column i of a 4 x 16 block).
+__device__ __forceinline__ bf16x8 frag_kn_tile(const uint8_t* tile, int nb, int kk, int lane) {
+  const int s = lane & 15;
+  const int n = nb + ((lane >> 4) & 1) * 16 + (s & 3) * 4;     // column this lane addresses
+  const int kbase = kk * 16 + (lane >> 5) * 8 + (s >> 2);
+  const int c = n >> 3;
+  const int inner = (n & 7) * 2;
+  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, tile + kn_tile_off(kbase, c) + inner));
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, tile + kn_tile_off(kbase + 4, c) + inner));
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Adapter packing: bf16 copies, zero padded to rpad, in the three layouts the kernels read.
+// ---------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) pack_adapters_kernel(const JobDev* __restrict__ jobs, int d_in, int d_out,
+                                                            uint16_t* __restrict__ atp, uint16_t* __restrict__ ap,
+                                                            uint16_t* __restrict__ bp) {
+  const JobDev jb = jobs[blockIdx.y];
+  if (jb.rpad == 0) return;
+  const uint16_t* A = static_cast<const uint16_t*>(jb.A);
+  const uint16_t* B = static_cast<const uint16_t*>(jb.B);
+  const int64_t na = (int64_t)jb.rpad * d_in;
+  const int64_t nb = (int64_t)jb.rpad * d_out;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < na; i += stride) {
+    {  // A_j^T [rpad, d_in]
+      const int p = (int)(i / d_in), k = (int)(i % d_in);
+      atp[jb.atp_off + i] = p < jb.rank ? A[(int64_t)k * jb.rank + p] : (uint16_t)0;
+    }
+    {  // A_j [d_in, rpad]
+      const int k = (int)(i / jb.rpad), p = (int)(i % jb.rpad);
+      ap[jb.ap_off + i] = p < jb.rank ? A[(int64_t)k * jb.rank + p] : (uint16_t)0;
+    }
+  }
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nb; i += stride) {
+    const int p = (int)(i / d_out);
+    bp[jb.bp_off + i] = p < jb.rank ? B[i] : (uint16_t)0;
+  }
+}
+
+void launch_pack_adapters(const JobDev* jobs, int num_jobs, int d_in, int d_out, int max_rpad, uint16_t* atp,
+                          uint16_t* ap, uint16_t* bp, hipStream_t st) {
+  if (max_rpad == 0) return;
+  const int64_t n = (int64_t)max_rpad * (d_in > d_out ? d_in : d_out);
+  int bx = (int)((n + 256 * 8 - 1) / (256 * 8));
+  if (bx > 512) bx = 512;
+  if (bx < 1) bx = 1;
+  hipLaunchKernelGGL(pack_adapters_kernel, dim3(bx, num_jobs), dim3(256), 0, st, jobs, d_in, d_out, atp, ap, bp);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Shrink:  out_j[t, p] = sum_k act[t, k] * P_j[p, k]      (Sec. 3.3: the compact |X_j| x r_j intermediate)
+// One workgroup = ROWS token rows of one job x 64 padded rank columns; 4 waves.
+// ---------------------------------------------------------------------------------------------------
+template <int ROWS>
+__global__ void __launch_bounds__(256) shrink_kernel(const JobDev* __restrict__ jobs,
+                                                     const ShrinkUnit* __restrict__ units,
+                                                     const uint16_t* __restrict__ act, int K,
+                                                     const uint16_t* __restrict__ packed, int packed_is_atp,
+                                                     float* __restrict__ S, uint16_t* __restrict__ Sb) {
+  constexpr int WM = ROWS / 32;          // waves along token rows
+  constexpr int WN = 4 / WM;             // waves along rank columns
+  constexpr int PW = kShrinkCols / WN;   // rank columns per wave
+  constexpr int NPB = PW / 32;           // 32-wide rank blocks per wave
+  constexpr int A_CH = ROWS * 8 / 256;   // 16-byte chunks per thread, activation tile
+  constexpr int P_CH = kShrinkCols * 8 / 256;
+
+  __shared__ __attribute__((aligned(16))) uint8_t lds[2 * (ROWS + kShrinkCols) * 128];
+  auto a_tile = [&](int buf) { return lds + buf * ((ROWS + kShrinkCols) * 128); };
+  auto p_tile = [&](int buf) { return lds + buf * ((ROWS + kShrinkCols) * 128) + ROWS * 128; };
+
+  const ShrinkUnit u = units[blockIdx.x];
+  const JobDev jb = jobs[u.job];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave % WM, wn = wave / WM;
+  const int p0 = u.pb * kShrinkCols;                     // first padded rank column of this unit
+  const int pvalid = min(kShrinkCols, jb.rpad - p0);     // > 0 by construction
+  const uint16_t* P = packed + (packed_is_atp ? jb.atp_off : jb.bp_off) + (int64_t)p0 * K;
+  const uint16_t* Arow = act + (int64_t)u.t0 * K;
+
+  f32x16 acc[NPB];
+#pragma unroll
+  for (int i = 0; i < NPB; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+
+  u32x4 areg[A_CH], preg[P_CH];
+  auto load_tiles = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i) {
+      const int id = tid + i * 256, r = id >> 3, c = id & 7;
+      const bool ok = r < u.nrows && k0 + c * 8 < K;
+      areg[i] = ok ? ldg16(Arow + (int64_t)r * K + k0 + c * 8) : u32x4{0, 0, 0, 0};
+    }
+#pragma unroll
+    for (int i = 0; i < P_CH; ++i) {
+      const int id = tid + i * 256, r = id >> 3, c = id & 7;
+      const bool ok = r < pvalid && k0 + c * 8 < K;
+      preg[i] = ok ? ldg16(P + (int64_t)r * K + k0 + c * 8) : u32x4{0, 0, 0, 0};
+    }
+  };
+  auto store_tiles = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i) {
+      const int id = tid + i * 256, r = id >> 3, c = id & 7;
+      *reinterpret_cast<u32x4*>(a_tile(buf) + row_tile_off(r, c)) = areg[i];
+    }
+#pragma unroll
+    for (int i = 0; i < P_CH; ++i) {
+      const int id = tid + i * 256, r = id >> 3, c = id & 7;
+      *reinterpret_cast<u32x4*>(p_tile(buf) + row_tile_off(r, c)) = preg[i];
+    }
+  };
+
+  const int nkt = (K + 63) / 64;
+  load_tiles(0);
+  store_tiles(0);
+  __syncthreads();
+  for (int kt = 0; kt < nkt; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < nkt) load_tiles((kt + 1) * 64);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      const bf16x8 xf = frag_row_tile(a_tile(buf), wm * 32, kk, lane);
+#pragma unroll
+      for (int i = 0; i < NPB; ++i) {
+        const bf16x8 pf = frag_row_tile(p_tile(buf), wn * PW + i * 32, kk, lane);
+        acc[i] = mfma32(pf, xf, acc[i]);
+      }
+    }
+    if (kt + 1 < nkt) store_tiles(buf ^ 1);
+    __syncthreads();
+  }
+
+  // lane: token row (lane % 32); registers: 4 consecutive rank columns per group g.
+  const int r = wm * 32 + (lane & 31);
+  if (r < u.nrows) {
+    const int64_t rowbase = jb.soff + (int64_t)(u.t0 + r - jb.row0) * jb.rpad;
+#pragma unroll
+    for (int i = 0; i < NPB; ++i)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int p = p0 + wn * PW + i * 32 + g * 8 + (lane >> 5) * 4;
+        if (p < jb.rpad) {
+          const float v0 = acc[i][g * 4 + 0], v1 = acc[i][g * 4 + 1], v2 = acc[i][g * 4 + 2], v3 = acc[i][g * 4 + 3];
+          *reinterpret_cast<float4*>(S + rowbase + p) = make_float4(v0, v1, v2, v3);
+          u32x2 b = {pack_bf16x2(jb.scale * v0, jb.scale * v1), pack_bf16x2(jb.scale * v2, jb.scale * v3)};
+          *reinterpret_cast<u32x2*>(Sb + rowbase + p) = b;
+        }
+      }
+  }
+}
+
+void launch_shrink(const JobDev* jobs, const ShrinkUnit* units, int num_units, int shrink_rows, const uint16_t* act,
+                   int K, const uint16_t* packed, bool packed_is_atp, float* S, uint16_t* Sb, hipStream_t st) {
+  if (num_units == 0) return;
+  if (shrink_rows == 128)
+    hipLaunchKernelGGL(shrink_kernel<128>, dim3(num_units), dim3(256), 0, st, jobs, units, act, K, packed,
+                       packed_is_atp ? 1 : 0, S, Sb);
+  else
+    hipLaunchKernelGGL(shrink_kernel<64>, dim3(num_units), dim3(256), 0, st, jobs, units, act, K, packed,
+                       packed_is_atp ? 1 : 0, S, Sb);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Segmented backbone GEMM with the adapter expand fused as extra K-steps:
+//   out[t, :] = act[t, :] . Wop  +  Sb_j[t, :] . Eop_j          (job j = owner of row t)
+// 256 x 256 output tile per workgroup of 8 waves (2 along tokens x 4 along features, 128 x 64 each),
+// K-steps of 64 double-buffered in LDS.  Row tiles are uniform over the concatenated batch and may
+// hold rows of several jobs: the backbone K-loop is job-blind, and each job present in the tile then
+// adds ceil(rpad_j / 64) K-steps in which only its own rows are non-zero.
+// ---------------------------------------------------------------------------------------------------
+struct GemmParams {
+  const JobDev* jobs;
+  const TileJobs* tile_jobs;
+  const uint16_t* act;      // [T, K]
+  const uint16_t* W;        // KN: [K, N]   else [N, K]
+  const uint16_t* Sb;       // packed scaled intermediates (bf16)
+  const uint16_t* packed;   // KN: B_j packed [rpad, N] at bp_off;  else A_j packed [N, rpad] at ap_off
+  uint16_t* out;            // [T, N]
+  int T, K, N;
+  int tiles_m, tiles_n;
+};
+
+template <bool KN>
+__global__ void __launch_bounds__(512) seg_gemm_kernel(GemmParams P) {
+  constexpr int BM = kGemmBM, BN = kGemmBN, BK = kGemmBK;
+  constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
+  __shared__ __attribute__((aligned(16))) uint8_t lds[2 * (A_BYTES + B_BYTES)];
+  auto a_tile = [&](int buf) { return lds + buf * (A_BYTES + B_BYTES); };
+  auto b_tile = [&](int buf) { return lds + buf * (A_BYTES + B_BYTES) + A_BYTES; };
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave & 1, wn = wave >> 1;
+
+  // Workgroup ids are dealt round-robin to the 8 XCDs; hand each XCD a contiguous run of logical tile
+  // ids, and walk tiles in groups of 8 row tiles so the 32 workgroups an XCD runs together share
+  // 8 activation panels and 4 weight panels in its L2.
+  int tm, tn;
+  {
+    const int nb = P.tiles_m * P.tiles_n, b = blockIdx.x;
+    const int q = nb >> 3, rem = nb & 7, x = b & 7;
+    const int L = x * q + min(x, rem) + (b >> 3);
+    constexpr int GM = 8;
+    const int per_group = GM * P.tiles_n;
+    const int grp = L / per_group, first_m = grp * GM;
+    const int gsize = min(GM, P.tiles_m - first_m);
+    const int Lg = L - grp * per_group;
+    tm = first_m + Lg % gsize;
+    tn = Lg / gsize;
+  }
+  const int row0 = tm * BM, col0 = tn * BN;
+  const int rows_valid = min(BM, P.T - row0);
+  const TileJobs tj = P.tile_jobs[tm];
+
+  f32x16 acc[2][4];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.f;
+
+  // --- K-step iterator: backbone steps, then the adapter steps of each job in the tile ----------------
+  int it_phase_job = -1;       // -1: backbone; otherwise current job
+  int it_k0 = 0;               // k offset inside the current phase
+  struct Step {
+    const uint16_t* a;  int64_t a_stride;  int r_lo, r_hi;  int kvalid;
+    const uint16_t* b;  int64_t b_stride;
+  };
+  auto next_step = [&](Step& s) -> bool {
+    if (it_phase_job < 0) {
+      if (it_k0 < P.K) {
+        s.a = P.act + (int64_t)row0 * P.K + it_k0;  s.a_stride = P.K;  s.r_lo = 0;  s.r_hi = rows_valid;
+        s.kvalid = min(BK, P.K - it_k0);
+        if (KN) { s.b = P.W + (int64_t)it_k0 * P.N + col0;  s.b_stride = P.N; }
+        else    { s.b = P.W + (int64_t)col0 * P.K + it_k0;  s.b_stride = P.K; }
+        it_k0 += BK;
+        return true;
+      }
+      it_phase_job = tj.first;  it_k0 = 0;
+    }
+    while (it_phase_job <= tj.last) {
+      const JobDev jb = P.jobs[it_phase_job];
+      const int lo = max(jb.row0 - row0, 0), hi = min(jb.row1 - row0, rows_valid);
+      if (jb.rpad > 0 && lo < hi && it_k0 < jb.rpad) {
+        // rows of other jobs are masked to zero, so the pointer is only dereferenced inside [lo, hi)
+        s.a = P.Sb + jb.soff + ((int64_t)row0 - jb.row0) * jb.rpad + it_k0;  s.a_stride = jb.rpad;
+        s.r_lo = lo;  s.r_hi = hi;  s.kvalid = min(BK, jb.rpad - it_k0);
+        if (KN) { s.b = P.packed + jb.bp_off + (int64_t)it_k0 * P.N + col0;  s.b_stride = P.N; }
+        else    { s.b = P.packed + jb.ap_off + (int64_t)col0 * jb.rpad + it_k0;  s.b_stride = jb.rpad; }
+        it_k0 += BK;
+        return true;
+      }
+      ++it_phase_job;  it_k0 = 0;
+    }
+    return false;
+  };
+
+  u32x4 areg[4], breg[4];
+  auto load_tiles = [&](const Step& s) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int id = tid + i * 512, r = id >> 3, c = id & 7;
+      const bool ok = r >= s.r_lo && r < s.r_hi && c * 8 < s.kvalid;
+      areg[i] = ok ? ldg16(s.a + (int64_t)r * s.a_stride + c * 8) : u32x4{0, 0, 0, 0};
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int id = tid + i * 512;
+      if (KN) {
+        const int k = id >> 5, c = id & 31;
+        const bool ok = k < s.kvalid && col0 + c * 8 < P.N;
+        breg[i] = ok ? ldg16(s.b + (int64_t)k * s.b_stride + c * 8) : u32x4{0, 0, 0, 0};
+      } else {
+        const int n = id >> 3, c = id & 7;
+        const bool ok = col0 + n < P.N && c * 8 < s.kvalid;
+        breg[i] = ok ? ldg16(s.b + (int64_t)n * s.b_stride + c * 8) : u32x4{0, 0, 0, 0};
+      }
+    }
+  };
+  auto store_tiles = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int id = tid + i * 512, r = id >> 3, c = id & 7;
+      *reinterpret_cast<u32x4*>(a_tile(buf) + row_tile_off(r, c)) = areg[i];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int id = tid + i * 512;
+      if (KN) *reinterpret_cast<u32x4*>(b_tile(buf) + kn_tile_off(id >> 5, id & 31)) = breg[i];
+      else    *reinterpret_cast<u32x4*>(b_tile(buf) + row_tile_off(id >> 3, id & 7)) = breg[i];
+    }
+  };
+
+  Step cur, nxt;
+  bool have = next_step(cur);
+  if (have) {
+    load_tiles(cur);
+    store_tiles(0);
+  }
+  __syncthreads();
+  int buf = 0;
+  while (have) {
+    const bool have_next = next_step(nxt);
+    if (have_next) load_tiles(nxt);
+    const int nkk = (cur.kvalid + 15) >> 4;
+    for (int kk = 0; kk < nkk; ++kk) {
+      bf16x8 xf[4], wf[2];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) xf[i] = frag_row_tile(a_tile(buf), wm * 128 + i * 32, kk, lane);
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        wf[j] = KN ? frag_kn_tile(b_tile(buf), wn * 64 + j * 32, kk, lane)
+                   : frag_row_tile(b_tile(buf), wn * 64 + j * 32, kk, lane);
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[j][i] = mfma32(wf[j], xf[i], acc[j][i]);
+    }
+    if (have_next) store_tiles(buf ^ 1);
+    __syncthreads();
+    buf ^= 1;
+    cur = nxt;
+    have = have_next;
+  }
+
+  // epilogue: lane = token row (lane % 32) of block i; 4 consecutive features per register group.
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = wm * 128 + i * 32 + (lane & 31);
+    if (r < rows_valid) {
+      uint16_t* orow = P.out + (int64_t)(row0 + r) * P.N;
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int n = col0 + wn * 64 + j * 32 + g * 8 + (lane >> 5) * 4;
+          if (n < P.N) {
+            u32x2 v = {pack_bf16x2(acc[j][i][g * 4 + 0], acc[j][i][g * 4 + 1]),
+                       pack_bf16x2(acc[j][i][g * 4 + 2], acc[j][i][g * 4 + 3])};
+            *reinterpret_cast<u32x2*>(orow + n) = v;
+          }
+        }
+    }
+  }
+}
+
+void launch_seg_gemm(bool w_is_kn, const JobDev* jobs, const TileJobs* tile_jobs, const uint16_t* act,
+                     const uint16_t* W, const uint16_t* Sb, const uint16_t* packed, uint16_t* out, int T, int K,
+                     int N, hipStream_t st) {
+  GemmParams P;
+  P.jobs = jobs;  P.tile_jobs = tile_jobs;  P.act = act;  P.W = W;  P.Sb = Sb;  P.packed = packed;  P.out = out;
+  P.T = T;  P.K = K;  P.N = N;
+  P.tiles_m = (T + kGemmBM - 1) / kGemmBM;
+  P.tiles_n = (N + kGemmBN - 1) / kGemmBN;
+  const int nb = P.tiles_m * P.tiles_n;
+  if (nb == 0) return;
+  if (w_is_kn) hipLaunchKernelGGL(seg_gemm_kernel<true>, dim3(nb), dim3(512), 0, st, P);
+  else         hipLaunchKernelGGL(seg_gemm_kernel<false>, dim3(nb), dim3(512), 0, st, P);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// dA / dB:  G_j[p, c] = scale_j * sum_{t in seg j} U_j[t, p] * V[t, c]
+//   dB_j: U = S_j (fp32, packed), V = dY;   dA_j^T: U = dS_j, V = X.
+// The streamed operand V never touches LDS: a lane loads 8 token rows x 8 columns (16 B each),
+// transposes the 8x8 block in registers and feeds column q of it to the q-th of 8 MFMAs, whose
+// output column (lane % 32) therefore stands for feature 8*(lane % 32) + q.  U is fp32 and is split
+// into bf16 hi + lo parts (two MFMAs) so the result keeps ~16 mantissa bits of U.
+// ---------------------------------------------------------------------------------------------------
+template <int MB>
+__global__ void __launch_bounds__(256) rank_grad_kernel(const JobDev* __restrict__ jobs,
+                                                        const GradUnit* __restrict__ units,
+                                                        const float* __restrict__ U,
+                                                        const uint16_t* __restrict__ V, int D,
+                                                        float* __restrict__ partial) {
+  __shared__ float red[MB * 8 * 16 * 64];
+  const GradUnit u = units[blockIdx.x];
+  const JobDev jb = jobs[u.job];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int pbase = u.pb * (kGradRanks * MB);
+  const int nmb = min(MB, (jb.rpad - pbase + kGradRanks - 1) / kGradRanks);   // rank blocks with any live row
+  const int col = u.cb * kGradCols + (lane & 31) * 8;
+  const bool col_ok = col < D;                                                // D % 8 == 0
+  const float* Uj = U + jb.soff;
+
+  f32x16 acc[MB][8];
+#pragma unroll
+  for (int m = 0; m < MB; ++m)
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[m][q][e] = 0.f;
+
+  for (int tg = u.t0 + wave * 16; tg < u.t1; tg += 64) {
+    const int tb = tg + (lane >> 5) * 8;
+    u32x4 v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int t = tb + e;
+      v[e] = (t < u.t1 && col_ok) ? ldg16(V + (int64_t)t * D + col) : u32x4{0, 0, 0, 0};
+    }
+    // 8x8 transpose of 16-bit elements: b[q] = tokens 0..7 of column q
+    bf16x8 b[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      u32x4 o;
+#pragma unroll
+      for (int d = 0; d < 4; ++d)
+        o[d] = __builtin_amdgcn_perm(v[2 * d + 1][q >> 1], v[2 * d][q >> 1], (q & 1) ? 0x07060302u : 0x05040100u);
+      b[q] = as_bf16x8(o);
+    }
+#pragma unroll
+    for (int m = 0; m < MB; ++m) {
+      if (m < nmb) {
+        const int p = pbase + m * kGradRanks + (lane & 31);
+        bf16x8 hi, lo;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int t = tb + e;
+          const float x = (t < u.t1 && p < jb.rpad) ? Uj[(int64_t)(t - jb.row0) * jb.rpad + p] : 0.f;
+          const __bf16 h = (__bf16)x;
+          hi[e] = h;
+          lo[e] = (__bf16)(x - (float)h);
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          acc[m][q] = mfma32(hi, b[q], acc[m][q]);
+          acc[m][q] = mfma32(lo, b[q], acc[m][q]);
+        }
+      }
+    }
+  }
+
+  // fixed-order sum of the four waves' accumulators: wave 0 += wave 1, += wave 2, += wave 3
+  for (int src = 1; src < 4; ++src) {
+    if (wave == src) {
+#pragma unroll
+      for (int m = 0; m < MB; ++m)
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) red[((m * 8 + q) * 16 + e) * 64 + lane] = acc[m][q][e];
+    }
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+      for (int m = 0; m < MB; ++m)
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) acc[m][q][e] += red[((m * 8 + q) * 16 + e) * 64 + lane];
+    }
+    __syncthreads();
+  }
+  if (wave == 0) {
+    float* out = partial + (int64_t)blockIdx.x * (MB * kGradRanks * kGradCols);
+#pragma unroll
+    for (int m = 0; m < MB; ++m)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int pl = m * kGradRanks + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+        float* o = out + pl * kGradCols + (lane & 31) * 8;
+        *reinterpret_cast<float4*>(o) = make_float4(acc[m][0][e], acc[m][1][e], acc[m][2][e], acc[m][3][e]);
+        *reinterpret_cast<float4*>(o + 4) = make_float4(acc[m][4][e], acc[m][5][e], acc[m][6][e], acc[m][7][e]);
+      }
+  }
+}
+
+void launch_rank_grad(int mb, const JobDev* jobs, const GradUnit* units, int num_units, const float* U,
+                      const uint16_t* V, int D, float* partial, hipStream_t st) {
+  if (num_units == 0) return;
+  if (mb == 1)
+    hipLaunchKernelGGL(rank_grad_kernel<1>, dim3(num_units), dim3(256), 0, st, jobs, units, U, V, D, partial);
+  else
+    hipLaunchKernelGGL(rank_grad_kernel<2>, dim3(num_units), dim3(256), 0, st, jobs, units, U, V, D, partial);
+}
+
+// Sum the partial tiles of one output tile in unit order, scale, and store (dB_j row-major [r, D];
+// dA_j is the transpose of the computed tile: [D, r]).
+__global__ void __launch_bounds__(256) grad_reduce_kernel(const JobDev* __restrict__ jobs,
+                                                          const GradGroup* __restrict__ groups,
+                                                          const float* __restrict__ partial, int D, int mb,
+                                                          int out_is_dA) {
+  const GradGroup g = groups[blockIdx.x];
+  const JobDev jb = jobs[g.job];
+  const int c = g.cb * kGradCols + threadIdx.x;
+  if (c >= D) return;
+  const int tile_rows = mb * kGradRanks;
+  const int64_t tile_elems = (int64_t)tile_rows * kGradCols;
+  float* dst = static_cast<float*>(out_is_dA ? jb.dA : jb.dB);
+  for (int pl = 0; pl < tile_rows; ++pl) {
+    const int p = g.pb * tile_rows + pl;
+    if (p >= jb.rank) break;
+    float s = 0.f;
+    for (int k = 0; k < g.nunits; ++k) s += partial[(int64_t)(g.unit0 + k) * tile_elems + pl * kGradCols + threadIdx.x];
+    s *= jb.scale;
+    if (out_is_dA) dst[(int64_t)c * jb.rank + p] = s;
+    else           dst[(int64_t)p * D + c] = s;
+  }
+}
+
+void launch_grad_reduce(int mb, const JobDev* jobs, const GradGroup* groups, int num_groups, const float* partial,
+                        int D, bool out_is_dA, hipStream_t st) {
+  if (num_groups == 0) return;
+  hipLaunchKernelGGL(grad_reduce_kernel, dim3(num_groups), dim3(256), 0, st, jobs, groups, partial, D, mb,
+                     out_is_dA ? 1 : 0);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// fp32 configuration: strided products C (+)= alpha * A.B, 64 x 64 tile per workgroup.  Operands and
+// results are fp32; the running sums are kept in fp64 so that long token reductions (dA, dB) stay
+// within 1e-5 of the exact value even where the result is close to zero.
+// ---------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) f32_units_kernel(const F32Unit* __restrict__ units,
+                                                        const F32Tile* __restrict__ tiles) {
+  __shared__ float As[16][65];
+  __shared__ float Bs[16][65];
+  const F32Tile t = tiles[blockIdx.x];
+  const F32Unit u = units[t.unit];
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  const int m0 = t.tm * 64, n0 = t.tn * 64;
+  double acc[4][4] = {};
+  for (int k0 = 0; k0 < u.K; k0 += 16) {
+    for (int i = threadIdx.x; i < 16 * 64; i += 256) {
+      const int kk = i & 15, mm = i >> 4;             // A tile: 64 rows x 16 k
+      const int m = m0 + mm, k = k0 + kk;
+      As[kk][mm] = (m < u.M && k < u.K) ? u.A[(int64_t)m * u.a_rs + (int64_t)k * u.a_cs] : 0.f;
+      const int nn = i & 63, kb = i >> 6;             // B tile: 16 k x 64 cols
+      const int n = n0 + nn, k2 = k0 + kb;
+      Bs[kb][nn] = (n < u.N && k2 < u.K) ? u.B[(int64_t)k2 * u.b_rs + (int64_t)n * u.b_cs] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) b[j] = Bs[kk][tx * 4 + j];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_fma((double)a[i], (double)b[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
+      if (m < u.M && n < u.N) {
+        float* c = u.C + (int64_t)m * u.c_rs + n;
+        const double v = (double)u.alpha * acc[i][j];
+        *c = (float)(u.accumulate ? (double)*c + v : v);
+      }
+    }
+}
+
+void launch_f32_units(const F32Unit* units, const F32Tile* tiles, int num_tiles, hipStream_t st) {
+  if (num_tiles == 0) return;
+  hipLaunchKernelGGL(f32_units_kernel, dim3(num_tiles), dim3(256), 0, st, units, tiles);
+}
+
+}  // namespace tlora

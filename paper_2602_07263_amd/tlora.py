@@ -1,0 +1,213 @@
+"""Thin ctypes binding of libtlora.so: argument marshalling only.
+
+The functions mirror the C ABI declared in include/tlora.h (same names).  `LayerProblem` is a
+convenience holder that keeps the host arrays and torch tensors of one problem alive and builds the
+`tlora_problem_t` struct from them.  Every step of the layer runs inside the library's kernels;
+there is no fallback: a missing library or a failed call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+TLORA_F32, TLORA_BF16 = 0, 1
+TLORA_BWD_REUSE_S = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtlora.so")
+_lib = None
+
+
+class TloraError(RuntimeError):
+    pass
+
+
+class tlora_problem_t(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("num_jobs", ctypes.c_int32),
+                ("d_in", ctypes.c_int32), ("d_out", ctypes.c_int32),
+                ("ranks", ctypes.POINTER(ctypes.c_int32)), ("offsets", ctypes.POINTER(ctypes.c_int64)),
+                ("scales", ctypes.POINTER(ctypes.c_float)),
+                ("X", ctypes.c_void_p), ("W", ctypes.c_void_p),
+                ("A", ctypes.POINTER(ctypes.c_void_p)), ("B", ctypes.POINTER(ctypes.c_void_p))]
+
+
+EXPORTS = ["tlora_workspace_bytes", "tlora_fwd", "tlora_bwd", "tlora_plan_dump", "tlora_set_option",
+           "tlora_strerror", "tlora_version"]
+
+
+def lib() -> ctypes.CDLL:
+    """Load libtlora.so (building it first only if it has never been built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from . import build as _build
+        _build.build()
+    L = ctypes.CDLL(LIB_PATH)
+    P = ctypes.POINTER(tlora_problem_t)
+    L.tlora_workspace_bytes.restype = ctypes.c_size_t
+    L.tlora_workspace_bytes.argtypes = [P]
+    L.tlora_fwd.restype = ctypes.c_int
+    L.tlora_fwd.argtypes = [P, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    L.tlora_bwd.restype = ctypes.c_int
+    L.tlora_bwd.argtypes = [P, ctypes.c_void_p, ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p),
+                            ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t,
+                            ctypes.c_void_p]
+    L.tlora_plan_dump.restype = ctypes.c_int
+    L.tlora_plan_dump.argtypes = [P, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64),
+                                  ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64),
+                                  ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32),
+                                  ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64)]
+    L.tlora_set_option.restype = ctypes.c_int
+    L.tlora_set_option.argtypes = [ctypes.c_char_p, ctypes.c_int64]
+    L.tlora_strerror.restype = ctypes.c_char_p
+    L.tlora_strerror.argtypes = [ctypes.c_int]
+    L.tlora_version.restype = ctypes.c_char_p
+    L.tlora_version.argtypes = []
+    _lib = L
+    return L
+
+
+def tlora_strerror(status: int) -> str:
+    return lib().tlora_strerror(int(status)).decode()
+
+
+def tlora_version() -> str:
+    return lib().tlora_version().decode()
+
+
+def _check(status: int, what: str) -> None:
+    if status != 0:
+        raise TloraError(f"{what} failed: {status} ({tlora_strerror(status)})")
+
+
+def tlora_set_option(name: str, value: int) -> None:
+    _check(lib().tlora_set_option(name.encode(), int(value)), f"tlora_set_option({name})")
+
+
+def make_problem(dtype: int, d_in: int, d_out: int, ranks: Sequence[int], offsets: Sequence[int],
+                 scales: Sequence[float], X_ptr: int, W_ptr: int, A_ptrs: Sequence[int],
+                 B_ptrs: Sequence[int]):
+    """Build a tlora_problem_t from plain integers; returns (struct, keepalive list)."""
+    J = len(ranks)
+    c_ranks = (ctypes.c_int32 * J)(*[int(r) for r in ranks])
+    c_off = (ctypes.c_int64 * (J + 1))(*[int(o) for o in offsets])
+    c_scales = (ctypes.c_float * J)(*[float(s) for s in scales])
+    c_A = (ctypes.c_void_p * J)(*[ctypes.c_void_p(int(p)) if p else None for p in A_ptrs])
+    c_B = (ctypes.c_void_p * J)(*[ctypes.c_void_p(int(p)) if p else None for p in B_ptrs])
+    prob = tlora_problem_t(int(dtype), J, int(d_in), int(d_out), c_ranks, c_off, c_scales,
+                           ctypes.c_void_p(int(X_ptr)) if X_ptr else None,
+                           ctypes.c_void_p(int(W_ptr)) if W_ptr else None, c_A, c_B)
+    return prob, [c_ranks, c_off, c_scales, c_A, c_B]
+
+
+def tlora_workspace_bytes(prob: tlora_problem_t) -> int:
+    return int(lib().tlora_workspace_bytes(ctypes.byref(prob)))
+
+
+def tlora_fwd(prob: tlora_problem_t, Y_ptr: int, ws_ptr: int, ws_bytes: int, stream: int = 0) -> None:
+    _check(lib().tlora_fwd(ctypes.byref(prob), ctypes.c_void_p(Y_ptr), ctypes.c_void_p(ws_ptr),
+                           ctypes.c_size_t(ws_bytes), ctypes.c_void_p(stream)), "tlora_fwd")
+
+
+def tlora_bwd(prob: tlora_problem_t, dY_ptr: int, dX_ptr: int, dA_ptrs: Optional[Sequence[int]],
+              dB_ptrs: Optional[Sequence[int]], flags: int, ws_ptr: int, ws_bytes: int, stream: int = 0) -> None:
+    J = prob.num_jobs
+    if dA_ptrs is None:
+        c_dA = c_dB = None
+    else:
+        c_dA = (ctypes.c_void_p * J)(*[ctypes.c_void_p(int(p)) if p else None for p in dA_ptrs])
+        c_dB = (ctypes.c_void_p * J)(*[ctypes.c_void_p(int(p)) if p else None for p in dB_ptrs])
+    _check(lib().tlora_bwd(ctypes.byref(prob), ctypes.c_void_p(dY_ptr), ctypes.c_void_p(dX_ptr) if dX_ptr else None,
+                           c_dA, c_dB, int(flags), ctypes.c_void_p(ws_ptr), ctypes.c_size_t(ws_bytes),
+                           ctypes.c_void_p(stream)), "tlora_bwd")
+
+
+def tlora_plan_dump(prob: tlora_problem_t) -> dict:
+    """The plan's integer bookkeeping as Python lists."""
+    J = prob.num_jobs
+    L = lib()
+    n = ctypes.c_int64(0)
+    rpad = (ctypes.c_int32 * J)()
+    soff = (ctypes.c_int64 * (J + 1))()
+    tile_rows = ctypes.c_int32(0)
+    _check(L.tlora_plan_dump(ctypes.byref(prob), rpad, soff, ctypes.byref(tile_rows), None, None, None, None,
+                             ctypes.byref(n)), "tlora_plan_dump")
+    nt = max(int(n.value), 1)
+    row0 = (ctypes.c_int64 * nt)()
+    nrows = (ctypes.c_int32 * nt)()
+    jf = (ctypes.c_int32 * nt)()
+    jl = (ctypes.c_int32 * nt)()
+    n2 = ctypes.c_int64(nt)
+    _check(L.tlora_plan_dump(ctypes.byref(prob), None, None, None, row0, nrows, jf, jl, ctypes.byref(n2)),
+           "tlora_plan_dump")
+    k = int(n.value)
+    return {"rpad": list(rpad), "soff": list(soff), "tile_rows": int(tile_rows.value),
+            "tiles": [(int(row0[i]), int(nrows[i]), int(jf[i]), int(jl[i])) for i in range(k)]}
+
+
+# ---- torch-backed convenience holder ---------------------------------------------------------------------
+class LayerProblem:
+    """Device tensors of one fused-layer problem plus the marshalled struct.
+
+    Torch only owns the device memory and supplies the stream; all computation is in libtlora.so."""
+
+    def __init__(self, dtype: str, d_in: int, d_out: int, ranks, offsets, scales, X, W, A: List, B: List):
+        import torch
+        self.torch = torch
+        self.dtype = dtype
+        self.code = TLORA_BF16 if dtype == "bf16" else TLORA_F32
+        self.d_in, self.d_out = int(d_in), int(d_out)
+        self.ranks = [int(r) for r in ranks]
+        self.offsets = [int(o) for o in offsets]
+        self.scales = [float(s) for s in scales]
+        self.X, self.W, self.A, self.B = X, W, list(A), list(B)
+        self.T = self.offsets[-1]
+        self.prob, self._keep = make_problem(
+            self.code, d_in, d_out, self.ranks, self.offsets, self.scales, X.data_ptr(), W.data_ptr(),
+            [a.data_ptr() if a is not None and a.numel() else 0 for a in self.A],
+            [b.data_ptr() if b is not None and b.numel() else 0 for b in self.B])
+        self.ws_bytes = tlora_workspace_bytes(self.prob)
+        if self.ws_bytes == 0:
+            raise TloraError("tlora_workspace_bytes: invalid problem")
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=X.device)
+
+    @classmethod
+    def from_numpy(cls, p, device="cuda"):
+        """Upload a workloads.Problem (float32 numpy arrays) in its dtype."""
+        import torch
+        tdt = torch.bfloat16 if p.dtype == "bf16" else torch.float32
+
+        def up(a):
+            return torch.from_numpy(a).to(device=device, dtype=tdt).contiguous()
+        return cls(p.dtype, p.d_in, p.d_out, p.ranks, p.offsets, p.scales, up(p.X), up(p.W),
+                   [up(a) for a in p.A], [up(b) for b in p.B])
+
+    def _stream(self) -> int:
+        return int(self.torch.cuda.current_stream().cuda_stream)
+
+    def new_outputs(self):
+        t = self.torch
+        tdt = t.bfloat16 if self.dtype == "bf16" else t.float32
+        dev = self.X.device
+        Y = t.empty((self.T, self.d_out), dtype=tdt, device=dev)
+        dX = t.empty((self.T, self.d_in), dtype=tdt, device=dev)
+        dA = [t.empty((self.d_in, r), dtype=t.float32, device=dev) for r in self.ranks]
+        dB = [t.empty((r, self.d_out), dtype=t.float32, device=dev) for r in self.ranks]
+        return Y, dX, dA, dB
+
+    def fwd(self, Y) -> None:
+        tlora_fwd(self.prob, Y.data_ptr(), self.ws.data_ptr(), self.ws_bytes, self._stream())
+
+    def bwd(self, dY, dX, dA, dB, reuse_S: bool = False) -> None:
+        tlora_bwd(self.prob, dY.data_ptr(), dX.data_ptr() if dX is not None else 0,
+                  None if dA is None else [a.data_ptr() if a.numel() else 0 for a in dA],
+                  None if dB is None else [b.data_ptr() if b.numel() else 0 for b in dB],
+                  TLORA_BWD_REUSE_S if reuse_S else 0, self.ws.data_ptr(), self.ws_bytes, self._stream())
+
+    def job_slice(self, j: int) -> "LayerProblem":
+        """Job j alone as a one-job problem over views of the same tensors (the per-job loop baseline)."""
+        lo, hi = self.offsets[j], self.offsets[j + 1]
+        return LayerProblem(self.dtype, self.d_in, self.d_out, [self.ranks[j]], [0, hi - lo], [self.scales[j]],
+                            self.X[lo:hi], self.W, [self.A[j]], [self.B[j]])

@@ -1,0 +1,114 @@
+"""Host-side checks that need no GPU: the C-ABI library loads and exports what include/tlora.h
+declares, rejects bad arguments before touching the device, and its integer bookkeeping (padded
+ranks, packed offsets, row tiles) is bit-identical to the oracle's independently written version."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import tlora_oracle as orc
+from paper_2602_07263_amd import tlora, workloads as wk
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _problem(ranks, tokens, d_in=64, d_out=128, dtype=tlora.TLORA_BF16, X=0x1000, W=0x2000):
+    off = np.concatenate([[0], np.cumsum(tokens)]).astype(np.int64)
+    J = len(ranks)
+    return tlora.make_problem(dtype, d_in, d_out, ranks, off, [2.0] * J, X, W, [0x3000] * J, [0x4000] * J)
+
+
+def test_library_exports_every_declared_symbol():
+    with open(os.path.join(ROOT, "include", "tlora.h")) as f:
+        text = re.sub(r"/\*.*?\*/", "", f.read(), flags=re.S)
+    declared = set(re.findall(r"\b(tlora_[a-z_]+)\s*\(", text))
+    assert declared == set(tlora.EXPORTS)
+    L = tlora.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+    assert tlora.tlora_version().startswith("tlora-gfx950")
+    assert tlora.tlora_strerror(0) == "ok" and "workspace" in tlora.tlora_strerror(-4)
+
+
+def test_invalid_problems_are_rejected_on_the_host():
+    L = tlora.lib()
+    ws = ctypes.c_void_p(0x10000)
+
+    def fwd(prob, Y=0x5000, ws_ptr=ws, nbytes=1 << 40):
+        return L.tlora_fwd(ctypes.byref(prob), ctypes.c_void_p(Y), ws_ptr, ctypes.c_size_t(nbytes), None)
+
+    ok, _k0 = _problem([4, 8], [10, 20])
+    assert tlora.tlora_workspace_bytes(ok) > 0
+    bad_dtype, _k1 = _problem([4], [10], dtype=7)
+    assert fwd(bad_dtype) == -3 and tlora.tlora_workspace_bytes(bad_dtype) == 0
+    bad_d, _k2 = _problem([4], [10], d_in=60)
+    assert fwd(bad_d) == -1
+    neg_rank, _k3 = _problem([-1], [10])
+    assert fwd(neg_rank) == -1
+    big_rank, _k4 = _problem([4096], [10])
+    assert fwd(big_rank) == -1
+    decreasing, keep = _problem([4, 4], [10, 5])
+    keep[1][2] = 3          # offsets = [0, 10, 3]
+    assert fwd(decreasing) == -1
+    nonzero_start, keep2 = _problem([4], [10])
+    keep2[1][0] = 1
+    assert fwd(nonzero_start) == -1
+    null_x, _k5 = _problem([4], [10], X=0)
+    assert fwd(null_x) == -2
+    assert fwd(ok, Y=0x5000, ws_ptr=None) == -4            # no workspace
+    assert fwd(ok, nbytes=16) == -4                       # workspace too small
+    assert fwd(ok, ws_ptr=ctypes.c_void_p(0x10010)) == -4  # workspace not 256-byte aligned
+    misaligned, _k6 = _problem([4], [10], X=0x1008)
+    assert fwd(misaligned) == -7
+    assert L.tlora_fwd(None, None, None, 0, None) == -2
+    # backward: dA and dB must be given together; unknown flags are refused
+    dA = (ctypes.c_void_p * 2)(0x6000, 0x7000)
+    rc = L.tlora_bwd(ctypes.byref(ok), ctypes.c_void_p(0x5000), None, dA, None, 0, ws, ctypes.c_size_t(1 << 40), None)
+    assert rc == -2
+    with pytest.raises(tlora.TloraError):
+        tlora.tlora_set_option("no_such_option", 1)
+    with pytest.raises(tlora.TloraError):
+        tlora.tlora_set_option("shrink_rows", 100)
+
+
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4])
+def test_plan_bookkeeping_is_bit_exact(cfg):
+    wl = wk.config(cfg)
+    off = wl.offsets
+    for proj in wl.projections[:2]:
+        prob, _keep = tlora.make_problem(tlora.TLORA_BF16, proj.d_in, proj.d_out, wl.ranks, off, wl.scales,
+                                         0x1000, 0x2000, [0x3000] * wl.num_jobs, [0x4000] * wl.num_jobs)
+        plan = tlora.tlora_plan_dump(prob)
+        assert plan["rpad"] == [orc.padded_rank(r) for r in wl.ranks]
+        assert plan["soff"] == orc.packed_offsets(wl.ranks, off)
+        assert plan["tiles"] == orc.row_tiles(off, plan["tile_rows"])
+
+
+def test_plan_handles_empty_segments_and_rank_zero():
+    ranks, tokens = [3, 0, 9, 1], [0, 300, 0, 5]
+    prob, _keep = _problem(ranks, tokens)
+    off = np.concatenate([[0], np.cumsum(tokens)])
+    plan = tlora.tlora_plan_dump(prob)
+    assert plan["rpad"] == [8, 0, 16, 8]
+    assert plan["soff"] == orc.packed_offsets(ranks, off) == [0, 0, 0, 0, 40]
+    assert plan["tiles"] == orc.row_tiles(off, plan["tile_rows"])
+    # all-empty batch: no tiles
+    prob0, _k = _problem([4, 4], [0, 0])
+    assert tlora.tlora_plan_dump(prob0)["tiles"] == []
+
+
+def test_workspace_grows_with_rank_work_not_with_dense_weights():
+    # Sec. 3.3: no per-job d_in x d_out buffer.  Doubling d_in and d_out (4x the dense weight) with
+    # few tokens must grow the workspace far less than 4x J dense matrices would.
+    small, _a = _problem([8] * 8, [16] * 8, d_in=1024, d_out=1024)
+    large, _b = _problem([8] * 8, [16] * 8, d_in=2048, d_out=2048)
+    ws_s, ws_l = tlora.tlora_workspace_bytes(small), tlora.tlora_workspace_bytes(large)
+    dense_per_job = 2048 * 2048 * 2
+    assert ws_l < dense_per_job                # less than ONE dense bf16 matrix, for all 8 jobs together
+    assert ws_l < 2.6 * ws_s                   # ~linear in (d_in + d_out)
+    # and it is linear in sum_j T_j r_j
+    a, _c = _problem([16] * 4, [1000] * 4)
+    b, _d = _problem([16] * 4, [2000] * 4)
+    assert tlora.tlora_workspace_bytes(b) < 2.1 * tlora.tlora_workspace_bytes(a)

@@ -1,0 +1,100 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 oracle on the same seeded
+inputs.  Tolerances: bf16 |err| <= 2e-2 (1 + |ref|); fp32 |err| <= 1e-5 (1 + |ref|) and a 1e-5
+Frobenius bound.  Small problems are compared element by element; the full-size configurations on
+all of dA_j / dB_j and on a row sample of Y / dX that holds every segment and tile edge."""
+import numpy as np
+import pytest
+
+from paper_2602_07263_amd import workloads as wk
+from tests import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+
+def _assert_ok(res, label):
+    bad = {k: v for k, v in res.items() if not v <= 1.0}
+    assert not bad, f"{label}: worst error / tolerance ratios {res}"
+
+
+def test_cfg0_fp32_full():
+    p = wk.generate(wk.config(0))
+    Y, dX, dA, dB, _ = pu.run_gpu(p, reuse_S=True)
+    _assert_ok(pu.compare(p, Y, dX, dA, dB), "cfg0")
+    Y, dX, dA, dB, _ = pu.run_gpu(p, reuse_S=False)
+    _assert_ok(pu.compare(p, Y, dX, dA, dB), "cfg0 recompute S")
+
+
+RAGGED = [
+    # name, d_in, d_out, ranks, tokens, scales
+    ("ragged_small", 192, 320, [1, 3, 8, 20, 0, 64, 96], [1, 17, 0, 333, 70, 300, 513], [0.5, 4.0, 2.0, 1.0, 2.0, 3.0, 0.75]),
+    ("one_token", 64, 64, [1], [1], [2.0]),
+    ("tile_edges", 256, 512, [8, 16, 24], [256, 255, 257], [2.0, 2.0, 2.0]),
+    ("rank_256_straddle", 320, 264, [256, 3, 130], [100, 700, 90], [1.5, 2.0, 0.5]),
+    ("narrow_features", 8, 8, [2, 5], [40, 300], [2.0, 1.0]),
+]
+
+
+@pytest.mark.parametrize("case", RAGGED, ids=[c[0] for c in RAGGED])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_ragged_edge_cases_full(case, dtype):
+    name, d_in, d_out, ranks, tokens, scales = case
+    p = wk.generate(wk.custom(name, dtype, d_in, d_out, ranks, tokens, scales), seed=11)
+    for reuse in (True, False):
+        Y, dX, dA, dB, _ = pu.run_gpu(p, reuse_S=reuse)
+        _assert_ok(pu.compare(p, Y, dX, dA, dB), f"{name}/{dtype}/reuse={reuse}")
+
+
+def test_all_segments_empty_and_rank_zero_jobs():
+    p = wk.generate(wk.custom("rank0", "bf16", 64, 128, [0, 0], [5, 300]), seed=3)
+    Y, dX, dA, dB, _ = pu.run_gpu(p)
+    _assert_ok(pu.compare(p, Y, dX, dA, dB), "rank0")
+    p = wk.generate(wk.custom("empty", "bf16", 64, 128, [4, 9], [0, 0]), seed=3)
+    Y, dX, dA, dB, _ = pu.run_gpu(p)
+    assert all(np.all(a == 0) for a in dA) and all(np.all(b == 0) for b in dB)
+
+
+def test_cfg1_bf16_full():
+    p = wk.generate(wk.config(1))
+    Y, dX, dA, dB, _ = pu.run_gpu(p)
+    _assert_ok(pu.compare(p, Y, dX, dA, dB), "cfg1")
+
+
+def test_zero_B_gives_backbone_only_and_jobs_do_not_leak():
+    wl = wk.custom("leak", "bf16", 128, 256, [8, 16, 4], [100, 300, 50])
+    p = wk.generate(wl, seed=5)
+    Y, dX, dA, dB, _ = pu.run_gpu(p)
+    # perturb job 1 only: outputs of jobs 0 and 2 must be bit-identical
+    p2 = wk.generate(wl, seed=5)
+    lo, hi = int(p.offsets[1]), int(p.offsets[2])
+    p2.X[lo:hi] = wk.round_to_bf16(p2.X[lo:hi] * 2 + 1)
+    p2.A[1] = wk.round_to_bf16(p2.A[1] * 3)
+    p2.B[1] = wk.round_to_bf16(p2.B[1] - 1)
+    Y2, dX2, dA2, dB2, _ = pu.run_gpu(p2)
+    for j in (0, 2):
+        sl = slice(int(p.offsets[j]), int(p.offsets[j + 1]))
+        assert np.array_equal(Y[sl], Y2[sl]) and np.array_equal(dX[sl], dX2[sl])
+        assert np.array_equal(dA[j], dA2[j]) and np.array_equal(dB[j], dB2[j])
+    # B = 0: dA = 0 exactly
+    p3 = wk.generate(wl, seed=5)
+    p3.B = [np.zeros_like(b) for b in p3.B]
+    Y3, dX3, dA3, dB3, _ = pu.run_gpu(p3)
+    assert all(np.all(a == 0) for a in dA3)
+    _assert_ok(pu.compare(p3, Y3, dX3, dA3, dB3), "B=0")
+
+
+def test_run_to_run_determinism():
+    p = wk.generate(wk.custom("det", "bf16", 512, 768, [8, 64, 33], [700, 1300, 129]), seed=2)
+    a = pu.run_gpu(p)
+    b = pu.run_gpu(p)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    for x, y in zip(a[2] + a[3], b[2] + b[3]):
+        assert np.array_equal(x, y)
+
+
+@pytest.mark.parametrize("cfg,proj", [(2, 0), (2, 2), (3, 1), (3, 6), (4, 0), (4, 1)])
+def test_full_size_configs_sampled(cfg, proj):
+    wl = wk.config(cfg)
+    p = wk.generate(wl, proj)
+    Y, dX, dA, dB, lp = pu.run_gpu(p)
+    rows = pu.sample_rows(p.offsets, 256, np.random.default_rng(cfg * 10 + proj))
+    _assert_ok(pu.compare(p, Y, dX, dA, dB, rows=rows), f"cfg{cfg}/{wl.projections[proj].name}")
