@@ -1,0 +1,251 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused multi-LoRA linear layer on one MI355X.
+
+One "step" = forward + backward of every projection of the workload (all hot-path kernels:
+adapter packing, shrink, segmented GEMM with fused expand, backward shrink, dX GEMM, dA / dB
+reductions) on synthetic tensors that are resident in HBM before the timed region starts.
+Prints ONE JSON line: algorithmic TFLOP/s of the whole step, the roofline of the dominant kernel
+(the segmented MFMA GEMM, timed with HIP events on the launch stream during the timed region), the
+speedup over the per-job loop of the same kernels, and the fp64 CPU oracle timed on a bounded
+sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+BF16_MFMA_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
+HBM_PEAK_GBS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="workload index (0-based); 2 = 8B-class MLP projections")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-loop-baseline", action="store_true")
+    ap.add_argument("--no-secondary", action="store_true", help="skip the extra 4096x4096 (config 1) measurement")
+    ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with HIP events")
+    return ap.parse_args()
+
+
+class ProjectionRun:
+    """Device tensors of one projection; `sets` rotating activation sets defeat last-level-cache reuse."""
+
+    def __init__(self, p, sets: int):
+        import torch
+        from paper_2602_07263_amd import tlora
+        self.lp = tlora.LayerProblem.from_numpy(p)
+        tdt = torch.bfloat16 if p.dtype == "bf16" else torch.float32
+        self.dY = [torch.from_numpy(p.dY).to(device="cuda", dtype=tdt)]
+        self.X = [self.lp.X]
+        for _ in range(sets - 1):
+            self.X.append(self.lp.X.clone())
+            self.dY.append(self.dY[0].clone())
+        self.out = [self.lp.new_outputs() for _ in range(sets)]
+        self.problems = [self.lp]
+        for i in range(1, sets):
+            self.problems.append(tlora.LayerProblem(p.dtype, p.d_in, p.d_out, p.ranks, p.offsets, p.scales,
+                                                    self.X[i], self.lp.W, self.lp.A, self.lp.B))
+        self.sets = sets
+        # per-job loop baseline: each job as its own one-job problem on views of set 0
+        self.jobs = None
+
+    def step(self, i: int):
+        k = i % self.sets
+        Y, dX, dA, dB = self.out[k]
+        self.problems[k].fwd(Y)
+        self.problems[k].bwd(self.dY[k], dX, dA, dB, reuse_S=True)
+
+    def build_job_loop(self):
+        self.jobs = []
+        lp = self.lp
+        Y, dX, dA, dB = self.out[0]
+        for j in range(len(lp.ranks)):
+            lo, hi = lp.offsets[j], lp.offsets[j + 1]
+            if hi == lo:
+                continue
+            self.jobs.append((lp.job_slice(j), Y[lo:hi], self.dY[0][lo:hi], dX[lo:hi], [dA[j]], [dB[j]]))
+
+    def step_job_loop(self):
+        for jp, Y, dY, dX, dA, dB in self.jobs:
+            jp.fwd(Y)
+        for jp, Y, dY, dX, dA, dB in self.jobs:
+            jp.bwd(dY, dX, dA, dB, reuse_S=True)
+
+
+def time_steps(fn, steps: int, warmup: int) -> float:
+    """Milliseconds per step over exactly `steps` calls, bracketed by device synchronisation."""
+    import torch
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        fn(warmup + i)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def measure_workload(cfg_index: int, steps: int, warmup: int, profile: bool, loop_baseline: bool):
+    from paper_2602_07263_amd import tlora, workloads as wk
+    wl = wk.config(cfg_index)
+    act_bytes = sum(wl.total_tokens * (p.d_in + p.d_out) * 2 * 2 for p in wl.projections)
+    sets = 1 if act_bytes > (1 << 30) else 4       # small activations would otherwise sit in the 256 MB cache
+    runs = []
+    for i in range(len(wl.projections)):
+        runs.append(ProjectionRun(wk.generate(wl, i), sets))
+
+    def step(i):
+        for r in runs:
+            r.step(i)
+
+    if profile:
+        tlora.tlora_profile(True)
+    for i in range(warmup):
+        step(i)
+    if profile:
+        tlora.tlora_profile(True)      # clear warm-up totals
+    ms = time_steps(step, steps, 0)
+    prof = tlora.tlora_profile_read() if profile else None
+    if profile:
+        tlora.tlora_profile(False)
+    res = {"wl": wl, "ms": ms, "prof": prof, "loop_ms": None}
+    if loop_baseline:
+        for r in runs:
+            r.build_job_loop()
+
+        def loop_step(i):
+            for r in runs:
+                r.step_job_loop()
+        n = max(3, steps // 4)
+        res["loop_ms"] = time_steps(loop_step, n, 2)
+    return res
+
+
+def gemm_roofline(wl, prof, steps):
+    """Roofline entry of the dominant kernel: the segmented GEMM (forward and dX launches together).
+    Algorithmic flops per launch = 2 T d_in d_out (backbone) + 2 sum_j T_j r_j d (fused adapter term),
+    averaged over the launches of one step."""
+    tr = float(sum(t * r for t, r in zip(wl.tokens, wl.ranks)))
+    T = float(wl.total_tokens)
+    flops_step = 0.0
+    for p in wl.projections:
+        flops_step += 2 * (2.0 * T * p.d_in * p.d_out) + 2.0 * tr * (p.d_in + p.d_out)
+    ms_total = prof["gemm_fwd"][0] + prof["gemm_bwd"][0]
+    n = prof["gemm_fwd"][1] + prof["gemm_bwd"][1]
+    if n == 0 or ms_total <= 0:
+        return None
+    launches_per_step = n / steps
+    flops_per_launch = flops_step / launches_per_step
+    avg_ms = ms_total / n
+    achieved = flops_per_launch / (avg_ms * 1e-3) / 1e12
+    return {"bound": "mfma", "kernel": "seg_gemm_kernel (fwd + dX launches)", "achieved": round(achieved, 2),
+            "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / BF16_MFMA_PEAK_TFLOPS, 4),
+            "avg_launch_ms": round(avg_ms, 4), "launches": n, "flops_per_launch": flops_per_launch,
+            "traffic": load_traffic()}
+
+
+def load_traffic():
+    """HBM bytes per GEMM launch from the committed rocprofv3 counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", "seg_gemm_hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get("bytes_per_launch")
+    except Exception:
+        return None
+
+
+def cpu_baseline(cfg_index: int):
+    """The fp64 oracle, as it stands, on a bounded sample: the first projection of the workload, fwd+bwd
+    (for workloads above 10 TFLOP per projection every job's segment is cut to its first quarter)."""
+    from oracle import tlora_oracle as orc
+    from paper_2602_07263_amd import workloads as wk
+    wl = wk.config(cfg_index)
+    frac = 4 if wl.flops(wl.projections[0]) > 1e13 else 1
+    tokens = [max(1, t // frac) for t in wl.tokens]
+    proj = wl.projections[0]
+    sub = wk.custom(wl.name + "_sample", wl.dtype, proj.d_in, proj.d_out, wl.ranks, tokens, wl.scales, index=wl.index)
+    p = wk.generate(sub)
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    t0 = time.perf_counter()
+    orc.forward(p.X, p.W, p.A, p.B, p.scales, p.offsets)
+    orc.backward(p.X, p.W, p.A, p.B, p.scales, p.offsets, p.dY)
+    dt = time.perf_counter() - t0
+    fl = sub.flops()
+    return {"value": round(fl / dt / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "seconds": round(dt, 2),
+            "sample": f"projection '{proj.name}' {proj.d_in}->{proj.d_out} of {wl.name}, "
+                      f"{'all' if frac == 1 else f'first 1/{frac} of each job`s'} tokens ({sum(tokens)}), "
+                      f"fwd+bwd, numpy fp64, {fl / 1e12:.2f} TFLOP"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    from paper_2602_07263_amd import tlora
+    tlora.lib()
+    torch.cuda.set_device(0)
+
+    main_res = measure_workload(args.config, args.steps, args.warmup, not args.no_profile, not args.no_loop_baseline)
+    wl = main_res["wl"]
+    tflops = wl.flops() / (main_res["ms"] * 1e-3) / 1e12
+    out = {
+        "metric": "fused multi-LoRA fwd+bwd TFLOP/s (% bf16 MFMA peak); speedup vs per-job loop",
+        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(main_res["ms"], 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name,
+                   "projections": [f"{p.name}:{p.d_in}->{p.d_out}" for p in wl.projections],
+                   "jobs": wl.num_jobs, "ranks": list(wl.ranks), "tokens": list(wl.tokens),
+                   "total_tokens": wl.total_tokens, "init": "X,dY~N(0,1); W~N(0,std .02); A~U(+-1/sqrt(d_in)); B~N(0,std .01)"},
+        "frac_of_bf16_mfma_peak": round(tflops / BF16_MFMA_PEAK_TFLOPS, 4),
+        "flops_per_step": wl.flops(),
+    }
+    if main_res["loop_ms"]:
+        out["per_job_loop_ms"] = round(main_res["loop_ms"], 4)
+        out["speedup_vs_per_job_loop"] = round(main_res["loop_ms"] / main_res["ms"], 3)
+    if main_res["prof"]:
+        out["roofline"] = gemm_roofline(wl, main_res["prof"], args.steps)
+        out["kernel_ms_per_step"] = {k: round(v[0] / args.steps, 4) for k, v in main_res["prof"].items() if v[1]}
+    else:
+        out["roofline"] = None
+    if not args.no_secondary and args.config != 1:
+        del main_res
+        torch.cuda.empty_cache()
+        sec = measure_workload(1, max(args.steps, 50), args.warmup, not args.no_profile, not args.no_loop_baseline)
+        w1 = sec["wl"]
+        t1 = w1.flops() / (sec["ms"] * 1e-3) / 1e12
+        out["also"] = {"workload": w1.name, "value": round(t1, 2), "unit": "TFLOP/s", "ms_per_step": round(sec["ms"], 4),
+                       "frac_of_bf16_mfma_peak": round(t1 / BF16_MFMA_PEAK_TFLOPS, 4)}
+        if sec["loop_ms"]:
+            out["also"]["speedup_vs_per_job_loop"] = round(sec["loop_ms"] / sec["ms"], 3)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.config)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

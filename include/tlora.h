@@ -114,6 +114,25 @@ int tlora_plan_dump(const tlora_problem_t* p, int32_t* rpad, int64_t* soff, int3
  * Returns TLORA_EINVAL for an unknown name or an illegal value. */
 int tlora_set_option(const char* name, int64_t value);
 
+/* Per-kernel timing, the runtime signal a nano-batch controller feeds on (Algorithm 1, Phase 3:
+ * Monitor_Speed).  While enabled, every kernel launch of tlora_fwd / tlora_bwd is bracketed by a
+ * pair of HIP events on the call's stream.  tlora_profile(1) enables and clears the totals,
+ * tlora_profile(0) disables.  tlora_profile_read waits for the recorded events, adds them to the
+ * totals and returns, for one kernel class, the summed milliseconds and the number of launches
+ * (either output may be NULL).  Returns TLORA_EINVAL for an unknown class. */
+typedef enum {
+  TLORA_K_PACK = 0,         /* adapter packing                                  */
+  TLORA_K_SHRINK = 1,       /* S_j = X_j.A_j and dS_j = dY_j.B_j^T              */
+  TLORA_K_GEMM_FWD = 2,     /* Y  = X.W   + fused expand                        */
+  TLORA_K_GEMM_BWD = 3,     /* dX = dY.W^T + fused adapter term                 */
+  TLORA_K_RANK_GRAD = 4,    /* token reductions of dA_j / dB_j (partial tiles)  */
+  TLORA_K_GRAD_REDUCE = 5,  /* fixed-order sum of the partial tiles             */
+  TLORA_K_F32 = 6,          /* fp32-configuration products                      */
+  TLORA_K_COUNT = 7
+} tlora_kernel_class_t;
+int tlora_profile(int enable);
+int tlora_profile_read(int kernel_class, double* total_ms, int64_t* launches);
+
 /* Static description of an error code. */
 const char* tlora_strerror(int status);
 

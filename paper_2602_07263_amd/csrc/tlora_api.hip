@@ -219,6 +219,60 @@ int upload_tables(const std::vector<uint8_t>& blob, void* dst, hipStream_t st) {
   return TLORA_OK;
 }
 
+// ---- optional per-kernel event timing ---------------------------------------------------------------------
+struct Pending {
+  int cls;
+  hipEvent_t a, b;
+};
+bool g_prof_on = false;
+std::vector<Pending> g_pending;
+std::vector<hipEvent_t> g_event_pool;
+double g_prof_ms[TLORA_K_COUNT] = {};
+int64_t g_prof_n[TLORA_K_COUNT] = {};
+
+hipEvent_t prof_event() {
+  if (!g_event_pool.empty()) {
+    hipEvent_t e = g_event_pool.back();
+    g_event_pool.pop_back();
+    return e;
+  }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+
+// Brackets one launch with events when profiling is on.
+struct Timed {
+  hipStream_t st;
+  Pending p{};
+  bool on;
+  Timed(int cls, hipStream_t s) : st(s), on(g_prof_on) {
+    if (!on) return;
+    p.cls = cls;  p.a = prof_event();  p.b = prof_event();
+    if (!p.a || !p.b) { on = false; return; }
+    (void)hipEventRecord(p.a, st);
+  }
+  ~Timed() {
+    if (!on) return;
+    (void)hipEventRecord(p.b, st);
+    g_pending.push_back(p);
+  }
+};
+
+int prof_drain() {
+  for (const Pending& p : g_pending) {
+    if (hipEventSynchronize(p.b) != hipSuccess) return TLORA_EHIP;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, p.a, p.b) != hipSuccess) return TLORA_EHIP;
+    g_prof_ms[p.cls] += ms;
+    g_prof_n[p.cls] += 1;
+    g_event_pool.push_back(p.a);
+    g_event_pool.push_back(p.b);
+  }
+  g_pending.clear();
+  return TLORA_OK;
+}
+
 int check_arch() {
   static int cached = 1;   // 1 = unknown
   if (cached != 1) return cached;
@@ -359,9 +413,11 @@ int tlora_fwd(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_byte
     if (rc != TLORA_OK) return rc;
     rc = upload_tables(blob, tb, st);
     if (rc != TLORA_OK) return rc;
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 2; ++i) {
+      Timed t(TLORA_K_F32, st);
       launch_f32_units(reinterpret_cast<const F32Unit*>(tb + L.units_at[i]),
                        reinterpret_cast<const F32Tile*>(tb + L.tiles_at[i]), L.ntiles[i], st);
+    }
     return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
   }
 
@@ -371,9 +427,16 @@ int tlora_fwd(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_byte
   uint16_t* atp = reinterpret_cast<uint16_t*>(ws + pl.off_atp);
   uint16_t* ap = reinterpret_cast<uint16_t*>(ws + pl.off_ap);
   uint16_t* bp = reinterpret_cast<uint16_t*>(ws + pl.off_bp);
-  launch_pack_adapters(jobs, pl.J, pl.d_in, pl.d_out, pl.max_rpad, atp, ap, bp, st);
-  launch_shrink(jobs, reinterpret_cast<const ShrinkUnit*>(tb + pl.tb_shrink), (int)pl.shrink_units.size(),
-                g_opt.shrink_rows, static_cast<const uint16_t*>(p->X), pl.d_in, atp, true, S, Sb, st);
+  {
+    Timed t(TLORA_K_PACK, st);
+    launch_pack_adapters(jobs, pl.J, pl.d_in, pl.d_out, pl.max_rpad, atp, ap, bp, st);
+  }
+  {
+    Timed t(TLORA_K_SHRINK, st);
+    launch_shrink(jobs, reinterpret_cast<const ShrinkUnit*>(tb + pl.tb_shrink), (int)pl.shrink_units.size(),
+                  g_opt.shrink_rows, static_cast<const uint16_t*>(p->X), pl.d_in, atp, true, S, Sb, st);
+  }
+  Timed tg(TLORA_K_GEMM_FWD, st);
   launch_seg_gemm(true, jobs, reinterpret_cast<const TileJobs*>(tb + pl.tb_tiles), static_cast<const uint16_t*>(p->X),
                   static_cast<const uint16_t*>(p->W), Sb, bp, static_cast<uint16_t*>(Y), pl.T, pl.d_in, pl.d_out, st);
   return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
@@ -447,9 +510,11 @@ int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* d
     if (rc != TLORA_OK) return rc;
     rc = upload_tables(blob, tb, st);
     if (rc != TLORA_OK) return rc;
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 2; ++i) {
+      Timed t(TLORA_K_F32, st);
       launch_f32_units(reinterpret_cast<const F32Unit*>(tb + L.units_at[i]),
                        reinterpret_cast<const F32Tile*>(tb + L.tiles_at[i]), L.ntiles[i], st);
+    }
     return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
   }
 
@@ -465,25 +530,47 @@ int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* d
   const uint16_t* Xb = static_cast<const uint16_t*>(p->X);
   const uint16_t* dYb = static_cast<const uint16_t*>(dY);
 
-  launch_pack_adapters(jobs, pl.J, pl.d_in, pl.d_out, pl.max_rpad, atp, ap, bp, st);
+  {
+    Timed t(TLORA_K_PACK, st);
+    launch_pack_adapters(jobs, pl.J, pl.d_in, pl.d_out, pl.max_rpad, atp, ap, bp, st);
+  }
   if (pl.T > 0) {
-    if (want_grads && !reuse_S)
+    if (want_grads && !reuse_S) {
+      Timed t(TLORA_K_SHRINK, st);
       launch_shrink(jobs, su, (int)pl.shrink_units.size(), g_opt.shrink_rows, Xb, pl.d_in, atp, true, S, Sb, st);
-    launch_shrink(jobs, su, (int)pl.shrink_units.size(), g_opt.shrink_rows, dYb, pl.d_out, bp, false, dS, dSb, st);
-    if (dX)
+    }
+    {
+      Timed t(TLORA_K_SHRINK, st);
+      launch_shrink(jobs, su, (int)pl.shrink_units.size(), g_opt.shrink_rows, dYb, pl.d_out, bp, false, dS, dSb, st);
+    }
+    if (dX) {
+      Timed t(TLORA_K_GEMM_BWD, st);
       launch_seg_gemm(false, jobs, reinterpret_cast<const TileJobs*>(tb + pl.tb_tiles), dYb,
                       static_cast<const uint16_t*>(p->W), dSb, ap, static_cast<uint16_t*>(dX), pl.T, pl.d_out, pl.d_in,
                       st);
+    }
   }
   if (want_grads) {
-    launch_rank_grad(pl.grad_mb, jobs, reinterpret_cast<const GradUnit*>(tb + pl.tb_gBu), (int)pl.gradB_units.size(), S,
-                     dYb, pl.d_out, partial, st);
-    launch_grad_reduce(pl.grad_mb, jobs, reinterpret_cast<const GradGroup*>(tb + pl.tb_gBg),
-                       (int)pl.gradB_groups.size(), partial, pl.d_out, false, st);
-    launch_rank_grad(pl.grad_mb, jobs, reinterpret_cast<const GradUnit*>(tb + pl.tb_gAu), (int)pl.gradA_units.size(), dS,
-                     Xb, pl.d_in, partial, st);
-    launch_grad_reduce(pl.grad_mb, jobs, reinterpret_cast<const GradGroup*>(tb + pl.tb_gAg),
-                       (int)pl.gradA_groups.size(), partial, pl.d_in, true, st);
+    {
+      Timed t(TLORA_K_RANK_GRAD, st);
+      launch_rank_grad(pl.grad_mb, jobs, reinterpret_cast<const GradUnit*>(tb + pl.tb_gBu), (int)pl.gradB_units.size(),
+                       S, dYb, pl.d_out, partial, st);
+    }
+    {
+      Timed t(TLORA_K_GRAD_REDUCE, st);
+      launch_grad_reduce(pl.grad_mb, jobs, reinterpret_cast<const GradGroup*>(tb + pl.tb_gBg),
+                         (int)pl.gradB_groups.size(), partial, pl.d_out, false, st);
+    }
+    {
+      Timed t(TLORA_K_RANK_GRAD, st);
+      launch_rank_grad(pl.grad_mb, jobs, reinterpret_cast<const GradUnit*>(tb + pl.tb_gAu), (int)pl.gradA_units.size(),
+                       dS, Xb, pl.d_in, partial, st);
+    }
+    {
+      Timed t(TLORA_K_GRAD_REDUCE, st);
+      launch_grad_reduce(pl.grad_mb, jobs, reinterpret_cast<const GradGroup*>(tb + pl.tb_gAg),
+                         (int)pl.gradA_groups.size(), partial, pl.d_in, true, st);
+    }
   }
   return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
 }
@@ -514,6 +601,28 @@ int tlora_plan_dump(const tlora_problem_t* p, int32_t* rpad, int64_t* soff, int3
     if (tile_job_first) tile_job_first[t] = pl.tile_jobs[t].first;
     if (tile_job_last) tile_job_last[t] = pl.tile_jobs[t].last;
   }
+  return TLORA_OK;
+}
+
+int tlora_profile(int enable) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  const int rc = prof_drain();
+  g_prof_on = enable != 0;
+  if (g_prof_on)
+    for (int i = 0; i < TLORA_K_COUNT; ++i) {
+      g_prof_ms[i] = 0.0;
+      g_prof_n[i] = 0;
+    }
+  return rc;
+}
+
+int tlora_profile_read(int kernel_class, double* total_ms, int64_t* launches) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  if (kernel_class < 0 || kernel_class >= TLORA_K_COUNT) return TLORA_EINVAL;
+  const int rc = prof_drain();
+  if (rc != TLORA_OK) return rc;
+  if (total_ms) *total_ms = g_prof_ms[kernel_class];
+  if (launches) *launches = g_prof_n[kernel_class];
   return TLORA_OK;
 }
 

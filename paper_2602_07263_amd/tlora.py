@@ -33,7 +33,8 @@ class tlora_problem_t(ctypes.Structure):
 
 
 EXPORTS = ["tlora_workspace_bytes", "tlora_fwd", "tlora_bwd", "tlora_plan_dump", "tlora_set_option",
-           "tlora_strerror", "tlora_version"]
+           "tlora_profile", "tlora_profile_read", "tlora_strerror", "tlora_version"]
+KERNEL_CLASSES = ["pack", "shrink", "gemm_fwd", "gemm_bwd", "rank_grad", "grad_reduce", "f32"]
 
 
 def lib() -> ctypes.CDLL:
@@ -61,6 +62,10 @@ def lib() -> ctypes.CDLL:
                                   ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64)]
     L.tlora_set_option.restype = ctypes.c_int
     L.tlora_set_option.argtypes = [ctypes.c_char_p, ctypes.c_int64]
+    L.tlora_profile.restype = ctypes.c_int
+    L.tlora_profile.argtypes = [ctypes.c_int]
+    L.tlora_profile_read.restype = ctypes.c_int
+    L.tlora_profile_read.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     L.tlora_strerror.restype = ctypes.c_char_p
     L.tlora_strerror.argtypes = [ctypes.c_int]
     L.tlora_version.restype = ctypes.c_char_p
@@ -84,6 +89,20 @@ def _check(status: int, what: str) -> None:
 
 def tlora_set_option(name: str, value: int) -> None:
     _check(lib().tlora_set_option(name.encode(), int(value)), f"tlora_set_option({name})")
+
+
+def tlora_profile(enable: bool) -> None:
+    _check(lib().tlora_profile(1 if enable else 0), "tlora_profile")
+
+
+def tlora_profile_read() -> dict:
+    """{kernel class name: (total milliseconds, launches)} since profiling was enabled."""
+    out = {}
+    for i, name in enumerate(KERNEL_CLASSES):
+        ms, n = ctypes.c_double(0.0), ctypes.c_int64(0)
+        _check(lib().tlora_profile_read(i, ctypes.byref(ms), ctypes.byref(n)), "tlora_profile_read")
+        out[name] = (float(ms.value), int(n.value))
+    return out
 
 
 def make_problem(dtype: int, d_in: int, d_out: int, ranks: Sequence[int], offsets: Sequence[int],
