@@ -30,14 +30,16 @@ struct Plan {
   int max_rpad = 0;
   int grad_mb = 1;
   std::vector<JobDev> jobs;
-  std::vector<TileJobs> tile_jobs;
+  std::vector<TileDev> tile_jobs;
   std::vector<ShrinkUnit> shrink_units;
   std::vector<GradUnit> gradB_units, gradA_units;      // dB: columns over d_out;  dA: columns over d_in
   std::vector<GradGroup> gradB_groups, gradA_groups;
   int64_t s_elems = 0;                                  // elements of the packed S (= dS) buffer
-  int64_t atp_elems = 0, ap_elems = 0, bp_elems = 0;
+  int64_t atp_elems = 0;
+  int r_total = 0;                                      // sum of rpad_j
+  int64_t sx_elems = 0;                                 // elements of the per-tile K-extension operands
   // workspace byte offsets
-  size_t off_tables = 0, off_S = 0, off_dS = 0, off_Sb = 0, off_dSb = 0, off_atp = 0, off_ap = 0, off_bp = 0,
+  size_t off_tables = 0, off_S = 0, off_dS = 0, off_Sx = 0, off_dSx = 0, off_atp = 0, off_ap = 0, off_bp = 0,
          off_partial = 0, total = 0;
   size_t tables_bytes = 0;
   // offsets of each table inside the table blob
@@ -93,7 +95,8 @@ int build_plan(const tlora_problem_t* p, Plan& pl) {
   pl.J = p->num_jobs;  pl.T = (int)p->offsets[p->num_jobs];  pl.d_in = p->d_in;  pl.d_out = p->d_out;
   pl.dtype = p->dtype;
   pl.jobs.resize(pl.J);
-  int64_t soff = 0, atp = 0, ap = 0, bp = 0;
+  int64_t soff = 0, atp = 0;
+  int64_t roff = 0;
   for (int j = 0; j < pl.J; ++j) {
     JobDev& jb = pl.jobs[j];
     memset(&jb, 0, sizeof(jb));
@@ -101,12 +104,14 @@ int build_plan(const tlora_problem_t* p, Plan& pl) {
     jb.rank = p->ranks[j];
     jb.rpad = (jb.rank + kRankGranule - 1) / kRankGranule * kRankGranule;
     jb.scale = p->scales[j];
-    jb.soff = soff;  jb.atp_off = atp;  jb.ap_off = ap;  jb.bp_off = bp;
+    jb.soff = soff;  jb.atp_off = atp;  jb.roff = (int32_t)roff;
     soff += (int64_t)(jb.row1 - jb.row0) * jb.rpad;
-    atp += (int64_t)jb.rpad * pl.d_in;  ap += (int64_t)jb.rpad * pl.d_in;  bp += (int64_t)jb.rpad * pl.d_out;
+    atp += (int64_t)jb.rpad * pl.d_in;
+    roff += jb.rpad;
     pl.max_rpad = std::max(pl.max_rpad, jb.rpad);
   }
-  pl.s_elems = soff;  pl.atp_elems = atp;  pl.ap_elems = ap;  pl.bp_elems = bp;
+  if (roff > (int64_t)1 << 24) return TLORA_EINVAL;
+  pl.s_elems = soff;  pl.atp_elems = atp;  pl.r_total = (int)roff;
   pl.grad_mb = pl.max_rpad > kGradRanks ? 2 : 1;
 
   // row tiles of the backbone GEMM (nano-batches of the concatenated batch, Sec. 3.3)
@@ -120,7 +125,14 @@ int build_plan(const tlora_problem_t* p, Plan& pl) {
       int last = j;
       for (int k = j; k < pl.J && pl.jobs[k].row0 < r1; ++k)
         if (pl.jobs[k].row1 > pl.jobs[k].row0) last = k;
-      pl.tile_jobs[tm].first = j;  pl.tile_jobs[tm].last = last;
+      TileDev& td = pl.tile_jobs[tm];
+      td.first = j;  td.last = last;
+      // adapter K-extension of the tile: padded ranks of jobs first..last, rounded up to the K-step
+      td.roff_first = pl.jobs[j].roff;
+      const int span = pl.jobs[last].roff + pl.jobs[last].rpad - td.roff_first;
+      td.kext = (span + kGemmBK - 1) / kGemmBK * kGemmBK;
+      td.aoff = pl.sx_elems;
+      pl.sx_elems += (int64_t)kGemmBM * td.kext;
     }
   }
   if (pl.dtype == TLORA_BF16) {
@@ -143,7 +155,7 @@ int build_plan(const tlora_problem_t* p, Plan& pl) {
   size_t o = 0;
   auto place = [&](size_t bytes) { const size_t at = o;  o = align_up(o + bytes, 256);  return at; };
   pl.tb_jobs = place(sizeof(JobDev) * pl.jobs.size());
-  pl.tb_tiles = place(sizeof(TileJobs) * pl.tile_jobs.size());
+  pl.tb_tiles = place(sizeof(TileDev) * pl.tile_jobs.size());
   pl.tb_shrink = place(sizeof(ShrinkUnit) * pl.shrink_units.size());
   pl.tb_gBu = place(sizeof(GradUnit) * pl.gradB_units.size());
   pl.tb_gBg = place(sizeof(GradGroup) * pl.gradB_groups.size());
@@ -173,11 +185,11 @@ int build_plan(const tlora_problem_t* p, Plan& pl) {
   pl.off_S = wplace(sizeof(float) * (size_t)pl.s_elems);
   pl.off_dS = wplace(sizeof(float) * (size_t)pl.s_elems);
   if (pl.dtype == TLORA_BF16) {
-    pl.off_Sb = wplace(2 * (size_t)pl.s_elems);
-    pl.off_dSb = wplace(2 * (size_t)pl.s_elems);
+    pl.off_Sx = wplace(2 * (size_t)pl.sx_elems);
+    pl.off_dSx = wplace(2 * (size_t)pl.sx_elems);
     pl.off_atp = wplace(2 * (size_t)pl.atp_elems);
-    pl.off_ap = wplace(2 * (size_t)pl.ap_elems);
-    pl.off_bp = wplace(2 * (size_t)pl.bp_elems);
+    pl.off_ap = wplace(2 * (size_t)pl.d_in * (size_t)(pl.r_total + 32));
+    pl.off_bp = wplace(2 * (size_t)pl.d_out * (size_t)(pl.r_total + 32));
     const size_t tile_bytes = sizeof(float) * (size_t)pl.grad_mb * kGradRanks * kGradCols;
     pl.off_partial = wplace(tile_bytes * std::max(pl.gradB_units.size(), pl.gradA_units.size()));
   }
@@ -423,22 +435,24 @@ int tlora_fwd(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_byte
 
   rc = upload_tables(blob, tb, st);
   if (rc != TLORA_OK) return rc;
-  uint16_t* Sb = reinterpret_cast<uint16_t*>(ws + pl.off_Sb);
+  uint16_t* Sx = reinterpret_cast<uint16_t*>(ws + pl.off_Sx);
   uint16_t* atp = reinterpret_cast<uint16_t*>(ws + pl.off_atp);
   uint16_t* ap = reinterpret_cast<uint16_t*>(ws + pl.off_ap);
   uint16_t* bp = reinterpret_cast<uint16_t*>(ws + pl.off_bp);
+  const TileDev* tiles = reinterpret_cast<const TileDev*>(tb + pl.tb_tiles);
   {
     Timed t(TLORA_K_PACK, st);
-    launch_pack_adapters(jobs, pl.J, pl.d_in, pl.d_out, pl.max_rpad, atp, ap, bp, st);
+    launch_pack_adapters(jobs, pl.J, pl.d_in, pl.d_out, pl.max_rpad, pl.r_total, atp, ap, bp, st);
+    launch_zero_fill(Sx, 2 * (size_t)pl.sx_elems, st);
   }
   {
     Timed t(TLORA_K_SHRINK, st);
-    launch_shrink(jobs, reinterpret_cast<const ShrinkUnit*>(tb + pl.tb_shrink), (int)pl.shrink_units.size(),
-                  g_opt.shrink_rows, static_cast<const uint16_t*>(p->X), pl.d_in, atp, true, S, Sb, st);
+    launch_shrink(jobs, tiles, reinterpret_cast<const ShrinkUnit*>(tb + pl.tb_shrink), (int)pl.shrink_units.size(),
+                  g_opt.shrink_rows, static_cast<const uint16_t*>(p->X), pl.d_in, atp, true, S, Sx, st);
   }
   Timed tg(TLORA_K_GEMM_FWD, st);
-  launch_seg_gemm(true, jobs, reinterpret_cast<const TileJobs*>(tb + pl.tb_tiles), static_cast<const uint16_t*>(p->X),
-                  static_cast<const uint16_t*>(p->W), Sb, bp, static_cast<uint16_t*>(Y), pl.T, pl.d_in, pl.d_out, st);
+  launch_seg_gemm(true, tiles, static_cast<const uint16_t*>(p->X), static_cast<const uint16_t*>(p->W), Sx, bp,
+                  pl.r_total, static_cast<uint16_t*>(Y), pl.T, pl.d_in, pl.d_out, st);
   return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
 }
 
@@ -520,34 +534,40 @@ int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* d
 
   rc = upload_tables(blob, tb, st);
   if (rc != TLORA_OK) return rc;
-  uint16_t* Sb = reinterpret_cast<uint16_t*>(ws + pl.off_Sb);
-  uint16_t* dSb = reinterpret_cast<uint16_t*>(ws + pl.off_dSb);
+  uint16_t* Sx = reinterpret_cast<uint16_t*>(ws + pl.off_Sx);
+  uint16_t* dSx = reinterpret_cast<uint16_t*>(ws + pl.off_dSx);
   uint16_t* atp = reinterpret_cast<uint16_t*>(ws + pl.off_atp);
   uint16_t* ap = reinterpret_cast<uint16_t*>(ws + pl.off_ap);
   uint16_t* bp = reinterpret_cast<uint16_t*>(ws + pl.off_bp);
   float* partial = reinterpret_cast<float*>(ws + pl.off_partial);
   const ShrinkUnit* su = reinterpret_cast<const ShrinkUnit*>(tb + pl.tb_shrink);
+  const TileDev* tiles = reinterpret_cast<const TileDev*>(tb + pl.tb_tiles);
   const uint16_t* Xb = static_cast<const uint16_t*>(p->X);
   const uint16_t* dYb = static_cast<const uint16_t*>(dY);
+  const bool redo_S = want_grads && !reuse_S;
 
   {
     Timed t(TLORA_K_PACK, st);
-    launch_pack_adapters(jobs, pl.J, pl.d_in, pl.d_out, pl.max_rpad, atp, ap, bp, st);
+    launch_pack_adapters(jobs, pl.J, pl.d_in, pl.d_out, pl.max_rpad, pl.r_total, atp, ap, bp, st);
+    if (pl.T > 0) {
+      launch_zero_fill(dSx, 2 * (size_t)pl.sx_elems, st);
+      if (redo_S) launch_zero_fill(Sx, 2 * (size_t)pl.sx_elems, st);
+    }
   }
   if (pl.T > 0) {
-    if (want_grads && !reuse_S) {
+    if (redo_S) {
       Timed t(TLORA_K_SHRINK, st);
-      launch_shrink(jobs, su, (int)pl.shrink_units.size(), g_opt.shrink_rows, Xb, pl.d_in, atp, true, S, Sb, st);
+      launch_shrink(jobs, tiles, su, (int)pl.shrink_units.size(), g_opt.shrink_rows, Xb, pl.d_in, atp, true, S, Sx, st);
     }
     {
       Timed t(TLORA_K_SHRINK, st);
-      launch_shrink(jobs, su, (int)pl.shrink_units.size(), g_opt.shrink_rows, dYb, pl.d_out, bp, false, dS, dSb, st);
+      launch_shrink(jobs, tiles, su, (int)pl.shrink_units.size(), g_opt.shrink_rows, dYb, pl.d_out, bp, false, dS, dSx,
+                    st);
     }
     if (dX) {
       Timed t(TLORA_K_GEMM_BWD, st);
-      launch_seg_gemm(false, jobs, reinterpret_cast<const TileJobs*>(tb + pl.tb_tiles), dYb,
-                      static_cast<const uint16_t*>(p->W), dSb, ap, static_cast<uint16_t*>(dX), pl.T, pl.d_out, pl.d_in,
-                      st);
+      launch_seg_gemm(false, tiles, dYb, static_cast<const uint16_t*>(p->W), dSx, ap, pl.r_total,
+                      static_cast<uint16_t*>(dX), pl.T, pl.d_out, pl.d_in, st);
     }
   }
   if (want_grads) {

@@ -9,7 +9,7 @@ namespace tlora {
 constexpr int kRankGranule = 8;     // ranks are padded to 8 elements = one 16-byte bf16 chunk
 constexpr int kGemmBM = 256;        // backbone GEMM macro tile (token rows x output columns)
 constexpr int kGemmBN = 256;
-constexpr int kGemmBK = 64;
+constexpr int kGemmBK = 32;
 constexpr int kShrinkCols = 64;     // rank columns per shrink work unit
 constexpr int kGradCols = 256;      // feature columns per dA/dB work unit (one wave row: 32 lanes x 8)
 constexpr int kGradRanks = 32;      // rank rows per MFMA block of the dA/dB kernel
@@ -20,19 +20,25 @@ struct JobDev {
   int32_t rank, rpad;      // r_j and r_j rounded up to kRankGranule
   float scale;
   int32_t pad_;
-  int64_t soff;            // element offset of the job's [T_j, rpad] block in S / dS / Sb / dSb
+  int64_t soff;            // element offset of the job's [T_j, rpad] block in the fp32 S / dS buffers
   int64_t atp_off;         // element offset of A_j^T packed [rpad, d_in]  (bf16)
-  int64_t ap_off;          // element offset of A_j   packed [d_in, rpad]  (bf16)
-  int64_t bp_off;          // element offset of B_j   packed [rpad, d_out] (bf16)
+  int32_t roff;            // sum of rpad_i over i < j: the job's row in B-all [R + 32, d_out] and its
+  int32_t pad2_;           //   column in A-all [d_in, R + 32]  (R = sum of all rpad_i)
   const void* A;           // caller's A_j [d_in, r_j]
   const void* B;           // caller's B_j [r_j, d_out]
   void* dA;                // caller's dA_j (fp32) or null
   void* dB;                // caller's dB_j (fp32) or null
 };
 
-// Row tile of the backbone GEMM: first and last job with a row inside the tile.
-struct TileJobs {
+// Row tile of the backbone GEMM (256 token rows of the concatenated batch).  Its adapter K-extension is
+// the padded-rank range [roff_first, roff_first + kext) of the jobs first..last that have a row inside
+// the tile; the bf16 operand s_j * S_j (resp. s_j * dS_j) of the tile is a dense zero-padded
+// [256, kext] matrix at element offset aoff, non-zero only where a row meets its own job's columns.
+struct TileDev {
   int32_t first, last;
+  int32_t kext;            // multiple of 32 (0: no adapter work in this tile)
+  int32_t roff_first;
+  int64_t aoff;
 };
 
 // Work unit of the shrink kernels (S_j = X_j.A_j and dS_j = dY_j.B_j^T): a block of token rows of

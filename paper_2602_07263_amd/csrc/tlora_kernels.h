@@ -9,21 +9,27 @@
 namespace tlora {
 
 // bf16 copies of the adapters in the layouts the MFMA kernels read (zero padded to rpad).
-void launch_pack_adapters(const JobDev* jobs, int num_jobs, int d_in, int d_out, int max_rpad,
-                          uint16_t* atp, uint16_t* ap, uint16_t* bp, hipStream_t st);
+// atp: per job A_j^T [rpad, d_in];  a_all: [d_in, R + 32] with job j in columns roff_j ..;  b_all: [R + 32, d_out]
+// with job j in rows roff_j ..  (R = r_total; the 32 trailing columns / rows are zero).
+void launch_pack_adapters(const JobDev* jobs, int num_jobs, int d_in, int d_out, int max_rpad, int r_total,
+                          uint16_t* atp, uint16_t* a_all, uint16_t* b_all, hipStream_t st);
+
+// Zero `bytes` (multiple of 16) of device memory with a plain store kernel.
+void launch_zero_fill(void* ptr, size_t bytes, hipStream_t st);
 
 // out_j[t, p] = sum_k act[t, k] * P_j[p, k]   (P_j = A_j^T packed, or B_j packed)
-// writes fp32 `S` and bf16 `Sb = scale_j * S` in the packed ragged layout.
-void launch_shrink(const JobDev* jobs, const ShrinkUnit* units, int num_units, int shrink_rows,
-                   const uint16_t* act, int K, const uint16_t* packed, bool packed_is_atp,
-                   float* S, uint16_t* Sb, hipStream_t st);
+// writes fp32 `S` (packed ragged layout) and bf16 `scale_j * S` into the per-tile K-extension matrices `Sx`.
+// packed_is_atp: P_j = atp + atp_off_j (row stride K);  otherwise P_j = b_all + roff_j * K.
+void launch_shrink(const JobDev* jobs, const TileDev* tiles, const ShrinkUnit* units, int num_units,
+                   int shrink_rows, const uint16_t* act, int K, const uint16_t* packed, bool packed_is_atp,
+                   float* S, uint16_t* Sx, hipStream_t st);
 
-// out[t, n] = sum_k act[t, k] * Wop[k, n] + sum_p Sb_j[t, p] * Eop_j[p, n]
-//   w_is_kn = true : W is [K, N] row-major (forward,  Eop_j = B_j packed [rpad, N])
-//   w_is_kn = false: W is [N, K] row-major (backward, Eop_j = A_j packed [N, rpad])
-void launch_seg_gemm(bool w_is_kn, const JobDev* jobs, const TileJobs* tile_jobs, const uint16_t* act,
-                     const uint16_t* W, const uint16_t* Sb, const uint16_t* packed, uint16_t* out, int T, int K,
-                     int N, hipStream_t st);
+// out[t, n] = sum_k act[t, k] * Wop[k, n] + sum_p Sx_tile[t, p] * Eop[roff_first + p, n]
+//   w_is_kn = true : W is [K, N] row-major (forward,  Eop = b_all [R + 32, N])
+//   w_is_kn = false: W is [N, K] row-major (backward, Eop = a_all^T, stored [N, R + 32])
+void launch_seg_gemm(bool w_is_kn, const TileDev* tiles, const uint16_t* act, const uint16_t* W,
+                     const uint16_t* Sx, const uint16_t* packed, int r_total, uint16_t* out, int T, int K, int N,
+                     hipStream_t st);
 
 // partial[u] = sum_{t in unit u} U_j[t, p] * V[t, c]   then   G_j = scale_j * sum_u partial[u]
 void launch_rank_grad(int mb, const JobDev* jobs, const GradUnit* units, int num_units, const float* U,

@@ -68,41 +68,69 @@ __device__ __forceinline__ bf16x8 frag_kn_tile(const uint8_t* tile, int nb, int 
 
 // ---------------------------------------------------------------------------------------------------
 // Adapter packing: bf16 copies, zero padded to rpad, in the three layouts the kernels read.
+//   atp   : per job, A_j^T [rpad, d_in]                      (shrink operand, k contiguous)
+//   a_all : [d_in, R + 32], job j in columns roff_j ..        (dX K-extension operand, k contiguous)
+//   b_all : [R + 32, d_out], job j in rows roff_j ..          (forward K-extension operand; dS shrink operand)
+// blockIdx.y == num_jobs zero-fills the 32 trailing columns / rows, which the last tile's K-extension
+// may read (against zero activations) when its rank range is rounded up to the K-step.
 // ---------------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) pack_adapters_kernel(const JobDev* __restrict__ jobs, int d_in, int d_out,
-                                                            uint16_t* __restrict__ atp, uint16_t* __restrict__ ap,
-                                                            uint16_t* __restrict__ bp) {
+__global__ void __launch_bounds__(256) pack_adapters_kernel(const JobDev* __restrict__ jobs, int num_jobs, int d_in,
+                                                            int d_out, int r_total, uint16_t* __restrict__ atp,
+                                                            uint16_t* __restrict__ a_all,
+                                                            uint16_t* __restrict__ b_all) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  const int64_t first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int ra = r_total + 32;
+  if ((int)blockIdx.y == num_jobs) {
+    for (int64_t i = first; i < (int64_t)32 * d_in; i += stride) a_all[(i >> 5) * ra + r_total + (i & 31)] = 0;
+    for (int64_t i = first; i < (int64_t)32 * d_out; i += stride) b_all[(int64_t)r_total * d_out + i] = 0;
+    return;
+  }
   const JobDev jb = jobs[blockIdx.y];
   if (jb.rpad == 0) return;
   const uint16_t* A = static_cast<const uint16_t*>(jb.A);
   const uint16_t* B = static_cast<const uint16_t*>(jb.B);
   const int64_t na = (int64_t)jb.rpad * d_in;
   const int64_t nb = (int64_t)jb.rpad * d_out;
-  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < na; i += stride) {
+  for (int64_t i = first; i < na; i += stride) {
     {  // A_j^T [rpad, d_in]
       const int p = (int)(i / d_in), k = (int)(i % d_in);
       atp[jb.atp_off + i] = p < jb.rank ? A[(int64_t)k * jb.rank + p] : (uint16_t)0;
     }
-    {  // A_j [d_in, rpad]
+    {  // A_j into its columns of a_all
       const int k = (int)(i / jb.rpad), p = (int)(i % jb.rpad);
-      ap[jb.ap_off + i] = p < jb.rank ? A[(int64_t)k * jb.rank + p] : (uint16_t)0;
+      a_all[(int64_t)k * ra + jb.roff + p] = p < jb.rank ? A[(int64_t)k * jb.rank + p] : (uint16_t)0;
     }
   }
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nb; i += stride) {
+  uint16_t* bdst = b_all + (int64_t)jb.roff * d_out;
+  for (int64_t i = first; i < nb; i += stride) {
     const int p = (int)(i / d_out);
-    bp[jb.bp_off + i] = p < jb.rank ? B[i] : (uint16_t)0;
+    bdst[i] = p < jb.rank ? B[i] : (uint16_t)0;
   }
 }
 
-void launch_pack_adapters(const JobDev* jobs, int num_jobs, int d_in, int d_out, int max_rpad, uint16_t* atp,
-                          uint16_t* ap, uint16_t* bp, hipStream_t st) {
+void launch_pack_adapters(const JobDev* jobs, int num_jobs, int d_in, int d_out, int max_rpad, int r_total,
+                          uint16_t* atp, uint16_t* a_all, uint16_t* b_all, hipStream_t st) {
   if (max_rpad == 0) return;
   const int64_t n = (int64_t)max_rpad * (d_in > d_out ? d_in : d_out);
   int bx = (int)((n + 256 * 8 - 1) / (256 * 8));
   if (bx > 512) bx = 512;
   if (bx < 1) bx = 1;
-  hipLaunchKernelGGL(pack_adapters_kernel, dim3(bx, num_jobs), dim3(256), 0, st, jobs, d_in, d_out, atp, ap, bp);
+  hipLaunchKernelGGL(pack_adapters_kernel, dim3(bx, num_jobs + 1), dim3(256), 0, st, jobs, num_jobs, d_in, d_out,
+                     r_total, atp, a_all, b_all);
+}
+
+__global__ void __launch_bounds__(256) zero_fill_kernel(u32x4* __restrict__ dst, size_t n16) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = u32x4{0, 0, 0, 0};
+}
+
+void launch_zero_fill(void* ptr, size_t bytes, hipStream_t st) {
+  const size_t n16 = bytes / 16;
+  if (n16 == 0) return;
+  size_t blocks = (n16 + 255) / 256;
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(zero_fill_kernel, dim3((unsigned)blocks), dim3(256), 0, st, static_cast<u32x4*>(ptr), n16);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -111,16 +139,18 @@ void launch_pack_adapters(const JobDev* jobs, int num_jobs, int d_in, int d_out,
 // ---------------------------------------------------------------------------------------------------
 template <int ROWS>
 __global__ void __launch_bounds__(256) shrink_kernel(const JobDev* __restrict__ jobs,
+                                                     const TileDev* __restrict__ tiles,
                                                      const ShrinkUnit* __restrict__ units,
                                                      const uint16_t* __restrict__ act, int K,
                                                      const uint16_t* __restrict__ packed, int packed_is_atp,
-                                                     float* __restrict__ S, uint16_t* __restrict__ Sb) {
+                                                     float* __restrict__ S, uint16_t* __restrict__ Sx) {
   constexpr int WM = ROWS / 32;          // waves along token rows
   constexpr int WN = 4 / WM;             // waves along rank columns
   constexpr int PW = kShrinkCols / WN;   // rank columns per wave
   constexpr int NPB = PW / 32;           // 32-wide rank blocks per wave
   constexpr int A_CH = ROWS * 8 / 256;   // 16-byte chunks per thread, activation tile
   constexpr int P_CH = kShrinkCols * 8 / 256;
+  static_assert(kGemmBM == 256, "the row -> GEMM tile lookup below shifts by 8");
 
   __shared__ __attribute__((aligned(16))) uint8_t lds[2 * (ROWS + kShrinkCols) * 128];
   auto a_tile = [&](int buf) { return lds + buf * ((ROWS + kShrinkCols) * 128); };
@@ -132,7 +162,7 @@ __global__ void __launch_bounds__(256) shrink_kernel(const JobDev* __restrict__ 
   const int wm = wave % WM, wn = wave / WM;
   const int p0 = u.pb * kShrinkCols;                     // first padded rank column of this unit
   const int pvalid = min(kShrinkCols, jb.rpad - p0);     // > 0 by construction
-  const uint16_t* P = packed + (packed_is_atp ? jb.atp_off : jb.bp_off) + (int64_t)p0 * K;
+  const uint16_t* P = packed + (packed_is_atp ? jb.atp_off : (int64_t)jb.roff * K) + (int64_t)p0 * K;
   const uint16_t* Arow = act + (int64_t)u.t0 * K;
 
   f32x16 acc[NPB];
@@ -192,7 +222,11 @@ __global__ void __launch_bounds__(256) shrink_kernel(const JobDev* __restrict__ 
   // lane: token row (lane % 32); registers: 4 consecutive rank columns per group g.
   const int r = wm * 32 + (lane & 31);
   if (r < u.nrows) {
-    const int64_t rowbase = jb.soff + (int64_t)(u.t0 + r - jb.row0) * jb.rpad;
+    const int t = u.t0 + r;
+    const int64_t rowbase = jb.soff + (int64_t)(t - jb.row0) * jb.rpad;
+    // the row's slot in its tile's K-extension matrix: [256, kext], this job at columns roff - roff_first
+    const TileDev td = tiles[t >> 8];
+    uint16_t* const xrow = Sx + td.aoff + (int64_t)(t & 255) * td.kext + (jb.roff - td.roff_first);
 #pragma unroll
     for (int i = 0; i < NPB; ++i)
 #pragma unroll
@@ -202,50 +236,68 @@ __global__ void __launch_bounds__(256) shrink_kernel(const JobDev* __restrict__ 
           const float v0 = acc[i][g * 4 + 0], v1 = acc[i][g * 4 + 1], v2 = acc[i][g * 4 + 2], v3 = acc[i][g * 4 + 3];
           *reinterpret_cast<float4*>(S + rowbase + p) = make_float4(v0, v1, v2, v3);
           u32x2 b = {pack_bf16x2(jb.scale * v0, jb.scale * v1), pack_bf16x2(jb.scale * v2, jb.scale * v3)};
-          *reinterpret_cast<u32x2*>(Sb + rowbase + p) = b;
+          *reinterpret_cast<u32x2*>(xrow + p) = b;
         }
       }
   }
 }
 
-void launch_shrink(const JobDev* jobs, const ShrinkUnit* units, int num_units, int shrink_rows, const uint16_t* act,
-                   int K, const uint16_t* packed, bool packed_is_atp, float* S, uint16_t* Sb, hipStream_t st) {
+void launch_shrink(const JobDev* jobs, const TileDev* tiles, const ShrinkUnit* units, int num_units, int shrink_rows,
+                   const uint16_t* act, int K, const uint16_t* packed, bool packed_is_atp, float* S, uint16_t* Sx,
+                   hipStream_t st) {
   if (num_units == 0) return;
   if (shrink_rows == 128)
-    hipLaunchKernelGGL(shrink_kernel<128>, dim3(num_units), dim3(256), 0, st, jobs, units, act, K, packed,
-                       packed_is_atp ? 1 : 0, S, Sb);
+    hipLaunchKernelGGL(shrink_kernel<128>, dim3(num_units), dim3(256), 0, st, jobs, tiles, units, act, K, packed,
+                       packed_is_atp ? 1 : 0, S, Sx);
   else
-    hipLaunchKernelGGL(shrink_kernel<64>, dim3(num_units), dim3(256), 0, st, jobs, units, act, K, packed,
-                       packed_is_atp ? 1 : 0, S, Sb);
+    hipLaunchKernelGGL(shrink_kernel<64>, dim3(num_units), dim3(256), 0, st, jobs, tiles, units, act, K, packed,
+                       packed_is_atp ? 1 : 0, S, Sx);
 }
 
 // ---------------------------------------------------------------------------------------------------
 // Segmented backbone GEMM with the adapter expand fused as extra K-steps:
 //   out[t, :] = act[t, :] . Wop  +  Sb_j[t, :] . Eop_j          (job j = owner of row t)
-// 256 x 256 output tile per workgroup of 8 waves (2 along tokens x 4 along features, 128 x 64 each),
-// K-steps of 64 double-buffered in LDS.  Row tiles are uniform over the concatenated batch and may
-// hold rows of several jobs: the backbone K-loop is job-blind, and each job present in the tile then
-// adds ceil(rpad_j / 64) K-steps in which only its own rows are non-zero.
+// 256 x 256 output tile per workgroup of 8 waves (2 along tokens x 4 along features, 128 x 64 each).
+// Row tiles are uniform over the concatenated batch and may hold rows of several jobs: the backbone
+// K-loop is job-blind, and each job present in the tile then adds ceil(rpad_j / 32) K-steps in which only
+// its own rows are non-zero.
+//
+// Backbone K-loop: K-steps of 32, four LDS stages of 32 KB (activation tile 256 x 32 + weight tile), filled by
+// asynchronous global->LDS loads that run three steps ahead of the MFMAs (96 KB in flight per CU: a
+// 256 x 256 tile needs ~32 B/clk from L2 at MFMA peak, and one 64 KB batch in flight delivers half of that).
 // ---------------------------------------------------------------------------------------------------
 struct GemmParams {
-  const JobDev* jobs;
-  const TileJobs* tile_jobs;
+  const TileDev* tiles;
   const uint16_t* act;      // [T, K]
   const uint16_t* W;        // KN: [K, N]   else [N, K]
-  const uint16_t* Sb;       // packed scaled intermediates (bf16)
-  const uint16_t* packed;   // KN: B_j packed [rpad, N] at bp_off;  else A_j packed [N, rpad] at ap_off
+  const uint16_t* Sx;       // per-tile K-extension operands [256, kext] (bf16, scaled, zero padded)
+  const uint16_t* packed;   // KN: b_all [R + 32, N];  else a_all [N, R + 32]
   uint16_t* out;            // [T, N]
   int T, K, N;
+  int ra;                   // R + 32: row stride of a_all
   int tiles_m, tiles_n;
 };
+
+// "row tile" with 32 k-values per row (64 B rows): 16-byte chunk c of row r sits at slot c ^ ((r >> 2) & 3),
+// so 16 consecutive rows read at one logical chunk cover all 64 banks once.
+__device__ __forceinline__ int row32_off(int r, int c) { return r * 64 + ((c ^ ((r >> 2) & 3)) << 4); }
+__device__ __forceinline__ bf16x8 frag_row32(const uint8_t* tile, int rb, int kk, int lane) {
+  const int r = rb + (lane & 31);
+  return as_bf16x8(*reinterpret_cast<const u32x4*>(tile + row32_off(r, kk * 2 + (lane >> 5))));
+}
 
 template <bool KN>
 __global__ void __launch_bounds__(512) seg_gemm_kernel(GemmParams P) {
   constexpr int BM = kGemmBM, BN = kGemmBN, BK = kGemmBK;
-  constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
-  __shared__ __attribute__((aligned(16))) uint8_t lds[2 * (A_BYTES + B_BYTES)];
-  auto a_tile = [&](int buf) { return lds + buf * (A_BYTES + B_BYTES); };
-  auto b_tile = [&](int buf) { return lds + buf * (A_BYTES + B_BYTES) + A_BYTES; };
+  static_assert(BM == 256 && BN == 256 && BK == 32, "tile shape is baked into the index arithmetic below");
+  constexpr int A_BYTES = BM * BK * 2;               // 16 KB; the weight tile has the same size
+  constexpr int STAGE_BYTES = 2 * A_BYTES;           // 32 KB
+  // Four stages as four separate arrays: the compiler tells an in-flight global->LDS load into one stage
+  // from LDS reads of another only when they are distinct objects.
+  __shared__ __attribute__((aligned(1024))) uint8_t st0[STAGE_BYTES];
+  __shared__ __attribute__((aligned(1024))) uint8_t st1[STAGE_BYTES];
+  __shared__ __attribute__((aligned(1024))) uint8_t st2[STAGE_BYTES];
+  __shared__ __attribute__((aligned(1024))) uint8_t st3[STAGE_BYTES];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave & 1, wn = wave >> 1;
@@ -268,7 +320,7 @@ __global__ void __launch_bounds__(512) seg_gemm_kernel(GemmParams P) {
   }
   const int row0 = tm * BM, col0 = tn * BN;
   const int rows_valid = min(BM, P.T - row0);
-  const TileJobs tj = P.tile_jobs[tm];
+  const TileDev td = P.tiles[tm];
 
   f32x16 acc[2][4];
 #pragma unroll
@@ -278,137 +330,183 @@ __global__ void __launch_bounds__(512) seg_gemm_kernel(GemmParams P) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.f;
 
-  // --- K-step iterator: backbone steps, then the adapter steps of each job in the tile ----------------
-  int it_phase_job = -1;       // -1: backbone; otherwise current job
-  int it_k0 = 0;               // k offset inside the current phase
-  struct Step {
-    const uint16_t* a;  int64_t a_stride;  int r_lo, r_hi;  int kvalid;
-    const uint16_t* b;  int64_t b_stride;
+  auto load_frags = [&](const uint8_t* S, int kk, bf16x8 (&xf)[4], bf16x8 (&wf)[2]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) xf[i] = frag_row32(S, wm * 128 + i * 32, kk, lane);
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+      wf[j] = KN ? frag_kn_tile(S + A_BYTES, wn * 64 + j * 32, kk, lane)
+                 : frag_row32(S + A_BYTES, wn * 64 + j * 32, kk, lane);
   };
-  auto next_step = [&](Step& s) -> bool {
-    if (it_phase_job < 0) {
-      if (it_k0 < P.K) {
-        s.a = P.act + (int64_t)row0 * P.K + it_k0;  s.a_stride = P.K;  s.r_lo = 0;  s.r_hi = rows_valid;
-        s.kvalid = min(BK, P.K - it_k0);
-        if (KN) { s.b = P.W + (int64_t)it_k0 * P.N + col0;  s.b_stride = P.N; }
-        else    { s.b = P.W + (int64_t)col0 * P.K + it_k0;  s.b_stride = P.K; }
-        it_k0 += BK;
-        return true;
-      }
-      it_phase_job = tj.first;  it_k0 = 0;
-    }
-    while (it_phase_job <= tj.last) {
-      const JobDev jb = P.jobs[it_phase_job];
-      const int lo = max(jb.row0 - row0, 0), hi = min(jb.row1 - row0, rows_valid);
-      if (jb.rpad > 0 && lo < hi && it_k0 < jb.rpad) {
-        // rows of other jobs are masked to zero, so the pointer is only dereferenced inside [lo, hi)
-        s.a = P.Sb + jb.soff + ((int64_t)row0 - jb.row0) * jb.rpad + it_k0;  s.a_stride = jb.rpad;
-        s.r_lo = lo;  s.r_hi = hi;  s.kvalid = min(BK, jb.rpad - it_k0);
-        if (KN) { s.b = P.packed + jb.bp_off + (int64_t)it_k0 * P.N + col0;  s.b_stride = P.N; }
-        else    { s.b = P.packed + jb.ap_off + (int64_t)col0 * jb.rpad + it_k0;  s.b_stride = jb.rpad; }
-        it_k0 += BK;
-        return true;
-      }
-      ++it_phase_job;  it_k0 = 0;
-    }
-    return false;
+  auto mma_slice = [&](const bf16x8 (&xf)[4], const bf16x8 (&wf)[2]) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[j][i] = mfma32(wf[j], xf[i], acc[j][i]);
+  };
+  // one K-step (32 k-values = two MFMA k-slices) out of a stage
+  auto compute = [&](const uint8_t* S) {
+    bf16x8 xa[4], wa[2], xb[4], wb[2];
+    load_frags(S, 0, xa, wa);
+    load_frags(S, 1, xb, wb);
+    mma_slice(xa, wa);
+    mma_slice(xb, wb);
   };
 
-  u32x4 areg[4], breg[4];
-  auto load_tiles = [&](const Step& s) {
+  // ---- the K-loop: K / 32 backbone steps, then kext / 32 adapter steps, one software pipeline ----------------
+  // Each wave issues 2 + 2 asynchronous 1 KB loads per step; lane l's 16 bytes land at (wave-uniform base)
+  // + 16 l, so the swizzled LDS layout is produced by choosing which global chunk each lane fetches.  Rows /
+  // columns beyond the problem edge are clamped to the last valid one: they only feed outputs that are never
+  // stored.  The adapter steps read the tile's dense [256, kext] operand (rows of other jobs are stored zeros)
+  // against rows roff_first.. of b_all (forward) or columns roff_first.. of a_all (backward).
+  const int nfull = P.K / BK;
+  const int next = td.kext / BK;
+  const int nsteps = nfull + next;
+  if (nsteps > 0) {
+    const uint16_t* asrc[2];
+    const uint16_t* bsrc[2];
+    const uint16_t* xa_src[2];
+    const uint16_t* xb_src[2];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int id = tid + i * 512, r = id >> 3, c = id & 7;
-      const bool ok = r >= s.r_lo && r < s.r_hi && c * 8 < s.kvalid;
-      areg[i] = ok ? ldg16(s.a + (int64_t)r * s.a_stride + c * 8) : u32x4{0, 0, 0, 0};
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int id = tid + i * 512;
+    for (int i = 0; i < 2; ++i) {
+      const int p = (wave * 2 + i) * 64 + lane;          // 16-byte slot inside the 16 KB tile
+      {
+        const int r = p >> 2, c = (p & 3) ^ ((r >> 2) & 3);
+        asrc[i] = P.act + (int64_t)(row0 + min(r, rows_valid - 1)) * P.K + c * 8;
+        xa_src[i] = P.Sx + td.aoff + (int64_t)r * td.kext + c * 8;      // all 256 rows of the operand exist
+      }
       if (KN) {
-        const int k = id >> 5, c = id & 31;
-        const bool ok = k < s.kvalid && col0 + c * 8 < P.N;
-        breg[i] = ok ? ldg16(s.b + (int64_t)k * s.b_stride + c * 8) : u32x4{0, 0, 0, 0};
+        const int k = p >> 5, c = (p & 31) ^ ((k & 3) << 2);
+        const int col = min(col0 + c * 8, P.N - 8);
+        bsrc[i] = P.W + (int64_t)k * P.N + col;
+        xb_src[i] = P.packed + (int64_t)(td.roff_first + k) * P.N + col;
       } else {
-        const int n = id >> 3, c = id & 7;
-        const bool ok = col0 + n < P.N && c * 8 < s.kvalid;
-        breg[i] = ok ? ldg16(s.b + (int64_t)n * s.b_stride + c * 8) : u32x4{0, 0, 0, 0};
+        const int n = p >> 2, c = (p & 3) ^ ((n >> 2) & 3);
+        const int nn = min(col0 + n, P.N - 1);
+        bsrc[i] = P.W + (int64_t)nn * P.K + c * 8;
+        xb_src[i] = P.packed + (int64_t)nn * P.ra + td.roff_first + c * 8;
       }
     }
-  };
-  auto store_tiles = [&](int buf) {
+    const int64_t bstep = KN ? (int64_t)BK * P.N : (int64_t)BK;   // same in both phases
+    if (nfull == 0) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int id = tid + i * 512, r = id >> 3, c = id & 7;
-      *reinterpret_cast<u32x4*>(a_tile(buf) + row_tile_off(r, c)) = areg[i];
+      for (int i = 0; i < 2; ++i) { asrc[i] = xa_src[i];  bsrc[i] = xb_src[i]; }
     }
+    int issued = 0;
+    auto issue = [&](uint8_t* S) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int id = tid + i * 512;
-      if (KN) *reinterpret_cast<u32x4*>(b_tile(buf) + kn_tile_off(id >> 5, id & 31)) = breg[i];
-      else    *reinterpret_cast<u32x4*>(b_tile(buf) + row_tile_off(id >> 3, id & 7)) = breg[i];
+      for (int i = 0; i < 2; ++i)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)asrc[i],
+                                         LDS_PTR(void, S + (wave * 2 + i) * 1024), 16, 0, 0);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)bsrc[i],
+                                         LDS_PTR(void, S + A_BYTES + (wave * 2 + i) * 1024), 16, 0, 0);
+      // Next source: advance inside a phase, jump to the adapter operands after the last backbone step, and
+      // stay put after the last step (the trailing issues re-load it into a stage nobody reads, which keeps
+      // the count of outstanding loads uniform).  Selects, not branches: a branch here would make the
+      // compiler wait for every outstanding load where the paths merge.
+      ++issued;
+      const bool to_ext = issued == nfull && next > 0;
+      const bool adv = issued < nsteps;
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        asrc[i] = to_ext ? xa_src[i] : asrc[i] + (adv ? BK : 0);
+        bsrc[i] = to_ext ? xb_src[i] : bsrc[i] + (adv ? bstep : 0);
+      }
+    };
+    auto landed = [&]() {
+      // Loads complete in order: with the 2 x 4 loads of the two younger steps still allowed in flight, this
+      // wave's loads of the current step have landed (and its own LDS reads of the stage about to be refilled
+      // are done); after the barrier so have everyone else's.
+      __builtin_amdgcn_s_waitcnt(0x0078);   // vmcnt(8) lgkmcnt(0)
+      __builtin_amdgcn_s_barrier();
+    };
+    issue(st0);
+    issue(st1);
+    issue(st2);
+    int kt = 0;
+    for (; kt + 4 <= nsteps; kt += 4) {
+      landed();  issue(st3);  compute(st0);
+      landed();  issue(st0);  compute(st1);
+      landed();  issue(st1);  compute(st2);
+      landed();  issue(st2);  compute(st3);
     }
-  };
-
-  Step cur, nxt;
-  bool have = next_step(cur);
-  if (have) {
-    load_tiles(cur);
-    store_tiles(0);
+    if (kt < nsteps)     { landed();  issue(st3);  compute(st0); }
+    if (kt + 1 < nsteps) { landed();  issue(st0);  compute(st1); }
+    if (kt + 2 < nsteps) { landed();  issue(st1);  compute(st2); }
+    __builtin_amdgcn_s_waitcnt(0x0070);     // vmcnt(0): the trailing re-loads must not land in reused LDS
   }
-  __syncthreads();
-  int buf = 0;
-  while (have) {
-    const bool have_next = next_step(nxt);
-    if (have_next) load_tiles(nxt);
-    const int nkk = (cur.kvalid + 15) >> 4;
+
+  // ---- K tail (K % 32 != 0): one register-staged, predicated step through stage 0 ---------------------------
+  if (P.K % BK) {
+    const int k0 = nfull * BK, kvalid = P.K - k0;
+    u32x4 areg[2], breg[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int id = tid + i * 512, r = id >> 2, c = id & 3;
+      const bool ok = r < rows_valid && c * 8 < kvalid;
+      areg[i] = ok ? ldg16(P.act + (int64_t)(row0 + r) * P.K + k0 + c * 8) : u32x4{0, 0, 0, 0};
+      if (KN) {
+        const int k = id >> 5, cc = id & 31;
+        const bool okb = k < kvalid && col0 + cc * 8 < P.N;
+        breg[i] = okb ? ldg16(P.W + (int64_t)(k0 + k) * P.N + col0 + cc * 8) : u32x4{0, 0, 0, 0};
+      } else {
+        const bool okb = col0 + r < P.N && c * 8 < kvalid;
+        breg[i] = okb ? ldg16(P.W + (int64_t)(col0 + r) * P.K + k0 + c * 8) : u32x4{0, 0, 0, 0};
+      }
+    }
+    __syncthreads();                       // every wave is done reading stage 0
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int id = tid + i * 512;
+      *reinterpret_cast<u32x4*>(st0 + row32_off(id >> 2, id & 3)) = areg[i];
+      if (KN) *reinterpret_cast<u32x4*>(st0 + A_BYTES + kn_tile_off(id >> 5, id & 31)) = breg[i];
+      else    *reinterpret_cast<u32x4*>(st0 + A_BYTES + row32_off(id >> 2, id & 3)) = breg[i];
+    }
+    __syncthreads();
+    const int nkk = (kvalid + 15) >> 4;
     for (int kk = 0; kk < nkk; ++kk) {
       bf16x8 xf[4], wf[2];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) xf[i] = frag_row_tile(a_tile(buf), wm * 128 + i * 32, kk, lane);
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-        wf[j] = KN ? frag_kn_tile(b_tile(buf), wn * 64 + j * 32, kk, lane)
-                   : frag_row_tile(b_tile(buf), wn * 64 + j * 32, kk, lane);
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) acc[j][i] = mfma32(wf[j], xf[i], acc[j][i]);
+      load_frags(st0, kk, xf, wf);
+      mma_slice(xf, wf);
     }
-    if (have_next) store_tiles(buf ^ 1);
-    __syncthreads();
-    buf ^= 1;
-    cur = nxt;
-    have = have_next;
   }
 
-  // epilogue: lane = token row (lane % 32) of block i; 4 consecutive features per register group.
+  // ---- epilogue: accumulators -> bf16 -> LDS (each stage array holds 64 output rows, 512 B per row, 16-byte
+  // chunk c of row R at slot c ^ (R & 31)) -> full 512-byte rows to global memory. -----------------------------
+  __syncthreads();
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int r = wm * 128 + i * 32 + (lane & 31);
-    if (r < rows_valid) {
-      uint16_t* orow = P.out + (int64_t)(row0 + r) * P.N;
+    uint8_t* const obuf = wm ? (i < 2 ? st2 : st3) : (i < 2 ? st0 : st1);
+    const int R = wm * 128 + i * 32 + (lane & 31);
+    uint8_t* const orow = obuf + (R & 63) * 512 + (lane >> 5) * 8;
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int n = col0 + wn * 64 + j * 32 + g * 8 + (lane >> 5) * 4;
-          if (n < P.N) {
-            u32x2 v = {pack_bf16x2(acc[j][i][g * 4 + 0], acc[j][i][g * 4 + 1]),
-                       pack_bf16x2(acc[j][i][g * 4 + 2], acc[j][i][g * 4 + 3])};
-            *reinterpret_cast<u32x2*>(orow + n) = v;
-          }
-        }
-    }
+      for (int g = 0; g < 4; ++g) {
+        const int c = wn * 8 + j * 4 + g;
+        u32x2 v = {pack_bf16x2(acc[j][i][g * 4 + 0], acc[j][i][g * 4 + 1]),
+                   pack_bf16x2(acc[j][i][g * 4 + 2], acc[j][i][g * 4 + 3])};
+        *reinterpret_cast<u32x2*>(orow + ((c ^ (R & 31)) << 4)) = v;
+      }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int it = 0; it < 16; ++it) {
+    const uint8_t* const obuf = it < 4 ? st0 : it < 8 ? st1 : it < 12 ? st2 : st3;
+    const int R = (tid >> 5) + it * 16, c = tid & 31;
+    const u32x4 v = *reinterpret_cast<const u32x4*>(obuf + (R & 63) * 512 + ((c ^ (R & 31)) << 4));
+    if (R < rows_valid && col0 + c * 8 < P.N)
+      *reinterpret_cast<u32x4*>(P.out + (int64_t)(row0 + R) * P.N + col0 + c * 8) = v;
   }
 }
 
-void launch_seg_gemm(bool w_is_kn, const JobDev* jobs, const TileJobs* tile_jobs, const uint16_t* act,
-                     const uint16_t* W, const uint16_t* Sb, const uint16_t* packed, uint16_t* out, int T, int K,
-                     int N, hipStream_t st) {
+void launch_seg_gemm(bool w_is_kn, const TileDev* tiles, const uint16_t* act, const uint16_t* W, const uint16_t* Sx,
+                     const uint16_t* packed, int r_total, uint16_t* out, int T, int K, int N, hipStream_t st) {
   GemmParams P;
-  P.jobs = jobs;  P.tile_jobs = tile_jobs;  P.act = act;  P.W = W;  P.Sb = Sb;  P.packed = packed;  P.out = out;
-  P.T = T;  P.K = K;  P.N = N;
+  P.tiles = tiles;  P.act = act;  P.W = W;  P.Sx = Sx;  P.packed = packed;  P.out = out;
+  P.T = T;  P.K = K;  P.N = N;  P.ra = r_total + 32;
   P.tiles_m = (T + kGemmBM - 1) / kGemmBM;
   P.tiles_n = (N + kGemmBN - 1) / kGemmBN;
   const int nb = P.tiles_m * P.tiles_n;

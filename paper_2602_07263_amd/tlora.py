@@ -15,7 +15,7 @@ TLORA_F32, TLORA_BF16 = 0, 1
 TLORA_BWD_REUSE_S = 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libtlora.so")
+LIB_PATH = os.environ.get("TLORA_LIB") or os.path.join(_HERE, "libtlora.so")
 _lib = None
 
 
