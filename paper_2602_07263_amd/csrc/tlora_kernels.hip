@@ -344,15 +344,6 @@ __global__ void __launch_bounds__(512) seg_gemm_kernel(GemmParams P) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) acc[j][i] = mfma32(wf[j], xf[i], acc[j][i]);
   };
-  // one K-step (32 k-values = two MFMA k-slices) out of a stage
-  auto compute = [&](const uint8_t* S) {
-    bf16x8 xa[4], wa[2], xb[4], wb[2];
-    load_frags(S, 0, xa, wa);
-    load_frags(S, 1, xb, wb);
-    mma_slice(xa, wa);
-    mma_slice(xb, wb);
-  };
-
   // ---- the K-loop: K / 32 backbone steps, then kext / 32 adapter steps, one software pipeline ----------------
   // Each wave issues 2 + 2 asynchronous 1 KB loads per step; lane l's 16 bytes land at (wave-uniform base)
   // + 16 l, so the swizzled LDS layout is produced by choosing which global chunk each lane fetches.  Rows /
@@ -421,6 +412,14 @@ __global__ void __launch_bounds__(512) seg_gemm_kernel(GemmParams P) {
       // are done); after the barrier so have everyone else's.
       __builtin_amdgcn_s_waitcnt(0x0078);   // vmcnt(8) lgkmcnt(0)
       __builtin_amdgcn_s_barrier();
+    };
+    // one K-step (32 k-values = two MFMA k-slices) out of a stage
+    auto compute = [&](const uint8_t* S) {
+      bf16x8 xa[4], wa[2], xb[4], wb[2];
+      load_frags(S, 0, xa, wa);
+      load_frags(S, 1, xb, wb);
+      mma_slice(xa, wa);
+      mma_slice(xb, wb);
     };
     issue(st0);
     issue(st1);
