@@ -99,7 +99,7 @@ int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* d
 /* Integer bookkeeping of the nano-batch plan (Sec. 3.3, nano-batches = partition of the combined
  * batch along the token dimension), for bit-exact checks.  All outputs are HOST arrays and each may
  * be NULL.  Per job: rpad[J] (rank rounded up to the 8-element granule), soff[J+1] (element
- * offset of job j's rows in the packed intermediate: sum_{i<j} T_i * rpad_i).  Per row tile of
+ * offset of job j's rows in the packed intermediate: sum_{i<j} ceil(T_i / 32) * 32 * rpad_i).  Per row tile of
  * the backbone GEMM (uniform tiles of `*tile_rows` rows over the concatenated batch; a tile may
  * hold rows of several jobs): tile_row0, tile_nrows, tile_job_first, tile_job_last (first / last
  * job with a row in the tile).  *n_tiles: in = capacity of the tile arrays, out = number of tiles

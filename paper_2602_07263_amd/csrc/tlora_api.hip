@@ -17,7 +17,7 @@ namespace {
 
 struct Options {
   int shrink_rows = 64;
-  int grad_tokens = 512;
+  int grad_tokens = 256;
 };
 Options g_opt;
 std::mutex g_mu;
@@ -28,18 +28,20 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 struct Plan {
   int J = 0, T = 0, d_in = 0, d_out = 0, dtype = 0;
   int max_rpad = 0;
-  int grad_mb = 1;
   std::vector<JobDev> jobs;
   std::vector<TileDev> tile_jobs;
   std::vector<ShrinkUnit> shrink_units;
-  std::vector<GradUnit> gradB_units, gradA_units;      // dB: columns over d_out;  dA: columns over d_in
+  std::vector<GradUnit> gradB_units, gradA_units;      // dB: columns over d_out;  dA: columns over d_in;
+                                                        // sorted by rank-block class mb = 1, 2, 4
+  int gradB_class_begin[4] = {0, 0, 0, 0}, gradA_class_begin[4] = {0, 0, 0, 0};
+  int64_t gradB_partial = 0, gradA_partial = 0;         // floats of partial tiles
   std::vector<GradGroup> gradB_groups, gradA_groups;
   int64_t s_elems = 0;                                  // elements of the packed S (= dS) buffer
   int64_t atp_elems = 0;
   int r_total = 0;                                      // sum of rpad_j
   int64_t sx_elems = 0;                                 // elements of the per-tile K-extension operands
   // workspace byte offsets
-  size_t off_tables = 0, off_S = 0, off_dS = 0, off_Sx = 0, off_dSx = 0, off_atp = 0, off_ap = 0, off_bp = 0,
+  size_t off_tables = 0, off_S = 0, off_dS = 0, off_Shi = 0, off_Slo = 0, off_dShi = 0, off_dSlo = 0, off_Sx = 0, off_dSx = 0, off_atp = 0, off_ap = 0, off_bp = 0,
          off_partial = 0, total = 0;
   size_t tables_bytes = 0;
   // offsets of each table inside the table blob
@@ -61,32 +63,58 @@ int validate(const tlora_problem_t* p) {
   return TLORA_OK;
 }
 
-void build_grad_units(const Plan& pl, int D, std::vector<GradUnit>& units, std::vector<GradGroup>& groups) {
-  const int mb = pl.grad_mb;
-  const int prow = kGradRanks * mb;
+// Work units of the dA / dB token reductions (rank-aware nano-batches of one job's tokens).  A job's rank
+// rows are cut into blocks of 32*mb with mb = 1, 2 or 4 chosen from its padded rank; a token chunk streams
+// chunk * 256 * 2 bytes of the activation and leaves a partial tile of 32*mb * 256 * 4 bytes that is written
+// and read once more, so the default chunk is 32 * (32*mb) tokens (partial traffic <= ~12 %).  If that gives
+// too few units to fill the GPU the chunks are shortened (not below `grad_tokens`).
+void build_grad_units(const Plan& pl, int D, std::vector<GradUnit>& units, std::vector<GradGroup>& groups,
+                      int class_begin[4], int64_t& partial_floats) {
   const int ncb = (D + kGradCols - 1) / kGradCols;
-  for (int j = 0; j < pl.J; ++j) {
-    const JobDev& jb = pl.jobs[j];
-    if (jb.rank == 0) continue;
-    const int Tj = jb.row1 - jb.row0;
-    // rank-aware token chunking: a chunk reads chunk*256*2 bytes and writes prow*256*4, so keep
-    // chunk >= 16 * rank rows; otherwise as many chunks as the token count allows.
-    int chunk = std::max(g_opt.grad_tokens, 16 * std::min(jb.rpad, prow));
-    chunk = (chunk + 63) / 64 * 64;
-    const int nchunks = Tj > 0 ? (Tj + chunk - 1) / chunk : 0;
-    const int npb = (jb.rpad + prow - 1) / prow;
-    for (int pb = 0; pb < npb; ++pb)
-      for (int cb = 0; cb < ncb; ++cb) {
-        GradGroup g{};
-        g.job = j;  g.cb = cb;  g.pb = pb;  g.unit0 = (int)units.size();  g.nunits = nchunks;
-        for (int c = 0; c < nchunks; ++c) {
-          GradUnit u{};
-          u.job = j;  u.t0 = jb.row0 + c * chunk;  u.t1 = std::min(jb.row1, u.t0 + chunk);  u.cb = cb;  u.pb = pb;
-          units.push_back(u);
+  auto class_mb = [](int rpad) { return rpad <= 32 ? 1 : rpad <= 64 ? 2 : 4; };
+  auto count_units = [&](double shrink) {
+    int64_t n = 0;
+    for (const JobDev& jb : pl.jobs) {
+      if (jb.rank == 0 || jb.row1 == jb.row0) continue;
+      const int mb = class_mb(jb.rpad), prow = kGradRanks * mb;
+      int chunk = std::max(g_opt.grad_tokens, (int)(32 * prow * shrink));
+      chunk = (chunk + kGradStep - 1) / kGradStep * kGradStep;
+      n += (int64_t)((jb.row1 - jb.row0 + chunk - 1) / chunk) * ncb * ((jb.rpad + prow - 1) / prow);
+    }
+    return n;
+  };
+  double shrink = 1.0;
+  const int64_t want = 1024;
+  while (shrink > 1.0 / 64 && count_units(shrink) < want) shrink *= 0.5;
+  partial_floats = 0;
+  const int classes[3] = {1, 2, 4};
+  for (int ci = 0; ci < 3; ++ci) {
+    class_begin[ci] = (int)units.size();
+    for (int j = 0; j < pl.J; ++j) {
+      const JobDev& jb = pl.jobs[j];
+      if (jb.rank == 0 || class_mb(jb.rpad) != classes[ci]) continue;
+      const int mb = classes[ci], prow = kGradRanks * mb;
+      const int Tj = jb.row1 - jb.row0;
+      int chunk = std::max(g_opt.grad_tokens, (int)(32 * prow * shrink));
+      chunk = (chunk + kGradStep - 1) / kGradStep * kGradStep;
+      const int nchunks = Tj > 0 ? (Tj + chunk - 1) / chunk : 0;
+      const int npb = (jb.rpad + prow - 1) / prow;
+      for (int pb = 0; pb < npb; ++pb)
+        for (int cb = 0; cb < ncb; ++cb) {
+          GradGroup g{};
+          g.job = j;  g.cb = cb;  g.pb = pb;  g.mb = mb;  g.nunits = nchunks;  g.part_off = partial_floats;
+          for (int c = 0; c < nchunks; ++c) {
+            GradUnit u{};
+            u.job = j;  u.t0 = jb.row0 + c * chunk;  u.t1 = std::min(jb.row1, u.t0 + chunk);  u.cb = cb;  u.pb = pb;
+            u.mb = mb;  u.part_off = partial_floats;
+            partial_floats += (int64_t)prow * kGradCols;
+            units.push_back(u);
+          }
+          groups.push_back(g);
         }
-        groups.push_back(g);
-      }
+    }
   }
+  class_begin[3] = (int)units.size();
 }
 
 int build_plan(const tlora_problem_t* p, Plan& pl) {
@@ -105,14 +133,14 @@ int build_plan(const tlora_problem_t* p, Plan& pl) {
     jb.rpad = (jb.rank + kRankGranule - 1) / kRankGranule * kRankGranule;
     jb.scale = p->scales[j];
     jb.soff = soff;  jb.atp_off = atp;  jb.roff = (int32_t)roff;
-    soff += (int64_t)(jb.row1 - jb.row0) * jb.rpad;
+    // rows of the packed intermediates are padded (with zeros) to the dA / dB kernel's token step
+    soff += (int64_t)((jb.row1 - jb.row0 + kGradStep - 1) / kGradStep * kGradStep) * jb.rpad;
     atp += (int64_t)jb.rpad * pl.d_in;
     roff += jb.rpad;
     pl.max_rpad = std::max(pl.max_rpad, jb.rpad);
   }
   if (roff > (int64_t)1 << 24) return TLORA_EINVAL;
   pl.s_elems = soff;  pl.atp_elems = atp;  pl.r_total = (int)roff;
-  pl.grad_mb = pl.max_rpad > kGradRanks ? 2 : 1;
 
   // row tiles of the backbone GEMM (nano-batches of the concatenated batch, Sec. 3.3)
   const int tiles_m = (pl.T + kGemmBM - 1) / kGemmBM;
@@ -147,8 +175,8 @@ int build_plan(const tlora_problem_t* p, Plan& pl) {
           pl.shrink_units.push_back(u);
         }
     }
-    build_grad_units(pl, pl.d_out, pl.gradB_units, pl.gradB_groups);
-    build_grad_units(pl, pl.d_in, pl.gradA_units, pl.gradA_groups);
+    build_grad_units(pl, pl.d_out, pl.gradB_units, pl.gradB_groups, pl.gradB_class_begin, pl.gradB_partial);
+    build_grad_units(pl, pl.d_in, pl.gradA_units, pl.gradA_groups, pl.gradA_class_begin, pl.gradA_partial);
   }
 
   // table blob
@@ -182,16 +210,21 @@ int build_plan(const tlora_problem_t* p, Plan& pl) {
   size_t w = 0;
   auto wplace = [&](size_t bytes) { const size_t at = w;  w = align_up(w + bytes, 256);  return at; };
   pl.off_tables = wplace(pl.tables_bytes);
-  pl.off_S = wplace(sizeof(float) * (size_t)pl.s_elems);
-  pl.off_dS = wplace(sizeof(float) * (size_t)pl.s_elems);
+  if (pl.dtype == TLORA_F32) {
+    pl.off_S = wplace(sizeof(float) * (size_t)pl.s_elems);
+    pl.off_dS = wplace(sizeof(float) * (size_t)pl.s_elems);
+  }
   if (pl.dtype == TLORA_BF16) {
+    pl.off_Shi = wplace(2 * (size_t)pl.s_elems);
+    pl.off_Slo = wplace(2 * (size_t)pl.s_elems);
+    pl.off_dShi = wplace(2 * (size_t)pl.s_elems);
+    pl.off_dSlo = wplace(2 * (size_t)pl.s_elems);
     pl.off_Sx = wplace(2 * (size_t)pl.sx_elems);
     pl.off_dSx = wplace(2 * (size_t)pl.sx_elems);
     pl.off_atp = wplace(2 * (size_t)pl.atp_elems);
     pl.off_ap = wplace(2 * (size_t)pl.d_in * (size_t)(pl.r_total + 32));
     pl.off_bp = wplace(2 * (size_t)pl.d_out * (size_t)(pl.r_total + 32));
-    const size_t tile_bytes = sizeof(float) * (size_t)pl.grad_mb * kGradRanks * kGradCols;
-    pl.off_partial = wplace(tile_bytes * std::max(pl.gradB_units.size(), pl.gradA_units.size()));
+    pl.off_partial = wplace(sizeof(float) * (size_t)std::max(pl.gradB_partial, pl.gradA_partial));
   }
   pl.total = std::max<size_t>(w, 256);
   return TLORA_OK;
@@ -399,9 +432,9 @@ int tlora_fwd(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_byte
   uint8_t* tb = ws + pl.off_tables;
   std::vector<uint8_t> blob = make_blob(pl);
   const JobDev* jobs = reinterpret_cast<const JobDev*>(tb + pl.tb_jobs);
-  float* S = reinterpret_cast<float*>(ws + pl.off_S);
 
   if (pl.dtype == TLORA_F32) {
+    float* S = reinterpret_cast<float*>(ws + pl.off_S);
     const float* X = static_cast<const float*>(p->X);
     const float* W = static_cast<const float*>(p->W);
     float* Yf = static_cast<float*>(Y);
@@ -448,7 +481,8 @@ int tlora_fwd(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_byte
   {
     Timed t(TLORA_K_SHRINK, st);
     launch_shrink(jobs, tiles, reinterpret_cast<const ShrinkUnit*>(tb + pl.tb_shrink), (int)pl.shrink_units.size(),
-                  g_opt.shrink_rows, static_cast<const uint16_t*>(p->X), pl.d_in, atp, true, S, Sx, st);
+                  g_opt.shrink_rows, static_cast<const uint16_t*>(p->X), pl.d_in, atp, true,
+                  reinterpret_cast<uint16_t*>(ws + pl.off_Shi), reinterpret_cast<uint16_t*>(ws + pl.off_Slo), Sx, st);
   }
   Timed tg(TLORA_K_GEMM_FWD, st);
   launch_seg_gemm(true, tiles, static_cast<const uint16_t*>(p->X), static_cast<const uint16_t*>(p->W), Sx, bp,
@@ -481,10 +515,10 @@ int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* d
   uint8_t* tb = ws + pl.off_tables;
   std::vector<uint8_t> blob = make_blob(pl);
   const JobDev* jobs = reinterpret_cast<const JobDev*>(tb + pl.tb_jobs);
-  float* S = reinterpret_cast<float*>(ws + pl.off_S);
-  float* dS = reinterpret_cast<float*>(ws + pl.off_dS);
 
   if (pl.dtype == TLORA_F32) {
+    float* S = reinterpret_cast<float*>(ws + pl.off_S);
+    float* dS = reinterpret_cast<float*>(ws + pl.off_dS);
     const float* X = static_cast<const float*>(p->X);
     const float* W = static_cast<const float*>(p->W);
     const float* dYf = static_cast<const float*>(dY);
@@ -536,6 +570,10 @@ int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* d
   if (rc != TLORA_OK) return rc;
   uint16_t* Sx = reinterpret_cast<uint16_t*>(ws + pl.off_Sx);
   uint16_t* dSx = reinterpret_cast<uint16_t*>(ws + pl.off_dSx);
+  uint16_t* Shi = reinterpret_cast<uint16_t*>(ws + pl.off_Shi);
+  uint16_t* Slo = reinterpret_cast<uint16_t*>(ws + pl.off_Slo);
+  uint16_t* dShi = reinterpret_cast<uint16_t*>(ws + pl.off_dShi);
+  uint16_t* dSlo = reinterpret_cast<uint16_t*>(ws + pl.off_dSlo);
   uint16_t* atp = reinterpret_cast<uint16_t*>(ws + pl.off_atp);
   uint16_t* ap = reinterpret_cast<uint16_t*>(ws + pl.off_ap);
   uint16_t* bp = reinterpret_cast<uint16_t*>(ws + pl.off_bp);
@@ -557,12 +595,13 @@ int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* d
   if (pl.T > 0) {
     if (redo_S) {
       Timed t(TLORA_K_SHRINK, st);
-      launch_shrink(jobs, tiles, su, (int)pl.shrink_units.size(), g_opt.shrink_rows, Xb, pl.d_in, atp, true, S, Sx, st);
+      launch_shrink(jobs, tiles, su, (int)pl.shrink_units.size(), g_opt.shrink_rows, Xb, pl.d_in, atp, true, Shi, Slo, Sx,
+                    st);
     }
     {
       Timed t(TLORA_K_SHRINK, st);
-      launch_shrink(jobs, tiles, su, (int)pl.shrink_units.size(), g_opt.shrink_rows, dYb, pl.d_out, bp, false, dS, dSx,
-                    st);
+      launch_shrink(jobs, tiles, su, (int)pl.shrink_units.size(), g_opt.shrink_rows, dYb, pl.d_out, bp, false, dShi, dSlo,
+                    dSx, st);
     }
     if (dX) {
       Timed t(TLORA_K_GEMM_BWD, st);
@@ -571,25 +610,30 @@ int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* d
     }
   }
   if (want_grads) {
+    const int classes[3] = {1, 2, 4};
     {
       Timed t(TLORA_K_RANK_GRAD, st);
-      launch_rank_grad(pl.grad_mb, jobs, reinterpret_cast<const GradUnit*>(tb + pl.tb_gBu), (int)pl.gradB_units.size(),
-                       S, dYb, pl.d_out, partial, st);
+      const GradUnit* gu = reinterpret_cast<const GradUnit*>(tb + pl.tb_gBu);
+      for (int ci = 0; ci < 3; ++ci)
+        launch_rank_grad(classes[ci], jobs, gu + pl.gradB_class_begin[ci],
+                         pl.gradB_class_begin[ci + 1] - pl.gradB_class_begin[ci], Shi, Slo, dYb, pl.d_out, partial, st);
     }
     {
       Timed t(TLORA_K_GRAD_REDUCE, st);
-      launch_grad_reduce(pl.grad_mb, jobs, reinterpret_cast<const GradGroup*>(tb + pl.tb_gBg),
-                         (int)pl.gradB_groups.size(), partial, pl.d_out, false, st);
+      launch_grad_reduce(jobs, reinterpret_cast<const GradGroup*>(tb + pl.tb_gBg), (int)pl.gradB_groups.size(), partial,
+                         pl.d_out, false, st);
     }
     {
       Timed t(TLORA_K_RANK_GRAD, st);
-      launch_rank_grad(pl.grad_mb, jobs, reinterpret_cast<const GradUnit*>(tb + pl.tb_gAu), (int)pl.gradA_units.size(),
-                       dS, Xb, pl.d_in, partial, st);
+      const GradUnit* gu = reinterpret_cast<const GradUnit*>(tb + pl.tb_gAu);
+      for (int ci = 0; ci < 3; ++ci)
+        launch_rank_grad(classes[ci], jobs, gu + pl.gradA_class_begin[ci],
+                         pl.gradA_class_begin[ci + 1] - pl.gradA_class_begin[ci], dShi, dSlo, Xb, pl.d_in, partial, st);
     }
     {
       Timed t(TLORA_K_GRAD_REDUCE, st);
-      launch_grad_reduce(pl.grad_mb, jobs, reinterpret_cast<const GradGroup*>(tb + pl.tb_gAg),
-                         (int)pl.gradA_groups.size(), partial, pl.d_in, true, st);
+      launch_grad_reduce(jobs, reinterpret_cast<const GradGroup*>(tb + pl.tb_gAg), (int)pl.gradA_groups.size(), partial,
+                         pl.d_in, true, st);
     }
   }
   return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;

@@ -11,8 +11,9 @@ constexpr int kGemmBM = 256;        // backbone GEMM macro tile (token rows x ou
 constexpr int kGemmBN = 256;
 constexpr int kGemmBK = 32;
 constexpr int kShrinkCols = 64;     // rank columns per shrink work unit
-constexpr int kGradCols = 256;      // feature columns per dA/dB work unit (one wave row: 32 lanes x 8)
+constexpr int kGradCols = 256;      // feature columns per dA/dB work unit (4 waves x 64)
 constexpr int kGradRanks = 32;      // rank rows per MFMA block of the dA/dB kernel
+constexpr int kGradStep = 32;       // tokens per pipeline step of the dA/dB kernel
 
 // One job's view of the problem (Sec. 3.2: one adapter branch per job on the shared backbone).
 struct JobDev {
@@ -50,23 +51,26 @@ struct ShrinkUnit {
   int32_t pb;              // rank-column block
 };
 
-// Work unit of the dA/dB kernels: tokens [t0, t1) of one job x kGradCols feature columns x a block
-// of rank rows; writes one partial tile that the reduce pass sums in unit order.
+// Work unit of the dA/dB kernels: tokens [t0, t1) of one job x kGradCols feature columns x a block of
+// 32 * mb rank rows; writes one partial tile [32 * mb, kGradCols] (fp32) at float offset part_off, which
+// the reduce pass sums in unit order.
 struct GradUnit {
   int32_t job;
   int32_t t0, t1;
   int32_t cb;              // feature-column block
-  int32_t pb;              // rank block (of kGradRanks * MB rows)
-  int32_t pad_;
+  int32_t pb;              // rank block (of 32 * mb rows)
+  int32_t mb;              // 1, 2 or 4
+  int64_t part_off;
 };
 
-// One output tile of dA_j / dB_j: the run of partial tiles that sum to it.
+// One output tile of dA_j / dB_j: the run of nunits consecutive partial tiles that sum to it.
 struct GradGroup {
   int32_t job;
   int32_t cb, pb;
-  int32_t unit0;           // first partial tile
-  int32_t nunits;          // number of partial tiles (token chunks)
+  int32_t mb;
+  int32_t nunits;          // number of partial tiles (token chunks); 0 for an empty segment
   int32_t pad_;
+  int64_t part_off;        // float offset of the first partial tile
 };
 
 // fp32 path: one strided matrix product  C (+)= alpha * A.B  (used for the fp32 configuration).

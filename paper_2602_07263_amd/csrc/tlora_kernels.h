@@ -18,11 +18,12 @@ void launch_pack_adapters(const JobDev* jobs, int num_jobs, int d_in, int d_out,
 void launch_zero_fill(void* ptr, size_t bytes, hipStream_t st);
 
 // out_j[t, p] = sum_k act[t, k] * P_j[p, k]   (P_j = A_j^T packed, or B_j packed)
-// writes fp32 `S` (packed ragged layout) and bf16 `scale_j * S` into the per-tile K-extension matrices `Sx`.
+// writes the result as bf16 hi + lo planes (packed ragged layout, each job's rows zero padded to a multiple of
+// 32) and bf16 `scale_j * S` into the per-tile K-extension matrices `Sx`.
 // packed_is_atp: P_j = atp + atp_off_j (row stride K);  otherwise P_j = b_all + roff_j * K.
 void launch_shrink(const JobDev* jobs, const TileDev* tiles, const ShrinkUnit* units, int num_units,
                    int shrink_rows, const uint16_t* act, int K, const uint16_t* packed, bool packed_is_atp,
-                   float* S, uint16_t* Sx, hipStream_t st);
+                   uint16_t* S_hi, uint16_t* S_lo, uint16_t* Sx, hipStream_t st);
 
 // out[t, n] = sum_k act[t, k] * Wop[k, n] + sum_p Sx_tile[t, p] * Eop[roff_first + p, n]
 //   w_is_kn = true : W is [K, N] row-major (forward,  Eop = b_all [R + 32, N])
@@ -32,10 +33,11 @@ void launch_seg_gemm(bool w_is_kn, const TileDev* tiles, const uint16_t* act, co
                      hipStream_t st);
 
 // partial[u] = sum_{t in unit u} U_j[t, p] * V[t, c]   then   G_j = scale_j * sum_u partial[u]
-void launch_rank_grad(int mb, const JobDev* jobs, const GradUnit* units, int num_units, const float* U,
-                      const uint16_t* V, int D, float* partial, hipStream_t st);
-void launch_grad_reduce(int mb, const JobDev* jobs, const GradGroup* groups, int num_groups, const float* partial,
-                        int D, bool out_is_dA, hipStream_t st);
+// `units` holds only units of the given mb class (1, 2 or 4 blocks of 32 rank rows).
+void launch_rank_grad(int mb, const JobDev* jobs, const GradUnit* units, int num_units, const uint16_t* U_hi,
+                      const uint16_t* U_lo, const uint16_t* V, int D, float* partial, hipStream_t st);
+void launch_grad_reduce(const JobDev* jobs, const GradGroup* groups, int num_groups, const float* partial, int D,
+                        bool out_is_dA, hipStream_t st);
 
 // fp32 configuration: strided products on plain FMA units.
 void launch_f32_units(const F32Unit* units, const F32Tile* tiles, int num_tiles, hipStream_t st);

@@ -32,6 +32,19 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, v);
 }
 
+// Asynchronous 16-byte-per-lane global->LDS load issued as raw instructions: lane l's 16 bytes land at LDS
+// byte address `lds_base` + 16 l (lds_base wave-uniform; it travels in M0).  Unlike the compiler builtin this
+// is invisible to the compiler's bookkeeping of outstanding loads, so it never adds a wait of its own: the
+// kernel that uses it orders everything by hand (s_waitcnt vmcnt + barrier before the data is read, and a
+// full drain before the LDS is reused or the kernel ends).  A kernel must not mix it with the builtin, which
+// also keeps its LDS base in M0.
+__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory");
+}
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+  return __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)LDS_PTR(const uint8_t, p));
+}
+
 // ---------------------------------------------------------------------------------------------------
 // LDS tile layouts.
 //  "row tile": R rows x 64 bf16 (128 B per row), k contiguous.  The 16-byte chunk c of row r sits at
@@ -143,7 +156,8 @@ __global__ void __launch_bounds__(256) shrink_kernel(const JobDev* __restrict__ 
                                                      const ShrinkUnit* __restrict__ units,
                                                      const uint16_t* __restrict__ act, int K,
                                                      const uint16_t* __restrict__ packed, int packed_is_atp,
-                                                     float* __restrict__ S, uint16_t* __restrict__ Sx) {
+                                                     uint16_t* __restrict__ Shi, uint16_t* __restrict__ Slo,
+                                                     uint16_t* __restrict__ Sx) {
   constexpr int WM = ROWS / 32;          // waves along token rows
   constexpr int WN = 4 / WM;             // waves along rank columns
   constexpr int PW = kShrinkCols / WN;   // rank columns per wave
@@ -220,12 +234,19 @@ __global__ void __launch_bounds__(256) shrink_kernel(const JobDev* __restrict__ 
   }
 
   // lane: token row (lane % 32); registers: 4 consecutive rank columns per group g.
+  // Outputs: the intermediate as bf16 hi + lo planes (hi = bf16(x), lo = bf16(x - hi): ~16 mantissa bits for
+  // the dA / dB contractions) in the packed ragged layout, whose rows are padded with zeros to a multiple of
+  // kGradStep per job (the job's last unit writes them: its accumulators there are zero); and bf16
+  // scale_j * x in the row's slot of its GEMM tile's K-extension operand.
   const int r = wm * 32 + (lane & 31);
-  if (r < u.nrows) {
+  const int jrow = u.t0 - jb.row0 + r;                                        // row inside the job
+  const bool last_unit = u.t0 + u.nrows == jb.row1;
+  const int jrows_padded = (jb.row1 - jb.row0 + kGradStep - 1) / kGradStep * kGradStep;
+  if (r < u.nrows || (last_unit && jrow < jrows_padded)) {
+    const bool live = r < u.nrows;
     const int t = u.t0 + r;
-    const int64_t rowbase = jb.soff + (int64_t)(t - jb.row0) * jb.rpad;
-    // the row's slot in its tile's K-extension matrix: [256, kext], this job at columns roff - roff_first
-    const TileDev td = tiles[t >> 8];
+    const int64_t rowbase = jb.soff + (int64_t)jrow * jb.rpad;
+    const TileDev td = tiles[min(t, jb.row1 - 1) >> 8];
     uint16_t* const xrow = Sx + td.aoff + (int64_t)(t & 255) * td.kext + (jb.roff - td.roff_first);
 #pragma unroll
     for (int i = 0; i < NPB; ++i)
@@ -233,25 +254,31 @@ __global__ void __launch_bounds__(256) shrink_kernel(const JobDev* __restrict__ 
       for (int g = 0; g < 4; ++g) {
         const int p = p0 + wn * PW + i * 32 + g * 8 + (lane >> 5) * 4;
         if (p < jb.rpad) {
-          const float v0 = acc[i][g * 4 + 0], v1 = acc[i][g * 4 + 1], v2 = acc[i][g * 4 + 2], v3 = acc[i][g * 4 + 3];
-          *reinterpret_cast<float4*>(S + rowbase + p) = make_float4(v0, v1, v2, v3);
-          u32x2 b = {pack_bf16x2(jb.scale * v0, jb.scale * v1), pack_bf16x2(jb.scale * v2, jb.scale * v3)};
-          *reinterpret_cast<u32x2*>(xrow + p) = b;
+          const float v[4] = {acc[i][g * 4 + 0], acc[i][g * 4 + 1], acc[i][g * 4 + 2], acc[i][g * 4 + 3]};
+          float lo[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) lo[e] = v[e] - (float)(__bf16)v[e];
+          *reinterpret_cast<u32x2*>(Shi + rowbase + p) = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+          *reinterpret_cast<u32x2*>(Slo + rowbase + p) = u32x2{pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3])};
+          if (live) {
+            u32x2 b = {pack_bf16x2(jb.scale * v[0], jb.scale * v[1]), pack_bf16x2(jb.scale * v[2], jb.scale * v[3])};
+            *reinterpret_cast<u32x2*>(xrow + p) = b;
+          }
         }
       }
   }
 }
 
 void launch_shrink(const JobDev* jobs, const TileDev* tiles, const ShrinkUnit* units, int num_units, int shrink_rows,
-                   const uint16_t* act, int K, const uint16_t* packed, bool packed_is_atp, float* S, uint16_t* Sx,
-                   hipStream_t st) {
+                   const uint16_t* act, int K, const uint16_t* packed, bool packed_is_atp, uint16_t* S_hi,
+                   uint16_t* S_lo, uint16_t* Sx, hipStream_t st) {
   if (num_units == 0) return;
   if (shrink_rows == 128)
     hipLaunchKernelGGL(shrink_kernel<128>, dim3(num_units), dim3(256), 0, st, jobs, tiles, units, act, K, packed,
-                       packed_is_atp ? 1 : 0, S, Sx);
+                       packed_is_atp ? 1 : 0, S_hi, S_lo, Sx);
   else
     hipLaunchKernelGGL(shrink_kernel<64>, dim3(num_units), dim3(256), 0, st, jobs, tiles, units, act, K, packed,
-                       packed_is_atp ? 1 : 0, S, Sx);
+                       packed_is_atp ? 1 : 0, S_hi, S_lo, Sx);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -516,149 +543,210 @@ void launch_seg_gemm(bool w_is_kn, const TileDev* tiles, const uint16_t* act, co
 
 // ---------------------------------------------------------------------------------------------------
 // dA / dB:  G_j[p, c] = scale_j * sum_{t in seg j} U_j[t, p] * V[t, c]
-//   dB_j: U = S_j (fp32, packed), V = dY;   dA_j^T: U = dS_j, V = X.
-// The streamed operand V never touches LDS: a lane loads 8 token rows x 8 columns (16 B each),
-// transposes the 8x8 block in registers and feeds column q of it to the q-th of 8 MFMAs, whose
-// output column (lane % 32) therefore stands for feature 8*(lane % 32) + q.  U is fp32 and is split
-// into bf16 hi + lo parts (two MFMAs) so the result keeps ~16 mantissa bits of U.
+//   dB_j: U = S_j, V = dY;   dA_j^T: U = dS_j, V = X.   U comes as two bf16 planes hi + lo (two MFMAs keep ~16
+//   mantissa bits of the fp32 intermediate), packed [T_j padded to 32, rpad_j] with zero pad rows.
+// The contraction runs over tokens, the row index of both operands, so both are staged in LDS as they lie
+// in memory (token-major) and read through the transposing LDS read.  One workgroup (4 waves) owns
+// kGradCols = 256 feature columns x 32*MB rank rows for a chunk of tokens; each wave takes 64 columns, so V
+// is read once for all rank rows.  Per step of 32 tokens a stage holds the V tile (32 x 256, 16 KB) and
+// the two U tiles (32 x 32*MB); four stages are filled by asynchronous global->LDS loads three steps
+// ahead.  V rows beyond the chunk are clamped to its last row: they meet the zero pad rows of U.
 // ---------------------------------------------------------------------------------------------------
+__device__ __forceinline__ bf16x8 frag_tr_u(const uint8_t* plane, int pitch, int sw_shift, int sw_mask, int nb, int kk,
+                                            int lane) {
+  const int s = lane & 15;
+  const int n = nb + ((lane >> 4) & 1) * 16 + (s & 3) * 4;     // rank column this lane addresses
+  const int k = kk * 16 + (lane >> 5) * 8 + (s >> 2);          // k and k + 4 share the swizzle term
+  const int c = (n >> 3) ^ (((k >> sw_shift) & sw_mask) << 2);
+  const uint8_t* a = plane + k * pitch + (c << 4) + (n & 7) * 2;
+  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a));
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a + 4 * pitch));
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
 template <int MB>
 __global__ void __launch_bounds__(256) rank_grad_kernel(const JobDev* __restrict__ jobs,
                                                         const GradUnit* __restrict__ units,
-                                                        const float* __restrict__ U,
+                                                        const uint16_t* __restrict__ Uhi,
+                                                        const uint16_t* __restrict__ Ulo,
                                                         const uint16_t* __restrict__ V, int D,
                                                         float* __restrict__ partial) {
-  __shared__ float red[MB * 8 * 16 * 64];
+  constexpr int RP = kGradRanks * MB;                       // rank rows of this unit
+  constexpr int UPITCH = 2 * RP;                            // bytes per token row of a U tile: 64, 128, 256
+  // 16-byte chunk c of token row k sits at slot c ^ (sw(k) << 2) so that the four rows one transposing read
+  // touches start in four distinct 64-byte bank groups: sw = 0 (64 B rows), (k >> 1) & 1 (128 B), k & 3 (256 B)
+  constexpr int SW_SHIFT = MB == 2 ? 1 : 0;
+  constexpr int SW_MASK = MB == 1 ? 0 : MB == 2 ? 1 : 3;
+  constexpr int UPLANE = kGradStep * UPITCH;                // 2 KB * MB
+  constexpr int VTILE = kGradStep * kGradCols * 2;          // 16 KB
+  constexpr int LOADS = 4 + MB;                             // asynchronous loads per wave per step
+  __shared__ __attribute__((aligned(1024))) uint8_t g0[VTILE];
+  __shared__ __attribute__((aligned(1024))) uint8_t g1[VTILE];
+  __shared__ __attribute__((aligned(1024))) uint8_t g2[VTILE];
+  __shared__ __attribute__((aligned(1024))) uint8_t g3[VTILE];
+  __shared__ __attribute__((aligned(1024))) uint8_t h0[2 * UPLANE];
+  __shared__ __attribute__((aligned(1024))) uint8_t h1[2 * UPLANE];
+  __shared__ __attribute__((aligned(1024))) uint8_t h2[2 * UPLANE];
+  __shared__ __attribute__((aligned(1024))) uint8_t h3[2 * UPLANE];
+
   const GradUnit u = units[blockIdx.x];
   const JobDev jb = jobs[u.job];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int pbase = u.pb * (kGradRanks * MB);
-  const int nmb = min(MB, (jb.rpad - pbase + kGradRanks - 1) / kGradRanks);   // rank blocks with any live row
-  const int col = u.cb * kGradCols + (lane & 31) * 8;
-  const bool col_ok = col < D;                                                // D % 8 == 0
-  const float* Uj = U + jb.soff;
+  const int col0 = u.cb * kGradCols;
+  const int pbase = u.pb * RP;
+  const int nsteps = (u.t1 - u.t0 + kGradStep - 1) / kGradStep;
 
-  f32x16 acc[MB][8];
+  f32x16 acc[MB][2];
 #pragma unroll
   for (int m = 0; m < MB; ++m)
 #pragma unroll
-    for (int q = 0; q < 8; ++q)
+    for (int n = 0; n < 2; ++n)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[m][q][e] = 0.f;
+      for (int e = 0; e < 16; ++e) acc[m][n][e] = 0.f;
 
-  for (int tg = u.t0 + wave * 16; tg < u.t1; tg += 64) {
-    const int tb = tg + (lane >> 5) * 8;
-    u32x4 v[8];
+  // V tile [32 tokens][512 B], same swizzle as the GEMM's weight tile: lane -> (token k, chunk c)
+  int vk[4], vcol[4];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int t = tb + e;
-      v[e] = (t < u.t1 && col_ok) ? ldg16(V + (int64_t)t * D + col) : u32x4{0, 0, 0, 0};
+  for (int i = 0; i < 4; ++i) {
+    const int p = (wave * 4 + i) * 64 + lane;
+    vk[i] = p >> 5;
+    const int c = (p & 31) ^ ((vk[i] & 3) << 2);
+    vcol[i] = min(col0 + c * 8, D - 8);               // columns beyond D are clamped; their results are not stored
+  }
+  // U tiles: hi plane then lo plane, 2 * MB KB each = 2 * MB wave-loads; wave w issues load q = w * MB + i of the
+  // 4 * MB.  Lanes whose rank chunk lies beyond rpad fetch the job's last chunk instead (no branch around an
+  // asynchronous load): what they deliver only feeds rank rows >= rpad of the tile, which are never stored.
+  const uint16_t* usrc[MB];
+  int udst[MB];
+#pragma unroll
+  for (int i = 0; i < MB; ++i) {
+    const int q = wave * MB + i;                      // 0 .. 4 MB - 1
+    const int plane = q / (2 * MB), within = q % (2 * MB);
+    const int slot = within * 64 + lane;              // 16-byte slot inside the plane
+    const int k = slot / (RP / 8), cphys = slot % (RP / 8);
+    const int c = cphys ^ (((k >> SW_SHIFT) & SW_MASK) << 2);
+    const int p = min(pbase + c * 8, jb.rpad - 8);
+    usrc[i] = (plane ? Ulo : Uhi) + jb.soff + (int64_t)(u.t0 - jb.row0 + k) * jb.rpad + p;
+    udst[i] = plane * UPLANE + within * 1024;
+  }
+  int f_step = 0;                                     // next step to fetch
+  auto issue = [&](uint8_t* S, uint8_t* H) {
+    const int st = min(f_step, nsteps - 1);           // trailing issues re-load the last step (uniform load count)
+    const uint32_t sbase = lds_addr(S + wave * 4096), hbase = lds_addr(H);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int t = min(u.t0 + st * kGradStep + vk[i], u.t1 - 1);
+      dma16(V + (int64_t)t * D + vcol[i], sbase + i * 1024);
     }
-    // 8x8 transpose of 16-bit elements: b[q] = tokens 0..7 of column q
-    bf16x8 b[8];
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      u32x4 o;
+    for (int i = 0; i < MB; ++i)
+      dma16(usrc[i] + (int64_t)st * kGradStep * jb.rpad, hbase + __builtin_amdgcn_readfirstlane(udst[i]));
+    ++f_step;
+  };
+  auto compute = [&](const uint8_t* S, const uint8_t* H) {
 #pragma unroll
-      for (int d = 0; d < 4; ++d)
-        o[d] = __builtin_amdgcn_perm(v[2 * d + 1][q >> 1], v[2 * d][q >> 1], (q & 1) ? 0x07060302u : 0x05040100u);
-      b[q] = as_bf16x8(o);
-    }
+    for (int kk = 0; kk < 2; ++kk) {
+      bf16x8 vf[2];
 #pragma unroll
-    for (int m = 0; m < MB; ++m) {
-      if (m < nmb) {
-        const int p = pbase + m * kGradRanks + (lane & 31);
-        bf16x8 hi, lo;
+      for (int n = 0; n < 2; ++n) vf[n] = frag_kn_tile(S, wave * 64 + n * 32, kk, lane);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const int t = tb + e;
-          const float x = (t < u.t1 && p < jb.rpad) ? Uj[(int64_t)(t - jb.row0) * jb.rpad + p] : 0.f;
-          const __bf16 h = (__bf16)x;
-          hi[e] = h;
-          lo[e] = (__bf16)(x - (float)h);
-        }
+      for (int m = 0; m < MB; ++m) {
+        const bf16x8 hi = frag_tr_u(H, UPITCH, SW_SHIFT, SW_MASK, m * 32, kk, lane);
+        const bf16x8 lo = frag_tr_u(H + UPLANE, UPITCH, SW_SHIFT, SW_MASK, m * 32, kk, lane);
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-          acc[m][q] = mfma32(hi, b[q], acc[m][q]);
-          acc[m][q] = mfma32(lo, b[q], acc[m][q]);
+        for (int n = 0; n < 2; ++n) {
+          acc[m][n] = mfma32(hi, vf[n], acc[m][n]);
+          acc[m][n] = mfma32(lo, vf[n], acc[m][n]);
         }
       }
     }
+  };
+  auto landed = [&]() {
+    // loads complete in order: all but those of the two youngest steps have landed
+    if (MB == 1) __builtin_amdgcn_s_waitcnt(0x007A);        // vmcnt(10) lgkmcnt(0)
+    else if (MB == 2) __builtin_amdgcn_s_waitcnt(0x007C);   // vmcnt(12)
+    else __builtin_amdgcn_s_waitcnt(0x4070);                // vmcnt(16)
+    __builtin_amdgcn_s_barrier();
+  };
+  static_assert(2 * LOADS == (MB == 1 ? 10 : MB == 2 ? 12 : 16), "wait counts above");
+  if (nsteps > 0) {
+    issue(g0, h0);
+    issue(g1, h1);
+    issue(g2, h2);
+    int kt = 0;
+    for (; kt + 4 <= nsteps; kt += 4) {
+      landed();  issue(g3, h3);  compute(g0, h0);
+      landed();  issue(g0, h0);  compute(g1, h1);
+      landed();  issue(g1, h1);  compute(g2, h2);
+      landed();  issue(g2, h2);  compute(g3, h3);
+    }
+    if (kt < nsteps)     { landed();  issue(g3, h3);  compute(g0, h0); }
+    if (kt + 1 < nsteps) { landed();  issue(g0, h0);  compute(g1, h1); }
+    if (kt + 2 < nsteps) { landed();  issue(g1, h1);  compute(g2, h2); }
+    __builtin_amdgcn_s_waitcnt(0x0070);   // drain the trailing loads before the workgroup's LDS is released
   }
 
-  // fixed-order sum of the four waves' accumulators: wave 0 += wave 1, += wave 2, += wave 3
-  for (int src = 1; src < 4; ++src) {
-    if (wave == src) {
+  // partial tile [RP][256]: lane holds column (lane % 32) of its n-block and 16 rank rows per m-block
+  float* out = partial + u.part_off;
 #pragma unroll
-      for (int m = 0; m < MB; ++m)
+  for (int m = 0; m < MB; ++m)
 #pragma unroll
-        for (int q = 0; q < 8; ++q)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) red[((m * 8 + q) * 16 + e) * 64 + lane] = acc[m][q][e];
-    }
-    __syncthreads();
-    if (wave == 0) {
-#pragma unroll
-      for (int m = 0; m < MB; ++m)
-#pragma unroll
-        for (int q = 0; q < 8; ++q)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) acc[m][q][e] += red[((m * 8 + q) * 16 + e) * 64 + lane];
-    }
-    __syncthreads();
-  }
-  if (wave == 0) {
-    float* out = partial + (int64_t)blockIdx.x * (MB * kGradRanks * kGradCols);
-#pragma unroll
-    for (int m = 0; m < MB; ++m)
+    for (int n = 0; n < 2; ++n)
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const int pl = m * kGradRanks + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-        float* o = out + pl * kGradCols + (lane & 31) * 8;
-        *reinterpret_cast<float4*>(o) = make_float4(acc[m][0][e], acc[m][1][e], acc[m][2][e], acc[m][3][e]);
-        *reinterpret_cast<float4*>(o + 4) = make_float4(acc[m][4][e], acc[m][5][e], acc[m][6][e], acc[m][7][e]);
+        const int pl = m * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+        out[pl * kGradCols + wave * 64 + n * 32 + (lane & 31)] = acc[m][n][e];
       }
-  }
 }
 
-void launch_rank_grad(int mb, const JobDev* jobs, const GradUnit* units, int num_units, const float* U,
-                      const uint16_t* V, int D, float* partial, hipStream_t st) {
+void launch_rank_grad(int mb, const JobDev* jobs, const GradUnit* units, int num_units, const uint16_t* U_hi,
+                      const uint16_t* U_lo, const uint16_t* V, int D, float* partial, hipStream_t st) {
   if (num_units == 0) return;
   if (mb == 1)
-    hipLaunchKernelGGL(rank_grad_kernel<1>, dim3(num_units), dim3(256), 0, st, jobs, units, U, V, D, partial);
+    hipLaunchKernelGGL(rank_grad_kernel<1>, dim3(num_units), dim3(256), 0, st, jobs, units, U_hi, U_lo, V, D, partial);
+  else if (mb == 2)
+    hipLaunchKernelGGL(rank_grad_kernel<2>, dim3(num_units), dim3(256), 0, st, jobs, units, U_hi, U_lo, V, D, partial);
   else
-    hipLaunchKernelGGL(rank_grad_kernel<2>, dim3(num_units), dim3(256), 0, st, jobs, units, U, V, D, partial);
+    hipLaunchKernelGGL(rank_grad_kernel<4>, dim3(num_units), dim3(256), 0, st, jobs, units, U_hi, U_lo, V, D, partial);
 }
 
 // Sum the partial tiles of one output tile in unit order, scale, and store (dB_j row-major [r, D];
-// dA_j is the transpose of the computed tile: [D, r]).
+// dA_j is the transpose of the computed tile: [D, r]).  One workgroup = 4 rank rows x 256 columns of a group.
 __global__ void __launch_bounds__(256) grad_reduce_kernel(const JobDev* __restrict__ jobs,
                                                           const GradGroup* __restrict__ groups,
-                                                          const float* __restrict__ partial, int D, int mb,
-                                                          int out_is_dA) {
+                                                          const float* __restrict__ partial, int D, int out_is_dA) {
   const GradGroup g = groups[blockIdx.x];
   const JobDev jb = jobs[g.job];
   const int c = g.cb * kGradCols + threadIdx.x;
-  if (c >= D) return;
-  const int tile_rows = mb * kGradRanks;
+  const int tile_rows = g.mb * kGradRanks;
+  const int pl0 = blockIdx.y * 4;
+  if (c >= D || pl0 >= tile_rows || g.pb * tile_rows + pl0 >= jb.rank) return;
   const int64_t tile_elems = (int64_t)tile_rows * kGradCols;
+  const float* src = partial + g.part_off + (int64_t)pl0 * kGradCols + threadIdx.x;
+  float s[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int k = 0; k < g.nunits; ++k) {          // fixed order: bit-reproducible
+#pragma unroll
+    for (int i = 0; i < 4; ++i) s[i] += src[k * tile_elems + i * kGradCols];
+  }
   float* dst = static_cast<float*>(out_is_dA ? jb.dA : jb.dB);
-  for (int pl = 0; pl < tile_rows; ++pl) {
-    const int p = g.pb * tile_rows + pl;
-    if (p >= jb.rank) break;
-    float s = 0.f;
-    for (int k = 0; k < g.nunits; ++k) s += partial[(int64_t)(g.unit0 + k) * tile_elems + pl * kGradCols + threadIdx.x];
-    s *= jb.scale;
-    if (out_is_dA) dst[(int64_t)c * jb.rank + p] = s;
-    else           dst[(int64_t)p * D + c] = s;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int p = g.pb * tile_rows + pl0 + i;
+    if (p < jb.rank) {
+      const float v = s[i] * jb.scale;
+      if (out_is_dA) dst[(int64_t)c * jb.rank + p] = v;
+      else           dst[(int64_t)p * D + c] = v;
+    }
   }
 }
 
-void launch_grad_reduce(int mb, const JobDev* jobs, const GradGroup* groups, int num_groups, const float* partial,
-                        int D, bool out_is_dA, hipStream_t st) {
+void launch_grad_reduce(const JobDev* jobs, const GradGroup* groups, int num_groups, const float* partial, int D,
+                        bool out_is_dA, hipStream_t st) {
   if (num_groups == 0) return;
-  hipLaunchKernelGGL(grad_reduce_kernel, dim3(num_groups), dim3(256), 0, st, jobs, groups, partial, D, mb,
-                     out_is_dA ? 1 : 0);
+  hipLaunchKernelGGL(grad_reduce_kernel, dim3(num_groups, 4 * kGradRanks / 4), dim3(256), 0, st, jobs, groups, partial,
+                     D, out_is_dA ? 1 : 0);
 }
 
 // ---------------------------------------------------------------------------------------------------

@@ -92,7 +92,7 @@ def test_plan_handles_empty_segments_and_rank_zero():
     off = np.concatenate([[0], np.cumsum(tokens)])
     plan = tlora.tlora_plan_dump(prob)
     assert plan["rpad"] == [8, 0, 16, 8]
-    assert plan["soff"] == orc.packed_offsets(ranks, off) == [0, 0, 0, 0, 40]
+    assert plan["soff"] == orc.packed_offsets(ranks, off) == [0, 0, 0, 0, 256]
     assert plan["tiles"] == orc.row_tiles(off, plan["tile_rows"])
     # all-empty batch: no tiles
     prob0, _k = _problem([4, 4], [0, 0])
