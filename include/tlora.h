@@ -110,6 +110,7 @@ int tlora_plan_dump(const tlora_problem_t* p, int32_t* rpad, int64_t* soff, int3
 
 /* Tuning knobs (process-wide, for experiments and for the tiling-independence tests).
  *   "shrink_rows"  : token rows per work unit of the shrink kernels        (64 | 128)
+ *   "shrink_stages": LDS stages of the streaming shrink kernel             (4 | 8)
  *   "grad_tokens"  : minimum tokens per work unit of the dA / dB kernels   (multiple of 64)
  * Returns TLORA_EINVAL for an unknown name or an illegal value. */
 int tlora_set_option(const char* name, int64_t value);

@@ -16,7 +16,8 @@ namespace tlora {
 namespace {
 
 struct Options {
-  int shrink_rows = 64;
+  int shrink_rows = 128;
+  int shrink_stages = 4;
   int grad_tokens = 256;
 };
 Options g_opt;
@@ -30,10 +31,10 @@ struct Plan {
   int max_rpad = 0;
   std::vector<JobDev> jobs;
   std::vector<TileDev> tile_jobs;
-  std::vector<ShrinkUnit> shrink_units;
+  std::vector<ShrinkUnit> shrink_units;                 // generic kernel: 64 rows x 64 rank columns
+  std::vector<ShrinkUnit> stream_units;                 // streaming kernel: shrink_rows x 128 rank columns
   std::vector<GradUnit> gradB_units, gradA_units;      // dB: columns over d_out;  dA: columns over d_in;
-                                                        // sorted by rank-block class mb = 1, 2, 4
-  int gradB_class_begin[4] = {0, 0, 0, 0}, gradA_class_begin[4] = {0, 0, 0, 0};
+
   int64_t gradB_partial = 0, gradA_partial = 0;         // floats of partial tiles
   std::vector<GradGroup> gradB_groups, gradA_groups;
   int64_t s_elems = 0;                                  // elements of the packed S (= dS) buffer
@@ -45,7 +46,7 @@ struct Plan {
          off_partial = 0, total = 0;
   size_t tables_bytes = 0;
   // offsets of each table inside the table blob
-  size_t tb_jobs = 0, tb_tiles = 0, tb_shrink = 0, tb_gBu = 0, tb_gBg = 0, tb_gAu = 0, tb_gAg = 0, tb_f32 = 0;
+  size_t tb_jobs = 0, tb_tiles = 0, tb_shrink = 0, tb_stream = 0, tb_gBu = 0, tb_gBg = 0, tb_gAu = 0, tb_gAg = 0, tb_f32 = 0;
   size_t f32_reserved = 0;
 };
 
@@ -64,22 +65,30 @@ int validate(const tlora_problem_t* p) {
 }
 
 // Work units of the dA / dB token reductions (rank-aware nano-batches of one job's tokens).  A job's rank
-// rows are cut into blocks of 32*mb with mb = 1, 2 or 4 chosen from its padded rank; a token chunk streams
-// chunk * 256 * 2 bytes of the activation and leaves a partial tile of 32*mb * 256 * 4 bytes that is written
-// and read once more, so the default chunk is 32 * (32*mb) tokens (partial traffic <= ~12 %).  If that gives
-// too few units to fill the GPU the chunks are shortened (not below `grad_tokens`).
+// rows are cut into blocks of 128, of which a unit multiplies only the live 32-row sub-blocks.  A token
+// chunk streams chunk * 256 * 2 bytes of the activation and leaves a partial tile of live_rows * 256 * 4
+// bytes that is written and read once more, so the default chunk is 32 * live_rows tokens (partial traffic
+// <= ~12 %).  If that gives too few units to fill the GPU the chunks are shortened (not below `grad_tokens`).
+// Units are issued longest first.
 void build_grad_units(const Plan& pl, int D, std::vector<GradUnit>& units, std::vector<GradGroup>& groups,
-                      int class_begin[4], int64_t& partial_floats) {
+                      int64_t& partial_floats) {
   const int ncb = (D + kGradCols - 1) / kGradCols;
-  auto class_mb = [](int rpad) { return rpad <= 32 ? 1 : rpad <= 64 ? 2 : 4; };
+  const int pb_rows = kGradMaxBlocks * kGradRanks;
+  auto live_blocks = [&](const JobDev& jb, int pb) {
+    return std::min(kGradMaxBlocks, (jb.rpad - pb * pb_rows + kGradRanks - 1) / kGradRanks);
+  };
+  auto chunk_of = [&](int live, double shrink) {
+    int chunk = std::max(g_opt.grad_tokens, (int)(32 * kGradRanks * live * shrink));
+    return (chunk + kGradStep - 1) / kGradStep * kGradStep;
+  };
   auto count_units = [&](double shrink) {
     int64_t n = 0;
     for (const JobDev& jb : pl.jobs) {
       if (jb.rank == 0 || jb.row1 == jb.row0) continue;
-      const int mb = class_mb(jb.rpad), prow = kGradRanks * mb;
-      int chunk = std::max(g_opt.grad_tokens, (int)(32 * prow * shrink));
-      chunk = (chunk + kGradStep - 1) / kGradStep * kGradStep;
-      n += (int64_t)((jb.row1 - jb.row0 + chunk - 1) / chunk) * ncb * ((jb.rpad + prow - 1) / prow);
+      for (int pb = 0; pb * pb_rows < jb.rpad; ++pb) {
+        const int chunk = chunk_of(live_blocks(jb, pb), shrink);
+        n += (int64_t)((jb.row1 - jb.row0 + chunk - 1) / chunk) * ncb;
+      }
     }
     return n;
   };
@@ -87,34 +96,33 @@ void build_grad_units(const Plan& pl, int D, std::vector<GradUnit>& units, std::
   const int64_t want = 1024;
   while (shrink > 1.0 / 64 && count_units(shrink) < want) shrink *= 0.5;
   partial_floats = 0;
-  const int classes[3] = {1, 2, 4};
-  for (int ci = 0; ci < 3; ++ci) {
-    class_begin[ci] = (int)units.size();
-    for (int j = 0; j < pl.J; ++j) {
-      const JobDev& jb = pl.jobs[j];
-      if (jb.rank == 0 || class_mb(jb.rpad) != classes[ci]) continue;
-      const int mb = classes[ci], prow = kGradRanks * mb;
-      const int Tj = jb.row1 - jb.row0;
-      int chunk = std::max(g_opt.grad_tokens, (int)(32 * prow * shrink));
-      chunk = (chunk + kGradStep - 1) / kGradStep * kGradStep;
+  for (int j = 0; j < pl.J; ++j) {
+    const JobDev& jb = pl.jobs[j];
+    if (jb.rank == 0) continue;
+    const int Tj = jb.row1 - jb.row0;
+    for (int pb = 0; pb * pb_rows < jb.rpad; ++pb) {
+      const int mb = live_blocks(jb, pb);
+      const int chunk = chunk_of(mb, shrink);
       const int nchunks = Tj > 0 ? (Tj + chunk - 1) / chunk : 0;
-      const int npb = (jb.rpad + prow - 1) / prow;
-      for (int pb = 0; pb < npb; ++pb)
-        for (int cb = 0; cb < ncb; ++cb) {
-          GradGroup g{};
-          g.job = j;  g.cb = cb;  g.pb = pb;  g.mb = mb;  g.nunits = nchunks;  g.part_off = partial_floats;
-          for (int c = 0; c < nchunks; ++c) {
-            GradUnit u{};
-            u.job = j;  u.t0 = jb.row0 + c * chunk;  u.t1 = std::min(jb.row1, u.t0 + chunk);  u.cb = cb;  u.pb = pb;
-            u.mb = mb;  u.part_off = partial_floats;
-            partial_floats += (int64_t)prow * kGradCols;
-            units.push_back(u);
-          }
-          groups.push_back(g);
+      for (int cb = 0; cb < ncb; ++cb) {
+        GradGroup g{};
+        g.job = j;  g.cb = cb;  g.pb = pb;  g.mb = mb;  g.nunits = nchunks;  g.part_off = partial_floats;
+        for (int c = 0; c < nchunks; ++c) {
+          GradUnit u{};
+          u.job = j;  u.t0 = jb.row0 + c * chunk;  u.t1 = std::min(jb.row1, u.t0 + chunk);  u.cb = cb;  u.pb = pb;
+          u.mb = mb;  u.part_off = partial_floats;
+          partial_floats += (int64_t)mb * kGradRanks * kGradCols;
+          units.push_back(u);
         }
+        groups.push_back(g);
+      }
     }
   }
-  class_begin[3] = (int)units.size();
+  // longest (then heaviest) first: the tail of the launch is made of the short units
+  std::stable_sort(units.begin(), units.end(), [](const GradUnit& a, const GradUnit& b) {
+    const int64_t ca = (int64_t)(a.t1 - a.t0) * (4 + a.mb), cb = (int64_t)(b.t1 - b.t0) * (4 + b.mb);
+    return ca > cb;
+  });
 }
 
 int build_plan(const tlora_problem_t* p, Plan& pl) {
@@ -168,15 +176,22 @@ int build_plan(const tlora_problem_t* p, Plan& pl) {
       const JobDev& jb = pl.jobs[j];
       if (jb.rpad == 0) continue;
       const int npb = (jb.rpad + kShrinkCols - 1) / kShrinkCols;
-      for (int t0 = jb.row0; t0 < jb.row1; t0 += g_opt.shrink_rows)
+      for (int t0 = jb.row0; t0 < jb.row1; t0 += 64)
         for (int pb = 0; pb < npb; ++pb) {
           ShrinkUnit u;
-          u.job = j;  u.t0 = t0;  u.nrows = std::min(g_opt.shrink_rows, jb.row1 - t0);  u.pb = pb;
+          u.job = j;  u.t0 = t0;  u.nrows = std::min(64, jb.row1 - t0);  u.pb = pb;
           pl.shrink_units.push_back(u);
         }
+      const int npb2 = (jb.rpad + 127) / 128;
+      for (int t0 = jb.row0; t0 < jb.row1; t0 += g_opt.shrink_rows)
+        for (int pb = 0; pb < npb2; ++pb) {
+          ShrinkUnit u;
+          u.job = j;  u.t0 = t0;  u.nrows = std::min(g_opt.shrink_rows, jb.row1 - t0);  u.pb = pb;
+          pl.stream_units.push_back(u);
+        }
     }
-    build_grad_units(pl, pl.d_out, pl.gradB_units, pl.gradB_groups, pl.gradB_class_begin, pl.gradB_partial);
-    build_grad_units(pl, pl.d_in, pl.gradA_units, pl.gradA_groups, pl.gradA_class_begin, pl.gradA_partial);
+    build_grad_units(pl, pl.d_out, pl.gradB_units, pl.gradB_groups, pl.gradB_partial);
+    build_grad_units(pl, pl.d_in, pl.gradA_units, pl.gradA_groups, pl.gradA_partial);
   }
 
   // table blob
@@ -185,6 +200,7 @@ int build_plan(const tlora_problem_t* p, Plan& pl) {
   pl.tb_jobs = place(sizeof(JobDev) * pl.jobs.size());
   pl.tb_tiles = place(sizeof(TileDev) * pl.tile_jobs.size());
   pl.tb_shrink = place(sizeof(ShrinkUnit) * pl.shrink_units.size());
+  pl.tb_stream = place(sizeof(ShrinkUnit) * pl.stream_units.size());
   pl.tb_gBu = place(sizeof(GradUnit) * pl.gradB_units.size());
   pl.tb_gBg = place(sizeof(GradGroup) * pl.gradB_groups.size());
   pl.tb_gAu = place(sizeof(GradUnit) * pl.gradA_units.size());
@@ -318,6 +334,18 @@ int prof_drain() {
   return TLORA_OK;
 }
 
+// S_j = X_j.A_j (or dS_j = dY_j.B_j^T): streaming kernel when the contraction length allows, else generic
+void run_shrink(const Plan& pl, const uint8_t* tb, const JobDev* jobs, const TileDev* tiles, const uint16_t* act, int K,
+                const uint16_t* packed, bool packed_is_atp, uint16_t* hi, uint16_t* lo, uint16_t* Sx, hipStream_t st) {
+  if (K % 32 == 0)
+    launch_shrink_stream(jobs, tiles, reinterpret_cast<const ShrinkUnit*>(tb + pl.tb_stream),
+                         (int)pl.stream_units.size(), g_opt.shrink_rows, g_opt.shrink_stages, act, K, packed, packed_is_atp,
+                         hi, lo, Sx, st);
+  else
+    launch_shrink(jobs, tiles, reinterpret_cast<const ShrinkUnit*>(tb + pl.tb_shrink), (int)pl.shrink_units.size(), 64,
+                  act, K, packed, packed_is_atp, hi, lo, Sx, st);
+}
+
 int check_arch() {
   static int cached = 1;   // 1 = unknown
   if (cached != 1) return cached;
@@ -341,6 +369,7 @@ std::vector<uint8_t> make_blob(const Plan& pl) {
   put(blob, pl.tb_jobs, pl.jobs);
   put(blob, pl.tb_tiles, pl.tile_jobs);
   put(blob, pl.tb_shrink, pl.shrink_units);
+  put(blob, pl.tb_stream, pl.stream_units);
   put(blob, pl.tb_gBu, pl.gradB_units);
   put(blob, pl.tb_gBg, pl.gradB_groups);
   put(blob, pl.tb_gAu, pl.gradA_units);
@@ -480,9 +509,8 @@ int tlora_fwd(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_byte
   }
   {
     Timed t(TLORA_K_SHRINK, st);
-    launch_shrink(jobs, tiles, reinterpret_cast<const ShrinkUnit*>(tb + pl.tb_shrink), (int)pl.shrink_units.size(),
-                  g_opt.shrink_rows, static_cast<const uint16_t*>(p->X), pl.d_in, atp, true,
-                  reinterpret_cast<uint16_t*>(ws + pl.off_Shi), reinterpret_cast<uint16_t*>(ws + pl.off_Slo), Sx, st);
+    run_shrink(pl, tb, jobs, tiles, static_cast<const uint16_t*>(p->X), pl.d_in, atp, true,
+               reinterpret_cast<uint16_t*>(ws + pl.off_Shi), reinterpret_cast<uint16_t*>(ws + pl.off_Slo), Sx, st);
   }
   Timed tg(TLORA_K_GEMM_FWD, st);
   launch_seg_gemm(true, tiles, static_cast<const uint16_t*>(p->X), static_cast<const uint16_t*>(p->W), Sx, bp,
@@ -578,7 +606,6 @@ int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* d
   uint16_t* ap = reinterpret_cast<uint16_t*>(ws + pl.off_ap);
   uint16_t* bp = reinterpret_cast<uint16_t*>(ws + pl.off_bp);
   float* partial = reinterpret_cast<float*>(ws + pl.off_partial);
-  const ShrinkUnit* su = reinterpret_cast<const ShrinkUnit*>(tb + pl.tb_shrink);
   const TileDev* tiles = reinterpret_cast<const TileDev*>(tb + pl.tb_tiles);
   const uint16_t* Xb = static_cast<const uint16_t*>(p->X);
   const uint16_t* dYb = static_cast<const uint16_t*>(dY);
@@ -595,13 +622,11 @@ int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* d
   if (pl.T > 0) {
     if (redo_S) {
       Timed t(TLORA_K_SHRINK, st);
-      launch_shrink(jobs, tiles, su, (int)pl.shrink_units.size(), g_opt.shrink_rows, Xb, pl.d_in, atp, true, Shi, Slo, Sx,
-                    st);
+      run_shrink(pl, tb, jobs, tiles, Xb, pl.d_in, atp, true, Shi, Slo, Sx, st);
     }
     {
       Timed t(TLORA_K_SHRINK, st);
-      launch_shrink(jobs, tiles, su, (int)pl.shrink_units.size(), g_opt.shrink_rows, dYb, pl.d_out, bp, false, dShi, dSlo,
-                    dSx, st);
+      run_shrink(pl, tb, jobs, tiles, dYb, pl.d_out, bp, false, dShi, dSlo, dSx, st);
     }
     if (dX) {
       Timed t(TLORA_K_GEMM_BWD, st);
@@ -610,13 +635,10 @@ int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* d
     }
   }
   if (want_grads) {
-    const int classes[3] = {1, 2, 4};
     {
       Timed t(TLORA_K_RANK_GRAD, st);
-      const GradUnit* gu = reinterpret_cast<const GradUnit*>(tb + pl.tb_gBu);
-      for (int ci = 0; ci < 3; ++ci)
-        launch_rank_grad(classes[ci], jobs, gu + pl.gradB_class_begin[ci],
-                         pl.gradB_class_begin[ci + 1] - pl.gradB_class_begin[ci], Shi, Slo, dYb, pl.d_out, partial, st);
+      launch_rank_grad(jobs, reinterpret_cast<const GradUnit*>(tb + pl.tb_gBu), (int)pl.gradB_units.size(), Shi, Slo,
+                       dYb, pl.d_out, partial, st);
     }
     {
       Timed t(TLORA_K_GRAD_REDUCE, st);
@@ -625,10 +647,8 @@ int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* d
     }
     {
       Timed t(TLORA_K_RANK_GRAD, st);
-      const GradUnit* gu = reinterpret_cast<const GradUnit*>(tb + pl.tb_gAu);
-      for (int ci = 0; ci < 3; ++ci)
-        launch_rank_grad(classes[ci], jobs, gu + pl.gradA_class_begin[ci],
-                         pl.gradA_class_begin[ci + 1] - pl.gradA_class_begin[ci], dShi, dSlo, Xb, pl.d_in, partial, st);
+      launch_rank_grad(jobs, reinterpret_cast<const GradUnit*>(tb + pl.tb_gAu), (int)pl.gradA_units.size(), dShi, dSlo,
+                       Xb, pl.d_in, partial, st);
     }
     {
       Timed t(TLORA_K_GRAD_REDUCE, st);
@@ -697,6 +717,11 @@ int tlora_set_option(const char* name, int64_t value) {
   if (n == "shrink_rows") {
     if (value != 64 && value != 128) return TLORA_EINVAL;
     g_opt.shrink_rows = (int)value;
+    return TLORA_OK;
+  }
+  if (n == "shrink_stages") {
+    if (value != 4 && value != 8) return TLORA_EINVAL;
+    g_opt.shrink_stages = (int)value;
     return TLORA_OK;
   }
   if (n == "grad_tokens") {

@@ -13,6 +13,7 @@ constexpr int kGemmBK = 32;
 constexpr int kShrinkCols = 64;     // rank columns per shrink work unit
 constexpr int kGradCols = 256;      // feature columns per dA/dB work unit (4 waves x 64)
 constexpr int kGradRanks = 32;      // rank rows per MFMA block of the dA/dB kernel
+constexpr int kGradMaxBlocks = 4;   // rank blocks of 32 per dA/dB work unit (128 rank rows)
 constexpr int kGradStep = 32;       // tokens per pipeline step of the dA/dB kernel
 
 // One job's view of the problem (Sec. 3.2: one adapter branch per job on the shared backbone).
@@ -51,15 +52,15 @@ struct ShrinkUnit {
   int32_t pb;              // rank-column block
 };
 
-// Work unit of the dA/dB kernels: tokens [t0, t1) of one job x kGradCols feature columns x a block of
-// 32 * mb rank rows; writes one partial tile [32 * mb, kGradCols] (fp32) at float offset part_off, which
-// the reduce pass sums in unit order.
+// Work unit of the dA/dB kernels: tokens [t0, t1) of one job x kGradCols feature columns x rank block pb
+// (128 rank rows, of which the first 32 * mb hold ranks below rpad); writes one partial tile
+// [32 * mb, kGradCols] (fp32) at float offset part_off, which the reduce pass sums in unit order.
 struct GradUnit {
   int32_t job;
   int32_t t0, t1;
   int32_t cb;              // feature-column block
-  int32_t pb;              // rank block (of 32 * mb rows)
-  int32_t mb;              // 1, 2 or 4
+  int32_t pb;              // rank block (of 128 rows)
+  int32_t mb;              // live 32-row blocks in it: 1 .. 4
   int64_t part_off;
 };
 

@@ -24,6 +24,10 @@ void launch_zero_fill(void* ptr, size_t bytes, hipStream_t st);
 void launch_shrink(const JobDev* jobs, const TileDev* tiles, const ShrinkUnit* units, int num_units,
                    int shrink_rows, const uint16_t* act, int K, const uint16_t* packed, bool packed_is_atp,
                    uint16_t* S_hi, uint16_t* S_lo, uint16_t* Sx, hipStream_t st);
+// Same result for K % 32 == 0 with streaming units (shrink_rows = 64 | 128 token rows x 128 rank columns).
+void launch_shrink_stream(const JobDev* jobs, const TileDev* tiles, const ShrinkUnit* units, int num_units,
+                          int shrink_rows, int stages, const uint16_t* act, int K, const uint16_t* packed,
+                          bool packed_is_atp, uint16_t* S_hi, uint16_t* S_lo, uint16_t* Sx, hipStream_t st);
 
 // out[t, n] = sum_k act[t, k] * Wop[k, n] + sum_p Sx_tile[t, p] * Eop[roff_first + p, n]
 //   w_is_kn = true : W is [K, N] row-major (forward,  Eop = b_all [R + 32, N])
@@ -33,8 +37,7 @@ void launch_seg_gemm(bool w_is_kn, const TileDev* tiles, const uint16_t* act, co
                      hipStream_t st);
 
 // partial[u] = sum_{t in unit u} U_j[t, p] * V[t, c]   then   G_j = scale_j * sum_u partial[u]
-// `units` holds only units of the given mb class (1, 2 or 4 blocks of 32 rank rows).
-void launch_rank_grad(int mb, const JobDev* jobs, const GradUnit* units, int num_units, const uint16_t* U_hi,
+void launch_rank_grad(const JobDev* jobs, const GradUnit* units, int num_units, const uint16_t* U_hi,
                       const uint16_t* U_lo, const uint16_t* V, int D, float* partial, hipStream_t st);
 void launch_grad_reduce(const JobDev* jobs, const GradGroup* groups, int num_groups, const float* partial, int D,
                         bool out_is_dA, hipStream_t st);

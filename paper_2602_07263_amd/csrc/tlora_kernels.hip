@@ -63,6 +63,14 @@ __device__ __forceinline__ bf16x8 frag_row_tile(const uint8_t* tile, int rb, int
   const int c = kk * 2 + (lane >> 5);
   return as_bf16x8(*reinterpret_cast<const u32x4*>(tile + row_tile_off(r, c)));
 }
+// "row tile" with 32 k-values per row (64 B rows): 16-byte chunk c of row r sits at slot c ^ ((r >> 2) & 3),
+// so 16 consecutive rows read at one logical chunk cover all 64 banks once.
+__device__ __forceinline__ int row32_off(int r, int c) { return r * 64 + ((c ^ ((r >> 2) & 3)) << 4); }
+__device__ __forceinline__ bf16x8 frag_row32(const uint8_t* tile, int rb, int kk, int lane) {
+  const int r = rb + (lane & 31);
+  return as_bf16x8(*reinterpret_cast<const u32x4*>(tile + row32_off(r, kk * 2 + (lane >> 5))));
+}
+
 // MFMA operand fragment of a kn tile: columns nb .. nb+31, k-step kk, through the transposing LDS read
 // (ds_read_b64_tr_b16: inside each group of 16 lanes, lane i receives element (i % 4) of the 8-byte
 // rows addressed by lanes 4e + i/4, e = 0..3 -- i.e. 4 consecutive k for column i of a 4 x 16 block).
@@ -269,16 +277,157 @@ __global__ void __launch_bounds__(256) shrink_kernel(const JobDev* __restrict__ 
   }
 }
 
+// s_waitcnt immediate: vmcnt(vm) lgkmcnt(0), export counter untouched (vmcnt is 6 bits, split 4 + 2)
+constexpr int waitcnt_vm_lgkm0(int vm) { return (vm & 15) | ((vm >> 4) << 14) | 0x0070; }
+
+// ---------------------------------------------------------------------------------------------------
+// Shrink, streaming version (needs K % 32 == 0): one workgroup = ROWS token rows of one job x up to 128 padded
+// rank columns.  K-steps of 32; a stage holds the activation tile (ROWS x 32) and the adapter tile
+// (128 x 32); NS stages are filled NS - 1 steps ahead by raw asynchronous global->LDS loads, so several KB
+// per wave stay in flight without holding registers -- the kernel is bound by how fast X (or dY) streams in.
+// ---------------------------------------------------------------------------------------------------
+template <int ROWS, int NS>
+__global__ void __launch_bounds__(256) shrink_stream_kernel(const JobDev* __restrict__ jobs,
+                                                            const TileDev* __restrict__ tiles,
+                                                            const ShrinkUnit* __restrict__ units,
+                                                            const uint16_t* __restrict__ act, int K,
+                                                            const uint16_t* __restrict__ packed, int packed_is_atp,
+                                                            uint16_t* __restrict__ Shi, uint16_t* __restrict__ Slo,
+                                                            uint16_t* __restrict__ Sx) {
+  constexpr int PCOLS = 128;                       // padded rank columns per unit
+  constexpr int WM = ROWS / 32, WN = 4 / WM;       // waves along token rows / along rank columns
+  constexpr int PW = PCOLS / WN, NPB = PW / 32;    // rank columns (and 32-wide blocks) per wave
+  constexpr int A_BYTES = ROWS * 64, P_BYTES = PCOLS * 64, STAGE = A_BYTES + P_BYTES;
+  constexpr int A_LD = A_BYTES / 1024 / 4, P_LD = P_BYTES / 1024 / 4;   // loads per wave per step
+  static_assert(kGemmBM == 256, "the row -> GEMM tile lookup below shifts by 8");
+  __shared__ __attribute__((aligned(1024))) uint8_t lds[NS * STAGE];
+
+  const ShrinkUnit u = units[blockIdx.x];
+  const JobDev jb = jobs[u.job];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, so LDS bases stay in SGPRs
+  const int wm = wave % WM, wn = wave / WM;
+  const int p0 = u.pb * PCOLS;
+  const int pvalid = min(PCOLS, jb.rpad - p0);     // > 0 by construction
+  const uint16_t* P = packed + (packed_is_atp ? jb.atp_off : (int64_t)jb.roff * K) + (int64_t)p0 * K;
+  const uint16_t* Arow = act + (int64_t)u.t0 * K;
+  const int nsteps = K / 32;
+
+  f32x16 acc[NPB];
+#pragma unroll
+  for (int i = 0; i < NPB; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+
+  // lane -> (row, 16-byte chunk) of the 64-byte-row tiles; rows beyond the unit / beyond rpad are clamped
+  // (they only feed outputs that are not stored, or that are stored as zeros)
+  const uint16_t* asrc[A_LD];
+  const uint16_t* psrc[P_LD];
+  bool plive[P_LD];        // adapter-tile lanes beyond rpad fetch nothing (the stale slots only feed unused rank
+                           // columns); lane 0 always fetches so every wave issues the same number of loads
+#pragma unroll
+  for (int i = 0; i < A_LD; ++i) {
+    const int q = (wave * A_LD + i) * 64 + lane, r = q >> 2, c = (q & 3) ^ ((r >> 2) & 3);
+    asrc[i] = Arow + (int64_t)min(r, u.nrows - 1) * K + c * 8;
+  }
+#pragma unroll
+  for (int i = 0; i < P_LD; ++i) {
+    const int q = (wave * P_LD + i) * 64 + lane, r = q >> 2, c = (q & 3) ^ ((r >> 2) & 3);
+    psrc[i] = P + (int64_t)min(r, pvalid - 1) * K + c * 8;
+    plive[i] = r < pvalid || lane == 0;
+  }
+  const uint32_t lds0 = lds_addr(lds);
+  int f_step = 0;
+  auto issue = [&]() {
+    const int st = min(f_step, nsteps - 1);        // trailing issues re-load the last step (uniform load count)
+    const uint32_t base = lds0 + (f_step % NS) * STAGE;
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i) dma16(asrc[i] + st * 32, base + (wave * A_LD + i) * 1024);
+#pragma unroll
+    for (int i = 0; i < P_LD; ++i)
+      if (plive[i]) dma16(psrc[i] + st * 32, base + A_BYTES + (wave * P_LD + i) * 1024);
+    ++f_step;
+  };
+  for (int i = 0; i < NS - 1; ++i) issue();
+  for (int kt = 0; kt < nsteps; ++kt) {
+    // loads complete in order: all but those of the NS - 2 youngest steps have landed
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NS - 2) * (A_LD + P_LD)));
+    __builtin_amdgcn_s_barrier();
+    issue();                                       // into the stage read in step kt - 1
+    const uint8_t* S = lds + (kt % NS) * STAGE;
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+      const bf16x8 xf = frag_row32(S, wm * 32, kk, lane);
+#pragma unroll
+      for (int i = 0; i < NPB; ++i) {
+        const bf16x8 pf = frag_row32(S + A_BYTES, wn * PW + i * 32, kk, lane);
+        acc[i] = mfma32(pf, xf, acc[i]);
+      }
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));   // drain before the workgroup's LDS is released
+
+  // Outputs as in shrink_kernel: bf16 hi + lo planes (pad rows of the job's last unit written as zeros) and
+  // bf16 scale_j * x into the row's slot of its GEMM tile's K-extension operand.
+  const int r = wm * 32 + (lane & 31);
+  const int jrow = u.t0 - jb.row0 + r;
+  const bool last_unit = u.t0 + u.nrows == jb.row1;
+  const int jrows_padded = (jb.row1 - jb.row0 + kGradStep - 1) / kGradStep * kGradStep;
+  if (r < u.nrows || (last_unit && jrow < jrows_padded)) {
+    const bool live = r < u.nrows;
+    const int t = u.t0 + r;
+    const int64_t rowbase = jb.soff + (int64_t)jrow * jb.rpad;
+    const TileDev td = tiles[min(t, jb.row1 - 1) >> 8];
+    uint16_t* const xrow = Sx + td.aoff + (int64_t)(t & 255) * td.kext + (jb.roff - td.roff_first);
+#pragma unroll
+    for (int i = 0; i < NPB; ++i)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int p = p0 + wn * PW + i * 32 + g * 8 + (lane >> 5) * 4;
+        if (p < jb.rpad) {
+          float v[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = live ? acc[i][g * 4 + e] : 0.f;
+          float lo[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) lo[e] = v[e] - (float)(__bf16)v[e];
+          *reinterpret_cast<u32x2*>(Shi + rowbase + p) = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+          *reinterpret_cast<u32x2*>(Slo + rowbase + p) = u32x2{pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3])};
+          if (live) {
+            u32x2 b = {pack_bf16x2(jb.scale * v[0], jb.scale * v[1]), pack_bf16x2(jb.scale * v[2], jb.scale * v[3])};
+            *reinterpret_cast<u32x2*>(xrow + p) = b;
+          }
+        }
+      }
+  }
+}
+
 void launch_shrink(const JobDev* jobs, const TileDev* tiles, const ShrinkUnit* units, int num_units, int shrink_rows,
                    const uint16_t* act, int K, const uint16_t* packed, bool packed_is_atp, uint16_t* S_hi,
                    uint16_t* S_lo, uint16_t* Sx, hipStream_t st) {
   if (num_units == 0) return;
-  if (shrink_rows == 128)
-    hipLaunchKernelGGL(shrink_kernel<128>, dim3(num_units), dim3(256), 0, st, jobs, tiles, units, act, K, packed,
-                       packed_is_atp ? 1 : 0, S_hi, S_lo, Sx);
-  else
-    hipLaunchKernelGGL(shrink_kernel<64>, dim3(num_units), dim3(256), 0, st, jobs, tiles, units, act, K, packed,
-                       packed_is_atp ? 1 : 0, S_hi, S_lo, Sx);
+  // generic kernel: units of 64 rows x 64 rank columns
+  hipLaunchKernelGGL(shrink_kernel<64>, dim3(num_units), dim3(256), 0, st, jobs, tiles, units, act, K, packed,
+                     packed_is_atp ? 1 : 0, S_hi, S_lo, Sx);
+  (void)shrink_rows;
+}
+
+void launch_shrink_stream(const JobDev* jobs, const TileDev* tiles, const ShrinkUnit* units, int num_units,
+                          int shrink_rows, int stages, const uint16_t* act, int K, const uint16_t* packed,
+                          bool packed_is_atp, uint16_t* S_hi, uint16_t* S_lo, uint16_t* Sx, hipStream_t st) {
+  if (num_units == 0) return;
+  const int atp = packed_is_atp ? 1 : 0;
+#define TLORA_SHRINK_LAUNCH(R, N)                                                                                     \
+  hipLaunchKernelGGL((shrink_stream_kernel<R, N>), dim3(num_units), dim3(256), 0, st, jobs, tiles, units, act, K, packed, \
+                     atp, S_hi, S_lo, Sx)
+  if (shrink_rows == 128) {
+    if (stages >= 8) TLORA_SHRINK_LAUNCH(128, 8);
+    else             TLORA_SHRINK_LAUNCH(128, 4);
+  } else {
+    if (stages >= 8) TLORA_SHRINK_LAUNCH(64, 8);
+    else             TLORA_SHRINK_LAUNCH(64, 4);
+  }
+#undef TLORA_SHRINK_LAUNCH
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -304,14 +453,6 @@ struct GemmParams {
   int ra;                   // R + 32: row stride of a_all
   int tiles_m, tiles_n;
 };
-
-// "row tile" with 32 k-values per row (64 B rows): 16-byte chunk c of row r sits at slot c ^ ((r >> 2) & 3),
-// so 16 consecutive rows read at one logical chunk cover all 64 banks once.
-__device__ __forceinline__ int row32_off(int r, int c) { return r * 64 + ((c ^ ((r >> 2) & 3)) << 4); }
-__device__ __forceinline__ bf16x8 frag_row32(const uint8_t* tile, int rb, int kk, int lane) {
-  const int r = rb + (lane & 31);
-  return as_bf16x8(*reinterpret_cast<const u32x4*>(tile + row32_off(r, kk * 2 + (lane >> 5))));
-}
 
 template <bool KN>
 __global__ void __launch_bounds__(512) seg_gemm_kernel(GemmParams P) {
@@ -566,19 +707,19 @@ __device__ __forceinline__ bf16x8 frag_tr_u(const uint8_t* plane, int pitch, int
   return __builtin_bit_cast(bf16x8, v);
 }
 
-template <int MB>
 __global__ void __launch_bounds__(256) rank_grad_kernel(const JobDev* __restrict__ jobs,
                                                         const GradUnit* __restrict__ units,
                                                         const uint16_t* __restrict__ Uhi,
                                                         const uint16_t* __restrict__ Ulo,
                                                         const uint16_t* __restrict__ V, int D,
                                                         float* __restrict__ partial) {
-  constexpr int RP = kGradRanks * MB;                       // rank rows of this unit
-  constexpr int UPITCH = 2 * RP;                            // bytes per token row of a U tile: 64, 128, 256
-  // 16-byte chunk c of token row k sits at slot c ^ (sw(k) << 2) so that the four rows one transposing read
-  // touches start in four distinct 64-byte bank groups: sw = 0 (64 B rows), (k >> 1) & 1 (128 B), k & 3 (256 B)
-  constexpr int SW_SHIFT = MB == 2 ? 1 : 0;
-  constexpr int SW_MASK = MB == 1 ? 0 : MB == 2 ? 1 : 3;
+  constexpr int MB = kGradMaxBlocks;                        // the U tile always has room for 4 blocks of 32 ranks;
+  constexpr int RP = kGradRanks * MB;                       // a unit multiplies only its u.mb live ones
+  constexpr int UPITCH = 2 * RP;                            // 256 bytes per token row of a U tile
+  // 16-byte chunk c of token row k sits at slot c ^ ((k & 3) << 2) so that the four rows one transposing read
+  // touches start in four distinct 64-byte bank groups
+  constexpr int SW_SHIFT = 0;
+  constexpr int SW_MASK = 3;
   constexpr int UPLANE = kGradStep * UPITCH;                // 2 KB * MB
   constexpr int VTILE = kGradStep * kGradCols * 2;          // 16 KB
   constexpr int LOADS = 4 + MB;                             // asynchronous loads per wave per step
@@ -616,10 +757,11 @@ __global__ void __launch_bounds__(256) rank_grad_kernel(const JobDev* __restrict
     vcol[i] = min(col0 + c * 8, D - 8);               // columns beyond D are clamped; their results are not stored
   }
   // U tiles: hi plane then lo plane, 2 * MB KB each = 2 * MB wave-loads; wave w issues load q = w * MB + i of the
-  // 4 * MB.  Lanes whose rank chunk lies beyond rpad fetch the job's last chunk instead (no branch around an
-  // asynchronous load): what they deliver only feeds rank rows >= rpad of the tile, which are never stored.
+  // 4 * MB.  Lanes whose rank chunk lies beyond rpad fetch nothing: the stale slots only feed rank rows >= rpad
+  // of the tile, which are never stored.
   const uint16_t* usrc[MB];
   int udst[MB];
+  bool ulive[MB];
 #pragma unroll
   for (int i = 0; i < MB; ++i) {
     const int q = wave * MB + i;                      // 0 .. 4 MB - 1
@@ -627,6 +769,7 @@ __global__ void __launch_bounds__(256) rank_grad_kernel(const JobDev* __restrict
     const int slot = within * 64 + lane;              // 16-byte slot inside the plane
     const int k = slot / (RP / 8), cphys = slot % (RP / 8);
     const int c = cphys ^ (((k >> SW_SHIFT) & SW_MASK) << 2);
+    ulive[i] = pbase + c * 8 < jb.rpad || lane == 0;    // lane 0 keeps every wave's load count the same
     const int p = min(pbase + c * 8, jb.rpad - 8);
     usrc[i] = (plane ? Ulo : Uhi) + jb.soff + (int64_t)(u.t0 - jb.row0 + k) * jb.rpad + p;
     udst[i] = plane * UPLANE + within * 1024;
@@ -642,7 +785,7 @@ __global__ void __launch_bounds__(256) rank_grad_kernel(const JobDev* __restrict
     }
 #pragma unroll
     for (int i = 0; i < MB; ++i)
-      dma16(usrc[i] + (int64_t)st * kGradStep * jb.rpad, hbase + __builtin_amdgcn_readfirstlane(udst[i]));
+      if (ulive[i]) dma16(usrc[i] + (int64_t)st * kGradStep * jb.rpad, hbase + __builtin_amdgcn_readfirstlane(udst[i]));
     ++f_step;
   };
   auto compute = [&](const uint8_t* S, const uint8_t* H) {
@@ -653,24 +796,24 @@ __global__ void __launch_bounds__(256) rank_grad_kernel(const JobDev* __restrict
       for (int n = 0; n < 2; ++n) vf[n] = frag_kn_tile(S, wave * 64 + n * 32, kk, lane);
 #pragma unroll
       for (int m = 0; m < MB; ++m) {
-        const bf16x8 hi = frag_tr_u(H, UPITCH, SW_SHIFT, SW_MASK, m * 32, kk, lane);
-        const bf16x8 lo = frag_tr_u(H + UPLANE, UPITCH, SW_SHIFT, SW_MASK, m * 32, kk, lane);
+        if (m < u.mb) {
+          const bf16x8 hi = frag_tr_u(H, UPITCH, SW_SHIFT, SW_MASK, m * 32, kk, lane);
+          const bf16x8 lo = frag_tr_u(H + UPLANE, UPITCH, SW_SHIFT, SW_MASK, m * 32, kk, lane);
 #pragma unroll
-        for (int n = 0; n < 2; ++n) {
-          acc[m][n] = mfma32(hi, vf[n], acc[m][n]);
-          acc[m][n] = mfma32(lo, vf[n], acc[m][n]);
+          for (int n = 0; n < 2; ++n) {
+            acc[m][n] = mfma32(hi, vf[n], acc[m][n]);
+            acc[m][n] = mfma32(lo, vf[n], acc[m][n]);
+          }
         }
       }
     }
   };
   auto landed = [&]() {
     // loads complete in order: all but those of the two youngest steps have landed
-    if (MB == 1) __builtin_amdgcn_s_waitcnt(0x007A);        // vmcnt(10) lgkmcnt(0)
-    else if (MB == 2) __builtin_amdgcn_s_waitcnt(0x007C);   // vmcnt(12)
-    else __builtin_amdgcn_s_waitcnt(0x4070);                // vmcnt(16)
+    __builtin_amdgcn_s_waitcnt(0x4070);                     // vmcnt(16) lgkmcnt(0)
     __builtin_amdgcn_s_barrier();
   };
-  static_assert(2 * LOADS == (MB == 1 ? 10 : MB == 2 ? 12 : 16), "wait counts above");
+  static_assert(2 * LOADS == 16, "wait count above");
   if (nsteps > 0) {
     issue(g0, h0);
     issue(g1, h1);
@@ -688,28 +831,26 @@ __global__ void __launch_bounds__(256) rank_grad_kernel(const JobDev* __restrict
     __builtin_amdgcn_s_waitcnt(0x0070);   // drain the trailing loads before the workgroup's LDS is released
   }
 
-  // partial tile [RP][256]: lane holds column (lane % 32) of its n-block and 16 rank rows per m-block
+  // partial tile [32 * u.mb][256]: lane holds column (lane % 32) of its n-block and 16 rank rows per m-block
   float* out = partial + u.part_off;
 #pragma unroll
-  for (int m = 0; m < MB; ++m)
+  for (int m = 0; m < MB; ++m) {
+    if (m < u.mb) {
 #pragma unroll
-    for (int n = 0; n < 2; ++n)
+      for (int n = 0; n < 2; ++n)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int pl = m * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-        out[pl * kGradCols + wave * 64 + n * 32 + (lane & 31)] = acc[m][n][e];
-      }
+        for (int e = 0; e < 16; ++e) {
+          const int pl = m * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+          out[pl * kGradCols + wave * 64 + n * 32 + (lane & 31)] = acc[m][n][e];
+        }
+    }
+  }
 }
 
-void launch_rank_grad(int mb, const JobDev* jobs, const GradUnit* units, int num_units, const uint16_t* U_hi,
+void launch_rank_grad(const JobDev* jobs, const GradUnit* units, int num_units, const uint16_t* U_hi,
                       const uint16_t* U_lo, const uint16_t* V, int D, float* partial, hipStream_t st) {
   if (num_units == 0) return;
-  if (mb == 1)
-    hipLaunchKernelGGL(rank_grad_kernel<1>, dim3(num_units), dim3(256), 0, st, jobs, units, U_hi, U_lo, V, D, partial);
-  else if (mb == 2)
-    hipLaunchKernelGGL(rank_grad_kernel<2>, dim3(num_units), dim3(256), 0, st, jobs, units, U_hi, U_lo, V, D, partial);
-  else
-    hipLaunchKernelGGL(rank_grad_kernel<4>, dim3(num_units), dim3(256), 0, st, jobs, units, U_hi, U_lo, V, D, partial);
+  hipLaunchKernelGGL(rank_grad_kernel, dim3(num_units), dim3(256), 0, st, jobs, units, U_hi, U_lo, V, D, partial);
 }
 
 // Sum the partial tiles of one output tile in unit order, scale, and store (dB_j row-major [r, D];
@@ -720,9 +861,10 @@ __global__ void __launch_bounds__(256) grad_reduce_kernel(const JobDev* __restri
   const GradGroup g = groups[blockIdx.x];
   const JobDev jb = jobs[g.job];
   const int c = g.cb * kGradCols + threadIdx.x;
-  const int tile_rows = g.mb * kGradRanks;
+  const int tile_rows = g.mb * kGradRanks;                 // live rows of this tile
+  const int pb_rows = kGradMaxBlocks * kGradRanks;         // rank rows per rank block
   const int pl0 = blockIdx.y * 4;
-  if (c >= D || pl0 >= tile_rows || g.pb * tile_rows + pl0 >= jb.rank) return;
+  if (c >= D || pl0 >= tile_rows || g.pb * pb_rows + pl0 >= jb.rank) return;
   const int64_t tile_elems = (int64_t)tile_rows * kGradCols;
   const float* src = partial + g.part_off + (int64_t)pl0 * kGradCols + threadIdx.x;
   float s[4] = {0.f, 0.f, 0.f, 0.f};
@@ -733,7 +875,7 @@ __global__ void __launch_bounds__(256) grad_reduce_kernel(const JobDev* __restri
   float* dst = static_cast<float*>(out_is_dA ? jb.dA : jb.dB);
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int p = g.pb * tile_rows + pl0 + i;
+    const int p = g.pb * pb_rows + pl0 + i;
     if (p < jb.rank) {
       const float v = s[i] * jb.scale;
       if (out_is_dA) dst[(int64_t)c * jb.rank + p] = v;
@@ -745,7 +887,7 @@ __global__ void __launch_bounds__(256) grad_reduce_kernel(const JobDev* __restri
 void launch_grad_reduce(const JobDev* jobs, const GradGroup* groups, int num_groups, const float* partial, int D,
                         bool out_is_dA, hipStream_t st) {
   if (num_groups == 0) return;
-  hipLaunchKernelGGL(grad_reduce_kernel, dim3(num_groups, 4 * kGradRanks / 4), dim3(256), 0, st, jobs, groups, partial,
+  hipLaunchKernelGGL(grad_reduce_kernel, dim3(num_groups, kGradMaxBlocks * kGradRanks / 4), dim3(256), 0, st, jobs, groups, partial,
                      D, out_is_dA ? 1 : 0);
 }
 
