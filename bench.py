@@ -37,6 +37,9 @@ def parse_args():
     ap.add_argument("--no-loop-baseline", action="store_true")
     ap.add_argument("--no-secondary", action="store_true", help="skip the extra 4096x4096 (config 1) measurement")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with HIP events")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy (outside the timed region) so that "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled against a known size")
     return ap.parse_args()
 
 
@@ -209,6 +212,12 @@ def main():
     tlora.lib()
     torch.cuda.set_device(0)
 
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")       # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     main_res = measure_workload(args.config, args.steps, args.warmup, not args.no_profile, not args.no_loop_baseline)
     wl = main_res["wl"]
     tflops = wl.flops() / (main_res["ms"] * 1e-3) / 1e12

@@ -454,7 +454,9 @@ struct GemmParams {
   int tiles_m, tiles_n;
 };
 
-template <bool KN>
+// KTAIL: the instantiation for K % 32 != 0 carries the extra predicated step; keeping it out of the common one
+// keeps its register pressure (and spills) away from every tile.
+template <bool KN, bool KTAIL>
 __global__ void __launch_bounds__(512) seg_gemm_kernel(GemmParams P) {
   constexpr int BM = kGemmBM, BN = kGemmBN, BK = kGemmBK;
   static_assert(BM == 256 && BN == 256 && BK == 32, "tile shape is baked into the index arithmetic below");
@@ -606,7 +608,7 @@ __global__ void __launch_bounds__(512) seg_gemm_kernel(GemmParams P) {
   }
 
   // ---- K tail (K % 32 != 0): one register-staged, predicated step through stage 0 ---------------------------
-  if (P.K % BK) {
+  if (KTAIL) {
     const int k0 = nfull * BK, kvalid = P.K - k0;
     u32x4 areg[2], breg[2];
 #pragma unroll
@@ -678,8 +680,14 @@ void launch_seg_gemm(bool w_is_kn, const TileDev* tiles, const uint16_t* act, co
   P.tiles_n = (N + kGemmBN - 1) / kGemmBN;
   const int nb = P.tiles_m * P.tiles_n;
   if (nb == 0) return;
-  if (w_is_kn) hipLaunchKernelGGL(seg_gemm_kernel<true>, dim3(nb), dim3(512), 0, st, P);
-  else         hipLaunchKernelGGL(seg_gemm_kernel<false>, dim3(nb), dim3(512), 0, st, P);
+  const bool tail = K % kGemmBK != 0;
+  if (w_is_kn) {
+    if (tail) hipLaunchKernelGGL((seg_gemm_kernel<true, true>), dim3(nb), dim3(512), 0, st, P);
+    else      hipLaunchKernelGGL((seg_gemm_kernel<true, false>), dim3(nb), dim3(512), 0, st, P);
+  } else {
+    if (tail) hipLaunchKernelGGL((seg_gemm_kernel<false, true>), dim3(nb), dim3(512), 0, st, P);
+    else      hipLaunchKernelGGL((seg_gemm_kernel<false, false>), dim3(nb), dim3(512), 0, st, P);
+  }
 }
 
 // ---------------------------------------------------------------------------------------------------
