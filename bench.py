@@ -122,9 +122,10 @@ def measure_workload(cfg_index: int, steps: int, warmup: int, profile: bool, loo
         tlora.tlora_profile(True)      # clear warm-up totals
     ms = time_steps(step, steps, 0)
     prof = tlora.tlora_profile_read() if profile else None
+    clock = tlora.tlora_profile_clock() if profile else None
     if profile:
         tlora.tlora_profile(False)
-    res = {"wl": wl, "ms": ms, "prof": prof, "loop_ms": None}
+    res = {"wl": wl, "ms": ms, "prof": prof, "clock": clock, "loop_ms": None}
     if loop_baseline:
         for r in runs:
             r.build_job_loop()
@@ -238,6 +239,12 @@ def main():
         out["speedup_vs_per_job_loop"] = round(main_res["loop_ms"] / main_res["ms"], 3)
     if main_res["prof"]:
         out["roofline"] = gemm_roofline(wl, main_res["prof"], args.steps)
+        if main_res["clock"] and min(main_res["clock"]) > 0:
+            ghz = sum(main_res["clock"]) / 2
+            out["roofline"]["sustained_shader_clock_ghz"] = round(ghz, 3)
+            out["roofline"]["peak_at_sustained_clock"] = round(BF16_MFMA_PEAK_TFLOPS * ghz / 2.4, 1)
+            out["roofline"]["frac_of_peak_at_sustained_clock"] = round(
+                out["roofline"]["achieved"] / (BF16_MFMA_PEAK_TFLOPS * ghz / 2.4), 4)
         out["kernel_ms_per_step"] = {k: round(v[0] / args.steps, 4) for k, v in main_res["prof"].items() if v[1]}
     else:
         out["roofline"] = None

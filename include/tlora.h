@@ -109,6 +109,7 @@ int tlora_plan_dump(const tlora_problem_t* p, int32_t* rpad, int64_t* soff, int3
                     int32_t* tile_job_last, int64_t* n_tiles);
 
 /* Tuning knobs (process-wide, for experiments and for the tiling-independence tests).
+ *   "gemm_waves"   : waves per workgroup of the segmented GEMM             (8: 128x64 per wave | 4: 128x128)
  *   "shrink_rows"  : token rows per work unit of the shrink kernels        (64 | 128)
  *   "shrink_stages": LDS stages of the streaming shrink kernel             (4 | 8)
  *   "grad_tokens"  : minimum tokens per work unit of the dA / dB kernels   (multiple of 64)
@@ -133,6 +134,11 @@ typedef enum {
 } tlora_kernel_class_t;
 int tlora_profile(int enable);
 int tlora_profile_read(int kernel_class, double* total_ms, int64_t* launches);
+/* Shader clock (GHz) that a sample of workgroups (every 64th) of the most recent profiled forward / backward
+ * segmented GEMM saw across their K-loops (summed cycle counter over summed 100 MHz real-time counter): the
+ * clock the chip actually sustained under that kernel's power draw, which scales the attainable MFMA rate.  Synchronises the device.  Either output may be NULL;
+ * 0.0 = no profiled launch yet.  The workspace of that call must still be allocated. */
+int tlora_profile_clock(double* ghz_fwd, double* ghz_bwd);
 
 /* Static description of an error code. */
 const char* tlora_strerror(int status);

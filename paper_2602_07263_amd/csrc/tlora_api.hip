@@ -19,6 +19,7 @@ struct Options {
   int shrink_rows = 128;
   int shrink_stages = 4;
   int grad_tokens = 256;
+  int gemm_waves = 8;
 };
 Options g_opt;
 std::mutex g_mu;
@@ -47,6 +48,7 @@ struct Plan {
   size_t tables_bytes = 0;
   // offsets of each table inside the table blob
   size_t tb_jobs = 0, tb_tiles = 0, tb_shrink = 0, tb_stream = 0, tb_gBu = 0, tb_gBg = 0, tb_gAu = 0, tb_gAg = 0, tb_f32 = 0;
+  size_t off_clock = 0;                                 // 4 words outside the uploaded tables: GEMM clock probe
   size_t f32_reserved = 0;
 };
 
@@ -226,6 +228,7 @@ int build_plan(const tlora_problem_t* p, Plan& pl) {
   size_t w = 0;
   auto wplace = [&](size_t bytes) { const size_t at = w;  w = align_up(w + bytes, 256);  return at; };
   pl.off_tables = wplace(pl.tables_bytes);
+  pl.off_clock = wplace(64);
   if (pl.dtype == TLORA_F32) {
     pl.off_S = wplace(sizeof(float) * (size_t)pl.s_elems);
     pl.off_dS = wplace(sizeof(float) * (size_t)pl.s_elems);
@@ -289,6 +292,7 @@ bool g_prof_on = false;
 std::vector<Pending> g_pending;
 std::vector<hipEvent_t> g_event_pool;
 double g_prof_ms[TLORA_K_COUNT] = {};
+unsigned long long* g_clock_slot[2] = {nullptr, nullptr};   // device slots of the last profiled fwd / dX GEMM
 int64_t g_prof_n[TLORA_K_COUNT] = {};
 
 hipEvent_t prof_event() {
@@ -512,9 +516,11 @@ int tlora_fwd(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_byte
     run_shrink(pl, tb, jobs, tiles, static_cast<const uint16_t*>(p->X), pl.d_in, atp, true,
                reinterpret_cast<uint16_t*>(ws + pl.off_Shi), reinterpret_cast<uint16_t*>(ws + pl.off_Slo), Sx, st);
   }
+  if (g_prof_on) launch_zero_fill(ws + pl.off_clock, 16, st);
   Timed tg(TLORA_K_GEMM_FWD, st);
   launch_seg_gemm(true, tiles, static_cast<const uint16_t*>(p->X), static_cast<const uint16_t*>(p->W), Sx, bp,
-                  pl.r_total, static_cast<uint16_t*>(Y), pl.T, pl.d_in, pl.d_out, st);
+                  pl.r_total, static_cast<uint16_t*>(Y), pl.T, pl.d_in, pl.d_out, g_opt.gemm_waves,
+                  g_prof_on ? (g_clock_slot[0] = reinterpret_cast<unsigned long long*>(ws + pl.off_clock)) : nullptr, st);
   return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
 }
 
@@ -629,9 +635,12 @@ int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* d
       run_shrink(pl, tb, jobs, tiles, dYb, pl.d_out, bp, false, dShi, dSlo, dSx, st);
     }
     if (dX) {
+      if (g_prof_on) launch_zero_fill(ws + pl.off_clock + 16, 16, st);
       Timed t(TLORA_K_GEMM_BWD, st);
       launch_seg_gemm(false, tiles, dYb, static_cast<const uint16_t*>(p->W), dSx, ap, pl.r_total,
-                      static_cast<uint16_t*>(dX), pl.T, pl.d_out, pl.d_in, st);
+                      static_cast<uint16_t*>(dX), pl.T, pl.d_out, pl.d_in, g_opt.gemm_waves,
+                      g_prof_on ? (g_clock_slot[1] = reinterpret_cast<unsigned long long*>(ws + pl.off_clock) + 2) : nullptr,
+                      st);
     }
   }
   if (want_grads) {
@@ -692,6 +701,7 @@ int tlora_profile(int enable) {
   std::lock_guard<std::mutex> lk(g_mu);
   const int rc = prof_drain();
   g_prof_on = enable != 0;
+  if (g_prof_on) g_clock_slot[0] = g_clock_slot[1] = nullptr;
   if (g_prof_on)
     for (int i = 0; i < TLORA_K_COUNT; ++i) {
       g_prof_ms[i] = 0.0;
@@ -710,6 +720,20 @@ int tlora_profile_read(int kernel_class, double* total_ms, int64_t* launches) {
   return TLORA_OK;
 }
 
+int tlora_profile_clock(double* ghz_fwd, double* ghz_bwd) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  double* out[2] = {ghz_fwd, ghz_bwd};
+  for (int i = 0; i < 2; ++i) {
+    if (!out[i]) continue;
+    *out[i] = 0.0;
+    if (!g_clock_slot[i]) continue;
+    unsigned long long h[2] = {0, 0};
+    if (hipMemcpy(h, g_clock_slot[i], sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) return TLORA_EHIP;
+    if (h[1] > 0) *out[i] = (double)h[0] / ((double)h[1] * 10.0);     // cycles per 10 ns tick -> GHz
+  }
+  return TLORA_OK;
+}
+
 int tlora_set_option(const char* name, int64_t value) {
   std::lock_guard<std::mutex> lk(g_mu);
   if (!name) return TLORA_ENULL;
@@ -717,6 +741,11 @@ int tlora_set_option(const char* name, int64_t value) {
   if (n == "shrink_rows") {
     if (value != 64 && value != 128) return TLORA_EINVAL;
     g_opt.shrink_rows = (int)value;
+    return TLORA_OK;
+  }
+  if (n == "gemm_waves") {
+    if (value != 4 && value != 8) return TLORA_EINVAL;
+    g_opt.gemm_waves = (int)value;
     return TLORA_OK;
   }
   if (n == "shrink_stages") {

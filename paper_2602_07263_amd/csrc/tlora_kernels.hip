@@ -452,12 +452,20 @@ struct GemmParams {
   int T, K, N;
   int ra;                   // R + 32: row stride of a_all
   int tiles_m, tiles_n;
+  unsigned long long* clk;  // optional: every 64th workgroup adds {cycles, 100 MHz ticks} of its K-loop (pre-zeroed)
 };
 
 // KTAIL: the instantiation for K % 32 != 0 carries the extra predicated step; keeping it out of the common one
 // keeps its register pressure (and spills) away from every tile.
-template <bool KN, bool KTAIL>
-__global__ void __launch_bounds__(512) seg_gemm_kernel(GemmParams P) {
+// NW: waves per workgroup.  8 = 2 x 4 waves of 128 x 64 (two waves per SIMD hide each other's latencies; the
+// default); 4 = 2 x 2 waves of 128 x 128 (256 accumulator registers per lane, a third less LDS read traffic per
+// flop, but every barrier wait idles the MFMA pipe: measured ~6 % slower).
+template <bool KN, bool KTAIL, int NW>
+__global__ void __launch_bounds__(NW * 64) seg_gemm_kernel(GemmParams P) {
+  constexpr int NT = NW * 64;                        // threads
+  constexpr int WCOLS = 256 / (NW / 2);              // output columns per wave: 64 or 128
+  constexpr int NJ = WCOLS / 32;                     // 32-wide column blocks per wave
+  constexpr int LD = 16 / NW;                        // 1 KB loads per wave per 16 KB tile
   constexpr int BM = kGemmBM, BN = kGemmBN, BK = kGemmBK;
   static_assert(BM == 256 && BN == 256 && BK == 32, "tile shape is baked into the index arithmetic below");
   constexpr int A_BYTES = BM * BK * 2;               // 16 KB; the weight tile has the same size
@@ -492,25 +500,25 @@ __global__ void __launch_bounds__(512) seg_gemm_kernel(GemmParams P) {
   const int rows_valid = min(BM, P.T - row0);
   const TileDev td = P.tiles[tm];
 
-  f32x16 acc[2][4];
+  f32x16 acc[NJ][4];
 #pragma unroll
-  for (int j = 0; j < 2; ++j)
+  for (int j = 0; j < NJ; ++j)
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.f;
 
-  auto load_frags = [&](const uint8_t* S, int kk, bf16x8 (&xf)[4], bf16x8 (&wf)[2]) {
+  auto load_frags = [&](const uint8_t* S, int kk, bf16x8 (&xf)[4], bf16x8 (&wf)[NJ]) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) xf[i] = frag_row32(S, wm * 128 + i * 32, kk, lane);
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
-      wf[j] = KN ? frag_kn_tile(S + A_BYTES, wn * 64 + j * 32, kk, lane)
-                 : frag_row32(S + A_BYTES, wn * 64 + j * 32, kk, lane);
+    for (int j = 0; j < NJ; ++j)
+      wf[j] = KN ? frag_kn_tile(S + A_BYTES, wn * WCOLS + j * 32, kk, lane)
+                 : frag_row32(S + A_BYTES, wn * WCOLS + j * 32, kk, lane);
   };
-  auto mma_slice = [&](const bf16x8 (&xf)[4], const bf16x8 (&wf)[2]) {
+  auto mma_slice = [&](const bf16x8 (&xf)[4], const bf16x8 (&wf)[NJ]) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < NJ; ++j)
 #pragma unroll
       for (int i = 0; i < 4; ++i) acc[j][i] = mfma32(wf[j], xf[i], acc[j][i]);
   };
@@ -523,14 +531,17 @@ __global__ void __launch_bounds__(512) seg_gemm_kernel(GemmParams P) {
   const int nfull = P.K / BK;
   const int next = td.kext / BK;
   const int nsteps = nfull + next;
+  const bool clocked = P.clk != nullptr && (blockIdx.x & 63) == 0;   // a sample of workgroups across the grid
+  unsigned long long cyc0 = 0, tick0 = 0;
+  if (clocked) { cyc0 = __builtin_readcyclecounter();  tick0 = __builtin_amdgcn_s_memrealtime(); }
   if (nsteps > 0) {
-    const uint16_t* asrc[2];
-    const uint16_t* bsrc[2];
-    const uint16_t* xa_src[2];
-    const uint16_t* xb_src[2];
+    const uint16_t* asrc[LD];
+    const uint16_t* bsrc[LD];
+    const uint16_t* xa_src[LD];
+    const uint16_t* xb_src[LD];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int p = (wave * 2 + i) * 64 + lane;          // 16-byte slot inside the 16 KB tile
+    for (int i = 0; i < LD; ++i) {
+      const int p = (wave * LD + i) * 64 + lane;          // 16-byte slot inside the 16 KB tile
       {
         const int r = p >> 2, c = (p & 3) ^ ((r >> 2) & 3);
         asrc[i] = P.act + (int64_t)(row0 + min(r, rows_valid - 1)) * P.K + c * 8;
@@ -551,18 +562,18 @@ __global__ void __launch_bounds__(512) seg_gemm_kernel(GemmParams P) {
     const int64_t bstep = KN ? (int64_t)BK * P.N : (int64_t)BK;   // same in both phases
     if (nfull == 0) {
 #pragma unroll
-      for (int i = 0; i < 2; ++i) { asrc[i] = xa_src[i];  bsrc[i] = xb_src[i]; }
+      for (int i = 0; i < LD; ++i) { asrc[i] = xa_src[i];  bsrc[i] = xb_src[i]; }
     }
     int issued = 0;
     auto issue = [&](uint8_t* S) {
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < LD; ++i)
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)asrc[i],
-                                         LDS_PTR(void, S + (wave * 2 + i) * 1024), 16, 0, 0);
+                                         LDS_PTR(void, S + (wave * LD + i) * 1024), 16, 0, 0);
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < LD; ++i)
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)bsrc[i],
-                                         LDS_PTR(void, S + A_BYTES + (wave * 2 + i) * 1024), 16, 0, 0);
+                                         LDS_PTR(void, S + A_BYTES + (wave * LD + i) * 1024), 16, 0, 0);
       // Next source: advance inside a phase, jump to the adapter operands after the last backbone step, and
       // stay put after the last step (the trailing issues re-load it into a stage nobody reads, which keeps
       // the count of outstanding loads uniform).  Selects, not branches: a branch here would make the
@@ -571,21 +582,21 @@ __global__ void __launch_bounds__(512) seg_gemm_kernel(GemmParams P) {
       const bool to_ext = issued == nfull && next > 0;
       const bool adv = issued < nsteps;
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
+      for (int i = 0; i < LD; ++i) {
         asrc[i] = to_ext ? xa_src[i] : asrc[i] + (adv ? BK : 0);
         bsrc[i] = to_ext ? xb_src[i] : bsrc[i] + (adv ? bstep : 0);
       }
     };
     auto landed = [&]() {
-      // Loads complete in order: with the 2 x 4 loads of the two younger steps still allowed in flight, this
+      // Loads complete in order: with the 2 x 2 LD loads of the two younger steps still allowed in flight, this
       // wave's loads of the current step have landed (and its own LDS reads of the stage about to be refilled
       // are done); after the barrier so have everyone else's.
-      __builtin_amdgcn_s_waitcnt(0x0078);   // vmcnt(8) lgkmcnt(0)
+      __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * 2 * LD));
       __builtin_amdgcn_s_barrier();
     };
     // one K-step (32 k-values = two MFMA k-slices) out of a stage
     auto compute = [&](const uint8_t* S) {
-      bf16x8 xa[4], wa[2], xb[4], wb[2];
+      bf16x8 xa[4], wa[NJ], xb[4], wb[NJ];
       load_frags(S, 0, xa, wa);
       load_frags(S, 1, xb, wb);
       mma_slice(xa, wa);
@@ -606,14 +617,19 @@ __global__ void __launch_bounds__(512) seg_gemm_kernel(GemmParams P) {
     if (kt + 2 < nsteps) { landed();  issue(st1);  compute(st2); }
     __builtin_amdgcn_s_waitcnt(0x0070);     // vmcnt(0): the trailing re-loads must not land in reused LDS
   }
+  if (clocked && tid == 0) {
+    atomicAdd(&P.clk[0], __builtin_readcyclecounter() - cyc0);        // integer sums: order does not matter
+    atomicAdd(&P.clk[1], __builtin_amdgcn_s_memrealtime() - tick0);
+  }
 
   // ---- K tail (K % 32 != 0): one register-staged, predicated step through stage 0 ---------------------------
   if (KTAIL) {
     const int k0 = nfull * BK, kvalid = P.K - k0;
-    u32x4 areg[2], breg[2];
+    constexpr int TCH = 1024 / NT;          // 16-byte chunks per thread and tile
+    u32x4 areg[TCH], breg[TCH];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int id = tid + i * 512, r = id >> 2, c = id & 3;
+    for (int i = 0; i < TCH; ++i) {
+      const int id = tid + i * NT, r = id >> 2, c = id & 3;
       const bool ok = r < rows_valid && c * 8 < kvalid;
       areg[i] = ok ? ldg16(P.act + (int64_t)(row0 + r) * P.K + k0 + c * 8) : u32x4{0, 0, 0, 0};
       if (KN) {
@@ -627,8 +643,8 @@ __global__ void __launch_bounds__(512) seg_gemm_kernel(GemmParams P) {
     }
     __syncthreads();                       // every wave is done reading stage 0
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int id = tid + i * 512;
+    for (int i = 0; i < TCH; ++i) {
+      const int id = tid + i * NT;
       *reinterpret_cast<u32x4*>(st0 + row32_off(id >> 2, id & 3)) = areg[i];
       if (KN) *reinterpret_cast<u32x4*>(st0 + A_BYTES + kn_tile_off(id >> 5, id & 31)) = breg[i];
       else    *reinterpret_cast<u32x4*>(st0 + A_BYTES + row32_off(id >> 2, id & 3)) = breg[i];
@@ -636,7 +652,7 @@ __global__ void __launch_bounds__(512) seg_gemm_kernel(GemmParams P) {
     __syncthreads();
     const int nkk = (kvalid + 15) >> 4;
     for (int kk = 0; kk < nkk; ++kk) {
-      bf16x8 xf[4], wf[2];
+      bf16x8 xf[4], wf[NJ];
       load_frags(st0, kk, xf, wf);
       mma_slice(xf, wf);
     }
@@ -651,20 +667,21 @@ __global__ void __launch_bounds__(512) seg_gemm_kernel(GemmParams P) {
     const int R = wm * 128 + i * 32 + (lane & 31);
     uint8_t* const orow = obuf + (R & 63) * 512 + (lane >> 5) * 8;
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < NJ; ++j)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const int c = wn * 8 + j * 4 + g;
+        const int c = wn * (WCOLS / 8) + j * 4 + g;
         u32x2 v = {pack_bf16x2(acc[j][i][g * 4 + 0], acc[j][i][g * 4 + 1]),
                    pack_bf16x2(acc[j][i][g * 4 + 2], acc[j][i][g * 4 + 3])};
         *reinterpret_cast<u32x2*>(orow + ((c ^ (R & 31)) << 4)) = v;
       }
   }
   __syncthreads();
+  constexpr int RPI = NT / 32;              // output rows per iteration
 #pragma unroll
-  for (int it = 0; it < 16; ++it) {
-    const uint8_t* const obuf = it < 4 ? st0 : it < 8 ? st1 : it < 12 ? st2 : st3;
-    const int R = (tid >> 5) + it * 16, c = tid & 31;
+  for (int it = 0; it < 256 / RPI; ++it) {
+    const uint8_t* const obuf = it * RPI < 64 ? st0 : it * RPI < 128 ? st1 : it * RPI < 192 ? st2 : st3;
+    const int R = (tid >> 5) + it * RPI, c = tid & 31;
     const u32x4 v = *reinterpret_cast<const u32x4*>(obuf + (R & 63) * 512 + ((c ^ (R & 31)) << 4));
     if (R < rows_valid && col0 + c * 8 < P.N)
       *reinterpret_cast<u32x4*>(P.out + (int64_t)(row0 + R) * P.N + col0 + c * 8) = v;
@@ -672,8 +689,10 @@ __global__ void __launch_bounds__(512) seg_gemm_kernel(GemmParams P) {
 }
 
 void launch_seg_gemm(bool w_is_kn, const TileDev* tiles, const uint16_t* act, const uint16_t* W, const uint16_t* Sx,
-                     const uint16_t* packed, int r_total, uint16_t* out, int T, int K, int N, hipStream_t st) {
+                     const uint16_t* packed, int r_total, uint16_t* out, int T, int K, int N, int waves,
+                     unsigned long long* clk, hipStream_t st) {
   GemmParams P;
+  P.clk = clk;
   P.tiles = tiles;  P.act = act;  P.W = W;  P.Sx = Sx;  P.packed = packed;  P.out = out;
   P.T = T;  P.K = K;  P.N = N;  P.ra = r_total + 32;
   P.tiles_m = (T + kGemmBM - 1) / kGemmBM;
@@ -681,13 +700,16 @@ void launch_seg_gemm(bool w_is_kn, const TileDev* tiles, const uint16_t* act, co
   const int nb = P.tiles_m * P.tiles_n;
   if (nb == 0) return;
   const bool tail = K % kGemmBK != 0;
-  if (w_is_kn) {
-    if (tail) hipLaunchKernelGGL((seg_gemm_kernel<true, true>), dim3(nb), dim3(512), 0, st, P);
-    else      hipLaunchKernelGGL((seg_gemm_kernel<true, false>), dim3(nb), dim3(512), 0, st, P);
+#define TLORA_GEMM_LAUNCH(KN, TAIL, NW) \
+  hipLaunchKernelGGL((seg_gemm_kernel<KN, TAIL, NW>), dim3(nb), dim3(NW * 64), 0, st, P)
+  if (waves == 4) {
+    if (w_is_kn) { if (tail) TLORA_GEMM_LAUNCH(true, true, 4);  else TLORA_GEMM_LAUNCH(true, false, 4); }
+    else         { if (tail) TLORA_GEMM_LAUNCH(false, true, 4); else TLORA_GEMM_LAUNCH(false, false, 4); }
   } else {
-    if (tail) hipLaunchKernelGGL((seg_gemm_kernel<false, true>), dim3(nb), dim3(512), 0, st, P);
-    else      hipLaunchKernelGGL((seg_gemm_kernel<false, false>), dim3(nb), dim3(512), 0, st, P);
+    if (w_is_kn) { if (tail) TLORA_GEMM_LAUNCH(true, true, 8);  else TLORA_GEMM_LAUNCH(true, false, 8); }
+    else         { if (tail) TLORA_GEMM_LAUNCH(false, true, 8); else TLORA_GEMM_LAUNCH(false, false, 8); }
   }
+#undef TLORA_GEMM_LAUNCH
 }
 
 // ---------------------------------------------------------------------------------------------------

@@ -33,7 +33,7 @@ class tlora_problem_t(ctypes.Structure):
 
 
 EXPORTS = ["tlora_workspace_bytes", "tlora_fwd", "tlora_bwd", "tlora_plan_dump", "tlora_set_option",
-           "tlora_profile", "tlora_profile_read", "tlora_strerror", "tlora_version"]
+           "tlora_profile", "tlora_profile_read", "tlora_profile_clock", "tlora_strerror", "tlora_version"]
 KERNEL_CLASSES = ["pack", "shrink", "gemm_fwd", "gemm_bwd", "rank_grad", "grad_reduce", "f32"]
 
 
@@ -66,6 +66,8 @@ def lib() -> ctypes.CDLL:
     L.tlora_profile.argtypes = [ctypes.c_int]
     L.tlora_profile_read.restype = ctypes.c_int
     L.tlora_profile_read.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+    L.tlora_profile_clock.restype = ctypes.c_int
+    L.tlora_profile_clock.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
     L.tlora_strerror.restype = ctypes.c_char_p
     L.tlora_strerror.argtypes = [ctypes.c_int]
     L.tlora_version.restype = ctypes.c_char_p
@@ -103,6 +105,13 @@ def tlora_profile_read() -> dict:
         _check(lib().tlora_profile_read(i, ctypes.byref(ms), ctypes.byref(n)), "tlora_profile_read")
         out[name] = (float(ms.value), int(n.value))
     return out
+
+
+def tlora_profile_clock():
+    """(GHz seen by the last profiled forward GEMM, GHz seen by the last profiled dX GEMM); 0.0 = none yet."""
+    a, b = ctypes.c_double(0.0), ctypes.c_double(0.0)
+    _check(lib().tlora_profile_clock(ctypes.byref(a), ctypes.byref(b)), "tlora_profile_clock")
+    return float(a.value), float(b.value)
 
 
 def make_problem(dtype: int, d_in: int, d_out: int, ranks: Sequence[int], offsets: Sequence[int],

@@ -98,3 +98,45 @@ def test_full_size_configs_sampled(cfg, proj):
     Y, dX, dA, dB, lp = pu.run_gpu(p)
     rows = pu.sample_rows(p.offsets, 256, np.random.default_rng(cfg * 10 + proj))
     _assert_ok(pu.compare(p, Y, dX, dA, dB, rows=rows), f"cfg{cfg}/{wl.projections[proj].name}")
+
+
+DEFAULT_OPTIONS = {"gemm_waves": 8, "shrink_rows": 128, "shrink_stages": 4, "grad_tokens": 256}
+TILINGS = [
+    {"gemm_waves": 4},
+    {"shrink_rows": 64, "shrink_stages": 8},
+    {"grad_tokens": 64},
+    {"grad_tokens": 2048, "shrink_rows": 64, "gemm_waves": 4},
+]
+
+
+@pytest.mark.parametrize("opts", TILINGS, ids=["-".join(f"{k}{v}" for k, v in o.items()) for o in TILINGS])
+def test_results_do_not_depend_on_the_tiling(opts):
+    """Nano-batch shapes (workgroup layout of the GEMM, token rows per shrink unit, token chunk of the dA / dB
+    reduction) change the summation order only: every tiling must meet the oracle tolerance (Sec. 3.3: the
+    nano-batch size is a performance knob, not part of the result)."""
+    from paper_2602_07263_amd import tlora
+    p = wk.generate(wk.custom("tiling", "bf16", 384, 640, [1, 12, 256, 40, 130], [300, 17, 700, 1, 520],
+                              [0.5, 2.0, 1.0, 4.0, 2.0]), seed=21)
+    try:
+        for k, v in opts.items():
+            tlora.tlora_set_option(k, v)
+        Y, dX, dA, dB, _ = pu.run_gpu(p, reuse_S=False)
+        _assert_ok(pu.compare(p, Y, dX, dA, dB), f"tiling {opts}")
+    finally:
+        for k, v in DEFAULT_OPTIONS.items():
+            tlora.tlora_set_option(k, v)
+
+
+def test_kernel_timing_hooks_count_every_launch():
+    from paper_2602_07263_amd import tlora
+    p = wk.generate(wk.custom("prof", "bf16", 128, 256, [8, 16], [100, 200]), seed=4)
+    tlora.tlora_profile(True)
+    try:
+        pu.run_gpu(p, reuse_S=True)
+        prof = tlora.tlora_profile_read()
+    finally:
+        tlora.tlora_profile(False)
+    assert prof["gemm_fwd"][1] == 1 and prof["gemm_bwd"][1] == 1
+    assert prof["shrink"][1] == 2 and prof["rank_grad"][1] == 2 and prof["grad_reduce"][1] == 2
+    assert prof["pack"][1] == 2 and prof["f32"][1] == 0
+    assert all(ms >= 0.0 for ms, _ in prof.values()) and prof["gemm_fwd"][0] > 0.0
