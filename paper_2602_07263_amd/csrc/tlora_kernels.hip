@@ -281,12 +281,12 @@ __global__ void __launch_bounds__(256) shrink_kernel(const JobDev* __restrict__ 
 constexpr int waitcnt_vm_lgkm0(int vm) { return (vm & 15) | ((vm >> 4) << 14) | 0x0070; }
 
 // ---------------------------------------------------------------------------------------------------
-// Shrink, streaming version (needs K % 32 == 0): one workgroup = ROWS token rows of one job x up to 128 padded
+// Shrink, streaming version (needs K % KS == 0, KS = 32 or 64 k-values per step): one workgroup = ROWS token rows of one job x up to 128 padded
 // rank columns.  K-steps of 32; a stage holds the activation tile (ROWS x 32) and the adapter tile
 // (128 x 32); NS stages are filled NS - 1 steps ahead by raw asynchronous global->LDS loads, so several KB
 // per wave stay in flight without holding registers -- the kernel is bound by how fast X (or dY) streams in.
 // ---------------------------------------------------------------------------------------------------
-template <int ROWS, int NS>
+template <int ROWS, int NS, int KS>
 __global__ void __launch_bounds__(256) shrink_stream_kernel(const JobDev* __restrict__ jobs,
                                                             const TileDev* __restrict__ tiles,
                                                             const ShrinkUnit* __restrict__ units,
@@ -297,7 +297,9 @@ __global__ void __launch_bounds__(256) shrink_stream_kernel(const JobDev* __rest
   constexpr int PCOLS = 128;                       // padded rank columns per unit
   constexpr int WM = ROWS / 32, WN = 4 / WM;       // waves along token rows / along rank columns
   constexpr int PW = PCOLS / WN, NPB = PW / 32;    // rank columns (and 32-wide blocks) per wave
-  constexpr int A_BYTES = ROWS * 64, P_BYTES = PCOLS * 64, STAGE = A_BYTES + P_BYTES;
+  constexpr int RB = KS * 2;                       // bytes per tile row: 64 (K-steps of 32) or 128 (of 64)
+  constexpr int CPR = RB / 16;                     // 16-byte chunks per tile row
+  constexpr int A_BYTES = ROWS * RB, P_BYTES = PCOLS * RB, STAGE = A_BYTES + P_BYTES;
   constexpr int A_LD = A_BYTES / 1024 / 4, P_LD = P_BYTES / 1024 / 4;   // loads per wave per step
   static_assert(kGemmBM == 256, "the row -> GEMM tile lookup below shifts by 8");
   __shared__ __attribute__((aligned(1024))) uint8_t lds[NS * STAGE];
@@ -311,7 +313,7 @@ __global__ void __launch_bounds__(256) shrink_stream_kernel(const JobDev* __rest
   const int pvalid = min(PCOLS, jb.rpad - p0);     // > 0 by construction
   const uint16_t* P = packed + (packed_is_atp ? jb.atp_off : (int64_t)jb.roff * K) + (int64_t)p0 * K;
   const uint16_t* Arow = act + (int64_t)u.t0 * K;
-  const int nsteps = K / 32;
+  const int nsteps = K / KS;
 
   f32x16 acc[NPB];
 #pragma unroll
@@ -327,12 +329,14 @@ __global__ void __launch_bounds__(256) shrink_stream_kernel(const JobDev* __rest
                            // columns); lane 0 always fetches so every wave issues the same number of loads
 #pragma unroll
   for (int i = 0; i < A_LD; ++i) {
-    const int q = (wave * A_LD + i) * 64 + lane, r = q >> 2, c = (q & 3) ^ ((r >> 2) & 3);
+    const int q = (wave * A_LD + i) * 64 + lane, r = q / CPR;
+    const int c = KS == 32 ? (q & 3) ^ ((r >> 2) & 3) : (q & 7) ^ ((r >> 1) & 7);
     asrc[i] = Arow + (int64_t)min(r, u.nrows - 1) * K + c * 8;
   }
 #pragma unroll
   for (int i = 0; i < P_LD; ++i) {
-    const int q = (wave * P_LD + i) * 64 + lane, r = q >> 2, c = (q & 3) ^ ((r >> 2) & 3);
+    const int q = (wave * P_LD + i) * 64 + lane, r = q / CPR;
+    const int c = KS == 32 ? (q & 3) ^ ((r >> 2) & 3) : (q & 7) ^ ((r >> 1) & 7);
     psrc[i] = P + (int64_t)min(r, pvalid - 1) * K + c * 8;
     plive[i] = r < pvalid || lane == 0;
   }
@@ -342,10 +346,10 @@ __global__ void __launch_bounds__(256) shrink_stream_kernel(const JobDev* __rest
     const int st = min(f_step, nsteps - 1);        // trailing issues re-load the last step (uniform load count)
     const uint32_t base = lds0 + (f_step % NS) * STAGE;
 #pragma unroll
-    for (int i = 0; i < A_LD; ++i) dma16(asrc[i] + st * 32, base + (wave * A_LD + i) * 1024);
+    for (int i = 0; i < A_LD; ++i) dma16(asrc[i] + st * KS, base + (wave * A_LD + i) * 1024);
 #pragma unroll
     for (int i = 0; i < P_LD; ++i)
-      if (plive[i]) dma16(psrc[i] + st * 32, base + A_BYTES + (wave * P_LD + i) * 1024);
+      if (plive[i]) dma16(psrc[i] + st * KS, base + A_BYTES + (wave * P_LD + i) * 1024);
     ++f_step;
   };
   for (int i = 0; i < NS - 1; ++i) issue();
@@ -356,11 +360,12 @@ __global__ void __launch_bounds__(256) shrink_stream_kernel(const JobDev* __rest
     issue();                                       // into the stage read in step kt - 1
     const uint8_t* S = lds + (kt % NS) * STAGE;
 #pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
-      const bf16x8 xf = frag_row32(S, wm * 32, kk, lane);
+    for (int kk = 0; kk < KS / 16; ++kk) {
+      const bf16x8 xf = KS == 32 ? frag_row32(S, wm * 32, kk, lane) : frag_row_tile(S, wm * 32, kk, lane);
 #pragma unroll
       for (int i = 0; i < NPB; ++i) {
-        const bf16x8 pf = frag_row32(S + A_BYTES, wn * PW + i * 32, kk, lane);
+        const bf16x8 pf = KS == 32 ? frag_row32(S + A_BYTES, wn * PW + i * 32, kk, lane)
+                                   : frag_row_tile(S + A_BYTES, wn * PW + i * 32, kk, lane);
         acc[i] = mfma32(pf, xf, acc[i]);
       }
     }
@@ -417,15 +422,18 @@ void launch_shrink_stream(const JobDev* jobs, const TileDev* tiles, const Shrink
                           bool packed_is_atp, uint16_t* S_hi, uint16_t* S_lo, uint16_t* Sx, hipStream_t st) {
   if (num_units == 0) return;
   const int atp = packed_is_atp ? 1 : 0;
-#define TLORA_SHRINK_LAUNCH(R, N)                                                                                     \
-  hipLaunchKernelGGL((shrink_stream_kernel<R, N>), dim3(num_units), dim3(256), 0, st, jobs, tiles, units, act, K, packed, \
-                     atp, S_hi, S_lo, Sx)
+#define TLORA_SHRINK_LAUNCH(R, N, KS)                                                                                  \
+  hipLaunchKernelGGL((shrink_stream_kernel<R, N, KS>), dim3(num_units), dim3(256), 0, st, jobs, tiles, units, act, K,  \
+                     packed, atp, S_hi, S_lo, Sx)
+  const bool wide = K % 64 == 0 && stages < 8;      // K-steps of 64: half as many barriers per byte
   if (shrink_rows == 128) {
-    if (stages >= 8) TLORA_SHRINK_LAUNCH(128, 8);
-    else             TLORA_SHRINK_LAUNCH(128, 4);
+    if (wide)             TLORA_SHRINK_LAUNCH(128, 4, 64);
+    else if (stages >= 8) TLORA_SHRINK_LAUNCH(128, 8, 32);
+    else                  TLORA_SHRINK_LAUNCH(128, 4, 32);
   } else {
-    if (stages >= 8) TLORA_SHRINK_LAUNCH(64, 8);
-    else             TLORA_SHRINK_LAUNCH(64, 4);
+    if (wide)             TLORA_SHRINK_LAUNCH(64, 4, 64);
+    else if (stages >= 8) TLORA_SHRINK_LAUNCH(64, 8, 32);
+    else                  TLORA_SHRINK_LAUNCH(64, 4, 32);
   }
 #undef TLORA_SHRINK_LAUNCH
 }
