@@ -20,6 +20,7 @@ struct Options {
   int shrink_stages = 4;
   int grad_tokens = 256;
   int gemm_waves = 8;
+  int gemm_k_step = 32;
 };
 Options g_opt;
 std::mutex g_mu;
@@ -238,8 +239,9 @@ int build_plan(const tlora_problem_t* p, Plan& pl) {
     pl.off_Slo = wplace(2 * (size_t)pl.s_elems);
     pl.off_dShi = wplace(2 * (size_t)pl.s_elems);
     pl.off_dSlo = wplace(2 * (size_t)pl.s_elems);
-    pl.off_Sx = wplace(2 * (size_t)pl.sx_elems);
-    pl.off_dSx = wplace(2 * (size_t)pl.sx_elems);
+    // + 256: a 64-wide K-step over a last 32-wide slice reads (and ignores) 64 bytes past each operand row
+    pl.off_Sx = wplace(2 * (size_t)pl.sx_elems + 256);
+    pl.off_dSx = wplace(2 * (size_t)pl.sx_elems + 256);
     pl.off_atp = wplace(2 * (size_t)pl.atp_elems);
     pl.off_ap = wplace(2 * (size_t)pl.d_in * (size_t)(pl.r_total + 32));
     pl.off_bp = wplace(2 * (size_t)pl.d_out * (size_t)(pl.r_total + 32));
@@ -519,7 +521,7 @@ int tlora_fwd(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_byte
   if (g_prof_on) launch_zero_fill(ws + pl.off_clock, 16, st);
   Timed tg(TLORA_K_GEMM_FWD, st);
   launch_seg_gemm(true, tiles, static_cast<const uint16_t*>(p->X), static_cast<const uint16_t*>(p->W), Sx, bp,
-                  pl.r_total, static_cast<uint16_t*>(Y), pl.T, pl.d_in, pl.d_out, g_opt.gemm_waves,
+                  pl.r_total, static_cast<uint16_t*>(Y), pl.T, pl.d_in, pl.d_out, g_opt.gemm_waves, g_opt.gemm_k_step,
                   g_prof_on ? (g_clock_slot[0] = reinterpret_cast<unsigned long long*>(ws + pl.off_clock)) : nullptr, st);
   return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
 }
@@ -638,7 +640,7 @@ int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* d
       if (g_prof_on) launch_zero_fill(ws + pl.off_clock + 16, 16, st);
       Timed t(TLORA_K_GEMM_BWD, st);
       launch_seg_gemm(false, tiles, dYb, static_cast<const uint16_t*>(p->W), dSx, ap, pl.r_total,
-                      static_cast<uint16_t*>(dX), pl.T, pl.d_out, pl.d_in, g_opt.gemm_waves,
+                      static_cast<uint16_t*>(dX), pl.T, pl.d_out, pl.d_in, g_opt.gemm_waves, g_opt.gemm_k_step,
                       g_prof_on ? (g_clock_slot[1] = reinterpret_cast<unsigned long long*>(ws + pl.off_clock) + 2) : nullptr,
                       st);
     }
@@ -746,6 +748,11 @@ int tlora_set_option(const char* name, int64_t value) {
   if (n == "gemm_waves") {
     if (value != 4 && value != 8) return TLORA_EINVAL;
     g_opt.gemm_waves = (int)value;
+    return TLORA_OK;
+  }
+  if (n == "gemm_k_step") {
+    if (value != 32 && value != 64) return TLORA_EINVAL;
+    g_opt.gemm_k_step = (int)value;
     return TLORA_OK;
   }
   if (n == "shrink_stages") {

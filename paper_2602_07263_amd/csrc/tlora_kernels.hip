@@ -468,16 +468,20 @@ struct GemmParams {
 // NW: waves per workgroup.  8 = 2 x 4 waves of 128 x 64 (two waves per SIMD hide each other's latencies; the
 // default); 4 = 2 x 2 waves of 128 x 128 (256 accumulator registers per lane, a third less LDS read traffic per
 // flop, but every barrier wait idles the MFMA pipe: measured ~6 % slower).
-template <bool KN, bool KTAIL, int NW>
+// BK: k-values per step.  32: four stages of 32 KB, loads three steps ahead.  64 (needs K % 64 == 0): two stages of
+// 64 KB, loads one step ahead; every row of a k-contiguous operand is then fetched as a whole 128-byte line
+// and there are half as many barriers.
+template <bool KN, bool KTAIL, int NW, int BK>
 __global__ void __launch_bounds__(NW * 64) seg_gemm_kernel(GemmParams P) {
   constexpr int NT = NW * 64;                        // threads
   constexpr int WCOLS = 256 / (NW / 2);              // output columns per wave: 64 or 128
   constexpr int NJ = WCOLS / 32;                     // 32-wide column blocks per wave
-  constexpr int LD = 16 / NW;                        // 1 KB loads per wave per 16 KB tile
-  constexpr int BM = kGemmBM, BN = kGemmBN, BK = kGemmBK;
-  static_assert(BM == 256 && BN == 256 && BK == 32, "tile shape is baked into the index arithmetic below");
-  constexpr int A_BYTES = BM * BK * 2;               // 16 KB; the weight tile has the same size
-  constexpr int STAGE_BYTES = 2 * A_BYTES;           // 32 KB
+  constexpr int BM = kGemmBM, BN = kGemmBN;
+  static_assert(BM == 256 && BN == 256 && (BK == 32 || BK == 64), "tile shape is baked into the index arithmetic");
+  static_assert(!(KTAIL && BK == 64), "the K tail goes with K-steps of 32");
+  constexpr int A_BYTES = BM * BK * 2;               // 16 | 32 KB; the weight tile has the same size
+  constexpr int LD = A_BYTES / 1024 / NW;            // 1 KB loads per wave per tile
+  constexpr int STAGE_BYTES = 32768;                 // BK = 32: one stage per array; BK = 64: one tile per array
   // Four stages as four separate arrays: the compiler tells an in-flight global->LDS load into one stage
   // from LDS reads of another only when they are distinct objects.
   __shared__ __attribute__((aligned(1024))) uint8_t st0[STAGE_BYTES];
@@ -516,13 +520,15 @@ __global__ void __launch_bounds__(NW * 64) seg_gemm_kernel(GemmParams P) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.f;
 
-  auto load_frags = [&](const uint8_t* S, int kk, bf16x8 (&xf)[4], bf16x8 (&wf)[NJ]) {
+  auto load_frags = [&](const uint8_t* SA, const uint8_t* SB, int kk, bf16x8 (&xf)[4], bf16x8 (&wf)[NJ]) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) xf[i] = frag_row32(S, wm * 128 + i * 32, kk, lane);
+    for (int i = 0; i < 4; ++i)
+      xf[i] = BK == 32 ? frag_row32(SA, wm * 128 + i * 32, kk, lane) : frag_row_tile(SA, wm * 128 + i * 32, kk, lane);
 #pragma unroll
     for (int j = 0; j < NJ; ++j)
-      wf[j] = KN ? frag_kn_tile(S + A_BYTES, wn * WCOLS + j * 32, kk, lane)
-                 : frag_row32(S + A_BYTES, wn * WCOLS + j * 32, kk, lane);
+      wf[j] = KN         ? frag_kn_tile(SB, wn * WCOLS + j * 32, kk, lane)
+              : BK == 32 ? frag_row32(SB, wn * WCOLS + j * 32, kk, lane)
+                         : frag_row_tile(SB, wn * WCOLS + j * 32, kk, lane);
   };
   auto mma_slice = [&](const bf16x8 (&xf)[4], const bf16x8 (&wf)[NJ]) {
 #pragma unroll
@@ -537,7 +543,8 @@ __global__ void __launch_bounds__(NW * 64) seg_gemm_kernel(GemmParams P) {
   // stored.  The adapter steps read the tile's dense [256, kext] operand (rows of other jobs are stored zeros)
   // against rows roff_first.. of b_all (forward) or columns roff_first.. of a_all (backward).
   const int nfull = P.K / BK;
-  const int next = td.kext / BK;
+  const int next = (td.kext + BK - 1) / BK;          // BK = 64: the last adapter step may hold only 32 k-values
+  const bool half_last = BK == 64 && (td.kext & 32) != 0;
   const int nsteps = nfull + next;
   const bool clocked = P.clk != nullptr && (blockIdx.x & 63) == 0;   // a sample of workgroups across the grid
   unsigned long long cyc0 = 0, tick0 = 0;
@@ -549,9 +556,10 @@ __global__ void __launch_bounds__(NW * 64) seg_gemm_kernel(GemmParams P) {
     const uint16_t* xb_src[LD];
 #pragma unroll
     for (int i = 0; i < LD; ++i) {
-      const int p = (wave * LD + i) * 64 + lane;          // 16-byte slot inside the 16 KB tile
+      const int p = (wave * LD + i) * 64 + lane;          // 16-byte slot inside the tile
       {
-        const int r = p >> 2, c = (p & 3) ^ ((r >> 2) & 3);
+        const int r = BK == 32 ? p >> 2 : p >> 3;
+        const int c = BK == 32 ? (p & 3) ^ ((r >> 2) & 3) : (p & 7) ^ ((r >> 1) & 7);
         asrc[i] = P.act + (int64_t)(row0 + min(r, rows_valid - 1)) * P.K + c * 8;
         xa_src[i] = P.Sx + td.aoff + (int64_t)r * td.kext + c * 8;      // all 256 rows of the operand exist
       }
@@ -561,7 +569,8 @@ __global__ void __launch_bounds__(NW * 64) seg_gemm_kernel(GemmParams P) {
         bsrc[i] = P.W + (int64_t)k * P.N + col;
         xb_src[i] = P.packed + (int64_t)(td.roff_first + k) * P.N + col;
       } else {
-        const int n = p >> 2, c = (p & 3) ^ ((n >> 2) & 3);
+        const int n = BK == 32 ? p >> 2 : p >> 3;
+        const int c = BK == 32 ? (p & 3) ^ ((n >> 2) & 3) : (p & 7) ^ ((n >> 1) & 7);
         const int nn = min(col0 + n, P.N - 1);
         bsrc[i] = P.W + (int64_t)nn * P.K + c * 8;
         xb_src[i] = P.packed + (int64_t)nn * P.ra + td.roff_first + c * 8;
@@ -573,15 +582,15 @@ __global__ void __launch_bounds__(NW * 64) seg_gemm_kernel(GemmParams P) {
       for (int i = 0; i < LD; ++i) { asrc[i] = xa_src[i];  bsrc[i] = xb_src[i]; }
     }
     int issued = 0;
-    auto issue = [&](uint8_t* S) {
+    auto issue = [&](uint8_t* SA, uint8_t* SB) {
 #pragma unroll
       for (int i = 0; i < LD; ++i)
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)asrc[i],
-                                         LDS_PTR(void, S + (wave * LD + i) * 1024), 16, 0, 0);
+                                         LDS_PTR(void, SA + (wave * LD + i) * 1024), 16, 0, 0);
 #pragma unroll
       for (int i = 0; i < LD; ++i)
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)bsrc[i],
-                                         LDS_PTR(void, S + A_BYTES + (wave * LD + i) * 1024), 16, 0, 0);
+                                         LDS_PTR(void, SB + (wave * LD + i) * 1024), 16, 0, 0);
       // Next source: advance inside a phase, jump to the adapter operands after the last backbone step, and
       // stay put after the last step (the trailing issues re-load it into a stage nobody reads, which keeps
       // the count of outstanding loads uniform).  Selects, not branches: a branch here would make the
@@ -595,34 +604,62 @@ __global__ void __launch_bounds__(NW * 64) seg_gemm_kernel(GemmParams P) {
         bsrc[i] = to_ext ? xb_src[i] : bsrc[i] + (adv ? bstep : 0);
       }
     };
-    auto landed = [&]() {
-      // Loads complete in order: with the 2 x 2 LD loads of the two younger steps still allowed in flight, this
-      // wave's loads of the current step have landed (and its own LDS reads of the stage about to be refilled
-      // are done); after the barrier so have everyone else's.
-      __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * 2 * LD));
-      __builtin_amdgcn_s_barrier();
-    };
-    // one K-step (32 k-values = two MFMA k-slices) out of a stage
-    auto compute = [&](const uint8_t* S) {
-      bf16x8 xa[4], wa[NJ], xb[4], wb[NJ];
-      load_frags(S, 0, xa, wa);
-      load_frags(S, 1, xb, wb);
-      mma_slice(xa, wa);
-      mma_slice(xb, wb);
-    };
-    issue(st0);
-    issue(st1);
-    issue(st2);
-    int kt = 0;
-    for (; kt + 4 <= nsteps; kt += 4) {
-      landed();  issue(st3);  compute(st0);
-      landed();  issue(st0);  compute(st1);
-      landed();  issue(st1);  compute(st2);
-      landed();  issue(st2);  compute(st3);
+    if constexpr (BK == 32) {
+      auto landed = [&]() {
+        // Loads complete in order: with the 2 x 2 LD loads of the two younger steps still allowed in flight, this
+        // wave's loads of the current step have landed (and its own LDS reads of the stage about to be refilled
+        // are done); after the barrier so have everyone else's.
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * 2 * LD));
+        __builtin_amdgcn_s_barrier();
+      };
+      // one K-step (32 k-values = two MFMA k-slices) out of a stage
+      auto compute = [&](const uint8_t* S) {
+        bf16x8 xa[4], wa[NJ], xb[4], wb[NJ];
+        load_frags(S, S + A_BYTES, 0, xa, wa);
+        load_frags(S, S + A_BYTES, 1, xb, wb);
+        mma_slice(xa, wa);
+        mma_slice(xb, wb);
+      };
+      issue(st0, st0 + A_BYTES);
+      issue(st1, st1 + A_BYTES);
+      issue(st2, st2 + A_BYTES);
+      int kt = 0;
+      for (; kt + 4 <= nsteps; kt += 4) {
+        landed();  issue(st3, st3 + A_BYTES);  compute(st0);
+        landed();  issue(st0, st0 + A_BYTES);  compute(st1);
+        landed();  issue(st1, st1 + A_BYTES);  compute(st2);
+        landed();  issue(st2, st2 + A_BYTES);  compute(st3);
+      }
+      if (kt < nsteps)     { landed();  issue(st3, st3 + A_BYTES);  compute(st0); }
+      if (kt + 1 < nsteps) { landed();  issue(st0, st0 + A_BYTES);  compute(st1); }
+      if (kt + 2 < nsteps) { landed();  issue(st1, st1 + A_BYTES);  compute(st2); }
+    } else {
+      auto landed = [&]() {               // nothing younger is in flight: the step's loads are the only ones
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
+        __builtin_amdgcn_s_barrier();
+      };
+      // one K-step (64 k-values = four MFMA k-slices; two when only the first half of the step is valid)
+      auto compute = [&](const uint8_t* SA, const uint8_t* SB, bool half) {
+        bf16x8 xa[4], wa[NJ], xb[4], wb[NJ];
+        load_frags(SA, SB, 0, xa, wa);
+        load_frags(SA, SB, 1, xb, wb);
+        mma_slice(xa, wa);
+        mma_slice(xb, wb);
+        if (!half) {
+          load_frags(SA, SB, 2, xa, wa);
+          load_frags(SA, SB, 3, xb, wb);
+          mma_slice(xa, wa);
+          mma_slice(xb, wb);
+        }
+      };
+      issue(st0, st1);
+      int kt = 0;
+      for (; kt + 2 <= nsteps; kt += 2) {
+        landed();  issue(st2, st3);  compute(st0, st1, false);
+        landed();  issue(st0, st1);  compute(st2, st3, half_last && kt + 2 == nsteps);
+      }
+      if (kt < nsteps) { landed();  issue(st2, st3);  compute(st0, st1, half_last); }
     }
-    if (kt < nsteps)     { landed();  issue(st3);  compute(st0); }
-    if (kt + 1 < nsteps) { landed();  issue(st0);  compute(st1); }
-    if (kt + 2 < nsteps) { landed();  issue(st1);  compute(st2); }
     __builtin_amdgcn_s_waitcnt(0x0070);     // vmcnt(0): the trailing re-loads must not land in reused LDS
   }
   if (clocked && tid == 0) {
@@ -661,7 +698,7 @@ __global__ void __launch_bounds__(NW * 64) seg_gemm_kernel(GemmParams P) {
     const int nkk = (kvalid + 15) >> 4;
     for (int kk = 0; kk < nkk; ++kk) {
       bf16x8 xf[4], wf[NJ];
-      load_frags(st0, kk, xf, wf);
+      load_frags(st0, st0 + A_BYTES, kk, xf, wf);
       mma_slice(xf, wf);
     }
   }
@@ -697,7 +734,7 @@ __global__ void __launch_bounds__(NW * 64) seg_gemm_kernel(GemmParams P) {
 }
 
 void launch_seg_gemm(bool w_is_kn, const TileDev* tiles, const uint16_t* act, const uint16_t* W, const uint16_t* Sx,
-                     const uint16_t* packed, int r_total, uint16_t* out, int T, int K, int N, int waves,
+                     const uint16_t* packed, int r_total, uint16_t* out, int T, int K, int N, int waves, int bk,
                      unsigned long long* clk, hipStream_t st) {
   GemmParams P;
   P.clk = clk;
@@ -708,14 +745,17 @@ void launch_seg_gemm(bool w_is_kn, const TileDev* tiles, const uint16_t* act, co
   const int nb = P.tiles_m * P.tiles_n;
   if (nb == 0) return;
   const bool tail = K % kGemmBK != 0;
-#define TLORA_GEMM_LAUNCH(KN, TAIL, NW) \
-  hipLaunchKernelGGL((seg_gemm_kernel<KN, TAIL, NW>), dim3(nb), dim3(NW * 64), 0, st, P)
+#define TLORA_GEMM_LAUNCH(KN, TAIL, NW, BK) \
+  hipLaunchKernelGGL((seg_gemm_kernel<KN, TAIL, NW, BK>), dim3(nb), dim3(NW * 64), 0, st, P)
   if (waves == 4) {
-    if (w_is_kn) { if (tail) TLORA_GEMM_LAUNCH(true, true, 4);  else TLORA_GEMM_LAUNCH(true, false, 4); }
-    else         { if (tail) TLORA_GEMM_LAUNCH(false, true, 4); else TLORA_GEMM_LAUNCH(false, false, 4); }
+    if (w_is_kn) { if (tail) TLORA_GEMM_LAUNCH(true, true, 4, 32);  else TLORA_GEMM_LAUNCH(true, false, 4, 32); }
+    else         { if (tail) TLORA_GEMM_LAUNCH(false, true, 4, 32); else TLORA_GEMM_LAUNCH(false, false, 4, 32); }
+  } else if (bk == 64 && K % 64 == 0) {
+    if (w_is_kn) TLORA_GEMM_LAUNCH(true, false, 8, 64);
+    else         TLORA_GEMM_LAUNCH(false, false, 8, 64);
   } else {
-    if (w_is_kn) { if (tail) TLORA_GEMM_LAUNCH(true, true, 8);  else TLORA_GEMM_LAUNCH(true, false, 8); }
-    else         { if (tail) TLORA_GEMM_LAUNCH(false, true, 8); else TLORA_GEMM_LAUNCH(false, false, 8); }
+    if (w_is_kn) { if (tail) TLORA_GEMM_LAUNCH(true, true, 8, 32);  else TLORA_GEMM_LAUNCH(true, false, 8, 32); }
+    else         { if (tail) TLORA_GEMM_LAUNCH(false, true, 8, 32); else TLORA_GEMM_LAUNCH(false, false, 8, 32); }
   }
 #undef TLORA_GEMM_LAUNCH
 }
