@@ -1,10 +1,11 @@
 // gfx950 (CDNA4) kernels of the fused multi-LoRA linear layer.
 //
-// Wavefront = 64 lanes.  The contractions run on v_mfma_f32_32x32x16_bf16: lane l feeds row/column
+// Wavefront = 64 lanes.  The rank-bound kernels contract on v_mfma_f32_32x32x16_bf16: lane l feeds row/column
 // (l % 32) of its operand with the 8 consecutive k-values 8*(l/32) .. +7, and owns, of the 32x32 fp32
-// result, column (l % 32) and rows 8*(i/4) + 4*(l/32) + (i%4) for accumulator register i.  All
-// kernels put the weight-side operand first, so a lane ends up with 4 consecutive output features of
-// one token and stores them with one 8- or 16-byte access.
+// result, column (l % 32) and rows 8*(i/4) + 4*(l/32) + (i%4) for accumulator register i.  The segmented GEMM
+// uses v_mfma_f32_16x16x32_bf16 (row/column l % 16, k-values 8*(l/16) .. +7; result column l % 16, rows
+// 4*(l/16) + i).  All kernels put the weight-side operand first, so a lane ends up with 4 consecutive output
+// features of one token and stores them with one 8- or 16-byte access.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -15,6 +16,7 @@ namespace tlora {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -23,6 +25,11 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+// 16 x 16 x 32: lane l supplies row (column) l % 16 of its operand, k-values 8 (l / 16) .. + 7, and receives
+// D[4 (l / 16) + i][l % 16], i = 0..3.
+__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 __device__ __forceinline__ u32x4 ldg16(const void* p) { return *reinterpret_cast<const u32x4*>(p); }
@@ -82,6 +89,32 @@ __device__ __forceinline__ bf16x8 frag_kn_tile(const uint8_t* tile, int nb, int 
   const int inner = (n & 7) * 2;
   s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, tile + kn_tile_off(kbase, c) + inner));
   s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, tile + kn_tile_off(kbase + 4, c) + inner));
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// Operand fragments of the 16 x 16 x 32 MFMA (the segmented GEMM): 16 rows x 32 k-values.
+//  k-contiguous tiles (64-byte rows when BK = 32, 128-byte rows when BK = 64): one 16-byte read per lane.
+template <int BK>
+__device__ __forceinline__ bf16x8 frag16_rows(const uint8_t* tile, int rb, int ks, int lane) {
+  const int r = rb + (lane & 15), g = lane >> 4;
+  return as_bf16x8(*reinterpret_cast<const u32x4*>(tile + (BK == 32 ? row32_off(r, g) : row_tile_off(r, ks * 4 + g))));
+}
+//  "kn16 tile": k-rows x 256 bf16 (512 B per row) as W lies in memory for the forward.  Chunk c of k-row k sits at
+//  slot c ^ ((k & 3) << 2) ^ (((k >> 3) & 1) << 1): the 4 k-rows x 32 bytes that one 16-lane group of a transposing
+//  read touches, and those of the neighbouring group (k + 8), fall into 16 distinct 16-byte bank groups.
+__device__ __forceinline__ int kn16_off(int k, int c) {
+  return k * 512 + ((c ^ ((k & 3) << 2) ^ (((k >> 3) & 1) << 1)) << 4);
+}
+__device__ __forceinline__ bf16x8 frag16_kn(const uint8_t* tile, int nb, int ks, int lane) {
+  const int s = lane & 15;
+  const int n = nb + (s & 3) * 4;                              // column this lane addresses
+  const int kbase = ks * 32 + (lane >> 4) * 8 + (s >> 2);
+  const int c = n >> 3;
+  const int inner = (n & 7) * 2;
+  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, tile + kn16_off(kbase, c) + inner));
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, tile + kn16_off(kbase + 4, c) + inner));
   typedef short s16x8 __attribute__((ext_vector_type(8)));
   s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   return __builtin_bit_cast(bf16x8, v);
@@ -467,7 +500,7 @@ struct GemmParams {
 // keeps its register pressure (and spills) away from every tile.
 // NW: waves per workgroup.  8 = 2 x 4 waves of 128 x 64 (two waves per SIMD hide each other's latencies; the
 // default); 4 = 2 x 2 waves of 128 x 128 (256 accumulator registers per lane, a third less LDS read traffic per
-// flop, but every barrier wait idles the MFMA pipe: measured ~6 % slower).
+// flop, but with one wave per SIMD every LDS and barrier wait idles the MFMA pipe: measured much slower).
 // BK: k-values per step.  32: four stages of 32 KB, loads three steps ahead.  64 (needs K % 64 == 0): two stages of
 // 64 KB, loads one step ahead; every row of a k-contiguous operand is then fetched as a whole 128-byte line
 // and there are half as many barriers.
@@ -475,7 +508,7 @@ template <bool KN, bool KTAIL, int NW, int BK>
 __global__ void __launch_bounds__(NW * 64) seg_gemm_kernel(GemmParams P) {
   constexpr int NT = NW * 64;                        // threads
   constexpr int WCOLS = 256 / (NW / 2);              // output columns per wave: 64 or 128
-  constexpr int NJ = WCOLS / 32;                     // 32-wide column blocks per wave
+  constexpr int NFB = WCOLS / 16;                    // 16-wide feature blocks per wave
   constexpr int BM = kGemmBM, BN = kGemmBN;
   static_assert(BM == 256 && BN == 256 && (BK == 32 || BK == 64), "tile shape is baked into the index arithmetic");
   static_assert(!(KTAIL && BK == 64), "the K tail goes with K-steps of 32");
@@ -512,29 +545,27 @@ __global__ void __launch_bounds__(NW * 64) seg_gemm_kernel(GemmParams P) {
   const int rows_valid = min(BM, P.T - row0);
   const TileDev td = P.tiles[tm];
 
-  f32x16 acc[NJ][4];
+  // 16 x 16 x 32 MFMAs: with dense random operands the chip sustains ~15 % more of them per second than of the
+  // 32 x 32 x 16 shape under its power limit (half the accumulator traffic per flop).
+  f32x4 acc[NFB][8];                                 // [feature block][token block of 16]
 #pragma unroll
-  for (int j = 0; j < NJ; ++j)
+  for (int j = 0; j < NFB; ++j)
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.f;
+    for (int i = 0; i < 8; ++i) acc[j][i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  auto load_frags = [&](const uint8_t* SA, const uint8_t* SB, int kk, bf16x8 (&xf)[4], bf16x8 (&wf)[NJ]) {
+  // one 32-deep k-slice ks of a stage: fragments, then NFB x 8 MFMAs
+  auto load_frags = [&](const uint8_t* SA, const uint8_t* SB, int ks, bf16x8 (&xf)[8], bf16x8 (&wf)[NFB]) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      xf[i] = BK == 32 ? frag_row32(SA, wm * 128 + i * 32, kk, lane) : frag_row_tile(SA, wm * 128 + i * 32, kk, lane);
+    for (int i = 0; i < 8; ++i) xf[i] = frag16_rows<BK>(SA, wm * 128 + i * 16, ks, lane);
 #pragma unroll
-    for (int j = 0; j < NJ; ++j)
-      wf[j] = KN         ? frag_kn_tile(SB, wn * WCOLS + j * 32, kk, lane)
-              : BK == 32 ? frag_row32(SB, wn * WCOLS + j * 32, kk, lane)
-                         : frag_row_tile(SB, wn * WCOLS + j * 32, kk, lane);
+    for (int j = 0; j < NFB; ++j)
+      wf[j] = KN ? frag16_kn(SB, wn * WCOLS + j * 16, ks, lane) : frag16_rows<BK>(SB, wn * WCOLS + j * 16, ks, lane);
   };
-  auto mma_slice = [&](const bf16x8 (&xf)[4], const bf16x8 (&wf)[NJ]) {
+  auto mma_slice = [&](const bf16x8 (&xf)[8], const bf16x8 (&wf)[NFB]) {
 #pragma unroll
-    for (int j = 0; j < NJ; ++j)
+    for (int j = 0; j < NFB; ++j)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) acc[j][i] = mfma32(wf[j], xf[i], acc[j][i]);
+      for (int i = 0; i < 8; ++i) acc[j][i] = mfma16(wf[j], xf[i], acc[j][i]);
   };
   // ---- the K-loop: K / 32 backbone steps, then kext / 32 adapter steps, one software pipeline ----------------
   // Each wave issues 2 + 2 asynchronous 1 KB loads per step; lane l's 16 bytes land at (wave-uniform base)
@@ -564,7 +595,7 @@ __global__ void __launch_bounds__(NW * 64) seg_gemm_kernel(GemmParams P) {
         xa_src[i] = P.Sx + td.aoff + (int64_t)r * td.kext + c * 8;      // all 256 rows of the operand exist
       }
       if (KN) {
-        const int k = p >> 5, c = (p & 31) ^ ((k & 3) << 2);
+        const int k = p >> 5, c = (p & 31) ^ ((k & 3) << 2) ^ (((k >> 3) & 1) << 1);    // kn16 tile slot -> chunk
         const int col = min(col0 + c * 8, P.N - 8);
         bsrc[i] = P.W + (int64_t)k * P.N + col;
         xb_src[i] = P.packed + (int64_t)(td.roff_first + k) * P.N + col;
@@ -612,13 +643,11 @@ __global__ void __launch_bounds__(NW * 64) seg_gemm_kernel(GemmParams P) {
         __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * 2 * LD));
         __builtin_amdgcn_s_barrier();
       };
-      // one K-step (32 k-values = two MFMA k-slices) out of a stage
+      // one K-step (32 k-values = one MFMA k-slice) out of a stage
       auto compute = [&](const uint8_t* S) {
-        bf16x8 xa[4], wa[NJ], xb[4], wb[NJ];
+        bf16x8 xa[8], wa[NFB];
         load_frags(S, S + A_BYTES, 0, xa, wa);
-        load_frags(S, S + A_BYTES, 1, xb, wb);
         mma_slice(xa, wa);
-        mma_slice(xb, wb);
       };
       issue(st0, st0 + A_BYTES);
       issue(st1, st1 + A_BYTES);
@@ -638,17 +667,13 @@ __global__ void __launch_bounds__(NW * 64) seg_gemm_kernel(GemmParams P) {
         __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
         __builtin_amdgcn_s_barrier();
       };
-      // one K-step (64 k-values = four MFMA k-slices; two when only the first half of the step is valid)
+      // one K-step (64 k-values = two MFMA k-slices; one when only the first half of the step is valid)
       auto compute = [&](const uint8_t* SA, const uint8_t* SB, bool half) {
-        bf16x8 xa[4], wa[NJ], xb[4], wb[NJ];
+        bf16x8 xa[8], wa[NFB], xb[8], wb[NFB];
         load_frags(SA, SB, 0, xa, wa);
-        load_frags(SA, SB, 1, xb, wb);
         mma_slice(xa, wa);
-        mma_slice(xb, wb);
         if (!half) {
-          load_frags(SA, SB, 2, xa, wa);
-          load_frags(SA, SB, 3, xb, wb);
-          mma_slice(xa, wa);
+          load_frags(SA, SB, 1, xb, wb);
           mma_slice(xb, wb);
         }
       };
@@ -691,14 +716,13 @@ __global__ void __launch_bounds__(NW * 64) seg_gemm_kernel(GemmParams P) {
     for (int i = 0; i < TCH; ++i) {
       const int id = tid + i * NT;
       *reinterpret_cast<u32x4*>(st0 + row32_off(id >> 2, id & 3)) = areg[i];
-      if (KN) *reinterpret_cast<u32x4*>(st0 + A_BYTES + kn_tile_off(id >> 5, id & 31)) = breg[i];
+      if (KN) *reinterpret_cast<u32x4*>(st0 + A_BYTES + kn16_off(id >> 5, id & 31)) = breg[i];
       else    *reinterpret_cast<u32x4*>(st0 + A_BYTES + row32_off(id >> 2, id & 3)) = breg[i];
     }
     __syncthreads();
-    const int nkk = (kvalid + 15) >> 4;
-    for (int kk = 0; kk < nkk; ++kk) {
-      bf16x8 xf[4], wf[NJ];
-      load_frags(st0, st0 + A_BYTES, kk, xf, wf);
+    {                                       // chunks and k-rows beyond kvalid were stored as zeros
+      bf16x8 xf[8], wf[NFB];
+      load_frags(st0, st0 + A_BYTES, 0, xf, wf);
       mma_slice(xf, wf);
     }
   }
@@ -707,19 +731,17 @@ __global__ void __launch_bounds__(NW * 64) seg_gemm_kernel(GemmParams P) {
   // chunk c of row R at slot c ^ (R & 31)) -> full 512-byte rows to global memory. -----------------------------
   __syncthreads();
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    uint8_t* const obuf = wm ? (i < 2 ? st2 : st3) : (i < 2 ? st0 : st1);
-    const int R = wm * 128 + i * 32 + (lane & 31);
-    uint8_t* const orow = obuf + (R & 63) * 512 + (lane >> 5) * 8;
+  for (int i = 0; i < 8; ++i) {
+    // lane l holds token (l % 16) of block i, features 4 (l / 16) .. + 3 of each feature block
+    uint8_t* const obuf = wm ? (i < 4 ? st2 : st3) : (i < 4 ? st0 : st1);
+    const int R = wm * 128 + i * 16 + (lane & 15);
+    uint8_t* const orow = obuf + (R & 63) * 512 + ((lane >> 4) & 1) * 8;
 #pragma unroll
-    for (int j = 0; j < NJ; ++j)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int c = wn * (WCOLS / 8) + j * 4 + g;
-        u32x2 v = {pack_bf16x2(acc[j][i][g * 4 + 0], acc[j][i][g * 4 + 1]),
-                   pack_bf16x2(acc[j][i][g * 4 + 2], acc[j][i][g * 4 + 3])};
-        *reinterpret_cast<u32x2*>(orow + ((c ^ (R & 31)) << 4)) = v;
-      }
+    for (int j = 0; j < NFB; ++j) {
+      const int c = wn * (WCOLS / 8) + j * 2 + (lane >> 5);
+      u32x2 v = {pack_bf16x2(acc[j][i][0], acc[j][i][1]), pack_bf16x2(acc[j][i][2], acc[j][i][3])};
+      *reinterpret_cast<u32x2*>(orow + ((c ^ (R & 31)) << 4)) = v;
+    }
   }
   __syncthreads();
   constexpr int RPI = NT / 32;              // output rows per iteration
