@@ -493,6 +493,7 @@ struct GemmParams {
   int T, K, N;
   int ra;                   // R + 32: row stride of a_all
   int tiles_m, tiles_n;
+  int pingpong;             // 0: all eight waves in step; 1: waves 0-3 and 4-7 run half a step apart
   unsigned long long* clk;  // optional: every 64th workgroup adds {cycles, 100 MHz ticks} of its K-loop (pre-zeroed)
 };
 
@@ -653,6 +654,41 @@ __global__ void __launch_bounds__(NW * 64) seg_gemm_kernel(GemmParams P) {
       issue(st1, st1 + A_BYTES);
       issue(st2, st2 + A_BYTES);
       int kt = 0;
+      if (NW == 8 && P.pingpong) {
+        // Two groups of four waves (one wave of each group per SIMD) run half a step apart: while one group issues
+        // its 32 MFMAs of a step, the other reads its fragments of the next step from LDS and issues its loads,
+        // so the MFMA pipe does not idle behind the burst of LDS reads that follows a common barrier.  Every
+        // half step ends in a workgroup barrier; the late group passes one extra barrier first, the early group
+        // one extra at the end.
+        const bool late = (wave >> 2) != 0;      // waves w and w + 4 share a SIMD
+        auto gate = [&]() {
+          __builtin_amdgcn_sched_barrier(0);
+          __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * 2 * LD));
+          __builtin_amdgcn_s_barrier();
+          __builtin_amdgcn_sched_barrier(0);
+        };
+        auto step = [&](const uint8_t* S, uint8_t* Sn) {
+          bf16x8 xa[8], wa[NFB];
+          gate();                                  // stage S has landed for everyone; Sn is no longer read
+          load_frags(S, S + A_BYTES, 0, xa, wa);
+          issue(Sn, Sn + A_BYTES);
+          gate();                                  // fragments are in registers
+          mma_slice(xa, wa);
+        };
+        if (late) gate();          // its share of the first stage must have landed before the early group reads it
+        for (; kt + 4 <= nsteps; kt += 4) {
+          step(st0, st3);
+          step(st1, st0);
+          step(st2, st1);
+          step(st3, st2);
+        }
+        if (kt < nsteps)     step(st0, st3);
+        if (kt + 1 < nsteps) step(st1, st0);
+        if (kt + 2 < nsteps) step(st2, st1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (!late) __builtin_amdgcn_s_barrier();
+        kt = nsteps;
+      }
       for (; kt + 4 <= nsteps; kt += 4) {
         landed();  issue(st3, st3 + A_BYTES);  compute(st0);
         landed();  issue(st0, st0 + A_BYTES);  compute(st1);
@@ -760,6 +796,7 @@ void launch_seg_gemm(bool w_is_kn, const TileDev* tiles, const uint16_t* act, co
                      unsigned long long* clk, hipStream_t st) {
   GemmParams P;
   P.clk = clk;
+  P.pingpong = bk >> 8;  bk &= 255;
   P.tiles = tiles;  P.act = act;  P.W = W;  P.Sx = Sx;  P.packed = packed;  P.out = out;
   P.T = T;  P.K = K;  P.N = N;  P.ra = r_total + 32;
   P.tiles_m = (T + kGemmBM - 1) / kGemmBM;
