@@ -109,11 +109,6 @@ int tlora_plan_dump(const tlora_problem_t* p, int32_t* rpad, int64_t* soff, int3
                     int32_t* tile_job_last, int64_t* n_tiles);
 
 /* Tuning knobs (process-wide, for experiments and for the tiling-independence tests).
- *   "gemm_waves"   : waves per workgroup of the segmented GEMM             (8: 128x64 per wave | 4: 128x128)
- *   "gemm_k_step"  : k-values per step of the segmented GEMM               (32: four 32 KB stages | 64: two 64 KB stages,
- *                    used when the contraction length is a multiple of 64; measured slower)
- *   "gemm_pingpong": 1 (default): the two waves of each SIMD run half a K-step apart, one reading LDS while the
- *                    other issues MFMAs | 0: all waves in step                                 (8-wave layout only)
  *   "shrink_rows"  : token rows per work unit of the shrink kernels        (64 | 128)
  *   "shrink_stages": LDS stages of the streaming shrink kernel             (4 | 8)
  *   "grad_tokens"  : minimum tokens per work unit of the dA / dB kernels   (multiple of 64)

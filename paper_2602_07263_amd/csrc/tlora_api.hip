@@ -19,9 +19,6 @@ struct Options {
   int shrink_rows = 128;
   int shrink_stages = 4;
   int grad_tokens = 256;
-  int gemm_waves = 8;
-  int gemm_k_step = 32;
-  int gemm_pingpong = 1;
 };
 Options g_opt;
 std::mutex g_mu;
@@ -522,7 +519,7 @@ int tlora_fwd(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_byte
   if (g_prof_on) launch_zero_fill(ws + pl.off_clock, 16, st);
   Timed tg(TLORA_K_GEMM_FWD, st);
   launch_seg_gemm(true, tiles, static_cast<const uint16_t*>(p->X), static_cast<const uint16_t*>(p->W), Sx, bp,
-                  pl.r_total, static_cast<uint16_t*>(Y), pl.T, pl.d_in, pl.d_out, g_opt.gemm_waves, g_opt.gemm_k_step | (g_opt.gemm_pingpong << 8),
+                  pl.r_total, static_cast<uint16_t*>(Y), pl.T, pl.d_in, pl.d_out,
                   g_prof_on ? (g_clock_slot[0] = reinterpret_cast<unsigned long long*>(ws + pl.off_clock)) : nullptr, st);
   return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
 }
@@ -641,7 +638,7 @@ int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* d
       if (g_prof_on) launch_zero_fill(ws + pl.off_clock + 16, 16, st);
       Timed t(TLORA_K_GEMM_BWD, st);
       launch_seg_gemm(false, tiles, dYb, static_cast<const uint16_t*>(p->W), dSx, ap, pl.r_total,
-                      static_cast<uint16_t*>(dX), pl.T, pl.d_out, pl.d_in, g_opt.gemm_waves, g_opt.gemm_k_step | (g_opt.gemm_pingpong << 8),
+                      static_cast<uint16_t*>(dX), pl.T, pl.d_out, pl.d_in,
                       g_prof_on ? (g_clock_slot[1] = reinterpret_cast<unsigned long long*>(ws + pl.off_clock) + 2) : nullptr,
                       st);
     }
@@ -744,21 +741,6 @@ int tlora_set_option(const char* name, int64_t value) {
   if (n == "shrink_rows") {
     if (value != 64 && value != 128) return TLORA_EINVAL;
     g_opt.shrink_rows = (int)value;
-    return TLORA_OK;
-  }
-  if (n == "gemm_waves") {
-    if (value != 4 && value != 8) return TLORA_EINVAL;
-    g_opt.gemm_waves = (int)value;
-    return TLORA_OK;
-  }
-  if (n == "gemm_pingpong") {
-    if (value != 0 && value != 1) return TLORA_EINVAL;
-    g_opt.gemm_pingpong = (int)value;
-    return TLORA_OK;
-  }
-  if (n == "gemm_k_step") {
-    if (value != 32 && value != 64) return TLORA_EINVAL;
-    g_opt.gemm_k_step = (int)value;
     return TLORA_OK;
   }
   if (n == "shrink_stages") {

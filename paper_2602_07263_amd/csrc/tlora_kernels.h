@@ -34,7 +34,6 @@ void launch_shrink_stream(const JobDev* jobs, const TileDev* tiles, const Shrink
 //   w_is_kn = false: W is [N, K] row-major (backward, Eop = a_all^T, stored [N, R + 32])
 void launch_seg_gemm(bool w_is_kn, const TileDev* tiles, const uint16_t* act, const uint16_t* W,
                      const uint16_t* Sx, const uint16_t* packed, int r_total, uint16_t* out, int T, int K, int N,
-                     int waves /* 4 or 8 per workgroup */, int bk /* k-values per step: 32 or 64 */,
                      unsigned long long* clk /* null, or 2 zeroed words: every 64th workgroup adds the shader
                                                 cycles and 100 MHz ticks of its K-loop */,
                      hipStream_t st);

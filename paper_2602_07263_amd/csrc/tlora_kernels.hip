@@ -48,6 +48,19 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 __device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory");
 }
+// Same load with the address given as a wave-uniform 64-bit base plus a 32-bit unsigned byte offset per lane.
+__device__ __forceinline__ void dma16s(uint32_t voff, const void* sbase, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_base)
+               : "memory");
+}
+// A pointer the program knows to be wave-uniform, moved into scalar registers (64-bit products are computed on the
+// vector ALU, and the "s" operand of the load above must really be a scalar register pair).
+__device__ __forceinline__ const char* uniform_ptr(const char* p) {
+  const uint64_t v = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return reinterpret_cast<const char*>(((uint64_t)hi << 32) | lo);
+}
 __device__ __forceinline__ uint32_t lds_addr(const void* p) {
   return __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)LDS_PTR(const uint8_t, p));
 }
@@ -479,9 +492,14 @@ void launch_shrink_stream(const JobDev* jobs, const TileDev* tiles, const Shrink
 // K-loop is job-blind, and each job present in the tile then adds ceil(rpad_j / 32) K-steps in which only
 // its own rows are non-zero.
 //
-// Backbone K-loop: K-steps of 32, four LDS stages of 32 KB (activation tile 256 x 32 + weight tile), filled by
-// asynchronous global->LDS loads that run three steps ahead of the MFMAs (96 KB in flight per CU: a
-// 256 x 256 tile needs ~32 B/clk from L2 at MFMA peak, and one 64 KB batch in flight delivers half of that).
+// K-loop: steps of 32 k-values (one 16 x 16 x 32 MFMA slice).  The operands stream through a ring of five
+// 32 KB LDS slots as an alternating sequence of tiles L_0, L_1, ...: L_q with q odd is an activation tile,
+// q even a weight tile, and L_q holds the k-values of steps q - 1 and q (256 rows x 64 k-values, 128 B per row
+// for a k-contiguous operand; 64 k-rows x 256 columns for the forward weight).  Step s reads the second half of
+// L_s and the first half of L_s+1, then L_s is free; L_s+4 is issued at step s, so three tiles (96 KB) are in
+// flight per CU.  Compared with loading both operands 32 k-values at a time, every row of a k-contiguous
+// operand is fetched as a whole 128-byte line: the same bytes in half as many L2 requests (a load-only
+// replica of the two streams sustains ~15.4 TB/s this way against ~11.5 TB/s).
 // ---------------------------------------------------------------------------------------------------
 struct GemmParams {
   const TileDev* tiles;
@@ -493,37 +511,29 @@ struct GemmParams {
   int T, K, N;
   int ra;                   // R + 32: row stride of a_all
   int tiles_m, tiles_n;
-  int pingpong;             // 0: all eight waves in step; 1: waves 0-3 and 4-7 run half a step apart
   unsigned long long* clk;  // optional: every 64th workgroup adds {cycles, 100 MHz ticks} of its K-loop (pre-zeroed)
 };
 
 // KTAIL: the instantiation for K % 32 != 0 carries the extra predicated step; keeping it out of the common one
-// keeps its register pressure (and spills) away from every tile.
-// NW: waves per workgroup.  8 = 2 x 4 waves of 128 x 64 (two waves per SIMD hide each other's latencies; the
-// default); 4 = 2 x 2 waves of 128 x 128 (256 accumulator registers per lane, a third less LDS read traffic per
-// flop, but with one wave per SIMD every LDS and barrier wait idles the MFMA pipe: measured much slower).
-// BK: k-values per step.  32: four stages of 32 KB, loads three steps ahead.  64 (needs K % 64 == 0): two stages of
-// 64 KB, loads one step ahead; every row of a k-contiguous operand is then fetched as a whole 128-byte line
-// and there are half as many barriers.
-template <bool KN, bool KTAIL, int NW, int BK>
-__global__ void __launch_bounds__(NW * 64) seg_gemm_kernel(GemmParams P) {
-  constexpr int NT = NW * 64;                        // threads
-  constexpr int WCOLS = 256 / (NW / 2);              // output columns per wave: 64 or 128
-  constexpr int NFB = WCOLS / 16;                    // 16-wide feature blocks per wave
+// keeps its register pressure away from every tile.
+template <bool KN, bool KTAIL>
+__global__ void __launch_bounds__(512) seg_gemm_kernel(GemmParams P) {
+  constexpr int NT = 512;                            // threads: 8 waves
+  constexpr int NFB = 4;                             // 16-wide feature blocks per wave (64 columns)
   constexpr int BM = kGemmBM, BN = kGemmBN;
-  static_assert(BM == 256 && BN == 256 && (BK == 32 || BK == 64), "tile shape is baked into the index arithmetic");
-  static_assert(!(KTAIL && BK == 64), "the K tail goes with K-steps of 32");
-  constexpr int A_BYTES = BM * BK * 2;               // 16 | 32 KB; the weight tile has the same size
-  constexpr int LD = A_BYTES / 1024 / NW;            // 1 KB loads per wave per tile
-  constexpr int STAGE_BYTES = 32768;                 // BK = 32: one stage per array; BK = 64: one tile per array
-  // Four stages as four separate arrays: the compiler tells an in-flight global->LDS load into one stage
-  // from LDS reads of another only when they are distinct objects.
-  __shared__ __attribute__((aligned(1024))) uint8_t st0[STAGE_BYTES];
-  __shared__ __attribute__((aligned(1024))) uint8_t st1[STAGE_BYTES];
-  __shared__ __attribute__((aligned(1024))) uint8_t st2[STAGE_BYTES];
-  __shared__ __attribute__((aligned(1024))) uint8_t st3[STAGE_BYTES];
+  static_assert(BM == 256 && BN == 256 && kGemmBK == 32, "tile shape is baked into the index arithmetic below");
+  constexpr int SLOT = 32768;
+  // 5 x 32 KB: the whole LDS of a CU.  The loads are raw instructions the compiler does not track; every wait on
+  // them is written out below.  (A spilled register in this loop would be fatal for the pipeline: its reload is a
+  // vector-memory load, and waiting for it means waiting for every tile in flight.)
+  __shared__ __attribute__((aligned(1024))) uint8_t lds[5 * SLOT];
+  uint8_t* const sl0 = lds;
+  uint8_t* const sl1 = lds + SLOT;
+  uint8_t* const sl2 = lds + 2 * SLOT;
+  uint8_t* const sl3 = lds + 3 * SLOT;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave & 1, wn = wave >> 1;
 
   // Workgroup ids are dealt round-robin to the 8 XCDs; hand each XCD a contiguous run of logical tile
@@ -539,8 +549,10 @@ __global__ void __launch_bounds__(NW * 64) seg_gemm_kernel(GemmParams P) {
     const int grp = L / per_group, first_m = grp * GM;
     const int gsize = min(GM, P.tiles_m - first_m);
     const int Lg = L - grp * per_group;
-    tm = first_m + Lg % gsize;
-    tn = Lg / gsize;
+    // (the divisions run on the vector ALU; everything derived from the tile id is wave-uniform and belongs in
+    // scalar registers)
+    tm = __builtin_amdgcn_readfirstlane(first_m + Lg % gsize);
+    tn = __builtin_amdgcn_readfirstlane(Lg / gsize);
   }
   const int row0 = tm * BM, col0 = tn * BN;
   const int rows_valid = min(BM, P.T - row0);
@@ -554,183 +566,210 @@ __global__ void __launch_bounds__(NW * 64) seg_gemm_kernel(GemmParams P) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[j][i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // one 32-deep k-slice ks of a stage: fragments, then NFB x 8 MFMAs
-  auto load_frags = [&](const uint8_t* SA, const uint8_t* SB, int ks, bf16x8 (&xf)[8], bf16x8 (&wf)[NFB]) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) xf[i] = frag16_rows<BK>(SA, wm * 128 + i * 16, ks, lane);
-#pragma unroll
-    for (int j = 0; j < NFB; ++j)
-      wf[j] = KN ? frag16_kn(SB, wn * WCOLS + j * 16, ks, lane) : frag16_rows<BK>(SB, wn * WCOLS + j * 16, ks, lane);
-  };
   auto mma_slice = [&](const bf16x8 (&xf)[8], const bf16x8 (&wf)[NFB]) {
 #pragma unroll
     for (int j = 0; j < NFB; ++j)
 #pragma unroll
       for (int i = 0; i < 8; ++i) acc[j][i] = mfma16(wf[j], xf[i], acc[j][i]);
   };
+
   // ---- the K-loop: K / 32 backbone steps, then kext / 32 adapter steps, one software pipeline ----------------
-  // Each wave issues 2 + 2 asynchronous 1 KB loads per step; lane l's 16 bytes land at (wave-uniform base)
-  // + 16 l, so the swizzled LDS layout is produced by choosing which global chunk each lane fetches.  Rows /
-  // columns beyond the problem edge are clamped to the last valid one: they only feed outputs that are never
-  // stored.  The adapter steps read the tile's dense [256, kext] operand (rows of other jobs are stored zeros)
-  // against rows roff_first.. of b_all (forward) or columns roff_first.. of a_all (backward).
-  const int nfull = P.K / BK;
-  const int next = (td.kext + BK - 1) / BK;          // BK = 64: the last adapter step may hold only 32 k-values
-  const bool half_last = BK == 64 && (td.kext & 32) != 0;
-  const int nsteps = nfull + next;
+  const int nfull = P.K / 32;
+  const int ntot = nfull + td.kext / 32;
   const bool clocked = P.clk != nullptr && (blockIdx.x & 63) == 0;   // a sample of workgroups across the grid
   unsigned long long cyc0 = 0, tick0 = 0;
   if (clocked) { cyc0 = __builtin_readcyclecounter();  tick0 = __builtin_amdgcn_s_memrealtime(); }
-  if (nsteps > 0) {
-    const uint16_t* asrc[LD];
-    const uint16_t* bsrc[LD];
-    const uint16_t* xa_src[LD];
-    const uint16_t* xb_src[LD];
+  if (ntot > 0) {
+    // Loads.  A tile is 2048 16-byte slots; wave w issues four 1 KB loads per tile, lane l's 16 bytes landing at
+    // slot (4 w + i) 64 + l.  Which k-values and which row / column that slot holds follows from the tile
+    // layout, so the source address is recomputed per load from the step index t of the lane's half of the
+    // tile: t < K / 32 reads the backbone operands, later steps the tile's dense [256, kext] adapter operand
+    // (rows of other jobs are stored zeros) against rows roff_first.. of b_all (forward) or columns roff_first..
+    // of a_all (backward).  Steps outside 0 .. ntot - 1 (first half of L_0, tiles past the end) and rows /
+    // columns beyond the problem edge are clamped to valid ones: they only fill LDS that is never read or feed
+    // outputs that are never stored.  Selects, not branches: a branch around a load would make the compiler
+    // wait for every outstanding load where the paths merge.
+    //  k-contiguous tile ("row tile", 128 B rows): slot p -> row p / 8, 16-byte chunk (p % 8) ^ ((row / 2) % 8).
+    // A tile whose two steps lie on the same side of the backbone / adapter boundary (all but one or two per
+    // operand) is loaded as wave-uniform base + per-lane 32-bit offset; the offsets are loop constants.  The
+    // others take the general path, which derives each lane's address from scratch.
+    const int lr = wave * 32 + (lane >> 3);                   // row / column of the tile for i = 0 (i adds 8)
+    const int coff = ((lane & 3) ^ (lane >> 4)) * 16;         // byte offset of the lane's chunk inside its 32-k half
+    const int h0 = (lane >> 2) & 1;                           // which half, for even i (odd i: the other one)
+    const char* const a_base = uniform_ptr(reinterpret_cast<const char*>(P.act + (int64_t)row0 * P.K));
+    const char* const x_base = uniform_ptr(reinterpret_cast<const char*>(P.Sx + td.aoff) - (int64_t)nfull * 64);
+    const char* const w_base = uniform_ptr(reinterpret_cast<const char*>(KN ? P.W + col0 : P.W + (int64_t)col0 * P.K));
+    const char* const e_base = uniform_ptr(
+        KN ? reinterpret_cast<const char*>(P.packed + (int64_t)td.roff_first * P.N + col0) - (int64_t)nfull * 64 * P.N
+           : reinterpret_cast<const char*>(P.packed + (int64_t)col0 * P.ra + td.roff_first) - (int64_t)nfull * 64);
+    const uint32_t lds0 = lds_addr(lds);
+    // Interior tiles (no row / column clamping) need two offsets per operand: the lane's row and chunk for even
+    // and for odd i; the 8 i rows between consecutive loads go into the uniform base.
+    const bool interior_m = rows_valid == BM, interior_n = col0 + BN <= P.N;
+    uint32_t k_off[2], x_off[2], kn_off[2];
 #pragma unroll
-    for (int i = 0; i < LD; ++i) {
-      const int p = (wave * LD + i) * 64 + lane;          // 16-byte slot inside the tile
-      {
-        const int r = BK == 32 ? p >> 2 : p >> 3;
-        const int c = BK == 32 ? (p & 3) ^ ((r >> 2) & 3) : (p & 7) ^ ((r >> 1) & 7);
-        asrc[i] = P.act + (int64_t)(row0 + min(r, rows_valid - 1)) * P.K + c * 8;
-        xa_src[i] = P.Sx + td.aoff + (int64_t)r * td.kext + c * 8;      // all 256 rows of the operand exist
-      }
-      if (KN) {
-        const int k = p >> 5, c = (p & 31) ^ ((k & 3) << 2) ^ (((k >> 3) & 1) << 1);    // kn16 tile slot -> chunk
-        const int col = min(col0 + c * 8, P.N - 8);
-        bsrc[i] = P.W + (int64_t)k * P.N + col;
-        xb_src[i] = P.packed + (int64_t)(td.roff_first + k) * P.N + col;
+    for (int par = 0; par < 2; ++par) {
+      k_off[par] = (uint32_t)lr * (uint32_t)(P.K * 2) + coff + (h0 ^ par) * 64;       // rows of K elements: act, NT weight
+      x_off[par] = (uint32_t)lr * (uint32_t)(td.kext * 2) + coff + (h0 ^ par) * 64;   // rows of the adapter operand
+      const int kl = wave * 8 + par * 2 + (lane >> 5);                                // forward weight: k-row of i = par
+      const int c = (lane & 31) ^ ((kl & 3) << 2) ^ (((kl >> 3) & 1) << 1);
+      kn_off[par] = KN ? (uint32_t)(kl & 31) * (uint32_t)(P.N * 2) + c * 16 : 0u;
+    }
+    auto issue_act = [&](int slot, int tq) {                  // activation tile holding steps tq, tq + 1 (tq >= 0)
+      const uint32_t dst = lds0 + slot * SLOT + wave * 4096;
+      if (interior_m && tq + 1 < nfull) {
+        const char* const sb = a_base + (int64_t)tq * 64;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) dma16s(k_off[i & 1], uniform_ptr(sb + (int64_t)i * 16 * P.K), dst + i * 1024);
+      } else if (tq >= nfull && tq + 1 < ntot) {
+        const char* const sb = x_base + (int64_t)tq * 64;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) dma16s(x_off[i & 1], uniform_ptr(sb + (int64_t)i * 16 * td.kext), dst + i * 1024);
       } else {
-        const int n = BK == 32 ? p >> 2 : p >> 3;
-        const int c = BK == 32 ? (p & 3) ^ ((n >> 2) & 3) : (p & 7) ^ ((n >> 1) & 7);
-        const int nn = min(col0 + n, P.N - 1);
-        bsrc[i] = P.W + (int64_t)nn * P.K + c * 8;
-        xb_src[i] = P.packed + (int64_t)nn * P.ra + td.roff_first + c * 8;
-      }
-    }
-    const int64_t bstep = KN ? (int64_t)BK * P.N : (int64_t)BK;   // same in both phases
-    if (nfull == 0) {
+        int r0 = lr;
+        asm volatile("" : "+v"(r0));         // keep what this rare path derives out of the loop's live registers
 #pragma unroll
-      for (int i = 0; i < LD; ++i) { asrc[i] = xa_src[i];  bsrc[i] = xb_src[i]; }
-    }
-    int issued = 0;
-    auto issue = [&](uint8_t* SA, uint8_t* SB) {
-#pragma unroll
-      for (int i = 0; i < LD; ++i)
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)asrc[i],
-                                         LDS_PTR(void, SA + (wave * LD + i) * 1024), 16, 0, 0);
-#pragma unroll
-      for (int i = 0; i < LD; ++i)
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)bsrc[i],
-                                         LDS_PTR(void, SB + (wave * LD + i) * 1024), 16, 0, 0);
-      // Next source: advance inside a phase, jump to the adapter operands after the last backbone step, and
-      // stay put after the last step (the trailing issues re-load it into a stage nobody reads, which keeps
-      // the count of outstanding loads uniform).  Selects, not branches: a branch here would make the
-      // compiler wait for every outstanding load where the paths merge.
-      ++issued;
-      const bool to_ext = issued == nfull && next > 0;
-      const bool adv = issued < nsteps;
-#pragma unroll
-      for (int i = 0; i < LD; ++i) {
-        asrc[i] = to_ext ? xa_src[i] : asrc[i] + (adv ? BK : 0);
-        bsrc[i] = to_ext ? xb_src[i] : bsrc[i] + (adv ? bstep : 0);
+        for (int i = 0; i < 4; ++i) {
+          const int r = r0 + i * 8;
+          const int t = min(max(tq + (h0 ^ (i & 1)), 0), ntot - 1);
+          const bool ext = t >= nfull;
+          const uint32_t off = (ext ? (uint32_t)r * (uint32_t)(td.kext * 2)
+                                    : (uint32_t)min(r, rows_valid - 1) * (uint32_t)(P.K * 2)) + t * 64 + coff;
+          dma16((ext ? x_base : a_base) + off, dst + i * 1024);
+        }
       }
     };
-    if constexpr (BK == 32) {
-      auto landed = [&]() {
-        // Loads complete in order: with the 2 x 2 LD loads of the two younger steps still allowed in flight, this
-        // wave's loads of the current step have landed (and its own LDS reads of the stage about to be refilled
-        // are done); after the barrier so have everyone else's.
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * 2 * LD));
-        __builtin_amdgcn_s_barrier();
-      };
-      // one K-step (32 k-values = one MFMA k-slice) out of a stage
-      auto compute = [&](const uint8_t* S) {
-        bf16x8 xa[8], wa[NFB];
-        load_frags(S, S + A_BYTES, 0, xa, wa);
-        mma_slice(xa, wa);
-      };
-      issue(st0, st0 + A_BYTES);
-      issue(st1, st1 + A_BYTES);
-      issue(st2, st2 + A_BYTES);
-      int kt = 0;
-      if (NW == 8 && P.pingpong) {
-        // Two groups of four waves (one wave of each group per SIMD) run half a step apart: while one group issues
-        // its 32 MFMAs of a step, the other reads its fragments of the next step from LDS and issues its loads,
-        // so the MFMA pipe does not idle behind the burst of LDS reads that follows a common barrier.  Every
-        // half step ends in a workgroup barrier; the late group passes one extra barrier first, the early group
-        // one extra at the end.
-        const bool late = (wave >> 2) != 0;      // waves w and w + 4 share a SIMD
-        auto gate = [&]() {
-          __builtin_amdgcn_sched_barrier(0);
-          __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * 2 * LD));
-          __builtin_amdgcn_s_barrier();
-          __builtin_amdgcn_sched_barrier(0);
-        };
-        auto step = [&](const uint8_t* S, uint8_t* Sn) {
-          bf16x8 xa[8], wa[NFB];
-          gate();                                  // stage S has landed for everyone; Sn is no longer read
-          load_frags(S, S + A_BYTES, 0, xa, wa);
-          issue(Sn, Sn + A_BYTES);
-          gate();                                  // fragments are in registers
-          mma_slice(xa, wa);
-        };
-        if (late) gate();          // its share of the first stage must have landed before the early group reads it
-        for (; kt + 4 <= nsteps; kt += 4) {
-          step(st0, st3);
-          step(st1, st0);
-          step(st2, st1);
-          step(st3, st2);
+    auto issue_wgt = [&](int slot, int tq) {                  // weight tile holding steps tq, tq + 1
+      const uint32_t dst = lds0 + slot * SLOT + wave * 4096;
+      if (KN) {
+        //  "kn16 tile": slot p -> k-row p / 32 (0..63), chunk (p % 32) ^ swizzle(k-row); a wave's rows all belong
+        //  to one step, so base and step clamping are wave-uniform
+        const int t = min(max(tq + (wave >> 2), 0), ntot - 1);
+        const char* const sb = (t >= nfull ? e_base : w_base) + (int64_t)t * 64 * P.N;
+        if (interior_n) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            dma16s(kn_off[i & 1], uniform_ptr(sb + (int64_t)(i >> 1) * 8 * P.N), dst + i * 1024);   // i / 2: 4 k-rows on
+        } else {
+          int ln = lane;
+          asm volatile("" : "+v"(ln));
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int kl = wave * 8 + i * 2 + (ln >> 5);
+            const int c = (ln & 31) ^ ((kl & 3) << 2) ^ (((kl >> 3) & 1) << 1);
+            dma16(sb + (int64_t)(kl & 31) * (P.N * 2) + min(c * 16, (P.N - 8 - col0) * 2), dst + i * 1024);
+          }
         }
-        if (kt < nsteps)     step(st0, st3);
-        if (kt + 1 < nsteps) step(st1, st0);
-        if (kt + 2 < nsteps) step(st2, st1);
-        __builtin_amdgcn_sched_barrier(0);
-        if (!late) __builtin_amdgcn_s_barrier();
-        kt = nsteps;
-      }
-      for (; kt + 4 <= nsteps; kt += 4) {
-        landed();  issue(st3, st3 + A_BYTES);  compute(st0);
-        landed();  issue(st0, st0 + A_BYTES);  compute(st1);
-        landed();  issue(st1, st1 + A_BYTES);  compute(st2);
-        landed();  issue(st2, st2 + A_BYTES);  compute(st3);
-      }
-      if (kt < nsteps)     { landed();  issue(st3, st3 + A_BYTES);  compute(st0); }
-      if (kt + 1 < nsteps) { landed();  issue(st0, st0 + A_BYTES);  compute(st1); }
-      if (kt + 2 < nsteps) { landed();  issue(st1, st1 + A_BYTES);  compute(st2); }
-    } else {
-      auto landed = [&]() {               // nothing younger is in flight: the step's loads are the only ones
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
-        __builtin_amdgcn_s_barrier();
-      };
-      // one K-step (64 k-values = two MFMA k-slices; one when only the first half of the step is valid)
-      auto compute = [&](const uint8_t* SA, const uint8_t* SB, bool half) {
-        bf16x8 xa[8], wa[NFB], xb[8], wb[NFB];
-        load_frags(SA, SB, 0, xa, wa);
-        mma_slice(xa, wa);
-        if (!half) {
-          load_frags(SA, SB, 1, xb, wb);
-          mma_slice(xb, wb);
+      } else if (interior_n && tq >= 0 && tq + 1 < nfull) {
+        const char* const sb = w_base + (int64_t)tq * 64;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) dma16s(k_off[i & 1], uniform_ptr(sb + (int64_t)i * 16 * P.K), dst + i * 1024);
+      } else {                                // the few adapter steps of the backward weight operand included
+        int r0 = lr;
+        asm volatile("" : "+v"(r0));
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int n = min(r0 + i * 8, P.N - 1 - col0);
+          const int t = min(max(tq + (h0 ^ (i & 1)), 0), ntot - 1);
+          const bool ext = t >= nfull;
+          const uint32_t off = (uint32_t)n * (uint32_t)((ext ? P.ra : P.K) * 2) + t * 64 + coff;
+          dma16((ext ? e_base : w_base) + off, dst + i * 1024);
         }
-      };
-      issue(st0, st1);
-      int kt = 0;
-      for (; kt + 2 <= nsteps; kt += 2) {
-        landed();  issue(st2, st3);  compute(st0, st1, false);
-        landed();  issue(st0, st1);  compute(st2, st3, half_last && kt + 2 == nsteps);
       }
-      if (kt < nsteps) { landed();  issue(st2, st3);  compute(st0, st1, half_last); }
+    };
+    // The two groups of four waves (one wave of each group per SIMD: waves w and w + 4 share a SIMD) run half a
+    // step apart: while one group issues its 32 MFMAs of a step, the other reads its fragments of the next step
+    // from LDS and issues its loads, so the MFMA pipe does not idle behind the burst of LDS reads that follows a
+    // common barrier.  Every half step ends in a workgroup barrier; the late group passes one extra barrier
+    // first, the early group one extra at the end.  Loads complete in order: with the 2 x 4 loads of the two
+    // youngest tiles allowed in flight, everything older has landed, and after the barrier so has everyone
+    // else's share.
+    const bool late = (wave >> 2) != 0;
+    auto gate = [&]() {
+      __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(8));
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    // step s (s % 10 == U): second half of L_s, first half of L_s+1; then L_s+4 goes into the slot L_s-1 left
+    // Fragment addresses: one lane pattern for every k-contiguous tile (row l % 16 of a 16-row block, chunk
+    // l / 16 under the row swizzle; the second 32-k half is the same address with bit 6 flipped, block i adds
+    // 2048 bytes, the weight rows add a uniform constant) and four for the forward weight tile (one per feature
+    // block: its chunk swizzle mixes with the block index).  The empty asm in each step makes the compiler
+    // re-derive the per-slot addresses from these few registers instead of keeping all of them live.
+    uint32_t pa0 = (wm * 128 + (lane & 15)) * 128 + (((lane >> 4) ^ ((lane & 15) >> 1)) << 4);
+    const int wdelta = (wn * 64 - wm * 128) * 128;
+    uint32_t pk[NFB];
+#pragma unroll
+    for (int j = 0; j < NFB; ++j) {
+      const int sl = lane & 15, n = wn * 64 + j * 16 + (sl & 3) * 4;
+      const int kb = (lane >> 4) * 8 + (sl >> 2);
+      pk[j] = KN ? kn16_off(kb, n >> 3) + (n & 7) * 2 : 0;
     }
-    __builtin_amdgcn_s_waitcnt(0x0070);     // vmcnt(0): the trailing re-loads must not land in reused LDS
+#define TLORA_GEMM_STEP(U, s)                                                                                \
+  {                                                                                                          \
+    constexpr int slA = ((U) & 1) ? (U) % 5 : ((U) + 1) % 5, slB = ((U) & 1) ? ((U) + 1) % 5 : (U) % 5;      \
+    constexpr int hA = ((U) & 1) ? 1 : 0, hB = 1 - hA;                                                       \
+    bf16x8 xf[8], wf[NFB];                                                                                   \
+    asm volatile("" : "+v"(pa0));                                                                            \
+    gate();                                  /* L_s, L_s+1 have landed for everyone; L_s-1 is no longer read */ \
+    {                                                                                                        \
+      const uint8_t* const fa = lds + slA * SLOT + (pa0 ^ (hA * 64));                                        \
+      _Pragma("unroll") for (int i = 0; i < 8; ++i)                                                          \
+        xf[i] = as_bf16x8(*reinterpret_cast<const u32x4*>(fa + i * 2048));                                   \
+    }                                                                                                        \
+    if (KN) {                                                                                                \
+      _Pragma("unroll") for (int j = 0; j < NFB; ++j) {                                                      \
+        asm volatile("" : "+v"(pk[j]));                                                                      \
+        const uint8_t* const fw = lds + slB * SLOT + hB * 16384 + pk[j];                                     \
+        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, fw));                              \
+        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, fw + 2048));                       \
+        typedef short s16x8_ __attribute__((ext_vector_type(8)));                                            \
+        wf[j] = __builtin_bit_cast(bf16x8, (s16x8_)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7)); \
+      }                                                                                                      \
+    } else {                                                                                                 \
+      const uint8_t* const fw = lds + slB * SLOT + ((pa0 + wdelta) ^ (hB * 64));                             \
+      _Pragma("unroll") for (int j = 0; j < NFB; ++j)                                                        \
+        wf[j] = as_bf16x8(*reinterpret_cast<const u32x4*>(fw + j * 2048));                                   \
+    }                                                                                                        \
+    if (((U) & 1)) issue_act(((U) + 4) % 5, (s) + 3); else issue_wgt(((U) + 4) % 5, (s) + 3);                \
+    gate();                                  /* fragments are in registers */                              \
+    mma_slice(xf, wf);                                                                                       \
+  }
+    issue_wgt(0, -1);
+    issue_act(1, 0);
+    issue_wgt(2, 1);
+    issue_act(3, 2);
+    if (late) gate();              // its share of L_0, L_1 must have landed before the early group reads them
+    int s = 0;
+    for (; s + 10 <= ntot; s += 10) {
+      TLORA_GEMM_STEP(0, s)      TLORA_GEMM_STEP(1, s + 1)  TLORA_GEMM_STEP(2, s + 2)  TLORA_GEMM_STEP(3, s + 3)
+      TLORA_GEMM_STEP(4, s + 4)  TLORA_GEMM_STEP(5, s + 5)  TLORA_GEMM_STEP(6, s + 6)  TLORA_GEMM_STEP(7, s + 7)
+      TLORA_GEMM_STEP(8, s + 8)  TLORA_GEMM_STEP(9, s + 9)
+    }
+    if (s + 0 < ntot) TLORA_GEMM_STEP(0, s)
+    if (s + 1 < ntot) TLORA_GEMM_STEP(1, s + 1)
+    if (s + 2 < ntot) TLORA_GEMM_STEP(2, s + 2)
+    if (s + 3 < ntot) TLORA_GEMM_STEP(3, s + 3)
+    if (s + 4 < ntot) TLORA_GEMM_STEP(4, s + 4)
+    if (s + 5 < ntot) TLORA_GEMM_STEP(5, s + 5)
+    if (s + 6 < ntot) TLORA_GEMM_STEP(6, s + 6)
+    if (s + 7 < ntot) TLORA_GEMM_STEP(7, s + 7)
+    if (s + 8 < ntot) TLORA_GEMM_STEP(8, s + 8)
+#undef TLORA_GEMM_STEP
+    __builtin_amdgcn_sched_barrier(0);
+    if (!late) __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_s_waitcnt(0x0070);     // vmcnt(0): the trailing loads must not land in reused LDS
   }
   if (clocked && tid == 0) {
     atomicAdd(&P.clk[0], __builtin_readcyclecounter() - cyc0);        // integer sums: order does not matter
     atomicAdd(&P.clk[1], __builtin_amdgcn_s_memrealtime() - tick0);
   }
 
-  // ---- K tail (K % 32 != 0): one register-staged, predicated step through stage 0 ---------------------------
+  // ---- K tail (K % 32 != 0): one register-staged, zero-padded step through slot 0 (activation rows as 64-byte
+  // rows in its first 16 KB, the weight slice behind them) --------------------------------------------------
   if (KTAIL) {
-    const int k0 = nfull * BK, kvalid = P.K - k0;
+    const int k0 = nfull * 32, kvalid = P.K - k0;
     constexpr int TCH = 1024 / NT;          // 16-byte chunks per thread and tile
     u32x4 areg[TCH], breg[TCH];
 #pragma unroll
@@ -747,34 +786,39 @@ __global__ void __launch_bounds__(NW * 64) seg_gemm_kernel(GemmParams P) {
         breg[i] = okb ? ldg16(P.W + (int64_t)(col0 + r) * P.K + k0 + c * 8) : u32x4{0, 0, 0, 0};
       }
     }
-    __syncthreads();                       // every wave is done reading stage 0
+    __syncthreads();                       // every wave is done reading the slots
 #pragma unroll
     for (int i = 0; i < TCH; ++i) {
       const int id = tid + i * NT;
-      *reinterpret_cast<u32x4*>(st0 + row32_off(id >> 2, id & 3)) = areg[i];
-      if (KN) *reinterpret_cast<u32x4*>(st0 + A_BYTES + kn16_off(id >> 5, id & 31)) = breg[i];
-      else    *reinterpret_cast<u32x4*>(st0 + A_BYTES + row32_off(id >> 2, id & 3)) = breg[i];
+      *reinterpret_cast<u32x4*>(sl0 + row32_off(id >> 2, id & 3)) = areg[i];
+      if (KN) *reinterpret_cast<u32x4*>(sl0 + 16384 + kn16_off(id >> 5, id & 31)) = breg[i];
+      else    *reinterpret_cast<u32x4*>(sl0 + 16384 + row32_off(id >> 2, id & 3)) = breg[i];
     }
     __syncthreads();
     {                                       // chunks and k-rows beyond kvalid were stored as zeros
       bf16x8 xf[8], wf[NFB];
-      load_frags(st0, st0 + A_BYTES, 0, xf, wf);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) xf[i] = frag16_rows<32>(sl0, wm * 128 + i * 16, 0, lane);
+#pragma unroll
+      for (int j = 0; j < NFB; ++j)
+        wf[j] = KN ? frag16_kn(sl0 + 16384, wn * 64 + j * 16, 0, lane)
+                   : frag16_rows<32>(sl0 + 16384, wn * 64 + j * 16, 0, lane);
       mma_slice(xf, wf);
     }
   }
 
-  // ---- epilogue: accumulators -> bf16 -> LDS (each stage array holds 64 output rows, 512 B per row, 16-byte
+  // ---- epilogue: accumulators -> bf16 -> LDS (slots 0-3 hold 64 output rows each, 512 B per row, 16-byte
   // chunk c of row R at slot c ^ (R & 31)) -> full 512-byte rows to global memory. -----------------------------
   __syncthreads();
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     // lane l holds token (l % 16) of block i, features 4 (l / 16) .. + 3 of each feature block
-    uint8_t* const obuf = wm ? (i < 4 ? st2 : st3) : (i < 4 ? st0 : st1);
+    uint8_t* const obuf = wm ? (i < 4 ? sl2 : sl3) : (i < 4 ? sl0 : sl1);
     const int R = wm * 128 + i * 16 + (lane & 15);
     uint8_t* const orow = obuf + (R & 63) * 512 + ((lane >> 4) & 1) * 8;
 #pragma unroll
     for (int j = 0; j < NFB; ++j) {
-      const int c = wn * (WCOLS / 8) + j * 2 + (lane >> 5);
+      const int c = wn * 8 + j * 2 + (lane >> 5);
       u32x2 v = {pack_bf16x2(acc[j][i][0], acc[j][i][1]), pack_bf16x2(acc[j][i][2], acc[j][i][3])};
       *reinterpret_cast<u32x2*>(orow + ((c ^ (R & 31)) << 4)) = v;
     }
@@ -783,7 +827,7 @@ __global__ void __launch_bounds__(NW * 64) seg_gemm_kernel(GemmParams P) {
   constexpr int RPI = NT / 32;              // output rows per iteration
 #pragma unroll
   for (int it = 0; it < 256 / RPI; ++it) {
-    const uint8_t* const obuf = it * RPI < 64 ? st0 : it * RPI < 128 ? st1 : it * RPI < 192 ? st2 : st3;
+    const uint8_t* const obuf = it * RPI < 64 ? sl0 : it * RPI < 128 ? sl1 : it * RPI < 192 ? sl2 : sl3;
     const int R = (tid >> 5) + it * RPI, c = tid & 31;
     const u32x4 v = *reinterpret_cast<const u32x4*>(obuf + (R & 63) * 512 + ((c ^ (R & 31)) << 4));
     if (R < rows_valid && col0 + c * 8 < P.N)
@@ -792,11 +836,10 @@ __global__ void __launch_bounds__(NW * 64) seg_gemm_kernel(GemmParams P) {
 }
 
 void launch_seg_gemm(bool w_is_kn, const TileDev* tiles, const uint16_t* act, const uint16_t* W, const uint16_t* Sx,
-                     const uint16_t* packed, int r_total, uint16_t* out, int T, int K, int N, int waves, int bk,
+                     const uint16_t* packed, int r_total, uint16_t* out, int T, int K, int N,
                      unsigned long long* clk, hipStream_t st) {
   GemmParams P;
   P.clk = clk;
-  P.pingpong = bk >> 8;  bk &= 255;
   P.tiles = tiles;  P.act = act;  P.W = W;  P.Sx = Sx;  P.packed = packed;  P.out = out;
   P.T = T;  P.K = K;  P.N = N;  P.ra = r_total + 32;
   P.tiles_m = (T + kGemmBM - 1) / kGemmBM;
@@ -804,18 +847,9 @@ void launch_seg_gemm(bool w_is_kn, const TileDev* tiles, const uint16_t* act, co
   const int nb = P.tiles_m * P.tiles_n;
   if (nb == 0) return;
   const bool tail = K % kGemmBK != 0;
-#define TLORA_GEMM_LAUNCH(KN, TAIL, NW, BK) \
-  hipLaunchKernelGGL((seg_gemm_kernel<KN, TAIL, NW, BK>), dim3(nb), dim3(NW * 64), 0, st, P)
-  if (waves == 4) {
-    if (w_is_kn) { if (tail) TLORA_GEMM_LAUNCH(true, true, 4, 32);  else TLORA_GEMM_LAUNCH(true, false, 4, 32); }
-    else         { if (tail) TLORA_GEMM_LAUNCH(false, true, 4, 32); else TLORA_GEMM_LAUNCH(false, false, 4, 32); }
-  } else if (bk == 64 && K % 64 == 0) {
-    if (w_is_kn) TLORA_GEMM_LAUNCH(true, false, 8, 64);
-    else         TLORA_GEMM_LAUNCH(false, false, 8, 64);
-  } else {
-    if (w_is_kn) { if (tail) TLORA_GEMM_LAUNCH(true, true, 8, 32);  else TLORA_GEMM_LAUNCH(true, false, 8, 32); }
-    else         { if (tail) TLORA_GEMM_LAUNCH(false, true, 8, 32); else TLORA_GEMM_LAUNCH(false, false, 8, 32); }
-  }
+#define TLORA_GEMM_LAUNCH(KN, TAIL) hipLaunchKernelGGL((seg_gemm_kernel<KN, TAIL>), dim3(nb), dim3(512), 0, st, P)
+  if (w_is_kn) { if (tail) TLORA_GEMM_LAUNCH(true, true);  else TLORA_GEMM_LAUNCH(true, false); }
+  else         { if (tail) TLORA_GEMM_LAUNCH(false, true); else TLORA_GEMM_LAUNCH(false, false); }
 #undef TLORA_GEMM_LAUNCH
 }
 

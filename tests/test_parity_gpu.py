@@ -100,14 +100,11 @@ def test_full_size_configs_sampled(cfg, proj):
     _assert_ok(pu.compare(p, Y, dX, dA, dB, rows=rows), f"cfg{cfg}/{wl.projections[proj].name}")
 
 
-DEFAULT_OPTIONS = {"gemm_waves": 8, "gemm_k_step": 32, "gemm_pingpong": 1, "shrink_rows": 128, "shrink_stages": 4, "grad_tokens": 256}
+DEFAULT_OPTIONS = {"shrink_rows": 128, "shrink_stages": 4, "grad_tokens": 256}
 TILINGS = [
-    {"gemm_waves": 4},
-    {"gemm_k_step": 64},
-    {"gemm_pingpong": 0},
     {"shrink_rows": 64, "shrink_stages": 8},
     {"grad_tokens": 64},
-    {"grad_tokens": 2048, "shrink_rows": 64, "gemm_waves": 4},
+    {"grad_tokens": 2048, "shrink_rows": 64},
 ]
 
 
