@@ -75,7 +75,8 @@ typedef struct {
 } tlora_problem_t;
 
 /* Bytes of device workspace that tlora_fwd / tlora_bwd need for this problem (depends only on
- * dtype, J, d_in, d_out, ranks, offsets).  It grows with sum_j T_j * r_j and with r_j * (d_in + d_out);
+ * dtype, J, d_in, d_out, ranks, offsets).  It grows with sum_j T_j * r_j and with r_j * (d_in + d_out), plus
+ * one bf16 d_in x d_out buffer (the transposed W of the backward, shared by all jobs);
  * no d_in x d_out per-job buffer is ever used (Sec. 3.3: the merged adapter weight is not
  * materialised).  Returns 0 if the problem is invalid. */
 size_t tlora_workspace_bytes(const tlora_problem_t* p);
@@ -87,6 +88,9 @@ int tlora_fwd(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_byte
 
 /* flags for tlora_bwd */
 #define TLORA_BWD_REUSE_S 1   /* the workspace still holds S_j from tlora_fwd of this same problem */
+#define TLORA_BWD_REUSE_WT 2  /* the workspace still holds the transposed copy of W that an earlier tlora_bwd with
+                                 the same W, d_in, d_out, job table and workspace made (W is frozen: one copy
+                                 serves every later step) */
 
 /* Backward (derivatives of L = sum(dY * Y); Sec. 3.2 fixes only that each job's backward is
  * independent and that W gets no gradient).
@@ -111,6 +115,8 @@ int tlora_plan_dump(const tlora_problem_t* p, int32_t* rpad, int64_t* soff, int3
 /* Tuning knobs (process-wide, for experiments and for the tiling-independence tests).
  *   "shrink_rows"  : token rows per work unit of the shrink kernels        (64 | 128)
  *   "shrink_stages": LDS stages of the streaming shrink kernel             (4 | 8)
+ *   "dx_transposed_w": 1 (default): dX runs against a transposed copy of W kept in the workspace | 0: against W
+ *                    as it lies in memory (no copy, slower weight stream)
  *   "grad_tokens"  : minimum tokens per work unit of the dA / dB kernels   (multiple of 64)
  * Returns TLORA_EINVAL for an unknown name or an illegal value. */
 int tlora_set_option(const char* name, int64_t value);
@@ -129,7 +135,8 @@ typedef enum {
   TLORA_K_RANK_GRAD = 4,    /* token reductions of dA_j / dB_j (partial tiles)  */
   TLORA_K_GRAD_REDUCE = 5,  /* fixed-order sum of the partial tiles             */
   TLORA_K_F32 = 6,          /* fp32-configuration products                      */
-  TLORA_K_COUNT = 7
+  TLORA_K_WT = 7,           /* transposed copy of W for the dX product          */
+  TLORA_K_COUNT = 8
 } tlora_kernel_class_t;
 int tlora_profile(int enable);
 int tlora_profile_read(int kernel_class, double* total_ms, int64_t* launches);

@@ -19,6 +19,7 @@ struct Options {
   int shrink_rows = 128;
   int shrink_stages = 4;
   int grad_tokens = 256;
+  int dx_transposed_w = 1;
 };
 Options g_opt;
 std::mutex g_mu;
@@ -42,7 +43,7 @@ struct Plan {
   int r_total = 0;                                      // sum of rpad_j
   int64_t sx_elems = 0;                                 // elements of the per-tile K-extension operands
   // workspace byte offsets
-  size_t off_tables = 0, off_S = 0, off_dS = 0, off_Shi = 0, off_Slo = 0, off_dShi = 0, off_dSlo = 0, off_Sx = 0, off_dSx = 0, off_atp = 0, off_ap = 0, off_bp = 0,
+  size_t off_tables = 0, off_S = 0, off_dS = 0, off_Shi = 0, off_Slo = 0, off_dShi = 0, off_dSlo = 0, off_Sx = 0, off_dSx = 0, off_atp = 0, off_wt = 0, off_ap = 0, off_bp = 0,
          off_partial = 0, total = 0;
   size_t tables_bytes = 0;
   // offsets of each table inside the table blob
@@ -240,7 +241,8 @@ int build_plan(const tlora_problem_t* p, Plan& pl) {
     // + 256: a 64-wide K-step over a last 32-wide slice reads (and ignores) 64 bytes past each operand row
     pl.off_Sx = wplace(2 * (size_t)pl.sx_elems + 256);
     pl.off_dSx = wplace(2 * (size_t)pl.sx_elems + 256);
-    pl.off_atp = wplace(2 * (size_t)pl.atp_elems);
+    pl.off_atp = wplace(2 * ((size_t)pl.atp_elems + 32 * (size_t)pl.d_in));
+    pl.off_wt = wplace(2 * (size_t)pl.d_in * (size_t)pl.d_out);
     pl.off_ap = wplace(2 * (size_t)pl.d_in * (size_t)(pl.r_total + 32));
     pl.off_bp = wplace(2 * (size_t)pl.d_out * (size_t)(pl.r_total + 32));
     pl.off_partial = wplace(sizeof(float) * (size_t)std::max(pl.gradB_partial, pl.gradA_partial));
@@ -540,7 +542,7 @@ int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* d
       pl.jobs[j].dA = dA[j];
       pl.jobs[j].dB = dB[j];
     }
-  if (flags & ~TLORA_BWD_REUSE_S) return TLORA_EINVAL;
+  if (flags & ~(TLORA_BWD_REUSE_S | TLORA_BWD_REUSE_WT)) return TLORA_EINVAL;
   rc = check_arch();
   if (rc != TLORA_OK) return rc;
   const bool reuse_S = (flags & TLORA_BWD_REUSE_S) != 0;
@@ -635,9 +637,18 @@ int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* d
       run_shrink(pl, tb, jobs, tiles, dYb, pl.d_out, bp, false, dShi, dSlo, dSx, st);
     }
     if (dX) {
+      // dX = dY . W^T contracts over W's contiguous dimension.  Against a transposed copy of W the weight tiles
+      // are 64 rows of 512 contiguous bytes instead of 256 rows of 128, which the load stream handles markedly
+      // better (the copy costs one read and one write of W; W is frozen, so REUSE_WT skips it).
+      const bool wt = g_opt.dx_transposed_w != 0;
+      uint16_t* Wt = reinterpret_cast<uint16_t*>(ws + pl.off_wt);
+      if (wt && !(flags & TLORA_BWD_REUSE_WT)) {
+        Timed t(TLORA_K_WT, st);
+        launch_transpose_bf16(static_cast<const uint16_t*>(p->W), Wt, pl.d_in, pl.d_out, st);
+      }
       if (g_prof_on) launch_zero_fill(ws + pl.off_clock + 16, 16, st);
       Timed t(TLORA_K_GEMM_BWD, st);
-      launch_seg_gemm(false, tiles, dYb, static_cast<const uint16_t*>(p->W), dSx, ap, pl.r_total,
+      launch_seg_gemm(wt, tiles, dYb, wt ? Wt : static_cast<const uint16_t*>(p->W), dSx, wt ? atp : ap, pl.r_total,
                       static_cast<uint16_t*>(dX), pl.T, pl.d_out, pl.d_in,
                       g_prof_on ? (g_clock_slot[1] = reinterpret_cast<unsigned long long*>(ws + pl.off_clock) + 2) : nullptr,
                       st);
@@ -746,6 +757,11 @@ int tlora_set_option(const char* name, int64_t value) {
   if (n == "shrink_stages") {
     if (value != 4 && value != 8) return TLORA_EINVAL;
     g_opt.shrink_stages = (int)value;
+    return TLORA_OK;
+  }
+  if (n == "dx_transposed_w") {
+    if (value != 0 && value != 1) return TLORA_EINVAL;
+    g_opt.dx_transposed_w = (int)value;
     return TLORA_OK;
   }
   if (n == "grad_tokens") {

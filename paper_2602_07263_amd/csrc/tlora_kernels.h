@@ -9,10 +9,13 @@
 namespace tlora {
 
 // bf16 copies of the adapters in the layouts the MFMA kernels read (zero padded to rpad).
-// atp: per job A_j^T [rpad, d_in];  a_all: [d_in, R + 32] with job j in columns roff_j ..;  b_all: [R + 32, d_out]
+// atp: per job A_j^T [rpad, d_in], stacked in job order ([R + 32, d_in], trailing rows zero);  a_all: [d_in, R + 32] with job j in columns roff_j ..;  b_all: [R + 32, d_out]
 // with job j in rows roff_j ..  (R = r_total; the 32 trailing columns / rows are zero).
 void launch_pack_adapters(const JobDev* jobs, int num_jobs, int d_in, int d_out, int max_rpad, int r_total,
                           uint16_t* atp, uint16_t* a_all, uint16_t* b_all, hipStream_t st);
+
+// out[c, r] = in[r, c]; bf16 [rows, cols] row-major, rows and cols multiples of 8, 16-byte aligned.
+void launch_transpose_bf16(const uint16_t* in, uint16_t* out, int rows, int cols, hipStream_t st);
 
 // Zero `bytes` (multiple of 16) of device memory with a plain store kernel.
 void launch_zero_fill(void* ptr, size_t bytes, hipStream_t st);

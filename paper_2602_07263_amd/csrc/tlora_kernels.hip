@@ -135,7 +135,9 @@ __device__ __forceinline__ bf16x8 frag16_kn(const uint8_t* tile, int nb, int ks,
 
 // ---------------------------------------------------------------------------------------------------
 // Adapter packing: bf16 copies, zero padded to rpad, in the three layouts the kernels read.
-//   atp   : per job, A_j^T [rpad, d_in]                      (shrink operand, k contiguous)
+//   atp   : per job, A_j^T [rpad, d_in], stacked: [R + 32, d_in] with job j in rows roff_j ..
+//                                                             (shrink operand; dX K-extension operand when dX runs
+//                                                              against the transposed weight)
 //   a_all : [d_in, R + 32], job j in columns roff_j ..        (dX K-extension operand, k contiguous)
 //   b_all : [R + 32, d_out], job j in rows roff_j ..          (forward K-extension operand; dS shrink operand)
 // blockIdx.y == num_jobs zero-fills the 32 trailing columns / rows, which the last tile's K-extension
@@ -149,7 +151,10 @@ __global__ void __launch_bounds__(256) pack_adapters_kernel(const JobDev* __rest
   const int64_t first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int ra = r_total + 32;
   if ((int)blockIdx.y == num_jobs) {
-    for (int64_t i = first; i < (int64_t)32 * d_in; i += stride) a_all[(i >> 5) * ra + r_total + (i & 31)] = 0;
+    for (int64_t i = first; i < (int64_t)32 * d_in; i += stride) {
+      a_all[(i >> 5) * ra + r_total + (i & 31)] = 0;
+      atp[(int64_t)r_total * d_in + i] = 0;
+    }
     for (int64_t i = first; i < (int64_t)32 * d_out; i += stride) b_all[(int64_t)r_total * d_out + i] = 0;
     return;
   }
@@ -185,6 +190,39 @@ void launch_pack_adapters(const JobDev* jobs, int num_jobs, int d_in, int d_out,
   if (bx < 1) bx = 1;
   hipLaunchKernelGGL(pack_adapters_kernel, dim3(bx, num_jobs + 1), dim3(256), 0, st, jobs, num_jobs, d_in, d_out,
                      r_total, atp, a_all, b_all);
+}
+
+// out[c, r] = in[r, c] for a row-major bf16 matrix [rows, cols] (both multiples of 8): 64 x 64 tiles through LDS,
+// 16-byte global accesses on both sides.
+__global__ void __launch_bounds__(256) transpose_bf16_kernel(const uint16_t* __restrict__ in, uint16_t* __restrict__ out,
+                                                             int rows, int cols) {
+  __shared__ uint16_t tile[64][72];        // [c][r]; 144-byte pitch keeps the 16-byte row reads aligned
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int r = (tid >> 3) + h * 32, cc = (tid & 7) * 8;
+    u32x4 v = {0, 0, 0, 0};
+    if (r0 + r < rows && c0 + cc < cols) v = ldg16(in + (int64_t)(r0 + r) * cols + c0 + cc);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      tile[cc + 2 * e][r] = (uint16_t)(v[e] & 0xffffu);
+      tile[cc + 2 * e + 1][r] = (uint16_t)(v[e] >> 16);
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int c = (tid >> 3) + h * 32, rr = (tid & 7) * 8;
+    if (c0 + c < cols && r0 + rr < rows)
+      *reinterpret_cast<u32x4*>(out + (int64_t)(c0 + c) * rows + r0 + rr) = *reinterpret_cast<const u32x4*>(&tile[c][rr]);
+  }
+}
+
+void launch_transpose_bf16(const uint16_t* in, uint16_t* out, int rows, int cols, hipStream_t st) {
+  if (rows == 0 || cols == 0) return;
+  hipLaunchKernelGGL(transpose_bf16_kernel, dim3((cols + 63) / 64, (rows + 63) / 64), dim3(256), 0, st, in, out, rows,
+                     cols);
 }
 
 __global__ void __launch_bounds__(256) zero_fill_kernel(u32x4* __restrict__ dst, size_t n16) {

@@ -100,8 +100,9 @@ def test_full_size_configs_sampled(cfg, proj):
     _assert_ok(pu.compare(p, Y, dX, dA, dB, rows=rows), f"cfg{cfg}/{wl.projections[proj].name}")
 
 
-DEFAULT_OPTIONS = {"shrink_rows": 128, "shrink_stages": 4, "grad_tokens": 256}
+DEFAULT_OPTIONS = {"dx_transposed_w": 1, "shrink_rows": 128, "shrink_stages": 4, "grad_tokens": 256}
 TILINGS = [
+    {"dx_transposed_w": 0},
     {"shrink_rows": 64, "shrink_stages": 8},
     {"grad_tokens": 64},
     {"grad_tokens": 2048, "shrink_rows": 64},
@@ -137,5 +138,5 @@ def test_kernel_timing_hooks_count_every_launch():
         tlora.tlora_profile(False)
     assert prof["gemm_fwd"][1] == 1 and prof["gemm_bwd"][1] == 1
     assert prof["shrink"][1] == 2 and prof["rank_grad"][1] == 2 and prof["grad_reduce"][1] == 2
-    assert prof["pack"][1] == 2 and prof["f32"][1] == 0
+    assert prof["pack"][1] == 2 and prof["f32"][1] == 0 and prof["w_transpose"][1] == 1
     assert all(ms >= 0.0 for ms, _ in prof.values()) and prof["gemm_fwd"][0] > 0.0
