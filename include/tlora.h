@@ -88,6 +88,8 @@ int tlora_fwd(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_byte
 
 /* flags for tlora_bwd */
 #define TLORA_BWD_REUSE_S 1   /* the workspace still holds S_j from tlora_fwd of this same problem */
+#define TLORA_BWD_ACCUMULATE 4 /* dA_j += ..., dB_j += ... instead of overwriting them (gradient accumulation over the
+                                 nano-batches or micro-batches of one step); dX is always overwritten */
 #define TLORA_BWD_REUSE_WT 2  /* the workspace still holds the transposed copy of W that an earlier tlora_bwd with
                                  the same W, d_in, d_out, job table and workspace made (W is frozen: one copy
                                  serves every later step) */
@@ -99,6 +101,48 @@ int tlora_fwd(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_byte
  *   Both arrays may be NULL together to skip the adapter gradients. */
 int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* dA, void* const* dB,
               int flags, void* workspace, size_t ws_bytes, void* hip_stream);
+
+/* ---- Adaptive nano-batching (Sec. 3.3, "Adaptive Nano-Batching") --------------------------------------------
+ * The combined batch of the fused jobs is cut along the batch dimension into N nano-batches of about
+ * (sum_i B_i) / N samples each, which the fused kernels process one after the other; N is adapted online by an
+ * additive-increase / multiplicative-decrease controller fed with the measured completion time T_t of a step
+ * (the update rule printed in that paragraph):
+ *     N_{t+1} = N_t + alpha                 if T_t <= T_{t-1} - tau
+ *             = max(1, floor(beta N_t))     otherwise                     (alpha = 4, beta = 1/2 by default).
+ * Readings where the paper is silent: tau = tau_rel * T_{t-1} (tau_rel = 0.02 suggested); the first observation
+ * has no predecessor, so it is only recorded and N is kept; n_max > 0 caps N (a batch has only so many samples).
+ * The controller is plain host state owned by the caller; nothing here touches the GPU. */
+typedef struct {
+  int32_t n;          /* N_t: the number of nano-batches to use for the next step */
+  int32_t alpha;      /* additive step                                            */
+  int32_t n_max;      /* upper limit of N, 0 = none                               */
+  int32_t have_prev;  /* 0 until the first completion time has been seen          */
+  double beta;        /* multiplicative back-off factor, in (0, 1)                */
+  double tau_rel;     /* stability margin as a fraction of T_{t-1}                */
+  double t_prev;      /* T_{t-1}                                                  */
+} tlora_aimd_t;
+/* TLORA_EINVAL unless n0 >= 1, alpha >= 1, 0 < beta < 1, tau_rel >= 0, n_max >= 0. */
+int tlora_aimd_init(tlora_aimd_t* c, int32_t n0, int32_t alpha, double beta, double tau_rel, int32_t n_max);
+/* Feeds T_t (any unit, >= 0), applies the rule, stores N_{t+1} in c->n and in *n_next (may be NULL). */
+int tlora_aimd_update(tlora_aimd_t* c, double t_step, int32_t* n_next);
+
+/* Nano-batch n (0-based) of n_nano: `granule` tokens (a sequence) are the indivisible sample; with
+ * U = ceil(T / granule) samples the nano-batch covers samples floor(n U / n_nano) .. floor((n + 1) U / n_nano) - 1,
+ * i.e. token rows [*row0, *row1) = [min(T, granule floor(n U / n_nano)), min(T, granule floor((n + 1) U / n_nano))).
+ * sub_offsets: HOST [J+1], the offsets (relative to *row0) of the jobs' segments inside that range.  Outputs may
+ * be NULL.  Host-only integer arithmetic. */
+int tlora_nano_split(const tlora_problem_t* p, int32_t n_nano, int64_t granule, int32_t n, int64_t* row0,
+                     int64_t* row1, int64_t* sub_offsets);
+/* Workspace that tlora_fwd_nano / tlora_bwd_nano need: the largest nano-batch's.  0 if invalid. */
+size_t tlora_nano_workspace_bytes(const tlora_problem_t* p, int32_t n_nano, int64_t granule);
+/* tlora_fwd / tlora_bwd over the n_nano nano-batches, one after the other on `hip_stream`, sharing one
+ * workspace.  Same arguments and results as the plain calls (the results do not depend on n_nano beyond
+ * floating-point summation order: dA_j, dB_j are accumulated over the nano-batches in order).  Flags of
+ * tlora_bwd_nano: TLORA_BWD_ACCUMULATE, TLORA_BWD_REUSE_WT (S of a nano-batch is not kept, so no REUSE_S). */
+int tlora_fwd_nano(const tlora_problem_t* p, int32_t n_nano, int64_t granule, void* Y, void* workspace, size_t ws_bytes,
+                   void* hip_stream);
+int tlora_bwd_nano(const tlora_problem_t* p, int32_t n_nano, int64_t granule, const void* dY, void* dX,
+                   void* const* dA, void* const* dB, int flags, void* workspace, size_t ws_bytes, void* hip_stream);
 
 /* Integer bookkeeping of the nano-batch plan (Sec. 3.3, nano-batches = partition of the combined
  * batch along the token dimension), for bit-exact checks.  All outputs are HOST arrays and each may

@@ -4,6 +4,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <cmath>
 #include <mutex>
 #include <string>
 #include <vector>
@@ -22,7 +23,7 @@ struct Options {
   int dx_transposed_w = 1;
 };
 Options g_opt;
-std::mutex g_mu;
+std::recursive_mutex g_mu;   // the nano-batch entry points call tlora_fwd / tlora_bwd under it
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -227,6 +228,9 @@ int build_plan(const tlora_problem_t* p, Plan& pl) {
   // workspace layout
   size_t w = 0;
   auto wplace = [&](size_t bytes) { const size_t at = w;  w = align_up(w + bytes, 256);  return at; };
+  // the transposed W first: its place depends on nothing but d_in x d_out, so a copy made by one call is found
+  // by later calls on other token batches (nano-batches) that share the workspace
+  if (pl.dtype == TLORA_BF16) pl.off_wt = wplace(2 * (size_t)pl.d_in * (size_t)pl.d_out);
   pl.off_tables = wplace(pl.tables_bytes);
   pl.off_clock = wplace(64);
   if (pl.dtype == TLORA_F32) {
@@ -242,7 +246,7 @@ int build_plan(const tlora_problem_t* p, Plan& pl) {
     pl.off_Sx = wplace(2 * (size_t)pl.sx_elems + 256);
     pl.off_dSx = wplace(2 * (size_t)pl.sx_elems + 256);
     pl.off_atp = wplace(2 * ((size_t)pl.atp_elems + 32 * (size_t)pl.d_in));
-    pl.off_wt = wplace(2 * (size_t)pl.d_in * (size_t)pl.d_out);
+
     pl.off_ap = wplace(2 * (size_t)pl.d_in * (size_t)(pl.r_total + 32));
     pl.off_bp = wplace(2 * (size_t)pl.d_out * (size_t)(pl.r_total + 32));
     pl.off_partial = wplace(sizeof(float) * (size_t)std::max(pl.gradB_partial, pl.gradA_partial));
@@ -446,14 +450,14 @@ using namespace tlora;
 extern "C" {
 
 size_t tlora_workspace_bytes(const tlora_problem_t* p) {
-  std::lock_guard<std::mutex> lk(g_mu);
+  std::lock_guard<std::recursive_mutex> lk(g_mu);
   Plan pl;
   if (build_plan(p, pl) != TLORA_OK) return 0;
   return pl.total;
 }
 
 int tlora_fwd(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_bytes, void* hip_stream) {
-  std::lock_guard<std::mutex> lk(g_mu);
+  std::lock_guard<std::recursive_mutex> lk(g_mu);
   Plan pl;
   int rc = common_checks(p, pl, workspace, ws_bytes);
   if (rc != TLORA_OK) return rc;
@@ -528,7 +532,7 @@ int tlora_fwd(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_byte
 
 int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* dA, void* const* dB, int flags,
               void* workspace, size_t ws_bytes, void* hip_stream) {
-  std::lock_guard<std::mutex> lk(g_mu);
+  std::lock_guard<std::recursive_mutex> lk(g_mu);
   Plan pl;
   int rc = common_checks(p, pl, workspace, ws_bytes);
   if (rc != TLORA_OK) return rc;
@@ -542,7 +546,8 @@ int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* d
       pl.jobs[j].dA = dA[j];
       pl.jobs[j].dB = dB[j];
     }
-  if (flags & ~(TLORA_BWD_REUSE_S | TLORA_BWD_REUSE_WT)) return TLORA_EINVAL;
+  if (flags & ~(TLORA_BWD_REUSE_S | TLORA_BWD_REUSE_WT | TLORA_BWD_ACCUMULATE)) return TLORA_EINVAL;
+  const bool accumulate = (flags & TLORA_BWD_ACCUMULATE) != 0;
   rc = check_arch();
   if (rc != TLORA_OK) return rc;
   const bool reuse_S = (flags & TLORA_BWD_REUSE_S) != 0;
@@ -583,10 +588,10 @@ int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* d
       if (want_grads) {
         // dA_j = s_j X_j^T . dS_j : A(m = i, k = t) = X_j[t, i]
         f32_add(units[1], tiles[1], f32_unit(Xj, 1, pl.d_in, dSj, jb.rpad, 1, static_cast<float*>(jb.dA), jb.rank,
-                                             pl.d_in, jb.rank, Tj, jb.scale, false));
+                                             pl.d_in, jb.rank, Tj, jb.scale, accumulate));
         // dB_j = s_j S_j^T . dY_j : A(m = p, k = t) = S_j[t, p]
         f32_add(units[1], tiles[1], f32_unit(Sj, 1, jb.rpad, dYj, pl.d_out, 1, static_cast<float*>(jb.dB), pl.d_out,
-                                             jb.rank, pl.d_out, Tj, jb.scale, false));
+                                             jb.rank, pl.d_out, Tj, jb.scale, accumulate));
       }
     }
     F32Launch L;
@@ -663,7 +668,7 @@ int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* d
     {
       Timed t(TLORA_K_GRAD_REDUCE, st);
       launch_grad_reduce(jobs, reinterpret_cast<const GradGroup*>(tb + pl.tb_gBg), (int)pl.gradB_groups.size(), partial,
-                         pl.d_out, false, st);
+                         pl.d_out, false, accumulate, st);
     }
     {
       Timed t(TLORA_K_RANK_GRAD, st);
@@ -673,15 +678,140 @@ int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* d
     {
       Timed t(TLORA_K_GRAD_REDUCE, st);
       launch_grad_reduce(jobs, reinterpret_cast<const GradGroup*>(tb + pl.tb_gAg), (int)pl.gradA_groups.size(), partial,
-                         pl.d_in, true, st);
+                         pl.d_in, true, accumulate, st);
     }
   }
   return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
 }
 
+// ---- adaptive nano-batching (Sec. 3.3) --------------------------------------------------------------------
+int tlora_aimd_init(tlora_aimd_t* c, int32_t n0, int32_t alpha, double beta, double tau_rel, int32_t n_max) {
+  if (!c) return TLORA_ENULL;
+  if (n0 < 1 || alpha < 1 || !(beta > 0.0 && beta < 1.0) || !(tau_rel >= 0.0) || n_max < 0) return TLORA_EINVAL;
+  c->n = n_max > 0 ? std::min(n0, n_max) : n0;
+  c->alpha = alpha;  c->n_max = n_max;  c->have_prev = 0;
+  c->beta = beta;  c->tau_rel = tau_rel;  c->t_prev = 0.0;
+  return TLORA_OK;
+}
+
+int tlora_aimd_update(tlora_aimd_t* c, double t_step, int32_t* n_next) {
+  if (!c) return TLORA_ENULL;
+  if (!(t_step >= 0.0) || c->n < 1) return TLORA_EINVAL;
+  int64_t n = c->n;
+  if (c->have_prev) {
+    const double tau = c->tau_rel * c->t_prev;
+    if (t_step <= c->t_prev - tau) n = n + c->alpha;                              // additive increase
+    else n = std::max<int64_t>(1, (int64_t)std::floor(c->beta * (double)c->n));   // multiplicative decrease
+  }
+  if (c->n_max > 0) n = std::min<int64_t>(n, c->n_max);
+  n = std::min<int64_t>(n, INT32_MAX);
+  c->n = (int32_t)n;  c->t_prev = t_step;  c->have_prev = 1;
+  if (n_next) *n_next = c->n;
+  return TLORA_OK;
+}
+
+namespace {
+// token boundary n of N nano-batches: whole samples of `granule` tokens, floor(n U / N) of the U samples
+int64_t nano_bound(int64_t T, int64_t n, int64_t N, int64_t granule) {
+  const int64_t units = (T + granule - 1) / granule;
+  return std::min<int64_t>(T, granule * (int64_t)(((__int128)n * units) / N));
+}
+// sub-problem of one nano-batch: same jobs, the rows of each segment that fall into [b0, b1)
+struct NanoSub {
+  tlora_problem_t p;
+  std::vector<int64_t> off;
+  int64_t b0 = 0, b1 = 0;
+};
+int make_sub(const tlora_problem_t* p, int32_t n_nano, int64_t granule, int32_t n, NanoSub& s) {
+  const int rc = validate(p);
+  if (rc != TLORA_OK) return rc;
+  if (n_nano < 1 || granule < 1 || n < 0 || n >= n_nano) return TLORA_EINVAL;
+  const int64_t T = p->offsets[p->num_jobs];
+  s.b0 = nano_bound(T, n, n_nano, granule);
+  s.b1 = nano_bound(T, n + 1, n_nano, granule);
+  s.off.resize(p->num_jobs + 1);
+  for (int j = 0; j <= p->num_jobs; ++j) s.off[j] = std::min(std::max(p->offsets[j], s.b0), s.b1) - s.b0;
+  s.p = *p;
+  s.p.offsets = s.off.data();
+  const size_t elt = p->dtype == TLORA_F32 ? 4 : 2;
+  s.p.X = p->X ? static_cast<const uint8_t*>(p->X) + (size_t)s.b0 * p->d_in * elt : nullptr;
+  return TLORA_OK;
+}
+}  // namespace
+
+int tlora_nano_split(const tlora_problem_t* p, int32_t n_nano, int64_t granule, int32_t n, int64_t* row0,
+                     int64_t* row1, int64_t* sub_offsets) {
+  NanoSub s;
+  const int rc = make_sub(p, n_nano, granule, n, s);
+  if (rc != TLORA_OK) return rc;
+  if (row0) *row0 = s.b0;
+  if (row1) *row1 = s.b1;
+  if (sub_offsets) std::copy(s.off.begin(), s.off.end(), sub_offsets);
+  return TLORA_OK;
+}
+
+size_t tlora_nano_workspace_bytes(const tlora_problem_t* p, int32_t n_nano, int64_t granule) {
+  size_t need = 0;
+  for (int32_t n = 0; n < n_nano; ++n) {
+    NanoSub s;
+    if (make_sub(p, n_nano, granule, n, s) != TLORA_OK) return 0;
+    const size_t b = tlora_workspace_bytes(&s.p);
+    if (b == 0) return 0;
+    need = std::max(need, b);
+  }
+  return need;
+}
+
+int tlora_fwd_nano(const tlora_problem_t* p, int32_t n_nano, int64_t granule, void* Y, void* workspace, size_t ws_bytes,
+                   void* hip_stream) {
+  std::lock_guard<std::recursive_mutex> lk(g_mu);
+  if (!p) return TLORA_ENULL;
+  const size_t need = tlora_nano_workspace_bytes(p, n_nano, granule);
+  if (need == 0) return validate(p) != TLORA_OK ? validate(p) : TLORA_EINVAL;
+  if (!workspace || ws_bytes < need) return TLORA_EWORKSPACE;
+  const size_t elt = p->dtype == TLORA_F32 ? 4 : 2;
+  for (int32_t n = 0; n < n_nano; ++n) {          // one after the other, on the caller's stream
+    NanoSub s;
+    int rc = make_sub(p, n_nano, granule, n, s);
+    if (rc != TLORA_OK) return rc;
+    if (s.b1 == s.b0) continue;
+    rc = tlora_fwd(&s.p, Y ? static_cast<uint8_t*>(Y) + (size_t)s.b0 * p->d_out * elt : nullptr, workspace, ws_bytes,
+                   hip_stream);
+    if (rc != TLORA_OK) return rc;
+  }
+  return TLORA_OK;
+}
+
+int tlora_bwd_nano(const tlora_problem_t* p, int32_t n_nano, int64_t granule, const void* dY, void* dX, void* const* dA,
+                   void* const* dB, int flags, void* workspace, size_t ws_bytes, void* hip_stream) {
+  std::lock_guard<std::recursive_mutex> lk(g_mu);
+  if (!p) return TLORA_ENULL;
+  if (flags & ~(TLORA_BWD_REUSE_WT | TLORA_BWD_ACCUMULATE)) return TLORA_EINVAL;   // S of a nano-batch is not kept
+  const size_t need = tlora_nano_workspace_bytes(p, n_nano, granule);
+  if (need == 0) return validate(p) != TLORA_OK ? validate(p) : TLORA_EINVAL;
+  if (!workspace || ws_bytes < need) return TLORA_EWORKSPACE;
+  const size_t elt = p->dtype == TLORA_F32 ? 4 : 2;
+  bool first = true, wt_made = (flags & TLORA_BWD_REUSE_WT) != 0;
+  for (int32_t n = 0; n < n_nano; ++n) {
+    NanoSub s;
+    int rc = make_sub(p, n_nano, granule, n, s);
+    if (rc != TLORA_OK) return rc;
+    if (s.b1 == s.b0 && !(first && n == n_nano - 1)) continue;      // (an all-empty batch still zeroes dA / dB once)
+    // the adapter gradients are sums over the job's tokens: the first nano-batch overwrites, the others add
+    int f = (first ? (flags & TLORA_BWD_ACCUMULATE) : TLORA_BWD_ACCUMULATE) | (wt_made ? TLORA_BWD_REUSE_WT : 0);
+    rc = tlora_bwd(&s.p, dY ? static_cast<const uint8_t*>(dY) + (size_t)s.b0 * p->d_out * elt : nullptr,
+                   dX ? static_cast<uint8_t*>(dX) + (size_t)s.b0 * p->d_in * elt : nullptr, dA, dB, f, workspace,
+                   ws_bytes, hip_stream);
+    if (rc != TLORA_OK) return rc;
+    first = false;
+    if (dX && s.b1 > s.b0) wt_made = true;
+  }
+  return TLORA_OK;
+}
+
 int tlora_plan_dump(const tlora_problem_t* p, int32_t* rpad, int64_t* soff, int32_t* tile_rows, int64_t* tile_row0,
                     int32_t* tile_nrows, int32_t* tile_job_first, int32_t* tile_job_last, int64_t* n_tiles) {
-  std::lock_guard<std::mutex> lk(g_mu);
+  std::lock_guard<std::recursive_mutex> lk(g_mu);
   Plan pl;
   const int rc = build_plan(p, pl);
   if (rc != TLORA_OK) return rc;
@@ -709,7 +839,7 @@ int tlora_plan_dump(const tlora_problem_t* p, int32_t* rpad, int64_t* soff, int3
 }
 
 int tlora_profile(int enable) {
-  std::lock_guard<std::mutex> lk(g_mu);
+  std::lock_guard<std::recursive_mutex> lk(g_mu);
   const int rc = prof_drain();
   g_prof_on = enable != 0;
   if (g_prof_on) g_clock_slot[0] = g_clock_slot[1] = nullptr;
@@ -722,7 +852,7 @@ int tlora_profile(int enable) {
 }
 
 int tlora_profile_read(int kernel_class, double* total_ms, int64_t* launches) {
-  std::lock_guard<std::mutex> lk(g_mu);
+  std::lock_guard<std::recursive_mutex> lk(g_mu);
   if (kernel_class < 0 || kernel_class >= TLORA_K_COUNT) return TLORA_EINVAL;
   const int rc = prof_drain();
   if (rc != TLORA_OK) return rc;
@@ -732,7 +862,7 @@ int tlora_profile_read(int kernel_class, double* total_ms, int64_t* launches) {
 }
 
 int tlora_profile_clock(double* ghz_fwd, double* ghz_bwd) {
-  std::lock_guard<std::mutex> lk(g_mu);
+  std::lock_guard<std::recursive_mutex> lk(g_mu);
   double* out[2] = {ghz_fwd, ghz_bwd};
   for (int i = 0; i < 2; ++i) {
     if (!out[i]) continue;
@@ -746,7 +876,7 @@ int tlora_profile_clock(double* ghz_fwd, double* ghz_bwd) {
 }
 
 int tlora_set_option(const char* name, int64_t value) {
-  std::lock_guard<std::mutex> lk(g_mu);
+  std::lock_guard<std::recursive_mutex> lk(g_mu);
   if (!name) return TLORA_ENULL;
   const std::string n(name);
   if (n == "shrink_rows") {

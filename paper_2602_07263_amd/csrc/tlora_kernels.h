@@ -44,8 +44,9 @@ void launch_seg_gemm(bool w_is_kn, const TileDev* tiles, const uint16_t* act, co
 // partial[u] = sum_{t in unit u} U_j[t, p] * V[t, c]   then   G_j = scale_j * sum_u partial[u]
 void launch_rank_grad(const JobDev* jobs, const GradUnit* units, int num_units, const uint16_t* U_hi,
                       const uint16_t* U_lo, const uint16_t* V, int D, float* partial, hipStream_t st);
+// accumulate: G_j += ... instead of G_j = ...
 void launch_grad_reduce(const JobDev* jobs, const GradGroup* groups, int num_groups, const float* partial, int D,
-                        bool out_is_dA, hipStream_t st);
+                        bool out_is_dA, bool accumulate, hipStream_t st);
 
 // fp32 configuration: strided products on plain FMA units.
 void launch_f32_units(const F32Unit* units, const F32Tile* tiles, int num_tiles, hipStream_t st);

@@ -1067,7 +1067,8 @@ void launch_rank_grad(const JobDev* jobs, const GradUnit* units, int num_units, 
 // dA_j is the transpose of the computed tile: [D, r]).  One workgroup = 4 rank rows x 256 columns of a group.
 __global__ void __launch_bounds__(256) grad_reduce_kernel(const JobDev* __restrict__ jobs,
                                                           const GradGroup* __restrict__ groups,
-                                                          const float* __restrict__ partial, int D, int out_is_dA) {
+                                                          const float* __restrict__ partial, int D, int out_is_dA,
+                                                          int accumulate) {
   const GradGroup g = groups[blockIdx.x];
   const JobDev jb = jobs[g.job];
   const int c = g.cb * kGradCols + threadIdx.x;
@@ -1087,18 +1088,18 @@ __global__ void __launch_bounds__(256) grad_reduce_kernel(const JobDev* __restri
   for (int i = 0; i < 4; ++i) {
     const int p = g.pb * pb_rows + pl0 + i;
     if (p < jb.rank) {
+      float* const d = out_is_dA ? dst + (int64_t)c * jb.rank + p : dst + (int64_t)p * D + c;
       const float v = s[i] * jb.scale;
-      if (out_is_dA) dst[(int64_t)c * jb.rank + p] = v;
-      else           dst[(int64_t)p * D + c] = v;
+      *d = accumulate ? *d + v : v;
     }
   }
 }
 
 void launch_grad_reduce(const JobDev* jobs, const GradGroup* groups, int num_groups, const float* partial, int D,
-                        bool out_is_dA, hipStream_t st) {
+                        bool out_is_dA, bool accumulate, hipStream_t st) {
   if (num_groups == 0) return;
   hipLaunchKernelGGL(grad_reduce_kernel, dim3(num_groups, kGradMaxBlocks * kGradRanks / 4), dim3(256), 0, st, jobs, groups, partial,
-                     D, out_is_dA ? 1 : 0);
+                     D, out_is_dA ? 1 : 0, accumulate ? 1 : 0);
 }
 
 // ---------------------------------------------------------------------------------------------------

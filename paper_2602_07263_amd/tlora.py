@@ -13,6 +13,8 @@ from typing import List, Optional, Sequence
 
 TLORA_F32, TLORA_BF16 = 0, 1
 TLORA_BWD_REUSE_S = 1
+TLORA_BWD_REUSE_WT = 2
+TLORA_BWD_ACCUMULATE = 4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("TLORA_LIB") or os.path.join(_HERE, "libtlora.so")
@@ -32,7 +34,15 @@ class tlora_problem_t(ctypes.Structure):
                 ("A", ctypes.POINTER(ctypes.c_void_p)), ("B", ctypes.POINTER(ctypes.c_void_p))]
 
 
-EXPORTS = ["tlora_workspace_bytes", "tlora_fwd", "tlora_bwd", "tlora_plan_dump", "tlora_set_option",
+class tlora_aimd_t(ctypes.Structure):
+    _fields_ = [("n", ctypes.c_int32), ("alpha", ctypes.c_int32), ("n_max", ctypes.c_int32),
+                ("have_prev", ctypes.c_int32), ("beta", ctypes.c_double), ("tau_rel", ctypes.c_double),
+                ("t_prev", ctypes.c_double)]
+
+
+EXPORTS = ["tlora_workspace_bytes", "tlora_fwd", "tlora_bwd", "tlora_aimd_init", "tlora_aimd_update",
+           "tlora_nano_split", "tlora_nano_workspace_bytes", "tlora_fwd_nano", "tlora_bwd_nano",
+           "tlora_plan_dump", "tlora_set_option",
            "tlora_profile", "tlora_profile_read", "tlora_profile_clock", "tlora_strerror", "tlora_version"]
 KERNEL_CLASSES = ["pack", "shrink", "gemm_fwd", "gemm_bwd", "rank_grad", "grad_reduce", "f32", "w_transpose"]
 
@@ -55,6 +65,23 @@ def lib() -> ctypes.CDLL:
     L.tlora_bwd.argtypes = [P, ctypes.c_void_p, ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p),
                             ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t,
                             ctypes.c_void_p]
+    L.tlora_aimd_init.restype = ctypes.c_int
+    L.tlora_aimd_init.argtypes = [ctypes.POINTER(tlora_aimd_t), ctypes.c_int32, ctypes.c_int32, ctypes.c_double,
+                                  ctypes.c_double, ctypes.c_int32]
+    L.tlora_aimd_update.restype = ctypes.c_int
+    L.tlora_aimd_update.argtypes = [ctypes.POINTER(tlora_aimd_t), ctypes.c_double, ctypes.POINTER(ctypes.c_int32)]
+    L.tlora_nano_split.restype = ctypes.c_int
+    L.tlora_nano_split.argtypes = [P, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.POINTER(ctypes.c_int64),
+                                   ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64)]
+    L.tlora_nano_workspace_bytes.restype = ctypes.c_size_t
+    L.tlora_nano_workspace_bytes.argtypes = [P, ctypes.c_int32, ctypes.c_int64]
+    L.tlora_fwd_nano.restype = ctypes.c_int
+    L.tlora_fwd_nano.argtypes = [P, ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+                                 ctypes.c_void_p]
+    L.tlora_bwd_nano.restype = ctypes.c_int
+    L.tlora_bwd_nano.argtypes = [P, ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
+                                 ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_void_p), ctypes.c_int,
+                                 ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     L.tlora_plan_dump.restype = ctypes.c_int
     L.tlora_plan_dump.argtypes = [P, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64),
                                   ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64),
@@ -152,6 +179,56 @@ def tlora_bwd(prob: tlora_problem_t, dY_ptr: int, dX_ptr: int, dA_ptrs: Optional
                            ctypes.c_void_p(stream)), "tlora_bwd")
 
 
+def _grad_ptr_arrays(J, dA_ptrs, dB_ptrs):
+    if dA_ptrs is None:
+        return None, None
+    return ((ctypes.c_void_p * J)(*[ctypes.c_void_p(int(p)) if p else None for p in dA_ptrs]),
+            (ctypes.c_void_p * J)(*[ctypes.c_void_p(int(p)) if p else None for p in dB_ptrs]))
+
+
+def tlora_aimd_init(n0: int, alpha: int = 4, beta: float = 0.5, tau_rel: float = 0.02, n_max: int = 0) -> tlora_aimd_t:
+    c = tlora_aimd_t()
+    _check(lib().tlora_aimd_init(ctypes.byref(c), int(n0), int(alpha), float(beta), float(tau_rel), int(n_max)),
+           "tlora_aimd_init")
+    return c
+
+
+def tlora_aimd_update(c: tlora_aimd_t, t_step: float) -> int:
+    n = ctypes.c_int32(0)
+    _check(lib().tlora_aimd_update(ctypes.byref(c), float(t_step), ctypes.byref(n)), "tlora_aimd_update")
+    return int(n.value)
+
+
+def tlora_nano_split(prob: tlora_problem_t, n_nano: int, granule: int, n: int):
+    """(row0, row1, sub-offsets) of nano-batch n."""
+    r0, r1 = ctypes.c_int64(0), ctypes.c_int64(0)
+    sub = (ctypes.c_int64 * (prob.num_jobs + 1))()
+    _check(lib().tlora_nano_split(ctypes.byref(prob), int(n_nano), int(granule), int(n), ctypes.byref(r0),
+                                  ctypes.byref(r1), sub), "tlora_nano_split")
+    return int(r0.value), int(r1.value), list(sub)
+
+
+def tlora_nano_workspace_bytes(prob: tlora_problem_t, n_nano: int, granule: int) -> int:
+    return int(lib().tlora_nano_workspace_bytes(ctypes.byref(prob), int(n_nano), int(granule)))
+
+
+def tlora_fwd_nano(prob: tlora_problem_t, n_nano: int, granule: int, Y_ptr: int, ws_ptr: int, ws_bytes: int,
+                   stream: int = 0) -> None:
+    _check(lib().tlora_fwd_nano(ctypes.byref(prob), int(n_nano), int(granule), ctypes.c_void_p(Y_ptr),
+                                ctypes.c_void_p(ws_ptr), ctypes.c_size_t(ws_bytes), ctypes.c_void_p(stream)),
+           "tlora_fwd_nano")
+
+
+def tlora_bwd_nano(prob: tlora_problem_t, n_nano: int, granule: int, dY_ptr: int, dX_ptr: int,
+                   dA_ptrs: Optional[Sequence[int]], dB_ptrs: Optional[Sequence[int]], flags: int, ws_ptr: int,
+                   ws_bytes: int, stream: int = 0) -> None:
+    c_dA, c_dB = _grad_ptr_arrays(prob.num_jobs, dA_ptrs, dB_ptrs)
+    _check(lib().tlora_bwd_nano(ctypes.byref(prob), int(n_nano), int(granule), ctypes.c_void_p(dY_ptr),
+                                ctypes.c_void_p(dX_ptr) if dX_ptr else None, c_dA, c_dB, int(flags),
+                                ctypes.c_void_p(ws_ptr), ctypes.c_size_t(ws_bytes), ctypes.c_void_p(stream)),
+           "tlora_bwd_nano")
+
+
 def tlora_plan_dump(prob: tlora_problem_t) -> dict:
     """The plan's integer bookkeeping as Python lists."""
     J = prob.num_jobs
@@ -228,11 +305,21 @@ class LayerProblem:
     def fwd(self, Y) -> None:
         tlora_fwd(self.prob, Y.data_ptr(), self.ws.data_ptr(), self.ws_bytes, self._stream())
 
-    def bwd(self, dY, dX, dA, dB, reuse_S: bool = False) -> None:
+    def bwd(self, dY, dX, dA, dB, reuse_S: bool = False, flags: int = 0) -> None:
         tlora_bwd(self.prob, dY.data_ptr(), dX.data_ptr() if dX is not None else 0,
                   None if dA is None else [a.data_ptr() if a.numel() else 0 for a in dA],
                   None if dB is None else [b.data_ptr() if b.numel() else 0 for b in dB],
-                  TLORA_BWD_REUSE_S if reuse_S else 0, self.ws.data_ptr(), self.ws_bytes, self._stream())
+                  (TLORA_BWD_REUSE_S if reuse_S else 0) | flags, self.ws.data_ptr(), self.ws_bytes, self._stream())
+
+    def fwd_nano(self, n_nano: int, granule: int, Y) -> None:
+        """Forward over n_nano nano-batches (the workspace of the whole batch is large enough for any of them)."""
+        tlora_fwd_nano(self.prob, n_nano, granule, Y.data_ptr(), self.ws.data_ptr(), self.ws_bytes, self._stream())
+
+    def bwd_nano(self, n_nano: int, granule: int, dY, dX, dA, dB, flags: int = 0) -> None:
+        tlora_bwd_nano(self.prob, n_nano, granule, dY.data_ptr(), dX.data_ptr() if dX is not None else 0,
+                       None if dA is None else [a.data_ptr() if a.numel() else 0 for a in dA],
+                       None if dB is None else [b.data_ptr() if b.numel() else 0 for b in dB],
+                       flags, self.ws.data_ptr(), self.ws_bytes, self._stream())
 
     def job_slice(self, j: int) -> "LayerProblem":
         """Job j alone as a one-job problem over views of the same tensors (the per-job loop baseline)."""
