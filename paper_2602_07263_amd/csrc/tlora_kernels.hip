@@ -370,26 +370,27 @@ constexpr int waitcnt_vm_lgkm0(int vm) { return (vm & 15) | ((vm >> 4) << 14) | 
 // (128 x 32); NS stages are filled NS - 1 steps ahead by raw asynchronous global->LDS loads, so several KB
 // per wave stay in flight without holding registers -- the kernel is bound by how fast X (or dY) streams in.
 // ---------------------------------------------------------------------------------------------------
-template <int ROWS, int NS, int KS>
-__global__ void __launch_bounds__(256) shrink_stream_kernel(const JobDev* __restrict__ jobs,
-                                                            const TileDev* __restrict__ tiles,
-                                                            const ShrinkUnit* __restrict__ units,
-                                                            const uint16_t* __restrict__ act, int K,
-                                                            const uint16_t* __restrict__ packed, int packed_is_atp,
-                                                            uint16_t* __restrict__ Shi, uint16_t* __restrict__ Slo,
-                                                            uint16_t* __restrict__ Sx) {
-  constexpr int PCOLS = 128;                       // padded rank columns per unit
-  constexpr int WM = ROWS / 32, WN = 4 / WM;       // waves along token rows / along rank columns
+// PCOLS: rank columns staged per step.  A unit whose job has at most 32 padded rank columns stages a 32-column
+// adapter tile and spends the LDS it saves on more stages: the kernel is bound by the bytes of X in flight.
+template <int ROWS, int NS, int KS, int PCOLS>
+__device__ __forceinline__ void shrink_stream_body(uint8_t* lds, const ShrinkUnit u, const JobDev jb,
+                                                   const TileDev* __restrict__ tiles,
+                                                   const uint16_t* __restrict__ act, int K,
+                                                   const uint16_t* __restrict__ packed, int packed_is_atp,
+                                                   uint16_t* __restrict__ Shi, uint16_t* __restrict__ Slo,
+                                                   uint16_t* __restrict__ Sx) {
+  constexpr int WM = PCOLS == 32 ? 4 : ROWS / 32;  // waves along token rows
+  constexpr int WN = 4 / WM;                       // waves along rank columns
+  static_assert(WM * 32 == ROWS || PCOLS != 32, "a 32-column unit needs 128 token rows for its four waves");
   constexpr int PW = PCOLS / WN, NPB = PW / 32;    // rank columns (and 32-wide blocks) per wave
   constexpr int RB = KS * 2;                       // bytes per tile row: 64 (K-steps of 32) or 128 (of 64)
   constexpr int CPR = RB / 16;                     // 16-byte chunks per tile row
   constexpr int A_BYTES = ROWS * RB, P_BYTES = PCOLS * RB, STAGE = A_BYTES + P_BYTES;
   constexpr int A_LD = A_BYTES / 1024 / 4, P_LD = P_BYTES / 1024 / 4;   // loads per wave per step
   static_assert(kGemmBM == 256, "the row -> GEMM tile lookup below shifts by 8");
-  __shared__ __attribute__((aligned(1024))) uint8_t lds[NS * STAGE];
+  static_assert(NS * STAGE <= 160 * 1024, "LDS of a CU");
+  static_assert(P_LD >= 1, "at least one adapter load per wave and step");
 
-  const ShrinkUnit u = units[blockIdx.x];
-  const JobDev jb = jobs[u.job];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, so LDS bases stay in SGPRs
   const int wm = wave % WM, wn = wave / WM;
@@ -443,16 +444,22 @@ __global__ void __launch_bounds__(256) shrink_stream_kernel(const JobDev* __rest
     __builtin_amdgcn_s_barrier();
     issue();                                       // into the stage read in step kt - 1
     const uint8_t* S = lds + (kt % NS) * STAGE;
+    // all fragments of the step first, then the MFMAs: with one wave per SIMD a read -> wait -> MFMA chain per
+    // k-slice would pay the LDS latency KS / 16 times per step
+    bf16x8 xf[KS / 16], pf[KS / 16][NPB];
 #pragma unroll
     for (int kk = 0; kk < KS / 16; ++kk) {
-      const bf16x8 xf = KS == 32 ? frag_row32(S, wm * 32, kk, lane) : frag_row_tile(S, wm * 32, kk, lane);
+      xf[kk] = KS == 32 ? frag_row32(S, wm * 32, kk, lane) : frag_row_tile(S, wm * 32, kk, lane);
 #pragma unroll
-      for (int i = 0; i < NPB; ++i) {
-        const bf16x8 pf = KS == 32 ? frag_row32(S + A_BYTES, wn * PW + i * 32, kk, lane)
-                                   : frag_row_tile(S + A_BYTES, wn * PW + i * 32, kk, lane);
-        acc[i] = mfma32(pf, xf, acc[i]);
-      }
+      for (int i = 0; i < NPB; ++i)
+        pf[kk][i] = KS == 32 ? frag_row32(S + A_BYTES, wn * PW + i * 32, kk, lane)
+                             : frag_row_tile(S + A_BYTES, wn * PW + i * 32, kk, lane);
     }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int kk = 0; kk < KS / 16; ++kk)
+#pragma unroll
+      for (int i = 0; i < NPB; ++i) acc[i] = mfma32(pf[kk][i], xf[kk], acc[i]);
   }
   __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));   // drain before the workgroup's LDS is released
 
@@ -489,6 +496,27 @@ __global__ void __launch_bounds__(256) shrink_stream_kernel(const JobDev* __rest
         }
       }
   }
+}
+
+template <int ROWS, int NS, int KS>
+__global__ void __launch_bounds__(256) shrink_stream_kernel(const JobDev* __restrict__ jobs,
+                                                            const TileDev* __restrict__ tiles,
+                                                            const ShrinkUnit* __restrict__ units,
+                                                            const uint16_t* __restrict__ act, int K,
+                                                            const uint16_t* __restrict__ packed, int packed_is_atp,
+                                                            uint16_t* __restrict__ Shi, uint16_t* __restrict__ Slo,
+                                                            uint16_t* __restrict__ Sx) {
+  // NS stages of (ROWS + 128) rows, or -- 128-row units of low-rank jobs, K-steps of 64 -- 8 stages of 128 + 32 rows
+  constexpr int LOW = ROWS == 128 && KS == 64;
+  constexpr int BYTES = LOW ? 8 * (128 + 32) * 128 : NS * (ROWS + 128) * KS * 2;
+  constexpr int NS_HIGH = LOW ? 5 : NS;          // the LDS is there anyway: a fifth stage for the 128-column units
+  __shared__ __attribute__((aligned(1024))) uint8_t lds[BYTES];
+  const ShrinkUnit u = units[blockIdx.x];
+  const JobDev jb = jobs[u.job];
+  if (LOW && jb.rpad <= 32)
+    shrink_stream_body<128, 8, 64, 32>(lds, u, jb, tiles, act, K, packed, packed_is_atp, Shi, Slo, Sx);
+  else
+    shrink_stream_body<ROWS, NS_HIGH, KS, 128>(lds, u, jb, tiles, act, K, packed, packed_is_atp, Shi, Slo, Sx);
 }
 
 void launch_shrink(const JobDev* jobs, const TileDev* tiles, const ShrinkUnit* units, int num_units, int shrink_rows,
