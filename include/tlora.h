@@ -144,6 +144,31 @@ int tlora_fwd_nano(const tlora_problem_t* p, int32_t n_nano, int64_t granule, vo
 int tlora_bwd_nano(const tlora_problem_t* p, int32_t n_nano, int64_t granule, const void* dY, void* dX,
                    void* const* dA, void* const* dB, int flags, void* workspace, size_t ws_bytes, void* hip_stream);
 
+/* ---- Per-job optimizer step -------------------------------------------------------------------------------
+ * Sec. 3.2: jobs fused on the shared backbone keep their own optimizer state.  The paper names no optimizer; this
+ * is AdamW (decoupled weight decay) on any list of adapter tensors, each with its own hyper-parameters and step
+ * count, in one launch:
+ *     m = beta1 m + (1 - beta1) g;  v = beta2 v + (1 - beta2) g^2;
+ *     w = w - lr ( (m / (1 - beta1^t)) / (sqrt(v / (1 - beta2^t)) + eps) + weight_decay w )
+ * in fp32 on the fp32 master copy; `param` (what tlora_fwd / tlora_bwd read as A_j or B_j) is rewritten from it,
+ * rounded to nearest-even when dtype is TLORA_BF16.  `tensors` is a HOST array; every pointer inside is a DEVICE
+ * pointer; `master` may be NULL for TLORA_F32 (the update then runs on `param`).  grad is typically dA_j / dB_j
+ * of tlora_bwd.  Asynchronous on `hip_stream`; the workspace (256-byte aligned, tlora_adamw_workspace_bytes)
+ * holds the tensor table during the call. */
+typedef struct {
+  void* param;          /* DEVICE [n], bf16 or fp32 per `dtype`; rewritten          */
+  float* master;        /* DEVICE fp32 [n]; updated                                 */
+  const float* grad;    /* DEVICE fp32 [n]                                          */
+  float* m;             /* DEVICE fp32 [n] first moment; updated                    */
+  float* v;             /* DEVICE fp32 [n] second moment; updated                   */
+  int64_t n;            /* elements                                                 */
+  float lr, beta1, beta2, eps, weight_decay;
+  int32_t step;         /* t >= 1: the step being taken (bias correction)           */
+} tlora_adamw_tensor_t;
+size_t tlora_adamw_workspace_bytes(int32_t count);
+int tlora_adamw_step(const tlora_adamw_tensor_t* tensors, int32_t count, int32_t dtype, void* workspace,
+                     size_t ws_bytes, void* hip_stream);
+
 /* Integer bookkeeping of the nano-batch plan (Sec. 3.3, nano-batches = partition of the combined
  * batch along the token dimension), for bit-exact checks.  All outputs are HOST arrays and each may
  * be NULL.  Per job: rpad[J] (rank rounded up to the 8-element granule), soff[J+1] (element
@@ -180,7 +205,8 @@ typedef enum {
   TLORA_K_GRAD_REDUCE = 5,  /* fixed-order sum of the partial tiles             */
   TLORA_K_F32 = 6,          /* fp32-configuration products                      */
   TLORA_K_WT = 7,           /* transposed copy of W for the dX product          */
-  TLORA_K_COUNT = 8
+  TLORA_K_OPT = 8,          /* optimizer step                                   */
+  TLORA_K_COUNT = 9
 } tlora_kernel_class_t;
 int tlora_profile(int enable);
 int tlora_profile_read(int kernel_class, double* total_ms, int64_t* launches);

@@ -809,6 +809,51 @@ int tlora_bwd_nano(const tlora_problem_t* p, int32_t n_nano, int64_t granule, co
   return TLORA_OK;
 }
 
+// ---- per-job optimizer step ---------------------------------------------------------------------------------
+size_t tlora_adamw_workspace_bytes(int32_t count) {
+  if (count < 0) return 0;
+  return std::max<size_t>(256, align_up(sizeof(AdamwDev) * (size_t)count, 256));
+}
+
+int tlora_adamw_step(const tlora_adamw_tensor_t* tensors, int32_t count, int32_t dtype, void* workspace, size_t ws_bytes,
+                     void* hip_stream) {
+  std::lock_guard<std::recursive_mutex> lk(g_mu);
+  if (count < 0) return TLORA_EINVAL;
+  if (dtype != TLORA_F32 && dtype != TLORA_BF16) return TLORA_EDTYPE;
+  if (count > 0 && !tensors) return TLORA_ENULL;
+  if (count > 65535) return TLORA_EINVAL;
+  std::vector<uint8_t> blob(sizeof(AdamwDev) * (size_t)count);
+  AdamwDev* d = reinterpret_cast<AdamwDev*>(blob.data());
+  int64_t max_n = 0;
+  for (int i = 0; i < count; ++i) {
+    const tlora_adamw_tensor_t& t = tensors[i];
+    if (t.n < 0 || t.step < 1 || !(t.beta1 >= 0.f && t.beta1 < 1.f) || !(t.beta2 >= 0.f && t.beta2 < 1.f) ||
+        !(t.eps >= 0.f) || !(t.lr >= 0.f) || !(t.weight_decay >= 0.f))
+      return TLORA_EINVAL;
+    if (t.n > 0 && (!t.param || !t.grad || !t.m || !t.v)) return TLORA_ENULL;
+    if (t.n > 0 && dtype == TLORA_BF16 && !t.master) return TLORA_ENULL;   // a bf16 tensor cannot carry the update
+    d[i].param = t.param;  d[i].master = t.master;  d[i].grad = t.grad;  d[i].m = t.m;  d[i].v = t.v;  d[i].n = t.n;
+    d[i].lr = t.lr;  d[i].beta1 = t.beta1;  d[i].beta2 = t.beta2;  d[i].eps = t.eps;  d[i].weight_decay = t.weight_decay;
+    d[i].c1 = (float)(1.0 / (1.0 - std::pow((double)t.beta1, (double)t.step)));
+    d[i].c2 = (float)(1.0 / (1.0 - std::pow((double)t.beta2, (double)t.step)));
+    d[i].param_is_bf16 = dtype == TLORA_BF16;
+    max_n = std::max(max_n, t.n);
+  }
+  if (count == 0 || max_n == 0) return TLORA_OK;
+  if (!workspace || ws_bytes < tlora_adamw_workspace_bytes(count) || (reinterpret_cast<uintptr_t>(workspace) & 255))
+    return TLORA_EWORKSPACE;
+  int rc = check_arch();
+  if (rc != TLORA_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  rc = upload_tables(blob, workspace, st);
+  if (rc != TLORA_OK) return rc;
+  {
+    Timed t(TLORA_K_OPT, st);
+    launch_adamw(static_cast<const AdamwDev*>(workspace), count, max_n, st);
+  }
+  return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+}
+
 int tlora_plan_dump(const tlora_problem_t* p, int32_t* rpad, int64_t* soff, int32_t* tile_rows, int64_t* tile_row0,
                     int32_t* tile_nrows, int32_t* tile_job_first, int32_t* tile_job_last, int64_t* n_tiles) {
   std::lock_guard<std::recursive_mutex> lk(g_mu);

@@ -89,4 +89,17 @@ struct F32Tile {
   int32_t unit, tm, tn, pad_;
 };
 
+// one tensor of the optimizer step (device table entry)
+struct AdamwDev {
+  void* param;          // bf16 or fp32
+  float* master;        // may be null (fp32 param updated in place)
+  const float* grad;
+  float* m;
+  float* v;
+  int64_t n;
+  float lr, beta1, beta2, eps, weight_decay;
+  float c1, c2;         // 1 / (1 - beta1^t), 1 / (1 - beta2^t)
+  int32_t param_is_bf16;
+};
+
 }  // namespace tlora

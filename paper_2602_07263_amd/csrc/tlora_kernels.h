@@ -51,4 +51,7 @@ void launch_grad_reduce(const JobDev* jobs, const GradGroup* groups, int num_gro
 // fp32 configuration: strided products on plain FMA units.
 void launch_f32_units(const F32Unit* units, const F32Tile* tiles, int num_tiles, hipStream_t st);
 
+// AdamW step over a device table of `count` tensors (max_n = the largest element count).
+void launch_adamw(const AdamwDev* tensors, int count, int64_t max_n, hipStream_t st);
+
 }  // namespace tlora

@@ -1186,4 +1186,39 @@ void launch_f32_units(const F32Unit* units, const F32Tile* tiles, int num_tiles,
   hipLaunchKernelGGL(f32_units_kernel, dim3(num_tiles), dim3(256), 0, st, units, tiles);
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Per-job optimizer step (AdamW with decoupled weight decay) over a table of tensors: blockIdx.y = tensor,
+// blockIdx.x = chunk of 4096 elements.  fp32 arithmetic on the fp32 master copy; the tensor the layer reads is
+// rewritten from it (round-to-nearest-even for bf16).  Reads 16 and writes 14 (bf16) bytes per element.
+// ---------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) adamw_kernel(const AdamwDev* __restrict__ tensors) {
+  const AdamwDev t = tensors[blockIdx.y];
+  const int64_t base = (int64_t)blockIdx.x * 4096;
+  if (base >= t.n) return;
+  float* const wsrc = t.master ? t.master : static_cast<float*>(t.param);
+#pragma unroll 4
+  for (int k = 0; k < 16; ++k) {
+    const int64_t i = base + k * 256 + threadIdx.x;
+    if (i >= t.n) break;
+    const float g = t.grad[i];
+    const float m = t.beta1 * t.m[i] + (1.f - t.beta1) * g;
+    const float v = t.beta2 * t.v[i] + (1.f - t.beta2) * g * g;
+    const float w0 = wsrc[i];
+    const float w = w0 - t.lr * ((m * t.c1) / (sqrtf(v * t.c2) + t.eps) + t.weight_decay * w0);
+    t.m[i] = m;
+    t.v[i] = v;
+    wsrc[i] = w;
+    if (t.param_is_bf16) {
+      static_cast<uint16_t*>(t.param)[i] = (uint16_t)(pack_bf16x2(w, 0.f) & 0xffffu);
+    } else if (t.master) {
+      static_cast<float*>(t.param)[i] = w;
+    }
+  }
+}
+
+void launch_adamw(const AdamwDev* tensors, int count, int64_t max_n, hipStream_t st) {
+  if (count == 0 || max_n == 0) return;
+  hipLaunchKernelGGL(adamw_kernel, dim3((unsigned)((max_n + 4095) / 4096), count), dim3(256), 0, st, tensors);
+}
+
 }  // namespace tlora

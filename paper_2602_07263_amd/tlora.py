@@ -40,11 +40,19 @@ class tlora_aimd_t(ctypes.Structure):
                 ("t_prev", ctypes.c_double)]
 
 
-EXPORTS = ["tlora_workspace_bytes", "tlora_fwd", "tlora_bwd", "tlora_aimd_init", "tlora_aimd_update",
+class tlora_adamw_tensor_t(ctypes.Structure):
+    _fields_ = [("param", ctypes.c_void_p), ("master", ctypes.c_void_p), ("grad", ctypes.c_void_p),
+                ("m", ctypes.c_void_p), ("v", ctypes.c_void_p), ("n", ctypes.c_int64),
+                ("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float), ("eps", ctypes.c_float),
+                ("weight_decay", ctypes.c_float), ("step", ctypes.c_int32)]
+
+
+EXPORTS = ["tlora_workspace_bytes", "tlora_fwd", "tlora_bwd", "tlora_adamw_workspace_bytes", "tlora_adamw_step",
+           "tlora_aimd_init", "tlora_aimd_update",
            "tlora_nano_split", "tlora_nano_workspace_bytes", "tlora_fwd_nano", "tlora_bwd_nano",
            "tlora_plan_dump", "tlora_set_option",
            "tlora_profile", "tlora_profile_read", "tlora_profile_clock", "tlora_strerror", "tlora_version"]
-KERNEL_CLASSES = ["pack", "shrink", "gemm_fwd", "gemm_bwd", "rank_grad", "grad_reduce", "f32", "w_transpose"]
+KERNEL_CLASSES = ["pack", "shrink", "gemm_fwd", "gemm_bwd", "rank_grad", "grad_reduce", "f32", "w_transpose", "optimizer"]
 
 
 def lib() -> ctypes.CDLL:
@@ -65,6 +73,11 @@ def lib() -> ctypes.CDLL:
     L.tlora_bwd.argtypes = [P, ctypes.c_void_p, ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p),
                             ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t,
                             ctypes.c_void_p]
+    L.tlora_adamw_workspace_bytes.restype = ctypes.c_size_t
+    L.tlora_adamw_workspace_bytes.argtypes = [ctypes.c_int32]
+    L.tlora_adamw_step.restype = ctypes.c_int
+    L.tlora_adamw_step.argtypes = [ctypes.POINTER(tlora_adamw_tensor_t), ctypes.c_int32, ctypes.c_int32,
+                                   ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     L.tlora_aimd_init.restype = ctypes.c_int
     L.tlora_aimd_init.argtypes = [ctypes.POINTER(tlora_aimd_t), ctypes.c_int32, ctypes.c_int32, ctypes.c_double,
                                   ctypes.c_double, ctypes.c_int32]
@@ -184,6 +197,23 @@ def _grad_ptr_arrays(J, dA_ptrs, dB_ptrs):
         return None, None
     return ((ctypes.c_void_p * J)(*[ctypes.c_void_p(int(p)) if p else None for p in dA_ptrs]),
             (ctypes.c_void_p * J)(*[ctypes.c_void_p(int(p)) if p else None for p in dB_ptrs]))
+
+
+def tlora_adamw_workspace_bytes(count: int) -> int:
+    return int(lib().tlora_adamw_workspace_bytes(int(count)))
+
+
+def tlora_adamw_step(tensors: Sequence[dict], dtype: int, ws_ptr: int, ws_bytes: int, stream: int = 0) -> None:
+    """tensors: dicts with integer device pointers param / master / grad / m / v, n and the hyper-parameters."""
+    arr = (tlora_adamw_tensor_t * len(tensors))()
+    for a, t in zip(arr, tensors):
+        a.param, a.master, a.grad, a.m, a.v = (t["param"] or None, t.get("master") or None, t["grad"] or None,
+                                               t["m"] or None, t["v"] or None)
+        a.n = int(t["n"])
+        a.lr, a.beta1, a.beta2 = float(t["lr"]), float(t.get("beta1", 0.9)), float(t.get("beta2", 0.999))
+        a.eps, a.weight_decay, a.step = float(t.get("eps", 1e-8)), float(t.get("weight_decay", 0.0)), int(t["step"])
+    _check(lib().tlora_adamw_step(arr, len(tensors), int(dtype), ctypes.c_void_p(ws_ptr), ctypes.c_size_t(ws_bytes),
+                                  ctypes.c_void_p(stream)), "tlora_adamw_step")
 
 
 def tlora_aimd_init(n0: int, alpha: int = 4, beta: float = 0.5, tau_rel: float = 0.02, n_max: int = 0) -> tlora_aimd_t:
