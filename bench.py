@@ -199,6 +199,54 @@ def cpu_baseline(cfg_index: int):
                       f"fwd+bwd, numpy fp64, {fl / 1e12:.2f} TFLOP"}
 
 
+def measure_mlp_block(steps: int, warmup: int):
+    """The MLP half of a decoder layer over cfg2's three projections: RMSNorm, gate / up, gated SiLU, down,
+    residual, forward + backward, plus one AdamW step on all adapters.  Random device tensors of cfg2's shapes."""
+    import torch
+    from paper_2602_07263_amd import tlora, workloads as wk
+    wl = wk.config(2)
+    d, dff, T = 4096, 12288, wl.total_tokens
+    g = torch.Generator(device="cuda"); g.manual_seed(0)
+    bf = torch.bfloat16
+    rn = lambda *shape, std=1.0: (torch.randn(*shape, device="cuda", generator=g) * std).to(bf)
+    layers = {}
+    for name, (i, o) in dict(gate=(d, dff), up=(d, dff), down=(dff, d)).items():
+        layers[name] = (rn(i, o, std=0.02), [((torch.rand(i, r, device="cuda", generator=g) * 2 - 1) / i ** 0.5).to(bf)
+                                             for r in wl.ranks], [rn(r, o, std=0.01) for r in wl.ranks])
+    X, dOut = rn(T, d), rn(T, d)
+    gamma = torch.ones(d, device="cuda", dtype=bf)
+    blk = tlora.MlpBlock("bf16", d, dff, wl.ranks, wl.offsets, wl.scales, X, gamma, 1e-5, layers)
+    Out, dX, grads = torch.empty_like(X), torch.empty_like(X), blk.new_grads()
+    params = [t for n in layers for t in layers[n][1] + layers[n][2]]
+    gl = [t for n in layers for t in grads[n][0] + grads[n][1]]
+    master = [t.float() for t in params]
+    m = [torch.zeros_like(t) for t in master]
+    v = [torch.zeros_like(t) for t in master]
+    ows = torch.empty(tlora.tlora_adamw_workspace_bytes(len(params)), dtype=torch.uint8, device="cuda")
+    state = {"t": 0}
+
+    def step(_i):
+        state["t"] += 1
+        blk.fwd(Out)
+        blk.bwd(dOut, dX, grads)
+        tens = [dict(param=q.data_ptr(), master=w.data_ptr(), grad=gr.data_ptr(), m=a.data_ptr(), v=b.data_ptr(),
+                     n=q.numel(), lr=1e-4, weight_decay=0.0, step=state["t"])
+                for q, w, gr, a, b in zip(params, master, gl, m, v)]
+        tlora.tlora_adamw_step(tens, tlora.TLORA_BF16, ows.data_ptr(), ows.numel(),
+                               int(torch.cuda.current_stream().cuda_stream))
+    tlora.tlora_profile(True)
+    for i in range(warmup):
+        step(i)
+    tlora.tlora_profile(True)
+    ms = time_steps(step, steps, 0)
+    prof = tlora.tlora_profile_read()
+    tlora.tlora_profile(False)
+    return {"workload": "mlp_block over cfg2 projections (RMSNorm, gate/up, silu*up, down, residual; fwd+bwd+AdamW)",
+            "ms_per_step": round(ms, 4), "value": round(wl.flops() / (ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s",
+            "note": "flops counted: the three fused projections only",
+            "kernel_ms_per_step": {k: round(t[0] / steps, 4) for k, t in prof.items() if t[1]}}
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -258,6 +306,9 @@ def main():
                        "frac_of_bf16_mfma_peak": round(t1 / BF16_MFMA_PEAK_TFLOPS, 4)}
         if sec["loop_ms"]:
             out["also"]["speedup_vs_per_job_loop"] = round(sec["loop_ms"] / sec["ms"], 3)
+        del sec
+        torch.cuda.empty_cache()
+        out["also_mlp_block"] = measure_mlp_block(max(5, args.steps // 2), 2)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config)
     print(json.dumps(out))

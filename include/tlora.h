@@ -169,6 +169,41 @@ size_t tlora_adamw_workspace_bytes(int32_t count);
 int tlora_adamw_step(const tlora_adamw_tensor_t* tensors, int32_t count, int32_t dtype, void* workspace,
                      size_t ws_bytes, void* hip_stream);
 
+/* ---- MLP half of a decoder layer of the shared super-model ---------------------------------------------------
+ * Sec. 3.2: the group's jobs are fused on one frozen backbone whose linear layers carry the jobs' adapters on the
+ * jobs' own tokens; the backbones of Sec. 4.1 are pre-norm gated-MLP decoders.  For token rows X [T, d_model]:
+ *     Xn = X / sqrt(mean(X^2) + eps) * gamma;   G = fused(Xn; W_gate, A/B_gate);   U = fused(Xn; W_up, A/B_up);
+ *     Z = silu(G) * U;                          Out = X + fused(Z; W_down, A/B_down)
+ * where fused(.) is tlora_fwd.  The backward gives dX and every dA_j / dB_j of the three projections for
+ * L = sum(dOut * Out); backbone weights and gamma are frozen.  A job has one rank for its three projections.
+ * tlora_mlp_bwd must follow tlora_mlp_fwd of the same problem on the same workspace and stream: the workspace
+ * keeps Xn, rstd, G, U, Z and each projection's S_j.  gamma: DEVICE [d_model] in `dtype`; X, Out, dOut, dX:
+ * DEVICE [T, d_model], 16-byte aligned; d_model, d_ff multiples of 8.  flags: TLORA_BWD_ACCUMULATE,
+ * TLORA_BWD_REUSE_WT (applied to all three projections). */
+typedef struct {
+  int32_t dtype, num_jobs, d_model, d_ff;
+  const int32_t* ranks;      /* HOST [J]   */
+  const int64_t* offsets;    /* HOST [J+1] */
+  const float* scales;       /* HOST [J]   */
+  const void* X;             /* DEVICE [T, d_model] */
+  const void* gamma;         /* DEVICE [d_model]    */
+  float eps;
+  const void* W_gate;        /* DEVICE [d_model, d_ff] */
+  const void* W_up;          /* DEVICE [d_model, d_ff] */
+  const void* W_down;        /* DEVICE [d_ff, d_model] */
+  const void* const* A_gate; /* HOST arrays of J DEVICE pointers: [d_model, r_j] */
+  const void* const* B_gate; /*                                   [r_j, d_ff]    */
+  const void* const* A_up;
+  const void* const* B_up;
+  const void* const* A_down; /*                                   [d_ff, r_j]    */
+  const void* const* B_down; /*                                   [r_j, d_model] */
+} tlora_mlp_t;
+size_t tlora_mlp_workspace_bytes(const tlora_mlp_t* p);
+int tlora_mlp_fwd(const tlora_mlp_t* p, void* Out, void* workspace, size_t ws_bytes, void* hip_stream);
+int tlora_mlp_bwd(const tlora_mlp_t* p, const void* dOut, void* dX, void* const* dA_gate, void* const* dB_gate,
+                  void* const* dA_up, void* const* dB_up, void* const* dA_down, void* const* dB_down, int flags,
+                  void* workspace, size_t ws_bytes, void* hip_stream);
+
 /* Integer bookkeeping of the nano-batch plan (Sec. 3.3, nano-batches = partition of the combined
  * batch along the token dimension), for bit-exact checks.  All outputs are HOST arrays and each may
  * be NULL.  Per job: rpad[J] (rank rounded up to the 8-element granule), soff[J+1] (element
@@ -206,7 +241,8 @@ typedef enum {
   TLORA_K_F32 = 6,          /* fp32-configuration products                      */
   TLORA_K_WT = 7,           /* transposed copy of W for the dX product          */
   TLORA_K_OPT = 8,          /* optimizer step                                   */
-  TLORA_K_COUNT = 9
+  TLORA_K_GLUE = 9,         /* RMSNorm, gated SiLU, residual of the MLP block   */
+  TLORA_K_COUNT = 10
 } tlora_kernel_class_t;
 int tlora_profile(int enable);
 int tlora_profile_read(int kernel_class, double* total_ms, int64_t* launches);

@@ -854,6 +854,136 @@ int tlora_adamw_step(const tlora_adamw_tensor_t* tensors, int32_t count, int32_t
   return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
 }
 
+// ---- MLP block: RMSNorm -> gate / up (fused multi-LoRA) -> silu(G) * U -> down (fused multi-LoRA) -> + X -------
+namespace {
+struct MlpLayout {
+  tlora_problem_t gate, up, down;      // the three fused layers (X pointers filled in below)
+  size_t elt = 2;
+  int64_t T = 0;
+  size_t off_xn = 0, off_rstd = 0, off_g = 0, off_u = 0, off_z = 0, off_d = 0, off_dz = 0, off_dg = 0, off_du = 0,
+         off_dxa = 0, off_dxb = 0, off_ws_gate = 0, off_ws_up = 0, off_ws_down = 0;
+  size_t ws_gate = 0, ws_up = 0, ws_down = 0, total = 0;
+};
+int mlp_layout(const tlora_mlp_t* p, MlpLayout& L) {
+  if (!p) return TLORA_ENULL;
+  if (p->dtype != TLORA_F32 && p->dtype != TLORA_BF16) return TLORA_EDTYPE;
+  if (!(p->eps >= 0.f)) return TLORA_EINVAL;
+  auto layer = [&](int d_in, int d_out, const void* W, const void* const* A, const void* const* B) {
+    tlora_problem_t q;
+    memset(&q, 0, sizeof(q));
+    q.dtype = p->dtype;  q.num_jobs = p->num_jobs;  q.d_in = d_in;  q.d_out = d_out;
+    q.ranks = p->ranks;  q.offsets = p->offsets;  q.scales = p->scales;
+    q.X = nullptr;  q.W = W;  q.A = A;  q.B = B;
+    return q;
+  };
+  L.gate = layer(p->d_model, p->d_ff, p->W_gate, p->A_gate, p->B_gate);
+  L.up = layer(p->d_model, p->d_ff, p->W_up, p->A_up, p->B_up);
+  L.down = layer(p->d_ff, p->d_model, p->W_down, p->A_down, p->B_down);
+  L.gate.X = L.up.X = L.down.X = p->X;          // placeholder so that validation sees a non-null activation
+  int rc = validate(&L.gate);
+  if (rc == TLORA_OK) rc = validate(&L.up);
+  if (rc == TLORA_OK) rc = validate(&L.down);
+  if (rc != TLORA_OK) return rc;
+  L.T = p->offsets[p->num_jobs];
+  if (L.T > 0 && !p->gamma) return TLORA_ENULL;
+  L.elt = p->dtype == TLORA_F32 ? 4 : 2;
+  size_t w = 0;
+  auto place = [&](size_t bytes) { const size_t at = w;  w = align_up(w + bytes, 256);  return at; };
+  const size_t td = (size_t)L.T * p->d_model * L.elt, tf = (size_t)L.T * p->d_ff * L.elt;
+  L.off_xn = place(td);  L.off_rstd = place(sizeof(float) * (size_t)L.T);
+  L.off_g = place(tf);  L.off_u = place(tf);  L.off_z = place(tf);  L.off_d = place(td);
+  L.off_dz = place(tf);  L.off_dg = place(tf);  L.off_du = place(tf);  L.off_dxa = place(td);  L.off_dxb = place(td);
+  L.ws_gate = tlora_workspace_bytes(&L.gate);  L.ws_up = tlora_workspace_bytes(&L.up);
+  L.ws_down = tlora_workspace_bytes(&L.down);
+  if (!L.ws_gate || !L.ws_up || !L.ws_down) return TLORA_EINVAL;
+  L.off_ws_gate = place(L.ws_gate);  L.off_ws_up = place(L.ws_up);  L.off_ws_down = place(L.ws_down);
+  L.total = w;
+  return TLORA_OK;
+}
+}  // namespace
+
+size_t tlora_mlp_workspace_bytes(const tlora_mlp_t* p) {
+  MlpLayout L;
+  return mlp_layout(p, L) == TLORA_OK ? L.total : 0;
+}
+
+int tlora_mlp_fwd(const tlora_mlp_t* p, void* Out, void* workspace, size_t ws_bytes, void* hip_stream) {
+  std::lock_guard<std::recursive_mutex> lk(g_mu);
+  MlpLayout L;
+  int rc = mlp_layout(p, L);
+  if (rc != TLORA_OK) return rc;
+  if (!workspace || ws_bytes < L.total || (reinterpret_cast<uintptr_t>(workspace) & 255)) return TLORA_EWORKSPACE;
+  if (L.T > 0 && (!p->X || !Out)) return TLORA_ENULL;
+  if (misaligned16(p->X) || misaligned16(Out) || misaligned16(p->gamma)) return TLORA_EALIGN;
+  rc = check_arch();
+  if (rc != TLORA_OK) return rc;
+  if (L.T == 0) return TLORA_OK;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  uint8_t* ws = static_cast<uint8_t*>(workspace);
+  const bool bf = p->dtype == TLORA_BF16;
+  {
+    Timed t(TLORA_K_GLUE, st);
+    launch_rmsnorm_fwd(bf, p->X, p->gamma, p->eps, (int)L.T, p->d_model, ws + L.off_xn,
+                       reinterpret_cast<float*>(ws + L.off_rstd), st);
+  }
+  L.gate.X = L.up.X = ws + L.off_xn;
+  rc = tlora_fwd(&L.gate, ws + L.off_g, ws + L.off_ws_gate, L.ws_gate, hip_stream);
+  if (rc != TLORA_OK) return rc;
+  rc = tlora_fwd(&L.up, ws + L.off_u, ws + L.off_ws_up, L.ws_up, hip_stream);
+  if (rc != TLORA_OK) return rc;
+  {
+    Timed t(TLORA_K_GLUE, st);
+    launch_swiglu_fwd(bf, ws + L.off_g, ws + L.off_u, ws + L.off_z, L.T * p->d_ff, st);
+  }
+  L.down.X = ws + L.off_z;
+  rc = tlora_fwd(&L.down, ws + L.off_d, ws + L.off_ws_down, L.ws_down, hip_stream);
+  if (rc != TLORA_OK) return rc;
+  {
+    Timed t(TLORA_K_GLUE, st);
+    launch_residual_add(bf, p->X, ws + L.off_d, Out, L.T * p->d_model, st);
+  }
+  return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+}
+
+int tlora_mlp_bwd(const tlora_mlp_t* p, const void* dOut, void* dX, void* const* dA_gate, void* const* dB_gate,
+                  void* const* dA_up, void* const* dB_up, void* const* dA_down, void* const* dB_down, int flags,
+                  void* workspace, size_t ws_bytes, void* hip_stream) {
+  std::lock_guard<std::recursive_mutex> lk(g_mu);
+  MlpLayout L;
+  int rc = mlp_layout(p, L);
+  if (rc != TLORA_OK) return rc;
+  if (flags & ~(TLORA_BWD_ACCUMULATE | TLORA_BWD_REUSE_WT)) return TLORA_EINVAL;
+  if (!workspace || ws_bytes < L.total || (reinterpret_cast<uintptr_t>(workspace) & 255)) return TLORA_EWORKSPACE;
+  if (L.T > 0 && (!p->X || !dOut || !dX)) return TLORA_ENULL;
+  if (!dA_gate || !dB_gate || !dA_up || !dB_up || !dA_down || !dB_down) return TLORA_ENULL;
+  if (misaligned16(p->X) || misaligned16(dOut) || misaligned16(dX) || misaligned16(p->gamma)) return TLORA_EALIGN;
+  rc = check_arch();
+  if (rc != TLORA_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  uint8_t* ws = static_cast<uint8_t*>(workspace);
+  const bool bf = p->dtype == TLORA_BF16;
+  // every layer's workspace still holds its S_j from tlora_mlp_fwd
+  const int lf = flags | TLORA_BWD_REUSE_S;
+  L.gate.X = L.up.X = ws + L.off_xn;
+  L.down.X = ws + L.off_z;
+  rc = tlora_bwd(&L.down, dOut, ws + L.off_dz, dA_down, dB_down, lf, ws + L.off_ws_down, L.ws_down, hip_stream);
+  if (rc != TLORA_OK) return rc;
+  if (L.T > 0) {
+    Timed t(TLORA_K_GLUE, st);
+    launch_swiglu_bwd(bf, ws + L.off_g, ws + L.off_u, ws + L.off_dz, ws + L.off_dg, ws + L.off_du, L.T * p->d_ff, st);
+  }
+  rc = tlora_bwd(&L.gate, ws + L.off_dg, ws + L.off_dxa, dA_gate, dB_gate, lf, ws + L.off_ws_gate, L.ws_gate, hip_stream);
+  if (rc != TLORA_OK) return rc;
+  rc = tlora_bwd(&L.up, ws + L.off_du, ws + L.off_dxb, dA_up, dB_up, lf, ws + L.off_ws_up, L.ws_up, hip_stream);
+  if (rc != TLORA_OK) return rc;
+  if (L.T > 0) {
+    Timed t(TLORA_K_GLUE, st);
+    launch_rmsnorm_bwd(bf, p->X, p->gamma, reinterpret_cast<const float*>(ws + L.off_rstd), ws + L.off_dxa,
+                       ws + L.off_dxb, dOut, (int)L.T, p->d_model, dX, st);
+  }
+  return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+}
+
 int tlora_plan_dump(const tlora_problem_t* p, int32_t* rpad, int64_t* soff, int32_t* tile_rows, int64_t* tile_row0,
                     int32_t* tile_nrows, int32_t* tile_job_first, int32_t* tile_job_last, int64_t* n_tiles) {
   std::lock_guard<std::recursive_mutex> lk(g_mu);

@@ -54,4 +54,14 @@ void launch_f32_units(const F32Unit* units, const F32Tile* tiles, int num_tiles,
 // AdamW step over a device table of `count` tensors (max_n = the largest element count).
 void launch_adamw(const AdamwDev* tensors, int count, int64_t max_n, hipStream_t st);
 
+// Glue of the MLP block (bf16 = tensors are bf16, else fp32; d and n multiples of 8; rstd fp32 [T]).
+void launch_rmsnorm_fwd(bool bf16, const void* X, const void* gamma, float eps, int T, int d, void* Xn, float* rstd,
+                        hipStream_t st);
+void launch_rmsnorm_bwd(bool bf16, const void* X, const void* gamma, const float* rstd, const void* dXa,
+                        const void* dXb, const void* dOut, int T, int d, void* dX, hipStream_t st);
+void launch_swiglu_fwd(bool bf16, const void* G, const void* U, void* Z, int64_t n, hipStream_t st);
+void launch_swiglu_bwd(bool bf16, const void* G, const void* U, const void* dZ, void* dG, void* dU, int64_t n,
+                       hipStream_t st);
+void launch_residual_add(bool bf16, const void* X, const void* D, void* Out, int64_t n, hipStream_t st);
+
 }  // namespace tlora

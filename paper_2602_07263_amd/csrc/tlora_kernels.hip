@@ -9,6 +9,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
+
 #include "tlora_kernels.h"
 
 namespace tlora {
@@ -1219,6 +1221,177 @@ __global__ void __launch_bounds__(256) adamw_kernel(const AdamwDev* __restrict__
 void launch_adamw(const AdamwDev* tensors, int count, int64_t max_n, hipStream_t st) {
   if (count == 0 || max_n == 0) return;
   hipLaunchKernelGGL(adamw_kernel, dim3((unsigned)((max_n + 4095) / 4096), count), dim3(256), 0, st, tensors);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Glue of the MLP block around the three fused projections: RMSNorm, gated SiLU, residual.  All HBM-bound,
+// 16-byte accesses, fp32 arithmetic; BF = tensors are bf16 (else fp32).  8 elements per lane and access.
+// ---------------------------------------------------------------------------------------------------
+template <bool BF>
+__device__ __forceinline__ void load8(const void* p, int64_t i, float (&v)[8]) {
+  if (BF) {
+    const u32x4 r = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(p) + i);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      v[2 * e] = __builtin_bit_cast(float, r[e] << 16);
+      v[2 * e + 1] = __builtin_bit_cast(float, r[e] & 0xffff0000u);
+    }
+  } else {
+    const f32x4* f = reinterpret_cast<const f32x4*>(static_cast<const float*>(p) + i);
+    const f32x4 a = f[0], b = f[1];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { v[e] = a[e];  v[4 + e] = b[e]; }
+  }
+}
+template <bool BF>
+__device__ __forceinline__ void store8(void* p, int64_t i, const float (&v)[8]) {
+  if (BF) {
+    *reinterpret_cast<u32x4*>(static_cast<uint16_t*>(p) + i) =
+        u32x4{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])};
+  } else {
+    f32x4* f = reinterpret_cast<f32x4*>(static_cast<float*>(p) + i);
+    f[0] = f32x4{v[0], v[1], v[2], v[3]};
+    f[1] = f32x4{v[4], v[5], v[6], v[7]};
+  }
+}
+// sum over the 256 threads of a workgroup (every thread gets the total)
+__device__ __forceinline__ float block_sum(float x, float* red) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = x;
+  __syncthreads();
+  const float t = red[0] + red[1] + red[2] + red[3];
+  __syncthreads();
+  return t;
+}
+
+// Xn[t, :] = X[t, :] * rstd_t * gamma,  rstd_t = 1 / sqrt(mean(X[t, :]^2) + eps).  One workgroup per row.
+template <bool BF>
+__global__ void __launch_bounds__(256) rmsnorm_fwd_kernel(const void* __restrict__ X, const void* __restrict__ gamma,
+                                                          float eps, int d, void* __restrict__ Xn,
+                                                          float* __restrict__ rstd) {
+  __shared__ float red[4];
+  const int64_t row = (int64_t)blockIdx.x * d;
+  float ss = 0.f;
+  for (int c = threadIdx.x * 8; c < d; c += 2048) {
+    float v[8];
+    load8<BF>(X, row + c, v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ss += v[e] * v[e];
+  }
+  const float r = 1.0f / sqrtf(block_sum(ss, red) / (float)d + eps);
+  if (threadIdx.x == 0) rstd[blockIdx.x] = r;
+  for (int c = threadIdx.x * 8; c < d; c += 2048) {
+    float v[8], g[8];
+    load8<BF>(X, row + c, v);
+    load8<BF>(gamma, c, g);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = v[e] * r * g[e];
+    store8<BF>(Xn, row + c, v);
+  }
+}
+
+// dX[t, :] = dOut[t, :] + rstd_t * gd - X[t, :] * rstd_t^3 * sum(gd * X[t, :]) / d,   gd = (dXa + dXb) * gamma
+template <bool BF>
+__global__ void __launch_bounds__(256) rmsnorm_bwd_kernel(const void* __restrict__ X, const void* __restrict__ gamma,
+                                                          const float* __restrict__ rstd, const void* __restrict__ dXa,
+                                                          const void* __restrict__ dXb, const void* __restrict__ dOut,
+                                                          int d, void* __restrict__ dX) {
+  __shared__ float red[4];
+  const int64_t row = (int64_t)blockIdx.x * d;
+  float dot = 0.f;
+  for (int c = threadIdx.x * 8; c < d; c += 2048) {
+    float x[8], a[8], b[8], g[8];
+    load8<BF>(X, row + c, x);  load8<BF>(dXa, row + c, a);  load8<BF>(dXb, row + c, b);  load8<BF>(gamma, c, g);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) dot += (a[e] + b[e]) * g[e] * x[e];
+  }
+  const float r = rstd[blockIdx.x];
+  const float k = block_sum(dot, red) * r * r * r / (float)d;
+  for (int c = threadIdx.x * 8; c < d; c += 2048) {
+    float x[8], a[8], b[8], g[8], o[8];
+    load8<BF>(X, row + c, x);  load8<BF>(dXa, row + c, a);  load8<BF>(dXb, row + c, b);  load8<BF>(gamma, c, g);
+    load8<BF>(dOut, row + c, o);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = o[e] + r * (a[e] + b[e]) * g[e] - x[e] * k;
+    store8<BF>(dX, row + c, o);
+  }
+}
+
+// Z = silu(G) * U            (n8 = number of 8-element chunks)
+template <bool BF>
+__global__ void __launch_bounds__(256) swiglu_fwd_kernel(const void* __restrict__ G, const void* __restrict__ U,
+                                                         void* __restrict__ Z, int64_t n8) {
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += stride) {
+    float g[8], u[8];
+    load8<BF>(G, i * 8, g);  load8<BF>(U, i * 8, u);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) g[e] = g[e] / (1.0f + expf(-g[e])) * u[e];
+    store8<BF>(Z, i * 8, g);
+  }
+}
+// dU = dZ * silu(G),  dG = dZ * U * sig (1 + G (1 - sig)),  sig = 1 / (1 + exp(-G))
+template <bool BF>
+__global__ void __launch_bounds__(256) swiglu_bwd_kernel(const void* __restrict__ G, const void* __restrict__ U,
+                                                         const void* __restrict__ dZ, void* __restrict__ dG,
+                                                         void* __restrict__ dU, int64_t n8) {
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += stride) {
+    float g[8], u[8], z[8], dg[8], du[8];
+    load8<BF>(G, i * 8, g);  load8<BF>(U, i * 8, u);  load8<BF>(dZ, i * 8, z);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float sig = 1.0f / (1.0f + expf(-g[e]));
+      du[e] = z[e] * g[e] * sig;
+      dg[e] = z[e] * u[e] * sig * (1.0f + g[e] * (1.0f - sig));
+    }
+    store8<BF>(dG, i * 8, dg);  store8<BF>(dU, i * 8, du);
+  }
+}
+// Out = X + D
+template <bool BF>
+__global__ void __launch_bounds__(256) residual_add_kernel(const void* __restrict__ X, const void* __restrict__ D,
+                                                           void* __restrict__ Out, int64_t n8) {
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += stride) {
+    float x[8], y[8];
+    load8<BF>(X, i * 8, x);  load8<BF>(D, i * 8, y);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] += y[e];
+    store8<BF>(Out, i * 8, x);
+  }
+}
+
+static unsigned ew_blocks(int64_t n8) { return (unsigned)std::min<int64_t>((n8 + 255) / 256, 256 * 32); }
+
+void launch_rmsnorm_fwd(bool bf16, const void* X, const void* gamma, float eps, int T, int d, void* Xn, float* rstd,
+                        hipStream_t st) {
+  if (T == 0) return;
+  if (bf16) hipLaunchKernelGGL(rmsnorm_fwd_kernel<true>, dim3(T), dim3(256), 0, st, X, gamma, eps, d, Xn, rstd);
+  else      hipLaunchKernelGGL(rmsnorm_fwd_kernel<false>, dim3(T), dim3(256), 0, st, X, gamma, eps, d, Xn, rstd);
+}
+void launch_rmsnorm_bwd(bool bf16, const void* X, const void* gamma, const float* rstd, const void* dXa,
+                        const void* dXb, const void* dOut, int T, int d, void* dX, hipStream_t st) {
+  if (T == 0) return;
+  if (bf16) hipLaunchKernelGGL(rmsnorm_bwd_kernel<true>, dim3(T), dim3(256), 0, st, X, gamma, rstd, dXa, dXb, dOut, d, dX);
+  else      hipLaunchKernelGGL(rmsnorm_bwd_kernel<false>, dim3(T), dim3(256), 0, st, X, gamma, rstd, dXa, dXb, dOut, d, dX);
+}
+void launch_swiglu_fwd(bool bf16, const void* G, const void* U, void* Z, int64_t n, hipStream_t st) {
+  if (n == 0) return;
+  if (bf16) hipLaunchKernelGGL(swiglu_fwd_kernel<true>, dim3(ew_blocks(n / 8)), dim3(256), 0, st, G, U, Z, n / 8);
+  else      hipLaunchKernelGGL(swiglu_fwd_kernel<false>, dim3(ew_blocks(n / 8)), dim3(256), 0, st, G, U, Z, n / 8);
+}
+void launch_swiglu_bwd(bool bf16, const void* G, const void* U, const void* dZ, void* dG, void* dU, int64_t n,
+                       hipStream_t st) {
+  if (n == 0) return;
+  if (bf16) hipLaunchKernelGGL(swiglu_bwd_kernel<true>, dim3(ew_blocks(n / 8)), dim3(256), 0, st, G, U, dZ, dG, dU, n / 8);
+  else      hipLaunchKernelGGL(swiglu_bwd_kernel<false>, dim3(ew_blocks(n / 8)), dim3(256), 0, st, G, U, dZ, dG, dU, n / 8);
+}
+void launch_residual_add(bool bf16, const void* X, const void* D, void* Out, int64_t n, hipStream_t st) {
+  if (n == 0) return;
+  if (bf16) hipLaunchKernelGGL(residual_add_kernel<true>, dim3(ew_blocks(n / 8)), dim3(256), 0, st, X, D, Out, n / 8);
+  else      hipLaunchKernelGGL(residual_add_kernel<false>, dim3(ew_blocks(n / 8)), dim3(256), 0, st, X, D, Out, n / 8);
 }
 
 }  // namespace tlora

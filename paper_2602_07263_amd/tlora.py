@@ -40,6 +40,17 @@ class tlora_aimd_t(ctypes.Structure):
                 ("t_prev", ctypes.c_double)]
 
 
+class tlora_mlp_t(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("num_jobs", ctypes.c_int32), ("d_model", ctypes.c_int32),
+                ("d_ff", ctypes.c_int32), ("ranks", ctypes.POINTER(ctypes.c_int32)),
+                ("offsets", ctypes.POINTER(ctypes.c_int64)), ("scales", ctypes.POINTER(ctypes.c_float)),
+                ("X", ctypes.c_void_p), ("gamma", ctypes.c_void_p), ("eps", ctypes.c_float),
+                ("W_gate", ctypes.c_void_p), ("W_up", ctypes.c_void_p), ("W_down", ctypes.c_void_p),
+                ("A_gate", ctypes.POINTER(ctypes.c_void_p)), ("B_gate", ctypes.POINTER(ctypes.c_void_p)),
+                ("A_up", ctypes.POINTER(ctypes.c_void_p)), ("B_up", ctypes.POINTER(ctypes.c_void_p)),
+                ("A_down", ctypes.POINTER(ctypes.c_void_p)), ("B_down", ctypes.POINTER(ctypes.c_void_p))]
+
+
 class tlora_adamw_tensor_t(ctypes.Structure):
     _fields_ = [("param", ctypes.c_void_p), ("master", ctypes.c_void_p), ("grad", ctypes.c_void_p),
                 ("m", ctypes.c_void_p), ("v", ctypes.c_void_p), ("n", ctypes.c_int64),
@@ -48,11 +59,12 @@ class tlora_adamw_tensor_t(ctypes.Structure):
 
 
 EXPORTS = ["tlora_workspace_bytes", "tlora_fwd", "tlora_bwd", "tlora_adamw_workspace_bytes", "tlora_adamw_step",
+           "tlora_mlp_workspace_bytes", "tlora_mlp_fwd", "tlora_mlp_bwd",
            "tlora_aimd_init", "tlora_aimd_update",
            "tlora_nano_split", "tlora_nano_workspace_bytes", "tlora_fwd_nano", "tlora_bwd_nano",
            "tlora_plan_dump", "tlora_set_option",
            "tlora_profile", "tlora_profile_read", "tlora_profile_clock", "tlora_strerror", "tlora_version"]
-KERNEL_CLASSES = ["pack", "shrink", "gemm_fwd", "gemm_bwd", "rank_grad", "grad_reduce", "f32", "w_transpose", "optimizer"]
+KERNEL_CLASSES = ["pack", "shrink", "gemm_fwd", "gemm_bwd", "rank_grad", "grad_reduce", "f32", "w_transpose", "optimizer", "glue"]
 
 
 def lib() -> ctypes.CDLL:
@@ -73,6 +85,15 @@ def lib() -> ctypes.CDLL:
     L.tlora_bwd.argtypes = [P, ctypes.c_void_p, ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p),
                             ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t,
                             ctypes.c_void_p]
+    PM = ctypes.POINTER(tlora_mlp_t)
+    VPP = ctypes.POINTER(ctypes.c_void_p)
+    L.tlora_mlp_workspace_bytes.restype = ctypes.c_size_t
+    L.tlora_mlp_workspace_bytes.argtypes = [PM]
+    L.tlora_mlp_fwd.restype = ctypes.c_int
+    L.tlora_mlp_fwd.argtypes = [PM, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    L.tlora_mlp_bwd.restype = ctypes.c_int
+    L.tlora_mlp_bwd.argtypes = [PM, ctypes.c_void_p, ctypes.c_void_p, VPP, VPP, VPP, VPP, VPP, VPP, ctypes.c_int,
+                                ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     L.tlora_adamw_workspace_bytes.restype = ctypes.c_size_t
     L.tlora_adamw_workspace_bytes.argtypes = [ctypes.c_int32]
     L.tlora_adamw_step.restype = ctypes.c_int
@@ -356,3 +377,61 @@ class LayerProblem:
         lo, hi = self.offsets[j], self.offsets[j + 1]
         return LayerProblem(self.dtype, self.d_in, self.d_out, [self.ranks[j]], [0, hi - lo], [self.scales[j]],
                             self.X[lo:hi], self.W, [self.A[j]], [self.B[j]])
+
+
+class MlpBlock:
+    """Holder of one MLP-block problem (torch tensors) marshalling pointers to tlora_mlp_fwd / tlora_mlp_bwd.
+    `layers` = {"gate": (W, [A_j], [B_j]), "up": (...), "down": (...)}."""
+
+    def __init__(self, dtype: str, d_model: int, d_ff: int, ranks, offsets, scales, X, gamma, eps: float, layers):
+        import torch
+        self.torch, self.dtype, self.d_model, self.d_ff = torch, dtype, int(d_model), int(d_ff)
+        self.ranks, self.offsets = [int(r) for r in ranks], [int(o) for o in offsets]
+        self.T, J = self.offsets[-1], len(self.ranks)
+        self.X, self.gamma, self.layers = X, gamma, layers
+        self._keep = [(ctypes.c_int32 * J)(*self.ranks), (ctypes.c_int64 * (J + 1))(*self.offsets),
+                      (ctypes.c_float * J)(*[float(x) for x in scales])]
+
+        def ptrs(ts):
+            a = (ctypes.c_void_p * J)(*[ctypes.c_void_p(t.data_ptr()) if t.numel() else None for t in ts])
+            self._keep.append(a)
+            return a
+        self.prob = tlora_mlp_t(TLORA_BF16 if dtype == "bf16" else TLORA_F32, J, self.d_model, self.d_ff,
+                                self._keep[0], self._keep[1], self._keep[2],
+                                ctypes.c_void_p(X.data_ptr()) if self.T else None, ctypes.c_void_p(gamma.data_ptr()),
+                                float(eps), ctypes.c_void_p(layers["gate"][0].data_ptr()),
+                                ctypes.c_void_p(layers["up"][0].data_ptr()), ctypes.c_void_p(layers["down"][0].data_ptr()),
+                                ptrs(layers["gate"][1]), ptrs(layers["gate"][2]), ptrs(layers["up"][1]),
+                                ptrs(layers["up"][2]), ptrs(layers["down"][1]), ptrs(layers["down"][2]))
+        self.ws_bytes = int(lib().tlora_mlp_workspace_bytes(ctypes.byref(self.prob)))
+        if self.ws_bytes == 0:
+            raise TloraError("tlora_mlp_workspace_bytes: invalid problem")
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=X.device)
+
+    def _stream(self) -> int:
+        return int(self.torch.cuda.current_stream().cuda_stream)
+
+    def new_grads(self):
+        t = self.torch
+        dev = self.X.device
+        out = {}
+        for name, (W, A, B) in self.layers.items():
+            out[name] = ([t.empty(a.shape, dtype=t.float32, device=dev) for a in A],
+                         [t.empty(b.shape, dtype=t.float32, device=dev) for b in B])
+        return out
+
+    def fwd(self, Out) -> None:
+        _check(lib().tlora_mlp_fwd(ctypes.byref(self.prob), ctypes.c_void_p(Out.data_ptr()) if self.T else None,
+                                   ctypes.c_void_p(self.ws.data_ptr()), ctypes.c_size_t(self.ws_bytes),
+                                   ctypes.c_void_p(self._stream())), "tlora_mlp_fwd")
+
+    def bwd(self, dOut, dX, grads, flags: int = 0) -> None:
+        J = len(self.ranks)
+
+        def arr(ts):
+            return (ctypes.c_void_p * J)(*[ctypes.c_void_p(t.data_ptr()) if t.numel() else None for t in ts])
+        a = [arr(grads[n][k]) for n in ("gate", "up", "down") for k in (0, 1)]
+        _check(lib().tlora_mlp_bwd(ctypes.byref(self.prob), ctypes.c_void_p(dOut.data_ptr()) if self.T else None,
+                                   ctypes.c_void_p(dX.data_ptr()) if self.T else None, *a, int(flags),
+                                   ctypes.c_void_p(self.ws.data_ptr()), ctypes.c_size_t(self.ws_bytes),
+                                   ctypes.c_void_p(self._stream())), "tlora_mlp_bwd")

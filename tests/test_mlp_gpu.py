@@ -1,0 +1,78 @@
+"""GPU parity of the MLP block (RMSNorm -> gate / up -> gated SiLU -> down -> residual over fused multi-LoRA
+projections) against the fp64 oracle on the same seeded inputs.  For bf16 the oracle rounds the tensors the block
+keeps in memory between its kernels at the same points (its arithmetic stays fp64)."""
+import numpy as np
+import pytest
+
+from oracle import mlp_oracle as mo
+from paper_2602_07263_amd import workloads as wk
+from tests import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+
+def _make(dtype, d, dff, ranks, tokens, scales, seed):
+    rng = np.random.default_rng(seed)
+    rnd = wk.round_to_bf16 if dtype == "bf16" else (lambda a: a)
+    f = lambda a: rnd(np.asarray(a, dtype=np.float32))
+    T = sum(tokens)
+    off = np.concatenate([[0], np.cumsum(tokens)]).astype(np.int64)
+    X = f(rng.normal(size=(T, d)))
+    gamma = f(1.0 + 0.1 * rng.normal(size=d))
+    layers = {}
+    for name, (i, o) in dict(gate=(d, dff), up=(d, dff), down=(dff, d)).items():
+        W = f(rng.normal(size=(i, o)) / np.sqrt(i))
+        A = [f(rng.uniform(-1, 1, size=(i, r)) / np.sqrt(i)) for r in ranks]
+        B = [f(0.05 * rng.normal(size=(r, o))) for r in ranks]
+        layers[name] = (W, A, B)
+    dOut = f(rng.normal(size=(T, d)))
+    return X, gamma, layers, off, dOut
+
+
+CASES = [("bf16", 256, 640, [8, 0, 24, 3], [300, 0, 513, 70], [2.0, 1.0, 0.5, 4.0]),
+         ("f32", 64, 96, [4, 7], [50, 81], [2.0, 1.0])]
+
+
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_mlp_block_matches_oracle(case):
+    import torch
+    from paper_2602_07263_amd import tlora
+    dtype, d, dff, ranks, tokens, scales = case
+    X, gamma, layers, off, dOut = _make(dtype, d, dff, ranks, tokens, scales, seed=4)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    up = lambda a: torch.from_numpy(a).to(device="cuda", dtype=tdt).contiguous()
+    tl = {n: (up(W), [up(a) for a in A], [up(b) for b in B]) for n, (W, A, B) in layers.items()}
+    blk = tlora.MlpBlock(dtype, d, dff, ranks, off, scales, up(X), up(gamma), 1e-5, tl)
+    Out = torch.full((sum(tokens), d), float("nan"), dtype=tdt, device="cuda")
+    dX = torch.full_like(Out, float("nan"))
+    grads = blk.new_grads()
+    for n in grads:
+        for t in grads[n][0] + grads[n][1]:
+            t.fill_(float("nan"))
+    blk.fwd(Out)
+    blk.bwd(up(dOut), dX, grads)
+    torch.cuda.synchronize()
+    store = (lambda a: wk.round_to_bf16(a.astype(np.float32)).astype(np.float64)) if dtype == "bf16" else (lambda a: a)
+    out_r, _ = mo.forward(X, gamma, 1e-5, layers, scales, off, store)
+    dX_r, g_r = mo.backward(X, gamma, 1e-5, layers, scales, off, dOut, store)
+    tol = pu.BF16_TOL if dtype == "bf16" else 2e-5      # fp32: three chained fp32 layers and two fp32 glue stages
+
+    def ratio(got, ref):
+        # |err| <= tol (m + |ref|) with m = max(1, rms(ref)).  Out and dX have rms ~ 1, so this is the layer's bound.
+        # The adapter gradients are token sums of products of tensors the block stores in bf16 between its
+        # kernels: a GEMM output such as G differs from the oracle's by one bf16 ulp wherever the bf16 adapter
+        # operand moved it across a rounding boundary, which reaches a length-N sum as noise of about 2^-9 of the
+        # sum's typical size (its rms), also on the entries that happen to be near zero.
+        if ref.size == 0:
+            return 0.0
+        got = np.asarray(got, dtype=np.float64)
+        assert np.all(np.isfinite(got))
+        m = max(1.0, float(np.sqrt(np.mean(ref * ref))))
+        return float(np.max(np.abs(got - ref) / (tol * (m + np.abs(ref)))))
+    res = {"Out": pu.worst_ratio(Out.float().cpu().numpy(), out_r, tol),
+           "dX": pu.worst_ratio(dX.float().cpu().numpy(), dX_r, tol)}
+    for n in grads:
+        res["dA_" + n] = max([ratio(a.cpu().numpy(), r) for a, r in zip(grads[n][0], g_r[n][0])] + [0.0])
+        res["dB_" + n] = max([ratio(b.cpu().numpy(), r) for b, r in zip(grads[n][1], g_r[n][1])] + [0.0])
+    bad = {k: v for k, v in res.items() if not v <= 1.0}
+    assert not bad, f"{dtype}: worst error / tolerance ratios {res}"
