@@ -116,3 +116,19 @@ def test_workspace_grows_with_rank_work_not_with_dense_weights():
     a, _c = _problem([16] * 4, [1000] * 4)
     b, _d = _problem([16] * 4, [2000] * 4)
     assert tlora.tlora_workspace_bytes(b) < 2.1 * tlora.tlora_workspace_bytes(a)
+
+
+def test_header_is_plain_c():
+    """The boundary is a C ABI: the header must compile as C99 and as C++ with no other includes."""
+    import os
+    import subprocess
+    import tempfile
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    hdr = os.path.join(root, "include", "tlora.h")
+    with tempfile.TemporaryDirectory() as td:
+        for name, cc, std in (("t.c", "gcc", "-std=c99"), ("t.cpp", "g++", "-std=c++11")):
+            src = os.path.join(td, name)
+            with open(src, "w") as f:
+                f.write('#include "%s"\nint main(void) { tlora_problem_t p; (void)p; return sizeof(tlora_aimd_t) > 0 ? 0 : 1; }\n' % hdr)
+            r = subprocess.run([cc, std, "-Wall", "-Werror", "-pedantic", "-fsyntax-only", src], capture_output=True, text=True)
+            assert r.returncode == 0, r.stderr

@@ -140,3 +140,25 @@ def test_kernel_timing_hooks_count_every_launch():
     assert prof["shrink"][1] == 2 and prof["rank_grad"][1] == 2 and prof["grad_reduce"][1] == 2
     assert prof["pack"][1] == 2 and prof["f32"][1] == 0 and prof["w_transpose"][1] == 1
     assert all(ms >= 0.0 for ms, _ in prof.values()) and prof["gemm_fwd"][0] > 0.0
+
+
+def _random_case(rng):
+    """A small random problem that stresses the tile logic: short and long contractions (fewer K-steps than the
+    pipeline is deep, a K tail, adapters only), widths off the 256 grid, ranks from 0 to beyond one 32-step, many
+    jobs per row tile and jobs spanning several tiles."""
+    d_in = int(rng.choice([8, 24, 32, 40, 64, 96, 200, 256, 328, 512, 776]))
+    d_out = int(rng.choice([8, 16, 72, 256, 264, 520]))
+    J = int(rng.integers(1, 9))
+    ranks = [int(rng.choice([0, 1, 2, 5, 8, 16, 31, 32, 33, 64, 100, 130, 256, 300])) for _ in range(J)]
+    tokens = [int(rng.choice([0, 1, 3, 31, 32, 33, 100, 255, 256, 257, 400, 700])) for _ in range(J)]
+    scales = [float(rng.choice([0.5, 1.0, 2.0, 4.0])) for _ in range(J)]
+    return d_in, d_out, ranks, tokens, scales
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_small_problems(seed):
+    rng = np.random.default_rng(1000 + seed)
+    d_in, d_out, ranks, tokens, scales = _random_case(rng)
+    p = wk.generate(wk.custom(f"rand{seed}", "bf16", d_in, d_out, ranks, tokens, scales), seed=seed)
+    Y, dX, dA, dB, _ = pu.run_gpu(p, reuse_S=bool(seed & 1))
+    _assert_ok(pu.compare(p, Y, dX, dA, dB), f"seed {seed}: d {d_in}->{d_out} ranks {ranks} tokens {tokens}")
