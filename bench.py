@@ -88,17 +88,26 @@ class ProjectionRun:
             jp.bwd(dY, dX, dA, dB, reuse_S=True)
 
 
+LAST_STEP_TIMES = []      # per-step device times (ms) of the most recent time_steps call, from stream events
+
+
 def time_steps(fn, steps: int, warmup: int) -> float:
-    """Milliseconds per step over exactly `steps` calls, bracketed by device synchronisation."""
+    """Milliseconds per step over exactly `steps` calls, bracketed by device synchronisation.  Events between the
+    steps (same stream) additionally give the per-step times for the median / minimum."""
     import torch
     for i in range(warmup):
         fn(i)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    ev[0].record()
     for i in range(steps):
         fn(warmup + i)
+        ev[i + 1].record()
     torch.cuda.synchronize()
-    return (time.perf_counter() - t0) * 1e3 / steps
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    LAST_STEP_TIMES[:] = [ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]
+    return ms
 
 
 def measure_workload(cfg_index: int, steps: int, warmup: int, profile: bool, loop_baseline: bool):
@@ -121,11 +130,13 @@ def measure_workload(cfg_index: int, steps: int, warmup: int, profile: bool, loo
     if profile:
         tlora.tlora_profile(True)      # clear warm-up totals
     ms = time_steps(step, steps, 0)
+    step_times = sorted(LAST_STEP_TIMES)
     prof = tlora.tlora_profile_read() if profile else None
     clock = tlora.tlora_profile_clock() if profile else None
     if profile:
         tlora.tlora_profile(False)
-    res = {"wl": wl, "ms": ms, "prof": prof, "clock": clock, "loop_ms": None}
+    res = {"wl": wl, "ms": ms, "prof": prof, "clock": clock, "loop_ms": None,
+           "ms_median": step_times[len(step_times) // 2], "ms_min": step_times[0]}
     if loop_baseline:
         for r in runs:
             r.build_job_loop()
@@ -273,7 +284,8 @@ def main():
     out = {
         "metric": "fused multi-LoRA fwd+bwd TFLOP/s (% bf16 MFMA peak); speedup vs per-job loop",
         "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(main_res["ms"], 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": round(main_res["ms"], 4), "ms_per_step_median": round(main_res["ms_median"], 4),
+        "ms_per_step_min": round(main_res["ms_min"], 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name,
                    "projections": [f"{p.name}:{p.d_in}->{p.d_out}" for p in wl.projections],
