@@ -258,6 +258,49 @@ def measure_mlp_block(steps: int, warmup: int):
             "kernel_ms_per_step": {k: round(t[0] / steps, 4) for k, t in prof.items() if t[1]}}
 
 
+def measure_indexed(steps: int, warmup: int):
+    """cfg2's gate projection with the jobs' sequences (runs of 512 tokens) interleaved in the batch: the
+    token-indexed calls (gather pass + scattering GEMM epilogue) against the contiguous calls on the same data."""
+    import numpy as np
+    import torch
+    from paper_2602_07263_amd import tlora, workloads as wk
+    wl = wk.config(2)
+    pr = wl.projections[0]
+    T = wl.total_tokens
+    g = torch.Generator(device="cuda"); g.manual_seed(1)
+    bf = torch.bfloat16
+    X = torch.randn(T, pr.d_in, device="cuda", generator=g).to(bf)
+    dY = torch.randn(T, pr.d_out, device="cuda", generator=g).to(bf)
+    W = (torch.randn(pr.d_in, pr.d_out, device="cuda", generator=g) * 0.02).to(bf)
+    A = [((torch.rand(pr.d_in, r, device="cuda", generator=g) * 2 - 1) / pr.d_in ** 0.5).to(bf) for r in wl.ranks]
+    B = [(torch.randn(r, pr.d_out, device="cuda", generator=g) * 0.01).to(bf) for r in wl.ranks]
+    lp = tlora.LayerProblem("bf16", pr.d_in, pr.d_out, wl.ranks, wl.offsets, wl.scales, X, W, A, B)
+    job = np.repeat(np.arange(wl.num_jobs), wl.tokens)
+    seq = np.concatenate([np.arange(t) // 512 for t in wl.tokens])
+    order = np.lexsort((job, seq))
+    idx = np.empty(T, dtype=np.int32); idx[order] = np.arange(T, dtype=np.int32)
+    it = torch.from_numpy(idx).cuda()
+    ws_bytes = tlora.tlora_indexed_workspace_bytes(lp.prob)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    Y, dX, dA, dB = lp.new_outputs()
+    pa, pb = [a.data_ptr() for a in dA], [b.data_ptr() for b in dB]
+    st = int(torch.cuda.current_stream().cuda_stream)
+
+    def step_idx(_i):
+        tlora.tlora_fwd_indexed(lp.prob, it.data_ptr(), Y.data_ptr(), ws.data_ptr(), ws_bytes, st)
+        tlora.tlora_bwd_indexed(lp.prob, it.data_ptr(), dY.data_ptr(), dX.data_ptr(), pa, pb, tlora.TLORA_BWD_REUSE_S,
+                                ws.data_ptr(), ws_bytes, st)
+
+    def step_plain(_i):
+        lp.fwd(Y)
+        lp.bwd(dY, dX, dA, dB, reuse_S=True)
+    ms_idx = time_steps(step_idx, steps, warmup)
+    ms_plain = time_steps(step_plain, steps, warmup)
+    return {"workload": "cfg2 gate 4096->12288, sequences of 512 tokens of the 8 jobs interleaved",
+            "ms_per_step_indexed": round(ms_idx, 4), "ms_per_step_contiguous": round(ms_plain, 4),
+            "overhead": round(ms_idx / ms_plain - 1.0, 4)}
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -321,6 +364,8 @@ def main():
         del sec
         torch.cuda.empty_cache()
         out["also_mlp_block"] = measure_mlp_block(max(5, args.steps // 2), 2)
+        torch.cuda.empty_cache()
+        out["also_indexed"] = measure_indexed(max(5, args.steps // 2), 2)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config)
     print(json.dumps(out))

@@ -204,6 +204,21 @@ int tlora_mlp_bwd(const tlora_mlp_t* p, const void* dOut, void* dX, void* const*
                   void* const* dA_up, void* const* dB_up, void* const* dA_down, void* const* dB_down, int flags,
                   void* workspace, size_t ws_bytes, void* hip_stream);
 
+/* ---- General token -> adapter assignment --------------------------------------------------------------------
+ * Sec. 3.3 describes the kernel as gathering the tokens of adapter i and scattering the results back to the
+ * output tensor.  Here X, Y, dY, dX are in the batch's own (arbitrary) token order, and row_index (DEVICE int32 [T],
+ * a permutation of 0 .. T-1) lists the rows job by job: row_index[offsets[j] .. offsets[j+1]-1] are the rows of job
+ * j, in the order in which they enter that job's gradient sums.  Row t of Y / dX belongs to row t of X / dY.
+ * The activations are gathered into the workspace by a copy pass (X for the forward; X and dY for the backward)
+ * and the bf16 GEMMs scatter their output rows while storing them; the fp32 configuration scatters with a second
+ * copy pass.  Same arguments, flags and results as tlora_fwd / tlora_bwd otherwise (TLORA_BWD_REUSE_S included,
+ * under the same condition).  The permutation is not checked. */
+size_t tlora_indexed_workspace_bytes(const tlora_problem_t* p);
+int tlora_fwd_indexed(const tlora_problem_t* p, const int32_t* row_index, void* Y, void* workspace, size_t ws_bytes,
+                      void* hip_stream);
+int tlora_bwd_indexed(const tlora_problem_t* p, const int32_t* row_index, const void* dY, void* dX, void* const* dA,
+                      void* const* dB, int flags, void* workspace, size_t ws_bytes, void* hip_stream);
+
 /* Integer bookkeeping of the nano-batch plan (Sec. 3.3, nano-batches = partition of the combined
  * batch along the token dimension), for bit-exact checks.  All outputs are HOST arrays and each may
  * be NULL.  Per job: rpad[J] (rank rounded up to the 8-element granule), soff[J+1] (element
@@ -242,7 +257,8 @@ typedef enum {
   TLORA_K_WT = 7,           /* transposed copy of W for the dX product          */
   TLORA_K_OPT = 8,          /* optimizer step                                   */
   TLORA_K_GLUE = 9,         /* RMSNorm, gated SiLU, residual of the MLP block   */
-  TLORA_K_COUNT = 10
+  TLORA_K_PERMUTE = 10,     /* row gather / scatter of the token-indexed calls  */
+  TLORA_K_COUNT = 11
 } tlora_kernel_class_t;
 int tlora_profile(int enable);
 int tlora_profile_read(int kernel_class, double* total_ms, int64_t* launches);

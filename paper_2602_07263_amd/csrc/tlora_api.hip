@@ -23,6 +23,8 @@ struct Options {
   int dx_transposed_w = 1;
 };
 Options g_opt;
+// set (under g_mu) by the token-indexed entry points around their inner call: the GEMMs then scatter their output rows
+const int32_t* g_out_index = nullptr;
 std::recursive_mutex g_mu;   // the nano-batch entry points call tlora_fwd / tlora_bwd under it
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -525,7 +527,7 @@ int tlora_fwd(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_byte
   if (g_prof_on) launch_zero_fill(ws + pl.off_clock, 16, st);
   Timed tg(TLORA_K_GEMM_FWD, st);
   launch_seg_gemm(true, tiles, static_cast<const uint16_t*>(p->X), static_cast<const uint16_t*>(p->W), Sx, bp,
-                  pl.r_total, static_cast<uint16_t*>(Y), pl.T, pl.d_in, pl.d_out,
+                  pl.r_total, static_cast<uint16_t*>(Y), g_out_index, pl.T, pl.d_in, pl.d_out,
                   g_prof_on ? (g_clock_slot[0] = reinterpret_cast<unsigned long long*>(ws + pl.off_clock)) : nullptr, st);
   return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
 }
@@ -654,7 +656,7 @@ int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* d
       if (g_prof_on) launch_zero_fill(ws + pl.off_clock + 16, 16, st);
       Timed t(TLORA_K_GEMM_BWD, st);
       launch_seg_gemm(wt, tiles, dYb, wt ? Wt : static_cast<const uint16_t*>(p->W), dSx, wt ? atp : ap, pl.r_total,
-                      static_cast<uint16_t*>(dX), pl.T, pl.d_out, pl.d_in,
+                      static_cast<uint16_t*>(dX), g_out_index, pl.T, pl.d_out, pl.d_in,
                       g_prof_on ? (g_clock_slot[1] = reinterpret_cast<unsigned long long*>(ws + pl.off_clock) + 2) : nullptr,
                       st);
     }
@@ -981,6 +983,100 @@ int tlora_mlp_bwd(const tlora_mlp_t* p, const void* dOut, void* dX, void* const*
     launch_rmsnorm_bwd(bf, p->X, p->gamma, reinterpret_cast<const float*>(ws + L.off_rstd), ws + L.off_dxa,
                        ws + L.off_dxb, dOut, (int)L.T, p->d_model, dX, st);
   }
+  return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+}
+
+// ---- general token -> adapter assignment (Sec. 3.3: tokens of an adapter are gathered, results scattered back) ----
+namespace {
+struct IndexedLayout {
+  size_t inner = 0, off_x = 0, off_y = 0, off_dx = 0, total = 0, elt = 2;
+  int64_t T = 0;
+};
+int indexed_layout(const tlora_problem_t* p, IndexedLayout& L) {
+  const int rc = validate(p);
+  if (rc != TLORA_OK) return rc;
+  L.inner = tlora_workspace_bytes(p);
+  if (L.inner == 0) return TLORA_EINVAL;
+  L.T = p->offsets[p->num_jobs];
+  L.elt = p->dtype == TLORA_F32 ? 4 : 2;
+  L.off_x = align_up(L.inner, 256);
+  L.off_y = align_up(L.off_x + (size_t)L.T * p->d_in * L.elt, 256);
+  L.off_dx = align_up(L.off_y + (size_t)L.T * p->d_out * L.elt, 256);
+  // the fp32 configuration has no scattering epilogue: its sorted dX is staged and scattered by a copy pass
+  L.total = align_up(L.off_dx + (p->dtype == TLORA_F32 ? (size_t)L.T * p->d_in * L.elt : 0), 256);
+  return TLORA_OK;
+}
+struct OutIndexScope {        // the inner call's GEMM scatters its rows while this is alive
+  explicit OutIndexScope(const int32_t* idx) { g_out_index = idx; }
+  ~OutIndexScope() { g_out_index = nullptr; }
+};
+}  // namespace
+
+size_t tlora_indexed_workspace_bytes(const tlora_problem_t* p) {
+  IndexedLayout L;
+  return indexed_layout(p, L) == TLORA_OK ? L.total : 0;
+}
+
+int tlora_fwd_indexed(const tlora_problem_t* p, const int32_t* row_index, void* Y, void* workspace, size_t ws_bytes,
+                      void* hip_stream) {
+  std::lock_guard<std::recursive_mutex> lk(g_mu);
+  IndexedLayout L;
+  int rc = indexed_layout(p, L);
+  if (rc != TLORA_OK) return rc;
+  if (!workspace || ws_bytes < L.total || (reinterpret_cast<uintptr_t>(workspace) & 255)) return TLORA_EWORKSPACE;
+  if (L.T > 0 && (!row_index || !Y || !p->X)) return TLORA_ENULL;
+  if (misaligned16(Y) || misaligned16(p->X)) return TLORA_EALIGN;
+  rc = check_arch();
+  if (rc != TLORA_OK) return rc;
+  if (L.T == 0) return TLORA_OK;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  uint8_t* ws = static_cast<uint8_t*>(workspace);
+  {
+    Timed t(TLORA_K_PERMUTE, st);
+    launch_permute_rows(p->X, ws + L.off_x, row_index, L.T, (int64_t)p->d_in * L.elt, false, st);
+  }
+  tlora_problem_t q = *p;
+  q.X = ws + L.off_x;
+  if (p->dtype == TLORA_BF16) {
+    OutIndexScope scope(row_index);
+    return tlora_fwd(&q, Y, workspace, L.inner, hip_stream);
+  }
+  rc = tlora_fwd(&q, ws + L.off_y, workspace, L.inner, hip_stream);
+  if (rc != TLORA_OK) return rc;
+  Timed t(TLORA_K_PERMUTE, st);
+  launch_permute_rows(ws + L.off_y, Y, row_index, L.T, (int64_t)p->d_out * L.elt, true, st);
+  return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+}
+
+int tlora_bwd_indexed(const tlora_problem_t* p, const int32_t* row_index, const void* dY, void* dX, void* const* dA,
+                      void* const* dB, int flags, void* workspace, size_t ws_bytes, void* hip_stream) {
+  std::lock_guard<std::recursive_mutex> lk(g_mu);
+  IndexedLayout L;
+  int rc = indexed_layout(p, L);
+  if (rc != TLORA_OK) return rc;
+  if (!workspace || ws_bytes < L.total || (reinterpret_cast<uintptr_t>(workspace) & 255)) return TLORA_EWORKSPACE;
+  if (L.T > 0 && (!row_index || !dY || !p->X)) return TLORA_ENULL;
+  if (misaligned16(dY) || misaligned16(dX) || misaligned16(p->X)) return TLORA_EALIGN;
+  rc = check_arch();
+  if (rc != TLORA_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  uint8_t* ws = static_cast<uint8_t*>(workspace);
+  if (L.T > 0) {
+    Timed t(TLORA_K_PERMUTE, st);
+    // the sorted activations are gathered again: the region may have been reused since the forward
+    launch_permute_rows(p->X, ws + L.off_x, row_index, L.T, (int64_t)p->d_in * L.elt, false, st);
+    launch_permute_rows(dY, ws + L.off_y, row_index, L.T, (int64_t)p->d_out * L.elt, false, st);
+  }
+  tlora_problem_t q = *p;
+  q.X = ws + L.off_x;
+  if (p->dtype == TLORA_BF16 || !dX) {
+    OutIndexScope scope(row_index);
+    return tlora_bwd(&q, ws + L.off_y, dX, dA, dB, flags, workspace, L.inner, hip_stream);
+  }
+  rc = tlora_bwd(&q, ws + L.off_y, ws + L.off_dx, dA, dB, flags, workspace, L.inner, hip_stream);
+  if (rc != TLORA_OK) return rc;
+  Timed t(TLORA_K_PERMUTE, st);
+  launch_permute_rows(ws + L.off_dx, dX, row_index, L.T, (int64_t)p->d_in * L.elt, true, st);
   return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
 }
 

@@ -36,7 +36,8 @@ void launch_shrink_stream(const JobDev* jobs, const TileDev* tiles, const Shrink
 //   w_is_kn = true : W is [K, N] row-major (forward,  Eop = b_all [R + 32, N])
 //   w_is_kn = false: W is [N, K] row-major (backward, Eop = a_all^T, stored [N, R + 32])
 void launch_seg_gemm(bool w_is_kn, const TileDev* tiles, const uint16_t* act, const uint16_t* W,
-                     const uint16_t* Sx, const uint16_t* packed, int r_total, uint16_t* out, int T, int K, int N,
+                     const uint16_t* Sx, const uint16_t* packed, int r_total, uint16_t* out,
+                     const int32_t* out_index /* null, or the output row of every row (scatter) */, int T, int K, int N,
                      unsigned long long* clk /* null, or 2 zeroed words: every 64th workgroup adds the shader
                                                 cycles and 100 MHz ticks of its K-loop */,
                      hipStream_t st);
@@ -63,5 +64,9 @@ void launch_swiglu_fwd(bool bf16, const void* G, const void* U, void* Z, int64_t
 void launch_swiglu_bwd(bool bf16, const void* G, const void* U, const void* dZ, void* dG, void* dU, int64_t n,
                        hipStream_t st);
 void launch_residual_add(bool bf16, const void* X, const void* D, void* Out, int64_t n, hipStream_t st);
+
+// Row gather (dst[i] = src[index[i]]) / scatter (dst[index[i]] = src[i]); row_bytes a multiple of 16.
+void launch_permute_rows(const void* src, void* dst, const int32_t* index, int64_t rows, int64_t row_bytes, bool scatter,
+                         hipStream_t st);
 
 }  // namespace tlora

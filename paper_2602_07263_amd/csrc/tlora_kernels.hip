@@ -580,6 +580,7 @@ struct GemmParams {
   int ra;                   // R + 32: row stride of a_all
   int tiles_m, tiles_n;
   unsigned long long* clk;  // optional: every 64th workgroup adds {cycles, 100 MHz ticks} of its K-loop (pre-zeroed)
+  const int32_t* out_index; // optional: output row of tile row t (scatter); null = t itself
 };
 
 // KTAIL: the instantiation for K % 32 != 0 carries the extra predicated step; keeping it out of the common one
@@ -899,16 +900,19 @@ __global__ void __launch_bounds__(512) seg_gemm_kernel(GemmParams P) {
     const uint8_t* const obuf = it * RPI < 64 ? sl0 : it * RPI < 128 ? sl1 : it * RPI < 192 ? sl2 : sl3;
     const int R = (tid >> 5) + it * RPI, c = tid & 31;
     const u32x4 v = *reinterpret_cast<const u32x4*>(obuf + (R & 63) * 512 + ((c ^ (R & 31)) << 4));
-    if (R < rows_valid && col0 + c * 8 < P.N)
-      *reinterpret_cast<u32x4*>(P.out + (int64_t)(row0 + R) * P.N + col0 + c * 8) = v;
+    if (R < rows_valid && col0 + c * 8 < P.N) {
+      const int64_t orow = P.out_index ? P.out_index[row0 + R] : row0 + R;
+      *reinterpret_cast<u32x4*>(P.out + orow * P.N + col0 + c * 8) = v;
+    }
   }
 }
 
 void launch_seg_gemm(bool w_is_kn, const TileDev* tiles, const uint16_t* act, const uint16_t* W, const uint16_t* Sx,
-                     const uint16_t* packed, int r_total, uint16_t* out, int T, int K, int N,
+                     const uint16_t* packed, int r_total, uint16_t* out, const int32_t* out_index, int T, int K, int N,
                      unsigned long long* clk, hipStream_t st) {
   GemmParams P;
   P.clk = clk;
+  P.out_index = out_index;
   P.tiles = tiles;  P.act = act;  P.W = W;  P.Sx = Sx;  P.packed = packed;  P.out = out;
   P.T = T;  P.K = K;  P.N = N;  P.ra = r_total + 32;
   P.tiles_m = (T + kGemmBM - 1) / kGemmBM;
@@ -1392,6 +1396,25 @@ void launch_residual_add(bool bf16, const void* X, const void* D, void* Out, int
   if (n == 0) return;
   if (bf16) hipLaunchKernelGGL(residual_add_kernel<true>, dim3(ew_blocks(n / 8)), dim3(256), 0, st, X, D, Out, n / 8);
   else      hipLaunchKernelGGL(residual_add_kernel<false>, dim3(ew_blocks(n / 8)), dim3(256), 0, st, X, D, Out, n / 8);
+}
+
+// dst[i, :] = src[index[i], :] (gather) or dst[index[i], :] = src[i, :] (scatter); rows of `row_bytes` bytes
+// (a multiple of 16), one workgroup per 4 rows.
+__global__ void __launch_bounds__(256) permute_rows_kernel(const uint8_t* __restrict__ src, uint8_t* __restrict__ dst,
+                                                           const int32_t* __restrict__ index, int64_t rows,
+                                                           int64_t row_bytes, int scatter) {
+  const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (i >= rows) return;
+  const int64_t other = index[i];
+  const u32x4* s = reinterpret_cast<const u32x4*>(src + (scatter ? i : other) * row_bytes);
+  u32x4* d = reinterpret_cast<u32x4*>(dst + (scatter ? other : i) * row_bytes);
+  for (int64_t c = threadIdx.x & 63; c < row_bytes / 16; c += 64) d[c] = s[c];
+}
+void launch_permute_rows(const void* src, void* dst, const int32_t* index, int64_t rows, int64_t row_bytes, bool scatter,
+                         hipStream_t st) {
+  if (rows == 0 || row_bytes == 0) return;
+  hipLaunchKernelGGL(permute_rows_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st,
+                     static_cast<const uint8_t*>(src), static_cast<uint8_t*>(dst), index, rows, row_bytes, scatter ? 1 : 0);
 }
 
 }  // namespace tlora

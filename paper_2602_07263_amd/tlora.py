@@ -60,11 +60,12 @@ class tlora_adamw_tensor_t(ctypes.Structure):
 
 EXPORTS = ["tlora_workspace_bytes", "tlora_fwd", "tlora_bwd", "tlora_adamw_workspace_bytes", "tlora_adamw_step",
            "tlora_mlp_workspace_bytes", "tlora_mlp_fwd", "tlora_mlp_bwd",
+           "tlora_indexed_workspace_bytes", "tlora_fwd_indexed", "tlora_bwd_indexed",
            "tlora_aimd_init", "tlora_aimd_update",
            "tlora_nano_split", "tlora_nano_workspace_bytes", "tlora_fwd_nano", "tlora_bwd_nano",
            "tlora_plan_dump", "tlora_set_option",
            "tlora_profile", "tlora_profile_read", "tlora_profile_clock", "tlora_strerror", "tlora_version"]
-KERNEL_CLASSES = ["pack", "shrink", "gemm_fwd", "gemm_bwd", "rank_grad", "grad_reduce", "f32", "w_transpose", "optimizer", "glue"]
+KERNEL_CLASSES = ["pack", "shrink", "gemm_fwd", "gemm_bwd", "rank_grad", "grad_reduce", "f32", "w_transpose", "optimizer", "glue", "permute"]
 
 
 def lib() -> ctypes.CDLL:
@@ -94,6 +95,13 @@ def lib() -> ctypes.CDLL:
     L.tlora_mlp_bwd.restype = ctypes.c_int
     L.tlora_mlp_bwd.argtypes = [PM, ctypes.c_void_p, ctypes.c_void_p, VPP, VPP, VPP, VPP, VPP, VPP, ctypes.c_int,
                                 ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    L.tlora_indexed_workspace_bytes.restype = ctypes.c_size_t
+    L.tlora_indexed_workspace_bytes.argtypes = [P]
+    L.tlora_fwd_indexed.restype = ctypes.c_int
+    L.tlora_fwd_indexed.argtypes = [P, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    L.tlora_bwd_indexed.restype = ctypes.c_int
+    L.tlora_bwd_indexed.argtypes = [P, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, VPP, VPP, ctypes.c_int,
+                                    ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     L.tlora_adamw_workspace_bytes.restype = ctypes.c_size_t
     L.tlora_adamw_workspace_bytes.argtypes = [ctypes.c_int32]
     L.tlora_adamw_step.restype = ctypes.c_int
@@ -278,6 +286,26 @@ def tlora_bwd_nano(prob: tlora_problem_t, n_nano: int, granule: int, dY_ptr: int
                                 ctypes.c_void_p(dX_ptr) if dX_ptr else None, c_dA, c_dB, int(flags),
                                 ctypes.c_void_p(ws_ptr), ctypes.c_size_t(ws_bytes), ctypes.c_void_p(stream)),
            "tlora_bwd_nano")
+
+
+def tlora_indexed_workspace_bytes(prob: tlora_problem_t) -> int:
+    return int(lib().tlora_indexed_workspace_bytes(ctypes.byref(prob)))
+
+
+def tlora_fwd_indexed(prob: tlora_problem_t, index_ptr: int, Y_ptr: int, ws_ptr: int, ws_bytes: int, stream: int = 0) -> None:
+    _check(lib().tlora_fwd_indexed(ctypes.byref(prob), ctypes.c_void_p(index_ptr), ctypes.c_void_p(Y_ptr),
+                                   ctypes.c_void_p(ws_ptr), ctypes.c_size_t(ws_bytes), ctypes.c_void_p(stream)),
+           "tlora_fwd_indexed")
+
+
+def tlora_bwd_indexed(prob: tlora_problem_t, index_ptr: int, dY_ptr: int, dX_ptr: int,
+                      dA_ptrs: Optional[Sequence[int]], dB_ptrs: Optional[Sequence[int]], flags: int, ws_ptr: int,
+                      ws_bytes: int, stream: int = 0) -> None:
+    c_dA, c_dB = _grad_ptr_arrays(prob.num_jobs, dA_ptrs, dB_ptrs)
+    _check(lib().tlora_bwd_indexed(ctypes.byref(prob), ctypes.c_void_p(index_ptr), ctypes.c_void_p(dY_ptr),
+                                   ctypes.c_void_p(dX_ptr) if dX_ptr else None, c_dA, c_dB, int(flags),
+                                   ctypes.c_void_p(ws_ptr), ctypes.c_size_t(ws_bytes), ctypes.c_void_p(stream)),
+           "tlora_bwd_indexed")
 
 
 def tlora_plan_dump(prob: tlora_problem_t) -> dict:
