@@ -204,6 +204,73 @@ int tlora_mlp_bwd(const tlora_mlp_t* p, const void* dOut, void* dX, void* const*
                   void* const* dA_up, void* const* dB_up, void* const* dA_down, void* const* dB_down, int flags,
                   void* workspace, size_t ws_bytes, void* hip_stream);
 
+/* ---- Attention half of a decoder layer ---------------------------------------------------------------------
+ * The backbones of Sec. 4.1 are decoder-only transformers; their attention half, with the four projections as
+ * fused multi-LoRA layers (Sec. 3.2), is
+ *     Xn = RMSNorm(X) gamma;  Q, K, V = fused(Xn; W_q / W_k / W_v);  Q, K = rope(Q), rope(K);
+ *     Out = X + fused(attention(Q, K, V); W_o)
+ * with rotary position embedding (pairs (i, i + head_dim / 2), angle = position * rope_base^(-2 i / head_dim),
+ * position = index of the token inside its sequence) and causal grouped-query attention (query head h reads
+ * key / value head h / (n_heads / n_kv_heads); scores scaled by 1 / sqrt(head_dim)).  Sequences are runs of
+ * consecutive token rows: seq_offsets (HOST int64 [num_seqs + 1], seq_offsets[0] = 0, non-decreasing, last = T).
+ * Sequences do not interact; which job a sequence belongs to matters only to the projections (`offsets`).
+ * bf16 only (TLORA_EDTYPE otherwise), head_dim must be 128 (TLORA_EINVAL otherwise).  Tensors are DEVICE
+ * [T, heads * 128] row-major, heads side by side inside a row, 16-byte aligned.
+ *
+ * Primitives (their `workspace`: tlora_attention_workspace_bytes, 256-byte aligned):
+ *   tlora_rope           rotates X in place (inverse != 0: the transposed rotation = backward of the forward one)
+ *   tlora_attention_fwd  O [T, n_heads * 128] and lse (DEVICE fp32 [T, n_heads]: base-2 logarithm of the softmax
+ *                        denominator of the scaled scores, maximum included) from rotated Q, K and V
+ *   tlora_attention_bwd  dQ, dK, dV from dO and the forward's Q, K, V, O, lse; deterministic (fixed summation order)
+ * Probabilities are rounded to bf16 before they multiply V / dO, score gradients before they multiply K / Q;
+ * all sums are fp32.  Calls are asynchronous on hip_stream; host arrays are read before the call returns. */
+size_t tlora_attention_workspace_bytes(int32_t num_seqs, const int64_t* seq_offsets, int32_t n_heads);
+int tlora_rope(void* X, int32_t num_seqs, const int64_t* seq_offsets, int32_t heads, int32_t head_dim, float rope_base,
+               int32_t inverse, void* workspace, size_t ws_bytes, void* hip_stream);
+int tlora_attention_fwd(const void* Q, const void* K, const void* V, void* O, float* lse, int32_t num_seqs,
+                        const int64_t* seq_offsets, int32_t n_heads, int32_t n_kv_heads, int32_t head_dim, void* workspace,
+                        size_t ws_bytes, void* hip_stream);
+int tlora_attention_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* lse,
+                        void* dQ, void* dK, void* dV, int32_t num_seqs, const int64_t* seq_offsets, int32_t n_heads,
+                        int32_t n_kv_heads, int32_t head_dim, void* workspace, size_t ws_bytes, void* hip_stream);
+
+/* The block.  tlora_attn_fwd keeps Xn, the rotated Q and K, V, the attention output, lse and every projection's
+ * S_j in the workspace; tlora_attn_bwd must follow it on the same stream with the same workspace and returns dX
+ * (through the residual and the norm) and dA / dB of the four projections (same layout and flags as tlora_bwd:
+ * TLORA_BWD_ACCUMULATE, TLORA_BWD_REUSE_WT).  W_* and gamma are frozen. */
+typedef struct tlora_attn_t {
+  int32_t dtype;             /* TLORA_BF16 */
+  int32_t num_jobs;
+  int32_t d_model;
+  int32_t n_heads, n_kv_heads, head_dim;
+  float rope_base;           /* > 1 */
+  float eps;                 /* RMSNorm: x / sqrt(mean(x^2) + eps) */
+  const int32_t* ranks;      /* HOST [num_jobs] */
+  const int64_t* offsets;    /* HOST [num_jobs + 1] token rows of every job */
+  const float* scales;       /* HOST [num_jobs] */
+  int32_t num_seqs;
+  const int64_t* seq_offsets;/* HOST [num_seqs + 1] */
+  const void* X;             /* DEVICE [T, d_model] */
+  const void* gamma;         /* DEVICE [d_model] */
+  const void* W_q;           /* DEVICE [d_model, n_heads * head_dim] */
+  const void* W_k;           /* DEVICE [d_model, n_kv_heads * head_dim] */
+  const void* W_v;           /* DEVICE [d_model, n_kv_heads * head_dim] */
+  const void* W_o;           /* DEVICE [n_heads * head_dim, d_model] */
+  const void* const* A_q;    /* HOST arrays of DEVICE pointers, as tlora_problem_t.A / .B */
+  const void* const* B_q;
+  const void* const* A_k;
+  const void* const* B_k;
+  const void* const* A_v;
+  const void* const* B_v;
+  const void* const* A_o;
+  const void* const* B_o;
+} tlora_attn_t;
+size_t tlora_attn_workspace_bytes(const tlora_attn_t* p);
+int tlora_attn_fwd(const tlora_attn_t* p, void* Out, void* workspace, size_t ws_bytes, void* hip_stream);
+/* dA / dB: HOST arrays of 4 entries (q, k, v, o), each a HOST array [num_jobs] of DEVICE pointers */
+int tlora_attn_bwd(const tlora_attn_t* p, const void* dOut, void* dX, void* const* const* dA, void* const* const* dB,
+                   int flags, void* workspace, size_t ws_bytes, void* hip_stream);
+
 /* ---- General token -> adapter assignment --------------------------------------------------------------------
  * Sec. 3.3 describes the kernel as gathering the tokens of adapter i and scattering the results back to the
  * output tensor.  Here X, Y, dY, dX are in the batch's own (arbitrary) token order, and row_index (DEVICE int32 [T],
@@ -258,7 +325,10 @@ typedef enum {
   TLORA_K_OPT = 8,          /* optimizer step                                   */
   TLORA_K_GLUE = 9,         /* RMSNorm, gated SiLU, residual of the MLP block   */
   TLORA_K_PERMUTE = 10,     /* row gather / scatter of the token-indexed calls  */
-  TLORA_K_COUNT = 11
+  TLORA_K_ATTN_FWD = 11,    /* causal attention, forward                        */
+  TLORA_K_ATTN_BWD = 12,    /* causal attention, backward (3 kernels)           */
+  TLORA_K_ROPE = 13,        /* rotary embedding                                 */
+  TLORA_K_COUNT = 14
 } tlora_kernel_class_t;
 int tlora_profile(int enable);
 int tlora_profile_read(int kernel_class, double* total_ms, int64_t* launches);

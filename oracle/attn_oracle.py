@@ -62,6 +62,8 @@ def attention(Q, K, V, seq_offsets, n_heads, n_kv, hd):
     for s in range(len(seq_offsets) - 1):
         a, b = int(seq_offsets[s]), int(seq_offsets[s + 1])
         n = b - a
+        if n == 0:                      # a sequence without tokens contributes nothing
+            continue
         mask = np.triu(np.ones((n, n), dtype=bool), k=1)
         for h in range(n_heads):
             q = Q[a:b, h * hd:(h + 1) * hd]
@@ -76,6 +78,22 @@ def attention(Q, K, V, seq_offsets, n_heads, n_kv, hd):
     return O, probs
 
 
+def attention_lse2(Q, K, seq_offsets, n_heads, n_kv, hd):
+    """Base-2 logarithm of the softmax denominators: lse2[t, h] = log2(sum over visible keys of exp(S[t, key])), the
+    statistic the GPU forward hands to its backward."""
+    Q, K = np.asarray(Q, dtype=np.float64), np.asarray(K, dtype=np.float64)
+    out = np.zeros((Q.shape[0], n_heads))
+    g = n_heads // n_kv
+    for s in range(len(seq_offsets) - 1):
+        a, b = int(seq_offsets[s]), int(seq_offsets[s + 1])
+        for h in range(n_heads):
+            S = Q[a:b, h * hd:(h + 1) * hd] @ K[a:b, (h // g) * hd:(h // g + 1) * hd].T / np.sqrt(hd)
+            for t in range(b - a):
+                row = S[t, :t + 1]
+                out[a + t, h] = (row.max() + np.log(np.sum(np.exp(row - row.max())))) / np.log(2.0)
+    return out
+
+
 def attention_backward(Q, K, V, dO, seq_offsets, n_heads, n_kv, hd):
     Q, K, V, dO = (np.asarray(a, dtype=np.float64) for a in (Q, K, V, dO))
     _, probs = attention(Q, K, V, seq_offsets, n_heads, n_kv, hd)
@@ -83,6 +101,8 @@ def attention_backward(Q, K, V, dO, seq_offsets, n_heads, n_kv, hd):
     g = n_heads // n_kv
     for s in range(len(seq_offsets) - 1):
         a, b = int(seq_offsets[s]), int(seq_offsets[s + 1])
+        if a == b:
+            continue
         for h in range(n_heads):
             sl, kl = slice(h * hd, (h + 1) * hd), slice((h // g) * hd, (h // g + 1) * hd)
             P = probs[(s, h)]

@@ -981,7 +981,317 @@ int tlora_mlp_bwd(const tlora_mlp_t* p, const void* dOut, void* dX, void* const*
   if (L.T > 0) {
     Timed t(TLORA_K_GLUE, st);
     launch_rmsnorm_bwd(bf, p->X, p->gamma, reinterpret_cast<const float*>(ws + L.off_rstd), ws + L.off_dxa,
-                       ws + L.off_dxb, dOut, (int)L.T, p->d_model, dX, st);
+                       ws + L.off_dxb, nullptr, dOut, (int)L.T, p->d_model, dX, st);
+  }
+  return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+}
+
+// ---- attention half: rotary embedding, causal grouped-query attention, and the block around them ----------
+namespace {
+struct AttnPlan {
+  int64_t T = 0;
+  std::vector<AttnTile> tiles;
+  std::vector<int32_t> pos;
+  size_t off_tiles = 0, off_pos = 0, off_D = 0, blob_bytes = 0, total = 0;
+};
+// tables: [tiles | positions] (uploaded), then D fp32 [T, n_heads]
+int attn_plan(int32_t num_seqs, const int64_t* seq_offsets, int32_t n_heads, bool want_tables, AttnPlan& A) {
+  if (num_seqs < 0 || n_heads < 1) return TLORA_EINVAL;
+  if (!seq_offsets) return TLORA_ENULL;
+  if (seq_offsets[0] != 0) return TLORA_EINVAL;
+  size_t n_tiles = 0;
+  for (int32_t s = 0; s < num_seqs; ++s) {
+    const int64_t len = seq_offsets[s + 1] - seq_offsets[s];
+    if (len < 0 || seq_offsets[s + 1] > (int64_t)INT32_MAX) return TLORA_EINVAL;
+    n_tiles += (size_t)((len + 127) / 128);
+  }
+  A.T = seq_offsets[num_seqs];
+  if ((int64_t)A.T * n_heads > (int64_t)INT32_MAX) return TLORA_EINVAL;
+  if (want_tables) {
+    A.tiles.reserve(n_tiles);
+    A.pos.resize((size_t)A.T);
+    // longest sequences' last tiles first: a tile's work grows with t0, so the heavy ones start early
+    for (int32_t s = 0; s < num_seqs; ++s) {
+      const int64_t a = seq_offsets[s], len = seq_offsets[s + 1] - a;
+      for (int64_t t0 = 0; t0 < len; t0 += 128) A.tiles.push_back(AttnTile{(int32_t)a, (int32_t)len, (int32_t)t0, 0});
+      for (int64_t i = 0; i < len; ++i) A.pos[(size_t)(a + i)] = (int32_t)i;
+    }
+    std::stable_sort(A.tiles.begin(), A.tiles.end(), [](const AttnTile& x, const AttnTile& y) { return x.t0 > y.t0; });
+  }
+  size_t w = 0;
+  auto place = [&](size_t bytes) { const size_t at = w;  w = align_up(w + bytes, 256);  return at; };
+  A.off_tiles = place(n_tiles * sizeof(AttnTile));
+  A.off_pos = place((size_t)A.T * sizeof(int32_t));
+  A.blob_bytes = w;
+  A.off_D = place((size_t)A.T * n_heads * sizeof(float));
+  A.total = std::max<size_t>(w, 256);
+  return TLORA_OK;
+}
+int attn_upload(const AttnPlan& A, void* ws, hipStream_t st) {
+  std::vector<uint8_t> blob(A.blob_bytes, 0);
+  if (!A.tiles.empty()) memcpy(blob.data() + A.off_tiles, A.tiles.data(), A.tiles.size() * sizeof(AttnTile));
+  if (!A.pos.empty()) memcpy(blob.data() + A.off_pos, A.pos.data(), A.pos.size() * sizeof(int32_t));
+  if (blob.empty()) return TLORA_OK;
+  return upload_tables(blob, ws, st);
+}
+int attn_heads_ok(int32_t n_heads, int32_t n_kv, int32_t head_dim) {
+  if (head_dim != kAttnHeadDim) return TLORA_EINVAL;
+  if (n_heads < 1 || n_kv < 1 || n_heads % n_kv != 0 || n_heads > 65535) return TLORA_EINVAL;
+  return TLORA_OK;
+}
+inline bool bad_ws(const void* ws, size_t have, size_t need) {
+  return !ws || have < need || (reinterpret_cast<uintptr_t>(ws) & 255);
+}
+}  // namespace
+
+size_t tlora_attention_workspace_bytes(int32_t num_seqs, const int64_t* seq_offsets, int32_t n_heads) {
+  AttnPlan A;
+  return attn_plan(num_seqs, seq_offsets, n_heads, false, A) == TLORA_OK ? A.total : 0;
+}
+
+int tlora_rope(void* X, int32_t num_seqs, const int64_t* seq_offsets, int32_t heads, int32_t head_dim, float rope_base,
+               int32_t inverse, void* workspace, size_t ws_bytes, void* hip_stream) {
+  std::lock_guard<std::recursive_mutex> lk(g_mu);
+  if (head_dim != kAttnHeadDim || !(rope_base > 1.f) || heads > 65535) return TLORA_EINVAL;
+  AttnPlan A;
+  int rc = attn_plan(num_seqs, seq_offsets, heads, true, A);
+  if (rc != TLORA_OK) return rc;
+  if (bad_ws(workspace, ws_bytes, A.total)) return TLORA_EWORKSPACE;
+  if (A.T > 0 && !X) return TLORA_ENULL;
+  if (misaligned16(X)) return TLORA_EALIGN;
+  rc = check_arch();
+  if (rc != TLORA_OK || A.T == 0) return rc;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  uint8_t* ws = static_cast<uint8_t*>(workspace);
+  rc = attn_upload(A, ws, st);
+  if (rc != TLORA_OK) return rc;
+  {
+    Timed t(TLORA_K_ROPE, st);
+    launch_rope(static_cast<uint16_t*>(X), reinterpret_cast<const int32_t*>(ws + A.off_pos), A.T, heads, rope_base,
+                inverse != 0, st);
+  }
+  return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+}
+
+int tlora_attention_fwd(const void* Q, const void* K, const void* V, void* O, float* lse, int32_t num_seqs,
+                        const int64_t* seq_offsets, int32_t n_heads, int32_t n_kv_heads, int32_t head_dim, void* workspace,
+                        size_t ws_bytes, void* hip_stream) {
+  std::lock_guard<std::recursive_mutex> lk(g_mu);
+  int rc = attn_heads_ok(n_heads, n_kv_heads, head_dim);
+  if (rc != TLORA_OK) return rc;
+  AttnPlan A;
+  rc = attn_plan(num_seqs, seq_offsets, n_heads, true, A);
+  if (rc != TLORA_OK) return rc;
+  if (bad_ws(workspace, ws_bytes, A.total)) return TLORA_EWORKSPACE;
+  if (A.T > 0 && (!Q || !K || !V || !O || !lse)) return TLORA_ENULL;
+  if (misaligned16(Q) || misaligned16(K) || misaligned16(V) || misaligned16(O)) return TLORA_EALIGN;
+  rc = check_arch();
+  if (rc != TLORA_OK || A.T == 0) return rc;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  uint8_t* ws = static_cast<uint8_t*>(workspace);
+  rc = attn_upload(A, ws, st);
+  if (rc != TLORA_OK) return rc;
+  {
+    Timed t(TLORA_K_ATTN_FWD, st);
+    launch_attn_fwd(reinterpret_cast<const AttnTile*>(ws + A.off_tiles), (int)A.tiles.size(), static_cast<const uint16_t*>(Q),
+                    static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), lse,
+                    n_heads, n_kv_heads, st);
+  }
+  return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+}
+
+int tlora_attention_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* lse,
+                        void* dQ, void* dK, void* dV, int32_t num_seqs, const int64_t* seq_offsets, int32_t n_heads,
+                        int32_t n_kv_heads, int32_t head_dim, void* workspace, size_t ws_bytes, void* hip_stream) {
+  std::lock_guard<std::recursive_mutex> lk(g_mu);
+  int rc = attn_heads_ok(n_heads, n_kv_heads, head_dim);
+  if (rc != TLORA_OK) return rc;
+  AttnPlan A;
+  rc = attn_plan(num_seqs, seq_offsets, n_heads, true, A);
+  if (rc != TLORA_OK) return rc;
+  if (bad_ws(workspace, ws_bytes, A.total)) return TLORA_EWORKSPACE;
+  if (A.T > 0 && (!Q || !K || !V || !O || !dO || !lse || !dQ || !dK || !dV)) return TLORA_ENULL;
+  if (misaligned16(Q) || misaligned16(K) || misaligned16(V) || misaligned16(O) || misaligned16(dO) || misaligned16(dQ) ||
+      misaligned16(dK) || misaligned16(dV))
+    return TLORA_EALIGN;
+  rc = check_arch();
+  if (rc != TLORA_OK || A.T == 0) return rc;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  uint8_t* ws = static_cast<uint8_t*>(workspace);
+  rc = attn_upload(A, ws, st);
+  if (rc != TLORA_OK) return rc;
+  {
+    Timed t(TLORA_K_ATTN_BWD, st);
+    launch_attn_bwd(reinterpret_cast<const AttnTile*>(ws + A.off_tiles), (int)A.tiles.size(), static_cast<const uint16_t*>(Q),
+                    static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(V), static_cast<const uint16_t*>(O),
+                    static_cast<const uint16_t*>(dO), lse, reinterpret_cast<float*>(ws + A.off_D),
+                    static_cast<uint16_t*>(dQ), static_cast<uint16_t*>(dK), static_cast<uint16_t*>(dV), A.T, n_heads,
+                    n_kv_heads, st);
+  }
+  return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+}
+
+namespace {
+struct AttnLayout {
+  tlora_problem_t q, k, v, o;
+  AttnPlan A;
+  int64_t T = 0;
+  size_t off_attn = 0, off_xn = 0, off_rstd = 0, off_q = 0, off_k = 0, off_v = 0, off_o = 0, off_lse = 0, off_d = 0,
+         off_do = 0, off_dq = 0, off_dk = 0, off_dv = 0, off_dxa = 0, off_dxb = 0, off_dxc = 0, off_ws[4] = {0, 0, 0, 0};
+  size_t ws_l[4] = {0, 0, 0, 0}, total = 0;
+};
+int attn_layout(const tlora_attn_t* p, bool want_tables, AttnLayout& L) {
+  if (!p) return TLORA_ENULL;
+  if (p->dtype != TLORA_BF16) return TLORA_EDTYPE;
+  if (!(p->eps >= 0.f) || !(p->rope_base > 1.f)) return TLORA_EINVAL;
+  int rc = attn_heads_ok(p->n_heads, p->n_kv_heads, p->head_dim);
+  if (rc != TLORA_OK) return rc;
+  if (p->num_jobs < 0 || !p->offsets) return p->offsets ? TLORA_EINVAL : TLORA_ENULL;
+  const int dq = p->n_heads * p->head_dim, dkv = p->n_kv_heads * p->head_dim;
+  auto layer = [&](int d_in, int d_out, const void* W, const void* const* A, const void* const* B) {
+    tlora_problem_t q;
+    memset(&q, 0, sizeof(q));
+    q.dtype = p->dtype;  q.num_jobs = p->num_jobs;  q.d_in = d_in;  q.d_out = d_out;
+    q.ranks = p->ranks;  q.offsets = p->offsets;  q.scales = p->scales;
+    q.X = p->X;  q.W = W;  q.A = A;  q.B = B;      // X: placeholder so that validation sees a non-null activation
+    return q;
+  };
+  L.q = layer(p->d_model, dq, p->W_q, p->A_q, p->B_q);
+  L.k = layer(p->d_model, dkv, p->W_k, p->A_k, p->B_k);
+  L.v = layer(p->d_model, dkv, p->W_v, p->A_v, p->B_v);
+  L.o = layer(dq, p->d_model, p->W_o, p->A_o, p->B_o);
+  tlora_problem_t* ls[4] = {&L.q, &L.k, &L.v, &L.o};
+  for (tlora_problem_t* l : ls) {
+    rc = validate(l);
+    if (rc != TLORA_OK) return rc;
+  }
+  L.T = p->offsets[p->num_jobs];
+  rc = attn_plan(p->num_seqs, p->seq_offsets, p->n_heads, want_tables, L.A);
+  if (rc != TLORA_OK) return rc;
+  if (L.A.T != L.T) return TLORA_EINVAL;
+  if (L.T > 0 && !p->gamma) return TLORA_ENULL;
+  size_t w = 0;
+  auto place = [&](size_t bytes) { const size_t at = w;  w = align_up(w + bytes, 256);  return at; };
+  const size_t td = (size_t)L.T * p->d_model * 2, tq = (size_t)L.T * dq * 2, tk = (size_t)L.T * dkv * 2;
+  L.off_attn = place(L.A.total);
+  L.off_xn = place(td);  L.off_rstd = place(sizeof(float) * (size_t)L.T);
+  L.off_q = place(tq);  L.off_k = place(tk);  L.off_v = place(tk);  L.off_o = place(tq);
+  L.off_lse = place(sizeof(float) * (size_t)L.T * p->n_heads);
+  L.off_d = place(td);
+  L.off_do = place(tq);  L.off_dq = place(tq);  L.off_dk = place(tk);  L.off_dv = place(tk);
+  L.off_dxa = place(td);  L.off_dxb = place(td);  L.off_dxc = place(td);
+  for (int i = 0; i < 4; ++i) {
+    L.ws_l[i] = tlora_workspace_bytes(ls[i]);
+    if (!L.ws_l[i]) return TLORA_EINVAL;
+    L.off_ws[i] = place(L.ws_l[i]);
+  }
+  L.total = w;
+  return TLORA_OK;
+}
+}  // namespace
+
+size_t tlora_attn_workspace_bytes(const tlora_attn_t* p) {
+  AttnLayout L;
+  return attn_layout(p, false, L) == TLORA_OK ? L.total : 0;
+}
+
+int tlora_attn_fwd(const tlora_attn_t* p, void* Out, void* workspace, size_t ws_bytes, void* hip_stream) {
+  std::lock_guard<std::recursive_mutex> lk(g_mu);
+  AttnLayout L;
+  int rc = attn_layout(p, true, L);
+  if (rc != TLORA_OK) return rc;
+  if (bad_ws(workspace, ws_bytes, L.total)) return TLORA_EWORKSPACE;
+  if (L.T > 0 && (!p->X || !Out)) return TLORA_ENULL;
+  if (misaligned16(p->X) || misaligned16(Out) || misaligned16(p->gamma)) return TLORA_EALIGN;
+  rc = check_arch();
+  if (rc != TLORA_OK || L.T == 0) return rc;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  uint8_t* ws = static_cast<uint8_t*>(workspace);
+  uint8_t* aw = ws + L.off_attn;
+  rc = attn_upload(L.A, aw, st);
+  if (rc != TLORA_OK) return rc;
+  {
+    Timed t(TLORA_K_GLUE, st);
+    launch_rmsnorm_fwd(true, p->X, p->gamma, p->eps, (int)L.T, p->d_model, ws + L.off_xn,
+                       reinterpret_cast<float*>(ws + L.off_rstd), st);
+  }
+  L.q.X = L.k.X = L.v.X = ws + L.off_xn;
+  rc = tlora_fwd(&L.q, ws + L.off_q, ws + L.off_ws[0], L.ws_l[0], hip_stream);
+  if (rc == TLORA_OK) rc = tlora_fwd(&L.k, ws + L.off_k, ws + L.off_ws[1], L.ws_l[1], hip_stream);
+  if (rc == TLORA_OK) rc = tlora_fwd(&L.v, ws + L.off_v, ws + L.off_ws[2], L.ws_l[2], hip_stream);
+  if (rc != TLORA_OK) return rc;
+  const int32_t* pos = reinterpret_cast<const int32_t*>(aw + L.A.off_pos);
+  {
+    Timed t(TLORA_K_ROPE, st);
+    launch_rope(reinterpret_cast<uint16_t*>(ws + L.off_q), pos, L.T, p->n_heads, p->rope_base, false, st);
+    launch_rope(reinterpret_cast<uint16_t*>(ws + L.off_k), pos, L.T, p->n_kv_heads, p->rope_base, false, st);
+  }
+  {
+    Timed t(TLORA_K_ATTN_FWD, st);
+    launch_attn_fwd(reinterpret_cast<const AttnTile*>(aw + L.A.off_tiles), (int)L.A.tiles.size(),
+                    reinterpret_cast<const uint16_t*>(ws + L.off_q), reinterpret_cast<const uint16_t*>(ws + L.off_k),
+                    reinterpret_cast<const uint16_t*>(ws + L.off_v), reinterpret_cast<uint16_t*>(ws + L.off_o),
+                    reinterpret_cast<float*>(ws + L.off_lse), p->n_heads, p->n_kv_heads, st);
+  }
+  L.o.X = ws + L.off_o;
+  rc = tlora_fwd(&L.o, ws + L.off_d, ws + L.off_ws[3], L.ws_l[3], hip_stream);
+  if (rc != TLORA_OK) return rc;
+  {
+    Timed t(TLORA_K_GLUE, st);
+    launch_residual_add(true, p->X, ws + L.off_d, Out, L.T * p->d_model, st);
+  }
+  return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+}
+
+int tlora_attn_bwd(const tlora_attn_t* p, const void* dOut, void* dX, void* const* const* dA, void* const* const* dB,
+                   int flags, void* workspace, size_t ws_bytes, void* hip_stream) {
+  std::lock_guard<std::recursive_mutex> lk(g_mu);
+  AttnLayout L;
+  int rc = attn_layout(p, true, L);
+  if (rc != TLORA_OK) return rc;
+  if (flags & ~(TLORA_BWD_ACCUMULATE | TLORA_BWD_REUSE_WT)) return TLORA_EINVAL;
+  if (bad_ws(workspace, ws_bytes, L.total)) return TLORA_EWORKSPACE;
+  if (L.T > 0 && (!p->X || !dOut || !dX)) return TLORA_ENULL;
+  if (!dA || !dB) return TLORA_ENULL;
+  for (int i = 0; i < 4; ++i)
+    if (!dA[i] || !dB[i]) return TLORA_ENULL;
+  if (misaligned16(p->X) || misaligned16(dOut) || misaligned16(dX) || misaligned16(p->gamma)) return TLORA_EALIGN;
+  rc = check_arch();
+  if (rc != TLORA_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  uint8_t* ws = static_cast<uint8_t*>(workspace);
+  uint8_t* aw = ws + L.off_attn;
+  const int lf = flags | TLORA_BWD_REUSE_S;            // every projection's workspace still holds its S_j
+  L.q.X = L.k.X = L.v.X = ws + L.off_xn;
+  L.o.X = ws + L.off_o;
+  rc = tlora_bwd(&L.o, dOut, ws + L.off_do, dA[3], dB[3], lf, ws + L.off_ws[3], L.ws_l[3], hip_stream);
+  if (rc != TLORA_OK) return rc;
+  if (L.T > 0) {
+    const int32_t* pos = reinterpret_cast<const int32_t*>(aw + L.A.off_pos);   // tables uploaded by tlora_attn_fwd
+    {
+      Timed t(TLORA_K_ATTN_BWD, st);
+      launch_attn_bwd(reinterpret_cast<const AttnTile*>(aw + L.A.off_tiles), (int)L.A.tiles.size(),
+                      reinterpret_cast<const uint16_t*>(ws + L.off_q), reinterpret_cast<const uint16_t*>(ws + L.off_k),
+                      reinterpret_cast<const uint16_t*>(ws + L.off_v), reinterpret_cast<const uint16_t*>(ws + L.off_o),
+                      reinterpret_cast<const uint16_t*>(ws + L.off_do), reinterpret_cast<const float*>(ws + L.off_lse),
+                      reinterpret_cast<float*>(aw + L.A.off_D), reinterpret_cast<uint16_t*>(ws + L.off_dq),
+                      reinterpret_cast<uint16_t*>(ws + L.off_dk), reinterpret_cast<uint16_t*>(ws + L.off_dv), L.T,
+                      p->n_heads, p->n_kv_heads, st);
+    }
+    {
+      Timed t(TLORA_K_ROPE, st);
+      launch_rope(reinterpret_cast<uint16_t*>(ws + L.off_dq), pos, L.T, p->n_heads, p->rope_base, true, st);
+      launch_rope(reinterpret_cast<uint16_t*>(ws + L.off_dk), pos, L.T, p->n_kv_heads, p->rope_base, true, st);
+    }
+  }
+  rc = tlora_bwd(&L.q, ws + L.off_dq, ws + L.off_dxa, dA[0], dB[0], lf, ws + L.off_ws[0], L.ws_l[0], hip_stream);
+  if (rc == TLORA_OK) rc = tlora_bwd(&L.k, ws + L.off_dk, ws + L.off_dxb, dA[1], dB[1], lf, ws + L.off_ws[1], L.ws_l[1], hip_stream);
+  if (rc == TLORA_OK) rc = tlora_bwd(&L.v, ws + L.off_dv, ws + L.off_dxc, dA[2], dB[2], lf, ws + L.off_ws[2], L.ws_l[2], hip_stream);
+  if (rc != TLORA_OK) return rc;
+  if (L.T > 0) {
+    Timed t(TLORA_K_GLUE, st);
+    launch_rmsnorm_bwd(true, p->X, p->gamma, reinterpret_cast<const float*>(ws + L.off_rstd), ws + L.off_dxa,
+                       ws + L.off_dxb, ws + L.off_dxc, dOut, (int)L.T, p->d_model, dX, st);
   }
   return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
 }

@@ -58,8 +58,9 @@ void launch_adamw(const AdamwDev* tensors, int count, int64_t max_n, hipStream_t
 // Glue of the MLP block (bf16 = tensors are bf16, else fp32; d and n multiples of 8; rstd fp32 [T]).
 void launch_rmsnorm_fwd(bool bf16, const void* X, const void* gamma, float eps, int T, int d, void* Xn, float* rstd,
                         hipStream_t st);
+// dX = dOut + d/dX [RMSNorm(X) gamma] applied to (dXa + dXb [+ dXc]); dXc may be null
 void launch_rmsnorm_bwd(bool bf16, const void* X, const void* gamma, const float* rstd, const void* dXa,
-                        const void* dXb, const void* dOut, int T, int d, void* dX, hipStream_t st);
+                        const void* dXb, const void* dXc, const void* dOut, int T, int d, void* dX, hipStream_t st);
 void launch_swiglu_fwd(bool bf16, const void* G, const void* U, void* Z, int64_t n, hipStream_t st);
 void launch_swiglu_bwd(bool bf16, const void* G, const void* U, const void* dZ, void* dG, void* dU, int64_t n,
                        hipStream_t st);
@@ -68,5 +69,22 @@ void launch_residual_add(bool bf16, const void* X, const void* D, void* Out, int
 // Row gather (dst[i] = src[index[i]]) / scatter (dst[index[i]] = src[i]); row_bytes a multiple of 16.
 void launch_permute_rows(const void* src, void* dst, const int32_t* index, int64_t rows, int64_t row_bytes, bool scatter,
                          hipStream_t st);
+
+// ---- attention half (bf16, head size 128) -----------------------------------------------------------------
+constexpr int kAttnHeadDim = 128;
+// 128 consecutive tokens [t0, t0 + 128) of the sequence that starts at token seq_start and has seq_len tokens
+struct AttnTile {
+  int32_t seq_start, seq_len, t0, pad;
+};
+// Causal grouped-query attention over [T, heads * 128] tensors (Q, O, dO, dQ: Hq heads; K, V, dK, dV: Hkv heads,
+// Hq % Hkv == 0).  lse [T, Hq] fp32 = log2 of the softmax denominator (base-2 domain, including the maximum);
+// D [T, Hq] fp32 is scratch of the backward.  The backward is deterministic (no atomics).
+void launch_attn_fwd(const AttnTile* tiles, int n_tiles, const uint16_t* Q, const uint16_t* K, const uint16_t* V,
+                     uint16_t* O, float* lse, int Hq, int Hkv, hipStream_t st);
+void launch_attn_bwd(const AttnTile* tiles, int n_tiles, const uint16_t* Q, const uint16_t* K, const uint16_t* V,
+                     const uint16_t* O, const uint16_t* dO, const float* lse, float* D, uint16_t* dQ, uint16_t* dK,
+                     uint16_t* dV, int64_t T, int Hq, int Hkv, hipStream_t st);
+// In-place rotary embedding of x [T, heads * 128] at positions pos [T]; inverse = the transposed rotation.
+void launch_rope(uint16_t* x, const int32_t* pos, int64_t T, int heads, float base, bool inverse, hipStream_t st);
 
 }  // namespace tlora

@@ -1299,14 +1299,20 @@ __global__ void __launch_bounds__(256) rmsnorm_fwd_kernel(const void* __restrict
 template <bool BF>
 __global__ void __launch_bounds__(256) rmsnorm_bwd_kernel(const void* __restrict__ X, const void* __restrict__ gamma,
                                                           const float* __restrict__ rstd, const void* __restrict__ dXa,
-                                                          const void* __restrict__ dXb, const void* __restrict__ dOut,
-                                                          int d, void* __restrict__ dX) {
+                                                          const void* __restrict__ dXb, const void* __restrict__ dXc,
+                                                          const void* __restrict__ dOut, int d, void* __restrict__ dX) {
   __shared__ float red[4];
   const int64_t row = (int64_t)blockIdx.x * d;
   float dot = 0.f;
   for (int c = threadIdx.x * 8; c < d; c += 2048) {
     float x[8], a[8], b[8], g[8];
     load8<BF>(X, row + c, x);  load8<BF>(dXa, row + c, a);  load8<BF>(dXb, row + c, b);  load8<BF>(gamma, c, g);
+    if (dXc) {
+      float cc[8];
+      load8<BF>(dXc, row + c, cc);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) a[e] = a[e] + b[e] + cc[e], b[e] = 0.f;
+    }
 #pragma unroll
     for (int e = 0; e < 8; ++e) dot += (a[e] + b[e]) * g[e] * x[e];
   }
@@ -1316,6 +1322,12 @@ __global__ void __launch_bounds__(256) rmsnorm_bwd_kernel(const void* __restrict
     float x[8], a[8], b[8], g[8], o[8];
     load8<BF>(X, row + c, x);  load8<BF>(dXa, row + c, a);  load8<BF>(dXb, row + c, b);  load8<BF>(gamma, c, g);
     load8<BF>(dOut, row + c, o);
+    if (dXc) {
+      float cc[8];
+      load8<BF>(dXc, row + c, cc);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) a[e] = a[e] + b[e] + cc[e], b[e] = 0.f;
+    }
 #pragma unroll
     for (int e = 0; e < 8; ++e) o[e] = o[e] + r * (a[e] + b[e]) * g[e] - x[e] * k;
     store8<BF>(dX, row + c, o);
@@ -1376,10 +1388,10 @@ void launch_rmsnorm_fwd(bool bf16, const void* X, const void* gamma, float eps, 
   else      hipLaunchKernelGGL(rmsnorm_fwd_kernel<false>, dim3(T), dim3(256), 0, st, X, gamma, eps, d, Xn, rstd);
 }
 void launch_rmsnorm_bwd(bool bf16, const void* X, const void* gamma, const float* rstd, const void* dXa,
-                        const void* dXb, const void* dOut, int T, int d, void* dX, hipStream_t st) {
+                        const void* dXb, const void* dXc, const void* dOut, int T, int d, void* dX, hipStream_t st) {
   if (T == 0) return;
-  if (bf16) hipLaunchKernelGGL(rmsnorm_bwd_kernel<true>, dim3(T), dim3(256), 0, st, X, gamma, rstd, dXa, dXb, dOut, d, dX);
-  else      hipLaunchKernelGGL(rmsnorm_bwd_kernel<false>, dim3(T), dim3(256), 0, st, X, gamma, rstd, dXa, dXb, dOut, d, dX);
+  if (bf16) hipLaunchKernelGGL(rmsnorm_bwd_kernel<true>, dim3(T), dim3(256), 0, st, X, gamma, rstd, dXa, dXb, dXc, dOut, d, dX);
+  else      hipLaunchKernelGGL(rmsnorm_bwd_kernel<false>, dim3(T), dim3(256), 0, st, X, gamma, rstd, dXa, dXb, dXc, dOut, d, dX);
 }
 void launch_swiglu_fwd(bool bf16, const void* G, const void* U, void* Z, int64_t n, hipStream_t st) {
   if (n == 0) return;

@@ -51,6 +51,20 @@ class tlora_mlp_t(ctypes.Structure):
                 ("A_down", ctypes.POINTER(ctypes.c_void_p)), ("B_down", ctypes.POINTER(ctypes.c_void_p))]
 
 
+class tlora_attn_t(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("num_jobs", ctypes.c_int32), ("d_model", ctypes.c_int32),
+                ("n_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("rope_base", ctypes.c_float), ("eps", ctypes.c_float), ("ranks", ctypes.POINTER(ctypes.c_int32)),
+                ("offsets", ctypes.POINTER(ctypes.c_int64)), ("scales", ctypes.POINTER(ctypes.c_float)),
+                ("num_seqs", ctypes.c_int32), ("seq_offsets", ctypes.POINTER(ctypes.c_int64)),
+                ("X", ctypes.c_void_p), ("gamma", ctypes.c_void_p),
+                ("W_q", ctypes.c_void_p), ("W_k", ctypes.c_void_p), ("W_v", ctypes.c_void_p), ("W_o", ctypes.c_void_p),
+                ("A_q", ctypes.POINTER(ctypes.c_void_p)), ("B_q", ctypes.POINTER(ctypes.c_void_p)),
+                ("A_k", ctypes.POINTER(ctypes.c_void_p)), ("B_k", ctypes.POINTER(ctypes.c_void_p)),
+                ("A_v", ctypes.POINTER(ctypes.c_void_p)), ("B_v", ctypes.POINTER(ctypes.c_void_p)),
+                ("A_o", ctypes.POINTER(ctypes.c_void_p)), ("B_o", ctypes.POINTER(ctypes.c_void_p))]
+
+
 class tlora_adamw_tensor_t(ctypes.Structure):
     _fields_ = [("param", ctypes.c_void_p), ("master", ctypes.c_void_p), ("grad", ctypes.c_void_p),
                 ("m", ctypes.c_void_p), ("v", ctypes.c_void_p), ("n", ctypes.c_int64),
@@ -60,12 +74,15 @@ class tlora_adamw_tensor_t(ctypes.Structure):
 
 EXPORTS = ["tlora_workspace_bytes", "tlora_fwd", "tlora_bwd", "tlora_adamw_workspace_bytes", "tlora_adamw_step",
            "tlora_mlp_workspace_bytes", "tlora_mlp_fwd", "tlora_mlp_bwd",
+           "tlora_attention_workspace_bytes", "tlora_rope", "tlora_attention_fwd", "tlora_attention_bwd",
+           "tlora_attn_workspace_bytes", "tlora_attn_fwd", "tlora_attn_bwd",
            "tlora_indexed_workspace_bytes", "tlora_fwd_indexed", "tlora_bwd_indexed",
            "tlora_aimd_init", "tlora_aimd_update",
            "tlora_nano_split", "tlora_nano_workspace_bytes", "tlora_fwd_nano", "tlora_bwd_nano",
            "tlora_plan_dump", "tlora_set_option",
            "tlora_profile", "tlora_profile_read", "tlora_profile_clock", "tlora_strerror", "tlora_version"]
-KERNEL_CLASSES = ["pack", "shrink", "gemm_fwd", "gemm_bwd", "rank_grad", "grad_reduce", "f32", "w_transpose", "optimizer", "glue", "permute"]
+KERNEL_CLASSES = ["pack", "shrink", "gemm_fwd", "gemm_bwd", "rank_grad", "grad_reduce", "f32", "w_transpose", "optimizer", "glue", "permute",
+                  "attn_fwd", "attn_bwd", "rope"]
 
 
 def lib() -> ctypes.CDLL:
@@ -88,6 +105,22 @@ def lib() -> ctypes.CDLL:
                             ctypes.c_void_p]
     PM = ctypes.POINTER(tlora_mlp_t)
     VPP = ctypes.POINTER(ctypes.c_void_p)
+    PA = ctypes.POINTER(tlora_attn_t)
+    I64P, VP, I32, SZ = ctypes.POINTER(ctypes.c_int64), ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    L.tlora_attention_workspace_bytes.restype = SZ
+    L.tlora_attention_workspace_bytes.argtypes = [I32, I64P, I32]
+    L.tlora_rope.restype = ctypes.c_int
+    L.tlora_rope.argtypes = [VP, I32, I64P, I32, I32, ctypes.c_float, I32, VP, SZ, VP]
+    L.tlora_attention_fwd.restype = ctypes.c_int
+    L.tlora_attention_fwd.argtypes = [VP, VP, VP, VP, VP, I32, I64P, I32, I32, I32, VP, SZ, VP]
+    L.tlora_attention_bwd.restype = ctypes.c_int
+    L.tlora_attention_bwd.argtypes = [VP] * 9 + [I32, I64P, I32, I32, I32, VP, SZ, VP]
+    L.tlora_attn_workspace_bytes.restype = SZ
+    L.tlora_attn_workspace_bytes.argtypes = [PA]
+    L.tlora_attn_fwd.restype = ctypes.c_int
+    L.tlora_attn_fwd.argtypes = [PA, VP, VP, SZ, VP]
+    L.tlora_attn_bwd.restype = ctypes.c_int
+    L.tlora_attn_bwd.argtypes = [PA, VP, VP, ctypes.POINTER(VPP), ctypes.POINTER(VPP), ctypes.c_int, VP, SZ, VP]
     L.tlora_mlp_workspace_bytes.restype = ctypes.c_size_t
     L.tlora_mlp_workspace_bytes.argtypes = [PM]
     L.tlora_mlp_fwd.restype = ctypes.c_int
@@ -463,3 +496,103 @@ class MlpBlock:
                                    ctypes.c_void_p(dX.data_ptr()) if self.T else None, *a, int(flags),
                                    ctypes.c_void_p(self.ws.data_ptr()), ctypes.c_size_t(self.ws_bytes),
                                    ctypes.c_void_p(self._stream())), "tlora_mlp_bwd")
+
+
+class Attention:
+    """Rotary embedding and causal grouped-query attention over token rows cut into sequences by `seq_offsets`
+    (argument marshalling for tlora_rope / tlora_attention_fwd / tlora_attention_bwd; bf16, head size 128)."""
+
+    def __init__(self, seq_offsets, n_heads: int, n_kv_heads: int, device, head_dim: int = 128):
+        import torch
+        self.torch = torch
+        self.seq = [int(o) for o in seq_offsets]
+        self.S, self.T = len(self.seq) - 1, self.seq[-1]
+        self.n_heads, self.n_kv, self.hd = int(n_heads), int(n_kv_heads), int(head_dim)
+        self._seq = (ctypes.c_int64 * (self.S + 1))(*self.seq)
+        self.ws_bytes = int(lib().tlora_attention_workspace_bytes(self.S, self._seq, self.n_heads))
+        if self.ws_bytes == 0:
+            raise TloraError("tlora_attention_workspace_bytes: invalid problem")
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=device)
+
+    def _tail(self):
+        return (ctypes.c_void_p(self.ws.data_ptr()), ctypes.c_size_t(self.ws_bytes),
+                ctypes.c_void_p(int(self.torch.cuda.current_stream().cuda_stream)))
+
+    @staticmethod
+    def _p(t):
+        return ctypes.c_void_p(t.data_ptr()) if t.numel() else None
+
+    def rope(self, X, heads: int, base: float, inverse: bool = False) -> None:
+        _check(lib().tlora_rope(self._p(X), self.S, self._seq, int(heads), self.hd, float(base), int(bool(inverse)),
+                                *self._tail()), "tlora_rope")
+
+    def fwd(self, Q, K, V, O, lse) -> None:
+        p = self._p
+        _check(lib().tlora_attention_fwd(p(Q), p(K), p(V), p(O), p(lse), self.S, self._seq, self.n_heads, self.n_kv,
+                                         self.hd, *self._tail()), "tlora_attention_fwd")
+
+    def bwd(self, Q, K, V, O, dO, lse, dQ, dK, dV) -> None:
+        p = self._p
+        _check(lib().tlora_attention_bwd(p(Q), p(K), p(V), p(O), p(dO), p(lse), p(dQ), p(dK), p(dV), self.S, self._seq,
+                                         self.n_heads, self.n_kv, self.hd, *self._tail()), "tlora_attention_bwd")
+
+
+class AttnBlock:
+    """Holder of one attention-block problem (torch tensors) marshalling pointers to tlora_attn_fwd / tlora_attn_bwd.
+    `layers` = {"q": (W, [A_j], [B_j]), "k": (...), "v": (...), "o": (...)}."""
+    NAMES = ("q", "k", "v", "o")
+
+    def __init__(self, d_model: int, n_heads: int, n_kv_heads: int, rope_base: float, ranks, offsets, scales,
+                 seq_offsets, X, gamma, eps: float, layers, head_dim: int = 128):
+        import torch
+        self.torch, self.d_model = torch, int(d_model)
+        self.ranks, self.offsets = [int(r) for r in ranks], [int(o) for o in offsets]
+        self.seq = [int(o) for o in seq_offsets]
+        self.T, J = self.offsets[-1], len(self.ranks)
+        self.X, self.gamma, self.layers = X, gamma, layers
+        self._keep = [(ctypes.c_int32 * J)(*self.ranks), (ctypes.c_int64 * (J + 1))(*self.offsets),
+                      (ctypes.c_float * J)(*[float(x) for x in scales]), (ctypes.c_int64 * len(self.seq))(*self.seq)]
+
+        def ptrs(ts):
+            a = (ctypes.c_void_p * J)(*[ctypes.c_void_p(t.data_ptr()) if t.numel() else None for t in ts])
+            self._keep.append(a)
+            return a
+        ab = [ptrs(layers[n][k]) for n in self.NAMES for k in (1, 2)]
+        self.prob = tlora_attn_t(TLORA_BF16, J, self.d_model, int(n_heads), int(n_kv_heads), int(head_dim),
+                                 float(rope_base), float(eps), self._keep[0], self._keep[1], self._keep[2],
+                                 len(self.seq) - 1, self._keep[3],
+                                 ctypes.c_void_p(X.data_ptr()) if self.T else None, ctypes.c_void_p(gamma.data_ptr()),
+                                 *[ctypes.c_void_p(layers[n][0].data_ptr()) for n in self.NAMES], *ab)
+        self.ws_bytes = int(lib().tlora_attn_workspace_bytes(ctypes.byref(self.prob)))
+        if self.ws_bytes == 0:
+            raise TloraError("tlora_attn_workspace_bytes: invalid problem")
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=X.device)
+
+    def _stream(self) -> int:
+        return int(self.torch.cuda.current_stream().cuda_stream)
+
+    def new_grads(self):
+        t = self.torch
+        dev = self.X.device
+        return {n: ([t.empty(a.shape, dtype=t.float32, device=dev) for a in A],
+                    [t.empty(b.shape, dtype=t.float32, device=dev) for b in B]) for n, (W, A, B) in self.layers.items()}
+
+    def fwd(self, Out) -> None:
+        _check(lib().tlora_attn_fwd(ctypes.byref(self.prob), ctypes.c_void_p(Out.data_ptr()) if self.T else None,
+                                    ctypes.c_void_p(self.ws.data_ptr()), ctypes.c_size_t(self.ws_bytes),
+                                    ctypes.c_void_p(self._stream())), "tlora_attn_fwd")
+
+    def bwd(self, dOut, dX, grads, flags: int = 0) -> None:
+        J = len(self.ranks)
+        VPP = ctypes.POINTER(ctypes.c_void_p)
+
+        def arr(ts):
+            return (ctypes.c_void_p * J)(*[ctypes.c_void_p(t.data_ptr()) if t.numel() else None for t in ts])
+        da = [arr(grads[n][0]) for n in self.NAMES]
+        db = [arr(grads[n][1]) for n in self.NAMES]
+        dA = (VPP * 4)(*[ctypes.cast(a, VPP) for a in da])
+        dB = (VPP * 4)(*[ctypes.cast(a, VPP) for a in db])
+        _check(lib().tlora_attn_bwd(ctypes.byref(self.prob), ctypes.c_void_p(dOut.data_ptr()) if self.T else None,
+                                    ctypes.c_void_p(dX.data_ptr()) if self.T else None, dA, dB, int(flags),
+                                    ctypes.c_void_p(self.ws.data_ptr()), ctypes.c_size_t(self.ws_bytes),
+                                    ctypes.c_void_p(self._stream())), "tlora_attn_bwd")

@@ -1,0 +1,110 @@
+"""GPU parity of the attention primitives (rotary embedding, causal grouped-query attention forward and backward,
+bf16 with head size 128) against the fp64 oracle on the same seeded bf16 inputs."""
+import numpy as np
+import pytest
+
+from oracle import attn_oracle as ao
+from paper_2602_07263_amd import workloads as wk
+from tests import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+HD = 128
+
+
+def _bf(a):
+    return wk.round_to_bf16(np.asarray(a, dtype=np.float32))
+
+
+def _offsets(lens):
+    return np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+
+
+@pytest.mark.parametrize("lens,heads", [([1, 130, 0, 64, 257], 3), ([4100], 2)], ids=["ragged", "long"])
+def test_rope_matches_oracle(lens, heads):
+    import torch
+    from paper_2602_07263_amd import tlora
+    seq = _offsets(lens)
+    T = int(seq[-1])
+    x = _bf(np.random.default_rng(3).normal(size=(T, heads * HD)))
+    att = tlora.Attention(seq, heads, heads, "cuda")
+    for inverse in (False, True):
+        X = torch.from_numpy(x).to(device="cuda", dtype=torch.bfloat16)
+        att.rope(X, heads, 10000.0, inverse)
+        torch.cuda.synchronize()
+        ref = ao.rope(x, seq, heads, HD, 10000.0, transpose=inverse)
+        r = pu.worst_ratio(X.float().cpu().numpy(), ref, pu.BF16_TOL)
+        assert r <= 1.0, f"inverse={inverse}: worst error / tolerance {r}"
+
+
+# (sequence lengths, query heads, key/value heads): ragged lengths around the 32 / 64 / 128 tile edges, an empty
+# sequence, single tokens, one sequence of many tiles; group sizes 1, 2 and 4
+CASES = [([1, 130, 0, 64, 257, 31, 128], 4, 2),
+         ([33, 1, 1, 200], 2, 2),
+         ([1500, 7], 8, 2)]
+
+
+@pytest.mark.parametrize("case", CASES, ids=["ragged_g2", "small_g1", "long_g4"])
+def test_attention_fwd_bwd_match_oracle(case):
+    import torch
+    from paper_2602_07263_amd import tlora
+    lens, Hq, Hkv = case
+    seq = _offsets(lens)
+    T = int(seq[-1])
+    rng = np.random.default_rng(11)
+    Q, K, V, dO = (_bf(rng.normal(size=(T, h * HD))) for h in (Hq, Hkv, Hkv, Hq))
+    up = lambda a: torch.from_numpy(a).to(device="cuda", dtype=torch.bfloat16).contiguous()
+    nan = lambda h: torch.full((T, h * HD), float("nan"), dtype=torch.bfloat16, device="cuda")
+    att = tlora.Attention(seq, Hq, Hkv, "cuda")
+    tQ, tK, tV, tdO = up(Q), up(K), up(V), up(dO)
+    O, dQ, dK, dV = nan(Hq), nan(Hq), nan(Hkv), nan(Hkv)
+    lse = torch.full((T, Hq), float("nan"), dtype=torch.float32, device="cuda")
+    att.fwd(tQ, tK, tV, O, lse)
+    att.bwd(tQ, tK, tV, O, tdO, lse, dQ, dK, dV)
+    torch.cuda.synchronize()
+    O_r, _ = ao.attention(Q, K, V, seq, Hq, Hkv, HD)
+    lse_r = ao.attention_lse2(Q, K, seq, Hq, Hkv, HD)
+    dQ_r, dK_r, dV_r = ao.attention_backward(Q, K, V, dO, seq, Hq, Hkv, HD)
+    res = {"O": pu.worst_ratio(O.float().cpu().numpy(), O_r, pu.BF16_TOL),
+           "lse": pu.worst_ratio(lse.cpu().numpy(), lse_r, 1e-4),
+           "dQ": pu.worst_ratio(dQ.float().cpu().numpy(), dQ_r, pu.BF16_TOL),
+           "dK": pu.worst_ratio(dK.float().cpu().numpy(), dK_r, pu.BF16_TOL),
+           "dV": pu.worst_ratio(dV.float().cpu().numpy(), dV_r, pu.BF16_TOL)}
+    bad = {k: v for k, v in res.items() if not v <= 1.0}
+    assert not bad, f"worst error / tolerance ratios {res}"
+
+
+def test_attention_backward_is_deterministic():
+    import torch
+    from paper_2602_07263_amd import tlora
+    seq = _offsets([700, 90])
+    T, Hq, Hkv = int(seq[-1]), 4, 1
+    rng = np.random.default_rng(5)
+    up = lambda a: torch.from_numpy(_bf(a)).to(device="cuda", dtype=torch.bfloat16).contiguous()
+    Q, K, V, dO = (up(rng.normal(size=(T, h * HD))) for h in (Hq, Hkv, Hkv, Hq))
+    att = tlora.Attention(seq, Hq, Hkv, "cuda")
+    O = torch.empty_like(Q)
+    lse = torch.empty((T, Hq), dtype=torch.float32, device="cuda")
+    att.fwd(Q, K, V, O, lse)
+    outs = []
+    for _ in range(2):
+        g = [torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)]
+        att.bwd(Q, K, V, O, dO, lse, *g)
+        torch.cuda.synchronize()
+        outs.append([t.view(torch.int16).cpu() for t in g])
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
+def test_attention_rejects_bad_arguments():
+    import ctypes
+    from paper_2602_07263_amd import tlora
+    L = tlora.lib()
+    seq = (ctypes.c_int64 * 2)(0, 8)
+    assert L.tlora_attention_workspace_bytes(1, seq, 0) == 0
+    bad = (ctypes.c_int64 * 3)(0, 8, 4)
+    assert L.tlora_attention_workspace_bytes(2, bad, 4) == 0
+    ws = L.tlora_attention_workspace_bytes(1, seq, 4)
+    assert ws > 0
+    # head size other than 128, and query heads not a multiple of key/value heads
+    assert L.tlora_attention_fwd(None, None, None, None, None, 1, seq, 4, 2, 64, None, 0, None) != 0
+    assert L.tlora_attention_fwd(None, None, None, None, None, 1, seq, 3, 2, 128, None, 0, None) != 0

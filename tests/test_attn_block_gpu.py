@@ -1,0 +1,91 @@
+"""GPU parity of the attention block (RMSNorm -> q / k / v fused multi-LoRA projections -> rotary embedding -> causal
+grouped-query attention -> o projection -> residual) against the fp64 oracle on the same seeded bf16 inputs.  The
+oracle rounds the tensors the block keeps in memory between its kernels at the same points (its arithmetic stays
+fp64)."""
+import numpy as np
+import pytest
+
+from oracle import attn_oracle as ao
+from paper_2602_07263_amd import workloads as wk
+from tests import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+HD = 128
+
+
+def _make(d, Hq, Hkv, ranks, tokens, seed):
+    rng = np.random.default_rng(seed)
+    f = lambda a: wk.round_to_bf16(np.asarray(a, dtype=np.float32))
+    T = sum(tokens)
+    off = np.concatenate([[0], np.cumsum(tokens)]).astype(np.int64)
+    X = f(rng.normal(size=(T, d)))
+    gamma = f(1.0 + 0.1 * rng.normal(size=d))
+    layers = {}
+    for name, (i, o) in dict(q=(d, Hq * HD), k=(d, Hkv * HD), v=(d, Hkv * HD), o=(Hq * HD, d)).items():
+        W = f(rng.normal(size=(i, o)) / np.sqrt(i))
+        A = [f(rng.uniform(-1, 1, size=(i, r)) / np.sqrt(i)) for r in ranks]
+        B = [f(0.05 * rng.normal(size=(r, o))) for r in ranks]
+        layers[name] = (W, A, B)
+    dOut = f(rng.normal(size=(T, d)))
+    return X, gamma, layers, off, dOut
+
+
+def test_attn_block_matches_oracle():
+    import torch
+    from paper_2602_07263_amd import tlora
+    d, Hq, Hkv = 256, 4, 2
+    ranks, tokens, scales = [8, 0, 24, 3], [300, 0, 513, 70], [2.0, 1.0, 0.5, 4.0]
+    # every job's tokens are whole sequences: 100 + 200 | - | 1 + 299 + 213 | 70
+    seq = np.array([0, 100, 300, 301, 600, 813, 883], dtype=np.int64)
+    eps, base = 1e-5, 10000.0
+    X, gamma, layers, off, dOut = _make(d, Hq, Hkv, ranks, tokens, seed=6)
+    up = lambda a: torch.from_numpy(a).to(device="cuda", dtype=torch.bfloat16).contiguous()
+    tl = {n: (up(W), [up(a) for a in A], [up(b) for b in B]) for n, (W, A, B) in layers.items()}
+    blk = tlora.AttnBlock(d, Hq, Hkv, base, ranks, off, scales, seq, up(X), up(gamma), eps, tl)
+    Out = torch.full((sum(tokens), d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    dX = torch.full_like(Out, float("nan"))
+    grads = blk.new_grads()
+    for n in grads:
+        for t in grads[n][0] + grads[n][1]:
+            t.fill_(float("nan"))
+    blk.fwd(Out)
+    blk.bwd(up(dOut), dX, grads)
+    torch.cuda.synchronize()
+    store = lambda a: wk.round_to_bf16(a.astype(np.float32)).astype(np.float64)
+    args = (gamma, eps, layers, scales, off, seq, Hq, Hkv, HD, base)
+    out_r, _ = ao.block_forward(X, *args, store)
+    dX_r, g_r = ao.block_backward(X, *args, dOut, store)
+    tol = pu.BF16_TOL
+
+    def ratio(got, ref):
+        # |err| <= tol (m + |ref|), m = max(1, rms(ref)): the adapter gradients are token sums of products of tensors
+        # the block stores in bf16 between its kernels; one-ulp flips of those reach a sum as noise relative to the
+        # sum's typical size (its rms), also on entries that happen to be near zero.
+        if ref.size == 0:
+            return 0.0
+        got = np.asarray(got, dtype=np.float64)
+        assert np.all(np.isfinite(got))
+        m = max(1.0, float(np.sqrt(np.mean(ref * ref))))
+        return float(np.max(np.abs(got - ref) / (tol * (m + np.abs(ref)))))
+    res = {"Out": pu.worst_ratio(Out.float().cpu().numpy(), out_r, tol),
+           "dX": pu.worst_ratio(dX.float().cpu().numpy(), dX_r, tol)}
+    for n in grads:
+        res["dA_" + n] = max([ratio(a.cpu().numpy(), r) for a, r in zip(grads[n][0], g_r[n][0])] + [0.0])
+        res["dB_" + n] = max([ratio(b.cpu().numpy(), r) for b, r in zip(grads[n][1], g_r[n][1])] + [0.0])
+    bad = {k: v for k, v in res.items() if not v <= 1.0}
+    assert not bad, f"worst error / tolerance ratios {res}"
+
+
+def test_attn_block_rejects_fp32_and_mismatched_sequences():
+    import ctypes
+    import torch
+    from paper_2602_07263_amd import tlora
+    d, Hq, Hkv = 256, 2, 1
+    X, gamma, layers, off, _ = _make(d, Hq, Hkv, [4], [64], seed=1)
+    up = lambda a: torch.from_numpy(a).to(device="cuda", dtype=torch.bfloat16).contiguous()
+    tl = {n: (up(W), [up(a) for a in A], [up(b) for b in B]) for n, (W, A, B) in layers.items()}
+    with pytest.raises(tlora.TloraError):       # sequences cover 60 tokens, jobs 64
+        tlora.AttnBlock(d, Hq, Hkv, 10000.0, [4], off, [1.0], [0, 60], up(X), up(gamma), 1e-5, tl)
+    blk = tlora.AttnBlock(d, Hq, Hkv, 10000.0, [4], off, [1.0], [0, 64], up(X), up(gamma), 1e-5, tl)
+    blk.prob.dtype = tlora.TLORA_F32
+    assert tlora.lib().tlora_attn_workspace_bytes(ctypes.byref(blk.prob)) == 0
