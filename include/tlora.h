@@ -271,6 +271,23 @@ int tlora_attn_fwd(const tlora_attn_t* p, void* Out, void* workspace, size_t ws_
 int tlora_attn_bwd(const tlora_attn_t* p, const void* dOut, void* dX, void* const* const* dA, void* const* const* dB,
                    int flags, void* workspace, size_t ws_bytes, void* hip_stream);
 
+/* ---- One decoder layer --------------------------------------------------------------------------------------
+ * Sec. 3.2's shared super-model repeats one unit: the attention half followed by the MLP half,
+ *     H = attention block(X),   Out = MLP block(H),
+ * all seven projections being fused multi-LoRA layers on the same jobs.  `attn.X` is the layer's input; `mlp.X` is
+ * ignored (H lives in the workspace).  Both halves must name the same dtype (bf16), num_jobs, d_model, and equal
+ * ranks / offsets / scales (TLORA_EINVAL otherwise).  tlora_layer_bwd must follow tlora_layer_fwd on the same
+ * stream with the same workspace.  dA / dB: HOST arrays of 7 entries (q, k, v, o, gate, up, down), each a HOST
+ * array [num_jobs] of DEVICE pointers; flags as tlora_attn_bwd. */
+typedef struct tlora_layer_t {
+  tlora_attn_t attn;
+  tlora_mlp_t mlp;
+} tlora_layer_t;
+size_t tlora_layer_workspace_bytes(const tlora_layer_t* p);
+int tlora_layer_fwd(const tlora_layer_t* p, void* Out, void* workspace, size_t ws_bytes, void* hip_stream);
+int tlora_layer_bwd(const tlora_layer_t* p, const void* dOut, void* dX, void* const* const* dA, void* const* const* dB,
+                    int flags, void* workspace, size_t ws_bytes, void* hip_stream);
+
 /* ---- General token -> adapter assignment --------------------------------------------------------------------
  * Sec. 3.3 describes the kernel as gathering the tokens of adapter i and scattering the results back to the
  * output tensor.  Here X, Y, dY, dX are in the batch's own (arbitrary) token order, and row_index (DEVICE int32 [T],

@@ -1296,6 +1296,78 @@ int tlora_attn_bwd(const tlora_attn_t* p, const void* dOut, void* dX, void* cons
   return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
 }
 
+// ---- one decoder layer: attention block, then MLP block -----------------------------------------------------
+namespace {
+struct LayerLayout {
+  tlora_attn_t attn;
+  tlora_mlp_t mlp;
+  int64_t T = 0;
+  size_t off_h = 0, off_dh = 0, off_attn = 0, off_mlp = 0, ws_attn = 0, ws_mlp = 0, total = 0;
+};
+int layer_layout(const tlora_layer_t* p, LayerLayout& L) {
+  if (!p) return TLORA_ENULL;
+  L.attn = p->attn;
+  L.mlp = p->mlp;
+  const tlora_attn_t& a = L.attn;
+  const tlora_mlp_t& m = L.mlp;
+  if (a.dtype != TLORA_BF16 || m.dtype != TLORA_BF16) return TLORA_EDTYPE;
+  if (a.num_jobs != m.num_jobs || a.d_model != m.d_model || a.num_jobs < 0) return TLORA_EINVAL;
+  if (!a.offsets || !m.offsets) return TLORA_ENULL;
+  if (a.num_jobs > 0 && (!a.ranks || !m.ranks || !a.scales || !m.scales)) return TLORA_ENULL;
+  for (int j = 0; j < a.num_jobs; ++j)
+    if (a.ranks[j] != m.ranks[j] || a.scales[j] != m.scales[j] || a.offsets[j] != m.offsets[j]) return TLORA_EINVAL;
+  if (a.offsets[a.num_jobs] != m.offsets[a.num_jobs]) return TLORA_EINVAL;
+  L.mlp.X = a.X;                         // placeholder for validation; the real input is H
+  L.ws_attn = tlora_attn_workspace_bytes(&L.attn);
+  L.ws_mlp = tlora_mlp_workspace_bytes(&L.mlp);
+  if (!L.ws_attn || !L.ws_mlp) return TLORA_EINVAL;
+  L.T = a.offsets[a.num_jobs];
+  size_t w = 0;
+  auto place = [&](size_t bytes) { const size_t at = w;  w = align_up(w + bytes, 256);  return at; };
+  const size_t td = (size_t)L.T * a.d_model * 2;
+  L.off_h = place(td);  L.off_dh = place(td);
+  L.off_attn = place(L.ws_attn);  L.off_mlp = place(L.ws_mlp);
+  L.total = std::max<size_t>(w, 256);
+  return TLORA_OK;
+}
+}  // namespace
+
+size_t tlora_layer_workspace_bytes(const tlora_layer_t* p) {
+  LayerLayout L;
+  return layer_layout(p, L) == TLORA_OK ? L.total : 0;
+}
+
+int tlora_layer_fwd(const tlora_layer_t* p, void* Out, void* workspace, size_t ws_bytes, void* hip_stream) {
+  std::lock_guard<std::recursive_mutex> lk(g_mu);
+  LayerLayout L;
+  int rc = layer_layout(p, L);
+  if (rc != TLORA_OK) return rc;
+  if (bad_ws(workspace, ws_bytes, L.total)) return TLORA_EWORKSPACE;
+  uint8_t* ws = static_cast<uint8_t*>(workspace);
+  rc = tlora_attn_fwd(&L.attn, ws + L.off_h, ws + L.off_attn, L.ws_attn, hip_stream);
+  if (rc != TLORA_OK) return rc;
+  L.mlp.X = ws + L.off_h;
+  return tlora_mlp_fwd(&L.mlp, Out, ws + L.off_mlp, L.ws_mlp, hip_stream);
+}
+
+int tlora_layer_bwd(const tlora_layer_t* p, const void* dOut, void* dX, void* const* const* dA, void* const* const* dB,
+                    int flags, void* workspace, size_t ws_bytes, void* hip_stream) {
+  std::lock_guard<std::recursive_mutex> lk(g_mu);
+  LayerLayout L;
+  int rc = layer_layout(p, L);
+  if (rc != TLORA_OK) return rc;
+  if (bad_ws(workspace, ws_bytes, L.total)) return TLORA_EWORKSPACE;
+  if (!dA || !dB) return TLORA_ENULL;
+  for (int i = 0; i < 7; ++i)
+    if (!dA[i] || !dB[i]) return TLORA_ENULL;
+  uint8_t* ws = static_cast<uint8_t*>(workspace);
+  L.mlp.X = ws + L.off_h;
+  rc = tlora_mlp_bwd(&L.mlp, dOut, ws + L.off_dh, dA[4], dB[4], dA[5], dB[5], dA[6], dB[6], flags, ws + L.off_mlp, L.ws_mlp,
+                     hip_stream);
+  if (rc != TLORA_OK) return rc;
+  return tlora_attn_bwd(&L.attn, ws + L.off_dh, dX, dA, dB, flags, ws + L.off_attn, L.ws_attn, hip_stream);
+}
+
 // ---- general token -> adapter assignment (Sec. 3.3: tokens of an adapter are gathered, results scattered back) ----
 namespace {
 struct IndexedLayout {

@@ -65,6 +65,10 @@ class tlora_attn_t(ctypes.Structure):
                 ("A_o", ctypes.POINTER(ctypes.c_void_p)), ("B_o", ctypes.POINTER(ctypes.c_void_p))]
 
 
+class tlora_layer_t(ctypes.Structure):
+    _fields_ = [("attn", tlora_attn_t), ("mlp", tlora_mlp_t)]
+
+
 class tlora_adamw_tensor_t(ctypes.Structure):
     _fields_ = [("param", ctypes.c_void_p), ("master", ctypes.c_void_p), ("grad", ctypes.c_void_p),
                 ("m", ctypes.c_void_p), ("v", ctypes.c_void_p), ("n", ctypes.c_int64),
@@ -76,6 +80,7 @@ EXPORTS = ["tlora_workspace_bytes", "tlora_fwd", "tlora_bwd", "tlora_adamw_works
            "tlora_mlp_workspace_bytes", "tlora_mlp_fwd", "tlora_mlp_bwd",
            "tlora_attention_workspace_bytes", "tlora_rope", "tlora_attention_fwd", "tlora_attention_bwd",
            "tlora_attn_workspace_bytes", "tlora_attn_fwd", "tlora_attn_bwd",
+           "tlora_layer_workspace_bytes", "tlora_layer_fwd", "tlora_layer_bwd",
            "tlora_indexed_workspace_bytes", "tlora_fwd_indexed", "tlora_bwd_indexed",
            "tlora_aimd_init", "tlora_aimd_update",
            "tlora_nano_split", "tlora_nano_workspace_bytes", "tlora_fwd_nano", "tlora_bwd_nano",
@@ -121,6 +126,13 @@ def lib() -> ctypes.CDLL:
     L.tlora_attn_fwd.argtypes = [PA, VP, VP, SZ, VP]
     L.tlora_attn_bwd.restype = ctypes.c_int
     L.tlora_attn_bwd.argtypes = [PA, VP, VP, ctypes.POINTER(VPP), ctypes.POINTER(VPP), ctypes.c_int, VP, SZ, VP]
+    PL = ctypes.POINTER(tlora_layer_t)
+    L.tlora_layer_workspace_bytes.restype = SZ
+    L.tlora_layer_workspace_bytes.argtypes = [PL]
+    L.tlora_layer_fwd.restype = ctypes.c_int
+    L.tlora_layer_fwd.argtypes = [PL, VP, VP, SZ, VP]
+    L.tlora_layer_bwd.restype = ctypes.c_int
+    L.tlora_layer_bwd.argtypes = [PL, VP, VP, ctypes.POINTER(VPP), ctypes.POINTER(VPP), ctypes.c_int, VP, SZ, VP]
     L.tlora_mlp_workspace_bytes.restype = ctypes.c_size_t
     L.tlora_mlp_workspace_bytes.argtypes = [PM]
     L.tlora_mlp_fwd.restype = ctypes.c_int
@@ -596,3 +608,71 @@ class AttnBlock:
                                     ctypes.c_void_p(dX.data_ptr()) if self.T else None, dA, dB, int(flags),
                                     ctypes.c_void_p(self.ws.data_ptr()), ctypes.c_size_t(self.ws_bytes),
                                     ctypes.c_void_p(self._stream())), "tlora_attn_bwd")
+
+
+class DecoderLayer:
+    """Holder of one decoder-layer problem (torch tensors) marshalling pointers to tlora_layer_fwd / tlora_layer_bwd.
+    `layers` maps "q", "k", "v", "o", "gate", "up", "down" to (W, [A_j], [B_j]); gamma_attn / gamma_mlp are the two
+    RMSNorm weights."""
+    NAMES = ("q", "k", "v", "o", "gate", "up", "down")
+
+    def __init__(self, d_model: int, d_ff: int, n_heads: int, n_kv_heads: int, rope_base: float, ranks, offsets, scales,
+                 seq_offsets, X, gamma_attn, gamma_mlp, eps: float, layers, head_dim: int = 128):
+        import torch
+        self.torch, self.d_model, self.d_ff = torch, int(d_model), int(d_ff)
+        self.ranks, self.offsets = [int(r) for r in ranks], [int(o) for o in offsets]
+        self.seq = [int(o) for o in seq_offsets]
+        self.T, J = self.offsets[-1], len(self.ranks)
+        self.X, self.layers = X, layers
+        self._keep = [(ctypes.c_int32 * J)(*self.ranks), (ctypes.c_int64 * (J + 1))(*self.offsets),
+                      (ctypes.c_float * J)(*[float(x) for x in scales]), (ctypes.c_int64 * len(self.seq))(*self.seq),
+                      gamma_attn, gamma_mlp]
+
+        def ptrs(ts):
+            a = (ctypes.c_void_p * J)(*[ctypes.c_void_p(t.data_ptr()) if t.numel() else None for t in ts])
+            self._keep.append(a)
+            return a
+        w = lambda n: ctypes.c_void_p(layers[n][0].data_ptr())
+        ab = {n: (ptrs(layers[n][1]), ptrs(layers[n][2])) for n in self.NAMES}
+        xp = ctypes.c_void_p(X.data_ptr()) if self.T else None
+        attn = tlora_attn_t(TLORA_BF16, J, self.d_model, int(n_heads), int(n_kv_heads), int(head_dim), float(rope_base),
+                            float(eps), self._keep[0], self._keep[1], self._keep[2], len(self.seq) - 1, self._keep[3],
+                            xp, ctypes.c_void_p(gamma_attn.data_ptr()), w("q"), w("k"), w("v"), w("o"),
+                            *[ab[n][k] for n in ("q", "k", "v", "o") for k in (0, 1)])
+        mlp = tlora_mlp_t(TLORA_BF16, J, self.d_model, self.d_ff, self._keep[0], self._keep[1], self._keep[2], None,
+                          ctypes.c_void_p(gamma_mlp.data_ptr()), float(eps), w("gate"), w("up"), w("down"),
+                          *[ab[n][k] for n in ("gate", "up", "down") for k in (0, 1)])
+        self.prob = tlora_layer_t(attn, mlp)
+        self.ws_bytes = int(lib().tlora_layer_workspace_bytes(ctypes.byref(self.prob)))
+        if self.ws_bytes == 0:
+            raise TloraError("tlora_layer_workspace_bytes: invalid problem")
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=X.device)
+
+    def _stream(self) -> int:
+        return int(self.torch.cuda.current_stream().cuda_stream)
+
+    def new_grads(self):
+        t = self.torch
+        dev = self.X.device
+        return {n: ([t.empty(a.shape, dtype=t.float32, device=dev) for a in A],
+                    [t.empty(b.shape, dtype=t.float32, device=dev) for b in B]) for n, (W, A, B) in self.layers.items()}
+
+    def fwd(self, Out) -> None:
+        _check(lib().tlora_layer_fwd(ctypes.byref(self.prob), ctypes.c_void_p(Out.data_ptr()) if self.T else None,
+                                     ctypes.c_void_p(self.ws.data_ptr()), ctypes.c_size_t(self.ws_bytes),
+                                     ctypes.c_void_p(self._stream())), "tlora_layer_fwd")
+
+    def bwd(self, dOut, dX, grads, flags: int = 0) -> None:
+        J = len(self.ranks)
+        VPP = ctypes.POINTER(ctypes.c_void_p)
+
+        def arr(ts):
+            return (ctypes.c_void_p * J)(*[ctypes.c_void_p(t.data_ptr()) if t.numel() else None for t in ts])
+        da = [arr(grads[n][0]) for n in self.NAMES]
+        db = [arr(grads[n][1]) for n in self.NAMES]
+        dA = (VPP * 7)(*[ctypes.cast(a, VPP) for a in da])
+        dB = (VPP * 7)(*[ctypes.cast(a, VPP) for a in db])
+        _check(lib().tlora_layer_bwd(ctypes.byref(self.prob), ctypes.c_void_p(dOut.data_ptr()) if self.T else None,
+                                     ctypes.c_void_p(dX.data_ptr()) if self.T else None, dA, dB, int(flags),
+                                     ctypes.c_void_p(self.ws.data_ptr()), ctypes.c_size_t(self.ws_bytes),
+                                     ctypes.c_void_p(self._stream())), "tlora_layer_bwd")

@@ -74,5 +74,6 @@ def test_mlp_block_matches_oracle(case):
     for n in grads:
         res["dA_" + n] = max([ratio(a.cpu().numpy(), r) for a, r in zip(grads[n][0], g_r[n][0])] + [0.0])
         res["dB_" + n] = max([ratio(b.cpu().numpy(), r) for b, r in zip(grads[n][1], g_r[n][1])] + [0.0])
+    print({k: round(v, 3) for k, v in res.items()})
     bad = {k: v for k, v in res.items() if not v <= 1.0}
     assert not bad, f"{dtype}: worst error / tolerance ratios {res}"
