@@ -258,6 +258,57 @@ def measure_mlp_block(steps: int, warmup: int):
             "kernel_ms_per_step": {k: round(t[0] / steps, 4) for k, t in prof.items() if t[1]}}
 
 
+def measure_decoder_layer(steps: int, warmup: int):
+    """One whole decoder layer on cfg3 (16 jobs, 83 968 tokens, sequences of 2048 tokens; d_model 4096, 32 query / 8
+    key-value heads of 128, d_ff 12288): forward + backward + one AdamW step on all 7 x 16 adapter pairs."""
+    import torch
+    from paper_2602_07263_amd import tlora, workloads as wk
+    wl = wk.config(3)
+    d, dff, Hq, Hkv, hd, T, n = 4096, 12288, 32, 8, 128, wl.total_tokens, 2048
+    g = torch.Generator(device="cuda"); g.manual_seed(0)
+    bf = torch.bfloat16
+    rn = lambda *shape, std=1.0: (torch.randn(*shape, device="cuda", generator=g) * std).to(bf)
+    shapes = dict(q=(d, Hq * hd), k=(d, Hkv * hd), v=(d, Hkv * hd), o=(Hq * hd, d), gate=(d, dff), up=(d, dff), down=(dff, d))
+    layers = {name: (rn(i, o, std=i ** -0.5), [((torch.rand(i, r, device="cuda", generator=g) * 2 - 1) / i ** 0.5).to(bf)
+                                                for r in wl.ranks], [rn(r, o, std=0.01) for r in wl.ranks])
+              for name, (i, o) in shapes.items()}
+    X, dOut = rn(T, d), rn(T, d)
+    gamma = torch.ones(d, device="cuda", dtype=bf)
+    seq = list(range(0, T + 1, n))
+    layer = tlora.DecoderLayer(d, dff, Hq, Hkv, 500000.0, wl.ranks, wl.offsets, wl.scales, seq, X, gamma, gamma, 1e-5, layers)
+    Out, dX, grads = torch.empty_like(X), torch.empty_like(X), layer.new_grads()
+    params = [t for nm in layers for t in layers[nm][1] + layers[nm][2]]
+    gl = [t for nm in layers for t in grads[nm][0] + grads[nm][1]]
+    master = [t.float() for t in params]
+    m = [torch.zeros_like(t) for t in master]
+    v = [torch.zeros_like(t) for t in master]
+    ows = torch.empty(tlora.tlora_adamw_workspace_bytes(len(params)), dtype=torch.uint8, device="cuda")
+    state = {"t": 0}
+
+    def step(_i):
+        state["t"] += 1
+        layer.fwd(Out)
+        layer.bwd(dOut, dX, grads)
+        tens = [dict(param=q.data_ptr(), master=w.data_ptr(), grad=gr.data_ptr(), m=a.data_ptr(), v=b.data_ptr(),
+                     n=q.numel(), lr=1e-4, weight_decay=0.0, step=state["t"])
+                for q, w, gr, a, b in zip(params, master, gl, m, v)]
+        tlora.tlora_adamw_step(tens, tlora.TLORA_BF16, ows.data_ptr(), ows.numel(),
+                               int(torch.cuda.current_stream().cuda_stream))
+    for i in range(warmup):
+        step(i)
+    tlora.tlora_profile(True)
+    ms = time_steps(step, steps, 0)
+    prof = tlora.tlora_profile_read()
+    tlora.tlora_profile(False)
+    pairs = (T // n) * Hq * n * (n + 1) / 2
+    attn_flops = 14 * pairs * hd                    # 2 products forward, 5 backward, 2 flops per multiply-add
+    return {"workload": "decoder layer over cfg3 (7 fused projections, RMSNorm x2, rotary, causal GQA attention at "
+                        "sequence length 2048, gated SiLU, residuals; fwd+bwd+AdamW)",
+            "ms_per_step": round(ms, 4), "value": round((wl.flops() + attn_flops) / (ms * 1e-3) / 1e12, 2),
+            "unit": "TFLOP/s", "note": "flops counted: the seven fused projections + the causal half of the attention products",
+            "kernel_ms_per_step": {k: round(t[0] / steps, 4) for k, t in prof.items() if t[1]}}
+
+
 def measure_indexed(steps: int, warmup: int):
     """cfg2's gate projection with the jobs' sequences (runs of 512 tokens) interleaved in the batch: the
     token-indexed calls (gather pass + scattering GEMM epilogue) against the contiguous calls on the same data."""
@@ -366,6 +417,8 @@ def main():
         out["also_mlp_block"] = measure_mlp_block(max(5, args.steps // 2), 2)
         torch.cuda.empty_cache()
         out["also_indexed"] = measure_indexed(max(5, args.steps // 2), 2)
+        torch.cuda.empty_cache()
+        out["also_decoder_layer"] = measure_decoder_layer(max(3, args.steps // 4), 1)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config)
     print(json.dumps(out))

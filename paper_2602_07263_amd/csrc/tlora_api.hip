@@ -1036,7 +1036,7 @@ int attn_upload(const AttnPlan& A, void* ws, hipStream_t st) {
 }
 int attn_heads_ok(int32_t n_heads, int32_t n_kv, int32_t head_dim) {
   if (head_dim != kAttnHeadDim) return TLORA_EINVAL;
-  if (n_heads < 1 || n_kv < 1 || n_heads % n_kv != 0 || n_heads > 65535) return TLORA_EINVAL;
+  if (n_heads < 1 || n_kv < 1 || n_heads % n_kv != 0 || n_heads > 4096) return TLORA_EINVAL;   // 32-bit byte offsets inside a tile
   return TLORA_OK;
 }
 inline bool bad_ws(const void* ws, size_t have, size_t need) {
@@ -1052,7 +1052,7 @@ size_t tlora_attention_workspace_bytes(int32_t num_seqs, const int64_t* seq_offs
 int tlora_rope(void* X, int32_t num_seqs, const int64_t* seq_offsets, int32_t heads, int32_t head_dim, float rope_base,
                int32_t inverse, void* workspace, size_t ws_bytes, void* hip_stream) {
   std::lock_guard<std::recursive_mutex> lk(g_mu);
-  if (head_dim != kAttnHeadDim || !(rope_base > 1.f) || heads > 65535) return TLORA_EINVAL;
+  if (head_dim != kAttnHeadDim || !(rope_base > 1.f) || heads > 4096) return TLORA_EINVAL;
   AttnPlan A;
   int rc = attn_plan(num_seqs, seq_offsets, heads, true, A);
   if (rc != TLORA_OK) return rc;

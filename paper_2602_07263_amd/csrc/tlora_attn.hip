@@ -61,21 +61,41 @@ __device__ __forceinline__ bf16x8 frag_cols(const uint8_t* tile, int cb, int r16
   s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, tile + tile_off(r0 + 8, c) + inner));
   return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
-// copy `nrows` rows (zero beyond `valid`) of one head from global memory ([token][heads * 128]) into a tile
-template <int NROWS>
-__device__ __forceinline__ void load_tile_regs(const uint16_t* base, int64_t row_stride, int valid, u32x4 (&regs)[NROWS / 16]) {
-#pragma unroll
-  for (int i = 0; i < NROWS / 16; ++i) {
-    const int id = threadIdx.x + i * 256, r = id >> 4, c = id & 15;
-    regs[i] = r < valid ? *reinterpret_cast<const u32x4*>(base + (int64_t)r * row_stride + c * 8) : u32x4{0, 0, 0, 0};
-  }
+// Asynchronous 16-byte-per-lane global->LDS load issued as raw instructions: lane l's 16 bytes land at LDS byte
+// address lds_base + 16 l (lds_base wave-uniform, carried in M0); the global address is a wave-uniform 64-bit base
+// plus an unsigned 32-bit byte offset per lane.  The compiler does not track these loads: the kernels wait
+// (s_waitcnt vmcnt(0)) and synchronise by hand before reading what they wrote, and drain before they end.
+__device__ __forceinline__ void dma16s(uint32_t voff, const void* sbase, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_base)
+               : "memory");
 }
-template <int NROWS>
-__device__ __forceinline__ void store_tile_regs(uint8_t* tile, const u32x4 (&regs)[NROWS / 16]) {
+__device__ __forceinline__ const char* uniform_ptr(const void* p) {
+  const uint64_t v = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return reinterpret_cast<const char*>(((uint64_t)hi << 32) | lo);
+}
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+  return __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)LDS_PTR(const uint8_t, p));
+}
+// every load of this wave has landed (vmcnt = expcnt = lgkmcnt = 0), then the workgroup meets
+__device__ __forceinline__ void wait_all_and_sync() {
+  __builtin_amdgcn_s_waitcnt(0);
+  __builtin_amdgcn_s_barrier();
+}
+// One wave's share (LOADS x 4 rows) of an asynchronous tile copy: rows row0 + 4 i + lane / 16 of a [.., row_bytes]
+// global matrix whose rows past `last_row` repeat row `last_row` (finite stand-ins that a zero probability
+// multiplies), into the swizzled tile.  Rows row0 + 4 i are multiples of 4, so the swizzle of a lane's chunk
+// depends on i and the lane only.
+template <int LOADS>
+__device__ __forceinline__ void tile_dma(const char* sbase, uint32_t row_bytes, int row0, int last_row, uint32_t tile_lds,
+                                         int lane) {
+  const int lr = lane >> 4, slot = lane & 15;
 #pragma unroll
-  for (int i = 0; i < NROWS / 16; ++i) {
-    const int id = threadIdx.x + i * 256;
-    *reinterpret_cast<u32x4*>(tile + tile_off(id >> 4, id & 15)) = regs[i];
+  for (int i = 0; i < LOADS; ++i) {
+    const int r = row0 + 4 * i + lr;
+    const int c = slot ^ ((lr << 2) | (((row0 >> 2) + i) & 3));
+    dma16s((uint32_t)min(r, last_row) * row_bytes + (uint32_t)c * 16u, sbase, tile_lds + (uint32_t)(row0 + 4 * i) * ROWB);
   }
 }
 // the 8 k-slices of one token row as a "column" operand: lane l -> row (given), head-dim values 16 s + 8 (l / 32) ..
@@ -84,24 +104,31 @@ __device__ __forceinline__ void load_row_frags(const uint16_t* row, int lane, bf
   for (int s = 0; s < 8; ++s)
     f[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(row + 16 * s + 8 * (lane >> 5)));
 }
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+// key (query) index inside a 32-block that accumulator element i of lanes with lane / 32 = hl stands for
+__device__ __forceinline__ int acc_row(int i, int hl) { return 8 * (i >> 2) + 4 * hl + (i & 3); }
 
 }  // namespace
 
 // ---------------------------------------------------------------------------------------------------
 // Forward.  One workgroup = 128 queries of one sequence and head (4 waves x 32); keys / values stream through
-// LDS in tiles of 64, double buffered through registers.  c = log2(e) / sqrt(128); lse is kept in the base-2
-// domain: lse = max + log2(sum).
+// LDS in tiles of 64 (double buffered, asynchronous loads).  Scores stay unscaled in the accumulators; with
+// c = log2(e) / sqrt(128) the probabilities are exp2(c s - c m), one multiply-add and one exponential per score.
+// The running maximum only rescales the output accumulators when it moved in some lane of the wave, and only
+// tiles on the diagonal are masked.  lse = c m + log2(sum)  (base-2 domain).  Two workgroups share a CU so that
+// one's softmax overlaps the other's matrix products.
 // ---------------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) attn_fwd_kernel(const AttnTile* __restrict__ tiles, const uint16_t* __restrict__ Q,
-                                                       const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
-                                                       uint16_t* __restrict__ O, float* __restrict__ lse, int Hq, int Hkv,
-                                                       float c) {
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+attn_fwd_kernel(const AttnTile* __restrict__ tiles, const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
+                const uint16_t* __restrict__ V, uint16_t* __restrict__ O, float* __restrict__ lse, int Hq, int Hkv, float c) {
   __shared__ __attribute__((aligned(1024))) uint8_t kt[2][64 * ROWB];
   __shared__ __attribute__((aligned(1024))) uint8_t vt[2][64 * ROWB];
   const AttnTile t = tiles[blockIdx.x];
   const int h = blockIdx.y, hk = h / (Hq / Hkv);
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, hl = lane >> 5;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), hl = lane >> 5;
   const int q0w = t.t0 + wave * 32;
+  const bool active = q0w < t.seq_len;                               // a wave of padding rows only computes nothing
+  const int qmin = min(q0w, t.seq_len - 1), qmax = min(q0w + 31, t.seq_len - 1);
   const int qpos = min(q0w + (lane & 31), t.seq_len - 1);          // padded rows act like the last row; not stored
   const bool qvalid = q0w + (lane & 31) < t.seq_len;
   const int64_t qs = (int64_t)Hq * HD, ks = (int64_t)Hkv * HD;
@@ -109,27 +136,28 @@ __global__ void __launch_bounds__(256) attn_fwd_kernel(const AttnTile* __restric
   load_row_frags(Q + (int64_t)(t.seq_start + qpos) * qs + h * HD, lane, qf);
   const uint16_t* Kh = K + (int64_t)t.seq_start * ks + hk * HD;
   const uint16_t* Vh = V + (int64_t)t.seq_start * ks + hk * HD;
+  const uint32_t kv_row_bytes = (uint32_t)ks * 2u;
+  const uint32_t kt_lds = lds_addr(kt), vt_lds = lds_addr(vt);
   f32x16 oacc[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int e = 0; e < 16; ++e) oacc[i][e] = 0.f;
-  float m = kNegInf, lsum = 0.f;
+  float m = kNegInf, lsum = 0.f;                                     // lsum: this lane's half of the row sum
   const int nkv = min(t.seq_len, t.t0 + 128);                     // keys this workgroup can see
   const int ntiles = (nkv + 63) / 64;
-  u32x4 kr[4], vr[4];
-  load_tile_regs<64>(Kh, ks, nkv, kr);
-  load_tile_regs<64>(Vh, ks, nkv, vr);
-  store_tile_regs<64>(kt[0], kr);
-  store_tile_regs<64>(vt[0], vr);
-  for (int it = 0; it < ntiles; ++it) {
-    __syncthreads();
+  auto issue = [&](int it) {
     const int kvbase = it * 64;
-    if (it + 1 < ntiles) {
-      load_tile_regs<64>(Kh + (int64_t)(kvbase + 64) * ks, ks, nkv - kvbase - 64, kr);
-      load_tile_regs<64>(Vh + (int64_t)(kvbase + 64) * ks, ks, nkv - kvbase - 64, vr);
-    }
-    if (kvbase <= q0w + 31) {                                       // wave-uniform: something below the diagonal
+    const uint32_t buf = (uint32_t)(it & 1) * 64 * ROWB;
+    tile_dma<4>(uniform_ptr(Kh + (int64_t)kvbase * ks), kv_row_bytes, 16 * wave, nkv - 1 - kvbase, kt_lds + buf, lane);
+    tile_dma<4>(uniform_ptr(Vh + (int64_t)kvbase * ks), kv_row_bytes, 16 * wave, nkv - 1 - kvbase, vt_lds + buf, lane);
+  };
+  issue(0);
+  for (int it = 0; it < ntiles; ++it) {
+    wait_all_and_sync();                                              // tile `it` is in LDS; the other buffer is free
+    if (it + 1 < ntiles) issue(it + 1);
+    const int kvbase = it * 64;
+    if (active && kvbase <= qmax) {                                   // wave-uniform: something at or below the diagonal
       const uint8_t* kb = kt[it & 1];
       const uint8_t* vb = vt[it & 1];
       f32x16 sacc[2];
@@ -140,35 +168,38 @@ __global__ void __launch_bounds__(256) attn_fwd_kernel(const AttnTile* __restric
 #pragma unroll
         for (int s = 0; s < 8; ++s) sacc[j] = mfma32(frag_rows(kb, 32 * j, s, lane), qf[s], sacc[j]);
       }
-      float mx = kNegInf;
+      if (kvbase + 63 > qmin) {                                       // the tile reaches past some query of the wave
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int i = 0; i < 16; ++i)
+            if (kvbase + 32 * j + acc_row(i, hl) > qpos) sacc[j][i] = kNegInf;
+      }
+      float mx = sacc[0][0];
 #pragma unroll
       for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int kv = kvbase + 32 * j + 8 * (i >> 2) + 4 * hl + (i & 3);
-          const float v = kv <= qpos ? sacc[j][i] * c : kNegInf;     // kv <= qpos < seq_len
-          sacc[j][i] = v;
-          mx = fmaxf(mx, v);
-        }
+        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[j][i]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float mnew = fmaxf(m, mx);                               // finite: key 0 is visible to every query
-      const float alpha = m == kNegInf ? 0.f : exp2f(m - mnew);
-      float rs = 0.f;
+      const float mnew = fmaxf(m, mx);                                // finite: key 0 is visible to every query
+      if (__any(mnew != m)) {
+        const float alpha = fast_exp2((m - mnew) * c);                // 0 for m = -inf
+        lsum *= alpha;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) oacc[i][e] *= alpha;
+        m = mnew;
+      }
+      const float mc = m * c;
 #pragma unroll
       for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const float p = sacc[j][i] == kNegInf ? 0.f : exp2f(sacc[j][i] - mnew);
+          const float p = fast_exp2(fmaf(sacc[j][i], c, -mc));      // exp2(-inf) = 0 for masked scores
           sacc[j][i] = p;
-          rs += p;
+          lsum += p;
         }
-      rs += __shfl_xor(rs, 32, 64);
-      lsum = lsum * alpha + rs;
-      m = mnew;
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) oacc[i][e] *= alpha;
 #pragma unroll
       for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -178,13 +209,10 @@ __global__ void __launch_bounds__(256) attn_fwd_kernel(const AttnTile* __restric
           for (int db = 0; db < 4; ++db) oacc[db] = mfma32(frag_cols(vb, db, 32 * j + 16 * s2, lane), pf, oacc[db]);
         }
     }
-    if (it + 1 < ntiles) {
-      store_tile_regs<64>(kt[(it + 1) & 1], kr);
-      store_tile_regs<64>(vt[(it + 1) & 1], vr);
-    }
   }
   if (qvalid) {
-    const float inv = 1.f / lsum;
+    const float l = lsum + __shfl_xor(lsum, 32, 64);
+    const float inv = 1.f / l;
     uint16_t* orow = O + (int64_t)(t.seq_start + qpos) * qs + h * HD;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
@@ -193,7 +221,7 @@ __global__ void __launch_bounds__(256) attn_fwd_kernel(const AttnTile* __restric
         *reinterpret_cast<u32x2*>(orow + db * 32 + 8 * g + 4 * hl) =
             u32x2{pack2(oacc[db][4 * g] * inv, oacc[db][4 * g + 1] * inv),
                   pack2(oacc[db][4 * g + 2] * inv, oacc[db][4 * g + 3] * inv)};
-    if (hl == 0) lse[(int64_t)(t.seq_start + qpos) * Hq + h] = m + log2f(lsum);
+    if (hl == 0) lse[(int64_t)(t.seq_start + qpos) * Hq + h] = m * c + log2f(l);
   }
 }
 
@@ -216,17 +244,18 @@ __global__ void __launch_bounds__(256) attn_rowdot_kernel(const uint16_t* __rest
 // Backward, dQ.  Same decomposition as the forward: per 32 keys
 //   S^T = K Q^T,  P^T = exp2(c S^T - lse),  dP^T = V dO^T,  dS^T = P^T (dP^T - D),  dQ^T += K^T dS^T,  dQ = dQ / sqrt(128).
 // ---------------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) attn_bwd_dq_kernel(const AttnTile* __restrict__ tiles, const uint16_t* __restrict__ Q,
-                                                          const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
-                                                          const uint16_t* __restrict__ dO, const float* __restrict__ lse,
-                                                          const float* __restrict__ D, uint16_t* __restrict__ dQ, int Hq,
-                                                          int Hkv, float c, float scale) {
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+attn_bwd_dq_kernel(const AttnTile* __restrict__ tiles, const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
+                   const uint16_t* __restrict__ V, const uint16_t* __restrict__ dO, const float* __restrict__ lse,
+                   const float* __restrict__ D, uint16_t* __restrict__ dQ, int Hq, int Hkv, float c, float scale) {
   __shared__ __attribute__((aligned(1024))) uint8_t kt[2][64 * ROWB];
   __shared__ __attribute__((aligned(1024))) uint8_t vt[2][64 * ROWB];
   const AttnTile t = tiles[blockIdx.x];
   const int h = blockIdx.y, hk = h / (Hq / Hkv);
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, hl = lane >> 5;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), hl = lane >> 5;
   const int q0w = t.t0 + wave * 32;
+  const bool active = q0w < t.seq_len;
+  const int qmin = min(q0w, t.seq_len - 1), qmax = min(q0w + 31, t.seq_len - 1);
   const int qpos = min(q0w + (lane & 31), t.seq_len - 1);
   const bool qvalid = q0w + (lane & 31) < t.seq_len;
   const int64_t qs = (int64_t)Hq * HD, ks = (int64_t)Hkv * HD;
@@ -237,6 +266,8 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_kernel(const AttnTile* __rest
   const float L = lse[qrow * Hq + h], Dq = D[qrow * Hq + h];
   const uint16_t* Kh = K + (int64_t)t.seq_start * ks + hk * HD;
   const uint16_t* Vh = V + (int64_t)t.seq_start * ks + hk * HD;
+  const uint32_t kv_row_bytes = (uint32_t)ks * 2u;
+  const uint32_t kt_lds = lds_addr(kt), vt_lds = lds_addr(vt);
   f32x16 dq[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -244,21 +275,21 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_kernel(const AttnTile* __rest
     for (int e = 0; e < 16; ++e) dq[i][e] = 0.f;
   const int nkv = min(t.seq_len, t.t0 + 128);
   const int ntiles = (nkv + 63) / 64;
-  u32x4 kr[4], vr[4];
-  load_tile_regs<64>(Kh, ks, nkv, kr);
-  load_tile_regs<64>(Vh, ks, nkv, vr);
-  store_tile_regs<64>(kt[0], kr);
-  store_tile_regs<64>(vt[0], vr);
-  for (int it = 0; it < ntiles; ++it) {
-    __syncthreads();
+  auto issue = [&](int it) {
     const int kvbase = it * 64;
-    if (it + 1 < ntiles) {
-      load_tile_regs<64>(Kh + (int64_t)(kvbase + 64) * ks, ks, nkv - kvbase - 64, kr);
-      load_tile_regs<64>(Vh + (int64_t)(kvbase + 64) * ks, ks, nkv - kvbase - 64, vr);
-    }
-    if (kvbase <= q0w + 31) {
+    const uint32_t buf = (uint32_t)(it & 1) * 64 * ROWB;
+    tile_dma<4>(uniform_ptr(Kh + (int64_t)kvbase * ks), kv_row_bytes, 16 * wave, nkv - 1 - kvbase, kt_lds + buf, lane);
+    tile_dma<4>(uniform_ptr(Vh + (int64_t)kvbase * ks), kv_row_bytes, 16 * wave, nkv - 1 - kvbase, vt_lds + buf, lane);
+  };
+  issue(0);
+  for (int it = 0; it < ntiles; ++it) {
+    wait_all_and_sync();
+    if (it + 1 < ntiles) issue(it + 1);
+    const int kvbase = it * 64;
+    if (active && kvbase <= qmax) {
       const uint8_t* kb = kt[it & 1];
       const uint8_t* vb = vt[it & 1];
+      const bool diag = kvbase + 63 > qmin;
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         f32x16 sacc, dp;
@@ -269,12 +300,13 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_kernel(const AttnTile* __rest
           sacc = mfma32(frag_rows(kb, 32 * j, s, lane), qf[s], sacc);
           dp = mfma32(frag_rows(vb, 32 * j, s, lane), dof[s], dp);
         }
+        if (diag) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int kv = kvbase + 32 * j + 8 * (i >> 2) + 4 * hl + (i & 3);
-          const float p = kv <= qpos ? exp2f(sacc[i] * c - L) : 0.f;
-          sacc[i] = p * (dp[i] - Dq);                                 // dS^T
+          for (int i = 0; i < 16; ++i)
+            if (kvbase + 32 * j + acc_row(i, hl) > qpos) sacc[i] = kNegInf;
         }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sacc[i] = fast_exp2(fmaf(sacc[i], c, -L)) * (dp[i] - Dq);   // dS^T
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
           const bf16x8 dsf = pack8(sacc, 8 * s2);
@@ -282,10 +314,6 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_kernel(const AttnTile* __rest
           for (int db = 0; db < 4; ++db) dq[db] = mfma32(frag_cols(kb, db, 32 * j + 16 * s2, lane), dsf, dq[db]);
         }
       }
-    }
-    if (it + 1 < ntiles) {
-      store_tile_regs<64>(kt[(it + 1) & 1], kr);
-      store_tile_regs<64>(vt[(it + 1) & 1], vr);
     }
   }
   if (qvalid) {
@@ -302,9 +330,9 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_kernel(const AttnTile* __rest
 
 // ---------------------------------------------------------------------------------------------------
 // Backward, dK and dV.  One workgroup = 128 keys of one sequence and key/value head (4 waves x 32 keys); it walks
-// the query heads of the group and, for each, the query tiles at or after its keys.  Per 32 queries:
+// the query heads of the group and, for each, the queries at or after its keys in steps of 32:
 //   S = Q K^T,  P = exp2(c S - lse_q),  dV^T += dO^T P,  dP = dO V^T,  dS = P (dP - D_q),  dK^T += Q^T dS.
-// A lane owns one key column; lse and D of the 16 queries it sees come from LDS.  Sums run in a fixed order.
+// A lane owns one key column; lse and D of the queries come from LDS.  Sums run in a fixed order.
 // ---------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const AttnTile* __restrict__ tiles, const uint16_t* __restrict__ Q,
                                                            const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
@@ -316,53 +344,49 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const AttnTile* __res
   __shared__ float ls[2][32], ds[2][32];
   const AttnTile t = tiles[blockIdx.x];
   const int hk = blockIdx.y, G = Hq / Hkv;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, hl = lane >> 5;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), hl = lane >> 5;
   const int k0w = t.t0 + wave * 32;
+  const bool active = k0w < t.seq_len;
   const int kpos = min(k0w + (lane & 31), t.seq_len - 1);
+  const int kmax = min(k0w + 31, t.seq_len - 1);
   const bool kvalid = k0w + (lane & 31) < t.seq_len;
   const int64_t qs = (int64_t)Hq * HD, ks = (int64_t)Hkv * HD;
   const int64_t krow = t.seq_start + kpos;
   bf16x8 kf[8], vf[8];
   load_row_frags(K + krow * ks + hk * HD, lane, kf);
   load_row_frags(V + krow * ks + hk * HD, lane, vf);
+  const uint32_t q_row_bytes = (uint32_t)qs * 2u;
+  const uint32_t qt_lds = lds_addr(qt), dot_lds = lds_addr(dot);
   f32x16 dk[4], dv[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int e = 0; e < 16; ++e) { dk[i][e] = 0.f;  dv[i][e] = 0.f; }
-  const int q_first = t.t0 & ~31;                                   // queries before the first key see none of them
-  const int nq = (t.seq_len - q_first + 31) / 32;                   // query steps per head
+  const int q_first = t.t0;                                          // queries before the first key see none of them
+  const int nq = (t.seq_len - q_first + 31) / 32;                    // query steps per head
   const int nsteps = nq * G;
-  auto step_src = [&](int st, const uint16_t*& qp, const uint16_t*& dop, int& q0, int& hq) {
-    hq = hk * G + st / nq;
-    q0 = q_first + (st % nq) * 32;
-    qp = Q + (int64_t)(t.seq_start + q0) * qs + hq * HD;
-    dop = dO + (int64_t)(t.seq_start + q0) * qs + hq * HD;
-  };
-  u32x4 qr[2], dr[2];
   float lr = 0.f, dd = 0.f;
-  auto fetch = [&](int st) {
-    const uint16_t* qp;  const uint16_t* dop;  int q0, hq;
-    step_src(st, qp, dop, q0, hq);
-    load_tile_regs<32>(qp, qs, t.seq_len - q0, qr);
-    load_tile_regs<32>(dop, qs, t.seq_len - q0, dr);
+  auto issue = [&](int st) {
+    const int hq = hk * G + st / nq, q0 = q_first + (st % nq) * 32;
+    const uint32_t buf = (uint32_t)(st & 1) * 32 * ROWB;
+    const int64_t base = (int64_t)(t.seq_start + q0) * qs + hq * HD;
+    tile_dma<2>(uniform_ptr(Q + base), q_row_bytes, 8 * wave, t.seq_len - 1 - q0, qt_lds + buf, lane);
+    tile_dma<2>(uniform_ptr(dO + base), q_row_bytes, 8 * wave, t.seq_len - 1 - q0, dot_lds + buf, lane);
     if (threadIdx.x < 32) {
       const int qq = min(q0 + (int)threadIdx.x, t.seq_len - 1);
       lr = lse[(int64_t)(t.seq_start + qq) * Hq + hq];
       dd = D[(int64_t)(t.seq_start + qq) * Hq + hq];
     }
   };
-  auto stash = [&](int buf) {
-    store_tile_regs<32>(qt[buf], qr);
-    store_tile_regs<32>(dot[buf], dr);
-    if (threadIdx.x < 32) { ls[buf][threadIdx.x] = lr;  ds[buf][threadIdx.x] = dd; }
-  };
-  if (nsteps > 0) { fetch(0);  stash(0); }
+  if (nsteps > 0) {
+    issue(0);
+    if (threadIdx.x < 32) { ls[0][threadIdx.x] = lr;  ds[0][threadIdx.x] = dd; }
+  }
   for (int st = 0; st < nsteps; ++st) {
-    __syncthreads();
-    if (st + 1 < nsteps) fetch(st + 1);
+    wait_all_and_sync();
+    if (st + 1 < nsteps) issue(st + 1);
     const int q0 = q_first + (st % nq) * 32;
-    if (q0 + 31 >= k0w) {                                            // wave-uniform: some query at or after a key
+    if (active && q0 + 31 >= k0w) {                                  // wave-uniform: some query at or after a key
       const uint8_t* qb = qt[st & 1];
       const uint8_t* dob = dot[st & 1];
       f32x16 sacc, dp;
@@ -373,11 +397,18 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const AttnTile* __res
         sacc = mfma32(frag_rows(qb, 0, s, lane), kf[s], sacc);
         dp = mfma32(frag_rows(dob, 0, s, lane), vf[s], dp);
       }
+      if (q0 < kmax || q0 + 31 >= t.seq_len) {                       // some query before a key of the wave, or padding
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int q = q0 + acc_row(i, hl);
+          if (q < kpos || q >= t.seq_len) sacc[i] = kNegInf;
+        }
+      }
       f32x16 pm;
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        const int ql = 8 * (i >> 2) + 4 * hl + (i & 3), q = q0 + ql;
-        const float p = (q >= kpos && q < t.seq_len) ? exp2f(sacc[i] * c - ls[st & 1][ql]) : 0.f;
+        const int ql = acc_row(i, hl);
+        const float p = fast_exp2(fmaf(sacc[i], c, -ls[st & 1][ql]));
         pm[i] = p;
         sacc[i] = p * (dp[i] - ds[st & 1][ql]);                      // dS
       }
@@ -391,7 +422,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const AttnTile* __res
         }
       }
     }
-    if (st + 1 < nsteps) stash((st + 1) & 1);
+    if (st + 1 < nsteps && threadIdx.x < 32) { ls[(st + 1) & 1][threadIdx.x] = lr;  ds[(st + 1) & 1][threadIdx.x] = dd; }
   }
   if (kvalid) {
     uint16_t* krow_o = dK + krow * ks + hk * HD;
