@@ -69,6 +69,11 @@ __device__ __forceinline__ void dma16s(uint32_t voff, const void* sbase, uint32_
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_base)
                : "memory");
 }
+// 4 bytes per lane: lane l's word lands at lds_base + 4 l
+__device__ __forceinline__ void dma4s(uint32_t voff, const void* sbase, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_base)
+               : "memory");
+}
 __device__ __forceinline__ const char* uniform_ptr(const void* p) {
   const uint64_t v = reinterpret_cast<uint64_t>(p);
   const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
@@ -330,19 +335,25 @@ attn_bwd_dq_kernel(const AttnTile* __restrict__ tiles, const uint16_t* __restric
 
 // ---------------------------------------------------------------------------------------------------
 // Backward, dK and dV.  One workgroup = 128 keys of one sequence and key/value head (4 waves x 32 keys); it walks
-// the query heads of the group and, for each, the queries at or after its keys in steps of 32:
+// the query heads of the group and, for each, the queries at or after its keys in steps of 64 (two blocks of 32):
 //   S = Q K^T,  P = exp2(c S - lse_q),  dV^T += dO^T P,  dP = dO V^T,  dS = P (dP - D_q),  dK^T += Q^T dS.
-// A lane owns one key column; lse and D of the queries come from LDS.  Sums run in a fixed order.
+// A lane owns one key column; Q, dO, lse and D of a step arrive in LDS through asynchronous loads issued two
+// steps ahead (three stages; every wave issues the same 10 loads per step so that one counter value means
+// "everything but the newest step has landed").  Sums run in a fixed order.  Tiles are taken from the end of the
+// table: there the first keys of the long sequences come first, which have the most queries to walk.
 // ---------------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const AttnTile* __restrict__ tiles, const uint16_t* __restrict__ Q,
-                                                           const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
-                                                           const uint16_t* __restrict__ dO, const float* __restrict__ lse,
-                                                           const float* __restrict__ D, uint16_t* __restrict__ dK,
-                                                           uint16_t* __restrict__ dV, int Hq, int Hkv, float c, float scale) {
-  __shared__ __attribute__((aligned(1024))) uint8_t qt[2][32 * ROWB];      // 32 queries per step
-  __shared__ __attribute__((aligned(1024))) uint8_t dot[2][32 * ROWB];
-  __shared__ float ls[2][32], ds[2][32];
-  const AttnTile t = tiles[blockIdx.x];
+__global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const AttnTile* __restrict__ tiles, int n_tiles,
+                                                           const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
+                                                           const uint16_t* __restrict__ V, const uint16_t* __restrict__ dO,
+                                                           const float* __restrict__ lse, const float* __restrict__ D,
+                                                           uint16_t* __restrict__ dK, uint16_t* __restrict__ dV, int Hq,
+                                                           int Hkv, float c, float scale) {
+  constexpr int NS = 3, QS = 64;                                     // stages, queries per step
+  constexpr int kLoads = 10;                                         // asynchronous loads per wave and step
+  __shared__ __attribute__((aligned(1024))) uint8_t qt[NS][QS * ROWB];
+  __shared__ __attribute__((aligned(1024))) uint8_t dot[NS][QS * ROWB];
+  __shared__ __attribute__((aligned(256))) float ls[NS][QS], ds[NS][QS];
+  const AttnTile t = tiles[n_tiles - 1 - (int)blockIdx.x];
   const int hk = blockIdx.y, G = Hq / Hkv;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), hl = lane >> 5;
   const int k0w = t.t0 + wave * 32;
@@ -356,73 +367,82 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const AttnTile* __res
   load_row_frags(K + krow * ks + hk * HD, lane, kf);
   load_row_frags(V + krow * ks + hk * HD, lane, vf);
   const uint32_t q_row_bytes = (uint32_t)qs * 2u;
-  const uint32_t qt_lds = lds_addr(qt), dot_lds = lds_addr(dot);
+  const uint32_t qt_lds = lds_addr(qt), dot_lds = lds_addr(dot), ls_lds = lds_addr(ls), ds_lds = lds_addr(ds);
   f32x16 dk[4], dv[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int e = 0; e < 16; ++e) { dk[i][e] = 0.f;  dv[i][e] = 0.f; }
   const int q_first = t.t0;                                          // queries before the first key see none of them
-  const int nq = (t.seq_len - q_first + 31) / 32;                    // query steps per head
+  const int nq = (t.seq_len - q_first + QS - 1) / QS;                // query steps per head
   const int nsteps = nq * G;
-  float lr = 0.f, dd = 0.f;
   auto issue = [&](int st) {
-    const int hq = hk * G + st / nq, q0 = q_first + (st % nq) * 32;
-    const uint32_t buf = (uint32_t)(st & 1) * 32 * ROWB;
+    const int hq = hk * G + st / nq, q0 = q_first + (st % nq) * QS;
+    const int stage = st % NS, last = t.seq_len - 1 - q0;
     const int64_t base = (int64_t)(t.seq_start + q0) * qs + hq * HD;
-    tile_dma<2>(uniform_ptr(Q + base), q_row_bytes, 8 * wave, t.seq_len - 1 - q0, qt_lds + buf, lane);
-    tile_dma<2>(uniform_ptr(dO + base), q_row_bytes, 8 * wave, t.seq_len - 1 - q0, dot_lds + buf, lane);
-    if (threadIdx.x < 32) {
-      const int qq = min(q0 + (int)threadIdx.x, t.seq_len - 1);
-      lr = lse[(int64_t)(t.seq_start + qq) * Hq + hq];
-      dd = D[(int64_t)(t.seq_start + qq) * Hq + hq];
-    }
+    tile_dma<4>(uniform_ptr(Q + base), q_row_bytes, 16 * wave, last, qt_lds + (uint32_t)stage * QS * ROWB, lane);
+    tile_dma<4>(uniform_ptr(dO + base), q_row_bytes, 16 * wave, last, dot_lds + (uint32_t)stage * QS * ROWB, lane);
+    // per-query statistics, one word per lane (rows past the sequence repeat its last row); all waves write the
+    // same words
+    const uint32_t off = (uint32_t)min(lane, last) * (uint32_t)Hq * 4u;
+    const int64_t sbase = (int64_t)(t.seq_start + q0) * Hq + hq;
+    dma4s(off, uniform_ptr(lse + sbase), ls_lds + (uint32_t)stage * QS * 4);
+    dma4s(off, uniform_ptr(D + sbase), ds_lds + (uint32_t)stage * QS * 4);
   };
-  if (nsteps > 0) {
-    issue(0);
-    if (threadIdx.x < 32) { ls[0][threadIdx.x] = lr;  ds[0][threadIdx.x] = dd; }
-  }
+  if (nsteps > 0) issue(0);
+  if (nsteps > 1) issue(1);
   for (int st = 0; st < nsteps; ++st) {
-    wait_all_and_sync();
-    if (st + 1 < nsteps) issue(st + 1);
-    const int q0 = q_first + (st % nq) * 32;
-    if (active && q0 + 31 >= k0w) {                                  // wave-uniform: some query at or after a key
-      const uint8_t* qb = qt[st & 1];
-      const uint8_t* dob = dot[st & 1];
-      f32x16 sacc, dp;
+    // everything but the loads of step st + 1 has landed (vmcnt in bits 3:0 and 15:14, the other counters 0)
+    if (st + 1 < nsteps) __builtin_amdgcn_s_waitcnt(kLoads & 15);
+    else                 __builtin_amdgcn_s_waitcnt(0);
+    __builtin_amdgcn_s_barrier();
+    if (st + 2 < nsteps) issue(st + 2);
+    const int q0s = q_first + (st % nq) * QS;
+    const int stage = st % NS;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) { sacc[e] = 0.f;  dp[e] = 0.f; }
+    for (int half = 0; half < 2; ++half) {
+      const int q0 = q0s + 32 * half;
+      if (active && q0 + 31 >= k0w && q0 < t.seq_len) {              // wave-uniform: some query at or after a key
+        const uint8_t* qb = qt[stage];
+        const uint8_t* dob = dot[stage];
+        f32x16 sacc, dp;
 #pragma unroll
-      for (int s = 0; s < 8; ++s) {
-        sacc = mfma32(frag_rows(qb, 0, s, lane), kf[s], sacc);
-        dp = mfma32(frag_rows(dob, 0, s, lane), vf[s], dp);
-      }
-      if (q0 < kmax || q0 + 31 >= t.seq_len) {                       // some query before a key of the wave, or padding
+        for (int e = 0; e < 16; ++e) { sacc[e] = 0.f;  dp[e] = 0.f; }
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int q = q0 + acc_row(i, hl);
-          if (q < kpos || q >= t.seq_len) sacc[i] = kNegInf;
+        for (int s = 0; s < 8; ++s) {
+          sacc = mfma32(frag_rows(qb, 32 * half, s, lane), kf[s], sacc);
+          dp = mfma32(frag_rows(dob, 32 * half, s, lane), vf[s], dp);
         }
-      }
-      f32x16 pm;
+        if (q0 < kmax || q0 + 31 >= t.seq_len) {                     // some query before a key of the wave, or padding
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int ql = acc_row(i, hl);
-        const float p = fast_exp2(fmaf(sacc[i], c, -ls[st & 1][ql]));
-        pm[i] = p;
-        sacc[i] = p * (dp[i] - ds[st & 1][ql]);                      // dS
-      }
+          for (int i = 0; i < 16; ++i) {
+            const int q = q0 + acc_row(i, hl);
+            if (q < kpos || q >= t.seq_len) sacc[i] = kNegInf;
+          }
+        }
+        f32x16 pm;
 #pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2) {
-        const bf16x8 pf = pack8(pm, 8 * s2), dsf = pack8(sacc, 8 * s2);
+        for (int g = 0; g < 4; ++g) {
+          const f32x4 l4 = *reinterpret_cast<const f32x4*>(&ls[stage][32 * half + 8 * g + 4 * hl]);
+          const f32x4 d4 = *reinterpret_cast<const f32x4*>(&ds[stage][32 * half + 8 * g + 4 * hl]);
 #pragma unroll
-        for (int db = 0; db < 4; ++db) {
-          dv[db] = mfma32(frag_cols(dob, db, 16 * s2, lane), pf, dv[db]);
-          dk[db] = mfma32(frag_cols(qb, db, 16 * s2, lane), dsf, dk[db]);
+          for (int e = 0; e < 4; ++e) {
+            const float p = fast_exp2(fmaf(sacc[4 * g + e], c, -l4[e]));
+            pm[4 * g + e] = p;
+            sacc[4 * g + e] = p * (dp[4 * g + e] - d4[e]);             // dS
+          }
+        }
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          const bf16x8 pf = pack8(pm, 8 * s2), dsf = pack8(sacc, 8 * s2);
+#pragma unroll
+          for (int db = 0; db < 4; ++db) {
+            dv[db] = mfma32(frag_cols(dob, db, 32 * half + 16 * s2, lane), pf, dv[db]);
+            dk[db] = mfma32(frag_cols(qb, db, 32 * half + 16 * s2, lane), dsf, dk[db]);
+          }
         }
       }
     }
-    if (st + 1 < nsteps && threadIdx.x < 32) { ls[(st + 1) & 1][threadIdx.x] = lr;  ds[(st + 1) & 1][threadIdx.x] = dd; }
   }
   if (kvalid) {
     uint16_t* krow_o = dK + krow * ks + hk * HD;
@@ -476,8 +496,8 @@ void launch_attn_bwd(const AttnTile* tiles, int n_tiles, const uint16_t* Q, cons
   hipLaunchKernelGGL(attn_rowdot_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, dO, O, D, rows);
   hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3(n_tiles, Hq), dim3(256), 0, st, tiles, Q, K, V, dO, lse, D, dQ, Hq, Hkv, c,
                      scale);
-  hipLaunchKernelGGL(attn_bwd_dkv_kernel, dim3(n_tiles, Hkv), dim3(256), 0, st, tiles, Q, K, V, dO, lse, D, dK, dV, Hq, Hkv,
-                     c, scale);
+  hipLaunchKernelGGL(attn_bwd_dkv_kernel, dim3(n_tiles, Hkv), dim3(256), 0, st, tiles, n_tiles, Q, K, V, dO, lse, D, dK, dV,
+                     Hq, Hkv, c, scale);
 }
 void launch_rope(uint16_t* x, const int32_t* pos, int64_t T, int heads, float base, bool inverse, hipStream_t st) {
   const int64_t rows = T * heads;
