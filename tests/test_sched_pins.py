@@ -1,0 +1,105 @@
+"""Pins of the scheduler oracle (Sec. 3.4, Algorithm 1 Phase 1): a hand-worked example, exhaustive search over the
+partners on small queues, closed-form cases of the step-time model, and invariants of the result."""
+import itertools
+
+import numpy as np
+
+from oracle import sched_oracle as so
+
+# step time: 1 ms up to 1000 tokens (a nearly empty device), then 1 ms per further 1000 tokens
+MODEL = dict(tokens=[1000.0, 2000.0, 9000.0], ms=[1.0, 2.0, 9.0], rho=0.0)
+
+
+def job(tokens, rank=8, urgency=1.0, max_slowdown=1e9, steps=10):
+    return dict(tokens=tokens, rank=rank, urgency=urgency, max_slowdown=max_slowdown, steps=steps)
+
+
+def test_curve_closed_forms():
+    m = dict(tokens=[100.0, 300.0, 700.0], ms=[2.0, 3.0, 7.0], rho=0.0)
+    assert so.curve(m, 10) == 2.0 and so.curve(m, 100) == 2.0            # flat below the first point
+    assert so.curve(m, 200) == 2.5 and so.curve(m, 300) == 3.0 and so.curve(m, 500) == 5.0
+    assert so.curve(m, 900) == 9.0                                         # continues the last segment
+    jobs = [job(100, rank=4), job(200, rank=16)]
+    m["rho"] = 0.001
+    assert abs(so.step_ms(m, jobs, [0, 1]) - (3.0 + 0.001 * (400 + 3200))) < 1e-15
+    assert so.peak(m) == 100.0                                             # 300 / 3 = 700 / 7 = 100 > 100 / 2
+
+
+def test_hand_worked_example():
+    # three jobs of 400 tokens and one of 5000, equal urgency.  Alone: the small ones take 1 ms (400 tokens/ms,
+    # residual 0.6), the large one 5 ms (1000 tokens/ms, residual 0).  Queue order: large (residual 0) first.
+    # seed = large: with a small partner 5400 tokens take 5.4 ms = 1000 tokens/ms, time-sharing gives
+    # 5400 / 6 = 900 -> beneficial; all three partners tie, the first in queue order (job 0) wins.
+    # Next pass: {0,3} (residual 0) is the seed again; + job 1: 5800 / 5.8 = 1000 > 5800 / 6.4 -> merge; then job 2.
+    jobs = [job(400), job(400), job(400), job(5000)]
+    assert so.next_group(MODEL, jobs, [0, 1, 2, 3], [1.0] * 4) == [0, 1, 2, 3]
+    # a slowdown bound of 1.05 on the large job stops after one partner: 5.4 / 5 = 1.08 > 1.05 already -> alone
+    jobs[3]["max_slowdown"] = 1.05
+    assert so.next_group(MODEL, jobs, [0, 1, 2, 3], [1.0] * 4) == [3]
+    # ... and the three small ones then share one nearly empty device step: 1200 tokens in 1.2 ms vs 800 / 2
+    assert so.partition(MODEL, jobs) == [[3], [0, 1, 2]]
+    # urgency outranks residual: the urgent small job seeds, and takes the best partner (the large job: 1000/ms)
+    jobs[3]["max_slowdown"] = 1e9
+    g = so.next_group(MODEL, jobs, [0, 1, 2, 3], [1.0, 3.0, 1.0, 1.0])
+    assert 1 in g and 3 in g
+
+
+def test_linear_model_never_merges_and_flat_model_merges_everything():
+    rng = np.random.default_rng(0)
+    jobs = [job(int(t), rank=int(r)) for t, r in zip(rng.integers(100, 5000, 6), rng.choice([2, 4, 8, 16], 6))]
+    linear = dict(tokens=[1.0, 2.0], ms=[0.5, 1.0], rho=0.0)             # step time proportional to tokens: no gain
+    flat = dict(tokens=[1.0, 1e9], ms=[3.0, 3.0 + 1e-9], rho=0.0)       # an (almost) free ride for every partner
+    assert sorted(map(tuple, so.partition(linear, jobs))) == [(j,) for j in range(6)]
+    assert so.partition(flat, jobs) == [[0, 1, 2, 3, 4, 5]]
+
+
+def test_partner_choice_is_the_exhaustive_argmax():
+    rng = np.random.default_rng(1)
+    model = dict(tokens=[256.0, 1024.0, 4096.0, 16384.0], ms=[0.30, 0.42, 1.1, 3.9], rho=2e-7)
+    for trial in range(40):
+        n = int(rng.integers(2, 6))
+        jobs = [job(int(rng.integers(64, 6000)), rank=int(rng.choice([2, 4, 8, 16])),
+                    max_slowdown=float(rng.choice([1.2, 2.0, 1e9]))) for _ in range(n)]
+        urg = [float(u) for u in rng.choice([1.0, 1.5, 2.0], n)]
+        # first pass by hand: order the singletons, then score every partner of the seed independently
+        order = sorted(range(n), key=lambda j: (-urg[j], so.residual(model, jobs, [j]), j))
+        seed = order[0]
+        scored = []
+        for k in order[1:]:
+            u = sorted([seed, k])
+            t = so.step_ms(model, jobs, u)
+            ok = all(t / so.step_ms(model, jobs, [j]) <= jobs[j]["max_slowdown"] for j in u)
+            gain = so.throughput(model, jobs, u) > (jobs[seed]["tokens"] + jobs[k]["tokens"]) / (
+                so.step_ms(model, jobs, [seed]) + so.step_ms(model, jobs, [k]))
+            if ok and gain:
+                scored.append((so.throughput(model, jobs, u), k))
+        g = so.next_group(model, jobs, list(range(n)), urg)
+        if not scored:
+            assert g == [seed]
+        else:
+            best = max(s[0] for s in scored)
+            first_best = next(k for thr, k in scored if thr == best)
+            assert seed in g and first_best in g
+        # invariants: a finalized group respects every member's slowdown bound, and the partition covers all jobs once
+        assert so.feasible(model, jobs, g)
+        groups = so.partition(model, jobs, urg)
+        assert sorted(itertools.chain.from_iterable(groups)) == list(range(n))
+        assert all(so.feasible(model, jobs, grp) for grp in groups)
+
+
+def test_simulation_accounts_for_every_step():
+    rng = np.random.default_rng(2)
+    model = dict(tokens=[256.0, 1024.0, 4096.0, 16384.0], ms=[0.30, 0.42, 1.1, 3.9], rho=2e-7)
+    jobs = [job(int(rng.integers(64, 6000)), rank=int(rng.choice([2, 4, 8, 16])), steps=int(rng.integers(5, 60)))
+            for _ in range(7)]
+    trace, jct, now = so.simulate(model, jobs, horizon=16)
+    done = [0] * 7
+    t = 0.0
+    for g, steps in trace:
+        assert 1 <= steps <= 16
+        t += steps * so.step_ms(model, jobs, g)
+        for j in g:
+            done[j] += steps
+    assert done == [jb["steps"] for jb in jobs] and abs(t - now) < 1e-9 and max(jct) == now
+    # grouping cannot lose against running the jobs one after another, alone (a merge must beat time sharing)
+    assert now <= sum(jb["steps"] * so.step_ms(model, jobs, [j]) for j, jb in enumerate(jobs)) * (1 + 1e-12)
