@@ -303,6 +303,50 @@ int tlora_fwd_indexed(const tlora_problem_t* p, const int32_t* row_index, void* 
 int tlora_bwd_indexed(const tlora_problem_t* p, const int32_t* row_index, const void* dY, void* dX, void* const* dA,
                       void* const* dB, int flags, void* workspace, size_t ws_bytes, void* hip_stream);
 
+/* ---- Adapter scheduler (HOST only) -------------------------------------------------------------------------
+ * Sec. 3.4 / Algorithm 1, Phase 1, on one device: the queue of jobs (and already merged groups) is sorted by urgency
+ * (descending), then residual resources (ascending); the first entry seeds a group, the partner with the highest
+ * joint throughput is merged in and the union re-inserted, until no partner is beneficial; then the group is final.
+ * The paper leaves Throughput, residual and "beneficial" open; here, over a measured step-time model:
+ *     step_ms(G)    = curve(sum tokens_j) + ms_per_token_rank * sum tokens_j * rank_j
+ *                     curve: piecewise-linear through (tokens[i], ms[i]) (tokens ascending, n_points >= 2), flat
+ *                     below the first point, continued along the last segment above the last
+ *     throughput(G) = sum tokens_j / step_ms(G);  residual(G) = 1 - throughput(G) / max_i(tokens[i] / ms[i])
+ *     urgency(G)    = max over members;  a union is admissible when step_ms(G) / step_ms({j}) <= max_slowdown_j for
+ *                     every member, and beneficial when throughput(A + B) > (tokens_A + tokens_B) / (step_ms(A) +
+ *                     step_ms(B)), i.e. when it beats time-sharing the device.
+ * Ties: smaller first job index first; among equally good partners the first in queue order.  IEEE double, fixed
+ * order of operations: results are reproducible bit for bit.  No device is touched. */
+typedef struct tlora_sched_model_t {
+  int32_t n_points;
+  const double* tokens;        /* HOST [n_points] ascending, > 0 */
+  const double* ms;            /* HOST [n_points] > 0 */
+  double ms_per_token_rank;    /* >= 0 */
+} tlora_sched_model_t;
+typedef struct tlora_sched_job_t {
+  int64_t tokens;              /* tokens per training step, >= 1 */
+  int32_t rank;                /* >= 0 */
+  int32_t steps;               /* training steps to run (tlora_sched_simulate), >= 0 */
+  double urgency;              /* >= 0 (tlora_sched_partition; the simulation derives its own) */
+  double max_slowdown;         /* >= 1: bound on step_ms(group) / step_ms(job alone) */
+} tlora_sched_job_t;
+/* Predicted step time of the group members[0 .. n_members-1] (job indices). */
+int tlora_sched_step_ms(const tlora_sched_model_t* model, int32_t n_jobs, const tlora_sched_job_t* jobs,
+                        const int32_t* members, int32_t n_members, double* ms);
+/* Phase 1 repeated on what is left until every job has a group: group_of[j] = index of job j's group in the
+ * order the groups were finalized; *n_groups = their number. */
+int tlora_sched_partition(const tlora_sched_model_t* model, int32_t n_jobs, const tlora_sched_job_t* jobs,
+                          int32_t* group_of, int32_t* n_groups);
+/* Algorithm 1's outer loop on one device: group, run the group min(horizon, fewest steps left among its members)
+ * steps, update progress, recompute urgencies (elapsed time / (standalone step time * max(steps done, 1)); 1 at
+ * time 0), until every job has run its steps.  jct_ms [n_jobs] = completion times; *makespan_ms = the last one.
+ * Trace (optional, all three or none): round i ran trace_sizes[i] jobs, listed consecutively in trace_members, for
+ * trace_steps[i] steps; trace_sizes / trace_steps hold trace_capacity entries, trace_members trace_capacity *
+ * n_jobs; rounds beyond the capacity are not recorded.  *n_rounds = rounds run. */
+int tlora_sched_simulate(const tlora_sched_model_t* model, int32_t n_jobs, const tlora_sched_job_t* jobs, int32_t horizon,
+                         double* jct_ms, double* makespan_ms, int32_t* trace_members, int32_t* trace_sizes,
+                         int32_t* trace_steps, int64_t* n_rounds, int64_t trace_capacity);
+
 /* Integer bookkeeping of the nano-batch plan (Sec. 3.3, nano-batches = partition of the combined
  * batch along the token dimension), for bit-exact checks.  All outputs are HOST arrays and each may
  * be NULL.  Per job: rpad[J] (rank rounded up to the 8-element granule), soff[J+1] (element

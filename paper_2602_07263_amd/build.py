@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libtlora.so")
-SOURCES = ["tlora_api.hip", "tlora_kernels.hip", "tlora_attn.hip"]
+SOURCES = ["tlora_api.hip", "tlora_kernels.hip", "tlora_attn.hip", "tlora_sched.hip"]
 HEADERS = ["tlora_internal.h", "tlora_kernels.h", os.path.join("..", "..", "include", "tlora.h")]
 
 

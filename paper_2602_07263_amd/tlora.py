@@ -69,6 +69,16 @@ class tlora_layer_t(ctypes.Structure):
     _fields_ = [("attn", tlora_attn_t), ("mlp", tlora_mlp_t)]
 
 
+class tlora_sched_model_t(ctypes.Structure):
+    _fields_ = [("n_points", ctypes.c_int32), ("tokens", ctypes.POINTER(ctypes.c_double)),
+                ("ms", ctypes.POINTER(ctypes.c_double)), ("ms_per_token_rank", ctypes.c_double)]
+
+
+class tlora_sched_job_t(ctypes.Structure):
+    _fields_ = [("tokens", ctypes.c_int64), ("rank", ctypes.c_int32), ("steps", ctypes.c_int32),
+                ("urgency", ctypes.c_double), ("max_slowdown", ctypes.c_double)]
+
+
 class tlora_adamw_tensor_t(ctypes.Structure):
     _fields_ = [("param", ctypes.c_void_p), ("master", ctypes.c_void_p), ("grad", ctypes.c_void_p),
                 ("m", ctypes.c_void_p), ("v", ctypes.c_void_p), ("n", ctypes.c_int64),
@@ -81,6 +91,7 @@ EXPORTS = ["tlora_workspace_bytes", "tlora_fwd", "tlora_bwd", "tlora_adamw_works
            "tlora_attention_workspace_bytes", "tlora_rope", "tlora_attention_fwd", "tlora_attention_bwd",
            "tlora_attn_workspace_bytes", "tlora_attn_fwd", "tlora_attn_bwd",
            "tlora_layer_workspace_bytes", "tlora_layer_fwd", "tlora_layer_bwd",
+           "tlora_sched_step_ms", "tlora_sched_partition", "tlora_sched_simulate",
            "tlora_indexed_workspace_bytes", "tlora_fwd_indexed", "tlora_bwd_indexed",
            "tlora_aimd_init", "tlora_aimd_update",
            "tlora_nano_split", "tlora_nano_workspace_bytes", "tlora_fwd_nano", "tlora_bwd_nano",
@@ -126,6 +137,14 @@ def lib() -> ctypes.CDLL:
     L.tlora_attn_fwd.argtypes = [PA, VP, VP, SZ, VP]
     L.tlora_attn_bwd.restype = ctypes.c_int
     L.tlora_attn_bwd.argtypes = [PA, VP, VP, ctypes.POINTER(VPP), ctypes.POINTER(VPP), ctypes.c_int, VP, SZ, VP]
+    PSM, PSJ = ctypes.POINTER(tlora_sched_model_t), ctypes.POINTER(tlora_sched_job_t)
+    I32P, DP = ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_double)
+    L.tlora_sched_step_ms.restype = ctypes.c_int
+    L.tlora_sched_step_ms.argtypes = [PSM, I32, PSJ, I32P, I32, DP]
+    L.tlora_sched_partition.restype = ctypes.c_int
+    L.tlora_sched_partition.argtypes = [PSM, I32, PSJ, I32P, I32P]
+    L.tlora_sched_simulate.restype = ctypes.c_int
+    L.tlora_sched_simulate.argtypes = [PSM, I32, PSJ, I32, DP, DP, I32P, I32P, I32P, I64P, ctypes.c_int64]
     PL = ctypes.POINTER(tlora_layer_t)
     L.tlora_layer_workspace_bytes.restype = SZ
     L.tlora_layer_workspace_bytes.argtypes = [PL]
@@ -676,3 +695,47 @@ class DecoderLayer:
                                      ctypes.c_void_p(dX.data_ptr()) if self.T else None, dA, dB, int(flags),
                                      ctypes.c_void_p(self.ws.data_ptr()), ctypes.c_size_t(self.ws_bytes),
                                      ctypes.c_void_p(self._stream())), "tlora_layer_bwd")
+
+
+class Scheduler:
+    """Argument marshalling for the host-side adapter scheduler (tlora_sched_*).  model = dict(tokens=[..], ms=[..],
+    rho=ms per token and rank unit); jobs = dicts with tokens, rank and optionally steps, urgency, max_slowdown."""
+
+    def __init__(self, model, jobs):
+        n = len(model["tokens"])
+        self._x = (ctypes.c_double * n)(*[float(v) for v in model["tokens"]])
+        self._y = (ctypes.c_double * n)(*[float(v) for v in model["ms"]])
+        self.model = tlora_sched_model_t(n, self._x, self._y, float(model["rho"]))
+        self.n = len(jobs)
+        self.jobs = (tlora_sched_job_t * max(self.n, 1))(*[
+            tlora_sched_job_t(int(j["tokens"]), int(j["rank"]), int(j.get("steps", 0)), float(j.get("urgency", 1.0)),
+                              float(j.get("max_slowdown", 1e300))) for j in jobs])
+
+    def step_ms(self, members) -> float:
+        m = (ctypes.c_int32 * max(len(members), 1))(*[int(v) for v in members])
+        out = ctypes.c_double(0.0)
+        _check(lib().tlora_sched_step_ms(ctypes.byref(self.model), self.n, self.jobs, m, len(members), ctypes.byref(out)),
+               "tlora_sched_step_ms")
+        return float(out.value)
+
+    def partition(self):
+        """Groups in the order they were finalized, each a sorted list of job indices."""
+        group_of = (ctypes.c_int32 * max(self.n, 1))()
+        ng = ctypes.c_int32(0)
+        _check(lib().tlora_sched_partition(ctypes.byref(self.model), self.n, self.jobs, group_of, ctypes.byref(ng)),
+               "tlora_sched_partition")
+        return [[j for j in range(self.n) if group_of[j] == g] for g in range(ng.value)]
+
+    def simulate(self, horizon: int, trace_capacity: int = 4096):
+        """(trace, jct, makespan): trace = [(group, steps)] of the first trace_capacity rounds."""
+        jct = (ctypes.c_double * max(self.n, 1))()
+        mk, nr = ctypes.c_double(0.0), ctypes.c_int64(0)
+        tm = (ctypes.c_int32 * max(trace_capacity * self.n, 1))()
+        tsz, tst = (ctypes.c_int32 * max(trace_capacity, 1))(), (ctypes.c_int32 * max(trace_capacity, 1))()
+        _check(lib().tlora_sched_simulate(ctypes.byref(self.model), self.n, self.jobs, int(horizon), jct, ctypes.byref(mk),
+                                          tm, tsz, tst, ctypes.byref(nr), trace_capacity), "tlora_sched_simulate")
+        trace, at = [], 0
+        for i in range(min(int(nr.value), trace_capacity)):
+            trace.append(([int(tm[at + k]) for k in range(tsz[i])], int(tst[i])))
+            at += tsz[i]
+        return trace, [float(jct[j]) for j in range(self.n)], float(mk.value)
