@@ -309,6 +309,63 @@ def measure_decoder_layer(steps: int, warmup: int):
             "kernel_ms_per_step": {k: round(t[0] / steps, 4) for k, t in prof.items() if t[1]}}
 
 
+def measure_scheduler(steps: int, warmup: int):
+    """The adapter scheduler over a step-time model measured from this library: the model's points are fwd+bwd times of
+    the gate projection (4096 -> 12288) at seven token counts, its rank term comes from a rank-64 run; twelve jobs
+    in the paper's ranges (rank 2..16, batch 1..8 sequences of 512 tokens) are grouped, and every group's predicted
+    step time is compared with the fused call's measured one, the whole partition with the jobs run alone."""
+    import numpy as np
+    import torch
+    from paper_2602_07263_amd import tlora
+    d_in, d_out = 4096, 12288
+    g = torch.Generator(device="cuda"); g.manual_seed(2)
+    bf = torch.bfloat16
+    Tmax = 32768
+    X = torch.randn(Tmax, d_in, device="cuda", generator=g).to(bf)
+    dY = torch.randn(Tmax, d_out, device="cuda", generator=g).to(bf)
+    W = (torch.randn(d_in, d_out, device="cuda", generator=g) * 0.02).to(bf)
+    A = {r: ((torch.rand(d_in, r, device="cuda", generator=g) * 2 - 1) / d_in ** 0.5).to(bf) for r in (2, 4, 8, 16, 64)}
+    B = {r: (torch.randn(r, d_out, device="cuda", generator=g) * 0.01).to(bf) for r in (2, 4, 8, 16, 64)}
+
+    def timed(ranks, tokens):
+        off = [0] + list(np.cumsum(tokens))
+        T = off[-1]
+        pr = tlora.LayerProblem("bf16", d_in, d_out, ranks, off, [2.0] * len(ranks), X[:T], W, [A[r] for r in ranks],
+                                [B[r] for r in ranks])
+        Y, dX, dA, dB = pr.new_outputs()
+
+        def step(_i):
+            pr.fwd(Y)
+            pr.bwd(dY[:T], dX, dA, dB, reuse_S=True)
+        return time_steps(step, steps, warmup)
+    points = [256, 1024, 2048, 4096, 8192, 16384, 32768]
+    ms = [timed([8], [t]) for t in points]
+    rho = max(0.0, (timed([64], [16384]) - ms[5]) / (16384.0 * 56.0))
+    # the rank term is part of the measured points (rank 8): take it out so that the model adds it back per job
+    model = dict(tokens=[float(t) for t in points], ms=[m - rho * t * 8.0 for m, t in zip(ms, points)], rho=rho)
+    rng = np.random.default_rng(12)
+    jobs = [dict(tokens=int(512 * rng.choice([1, 2, 4, 8])), rank=int(rng.choice([2, 4, 8, 16])), steps=100,
+                 max_slowdown=float(rng.choice([2.0, 4.0, 1e300]))) for _ in range(12)]
+    sched = tlora.Scheduler(model, jobs)
+    groups = sched.partition()
+    rows, fused_ms, alone_ms = [], 0.0, 0.0
+    for grp in groups:
+        pred = sched.step_ms(grp)
+        meas = timed([jobs[j]["rank"] for j in grp], [jobs[j]["tokens"] for j in grp])
+        fused_ms += meas
+        rows.append({"jobs": grp, "tokens": sum(jobs[j]["tokens"] for j in grp), "predicted_ms": round(pred, 4),
+                     "measured_ms": round(meas, 4)})
+    for j, jb in enumerate(jobs):
+        alone_ms += timed([jb["rank"]], [jb["tokens"]])
+    _, jct, makespan = sched.simulate(16)
+    return {"workload": "12 jobs (rank 2..16, 512..4096 tokens) on the 4096->12288 projection, fwd+bwd",
+            "model": {"tokens": points, "ms": [round(m, 4) for m in ms], "ms_per_token_rank": rho},
+            "groups": rows, "partition_ms_per_step": round(fused_ms, 4), "jobs_alone_ms_per_step": round(alone_ms, 4),
+            "speedup_vs_jobs_alone": round(alone_ms / fused_ms, 3),
+            "worst_prediction_error": round(max(abs(r["predicted_ms"] / r["measured_ms"] - 1.0) for r in rows), 3),
+            "simulated_makespan_ms_100_steps_each": round(makespan, 2)}
+
+
 def measure_indexed(steps: int, warmup: int):
     """cfg2's gate projection with the jobs' sequences (runs of 512 tokens) interleaved in the batch: the
     token-indexed calls (gather pass + scattering GEMM epilogue) against the contiguous calls on the same data."""
@@ -419,6 +476,8 @@ def main():
         out["also_indexed"] = measure_indexed(max(5, args.steps // 2), 2)
         torch.cuda.empty_cache()
         out["also_decoder_layer"] = measure_decoder_layer(max(3, args.steps // 4), 1)
+        torch.cuda.empty_cache()
+        out["also_scheduler"] = measure_scheduler(max(5, args.steps // 2), 2)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config)
     print(json.dumps(out))

@@ -992,9 +992,10 @@ struct AttnPlan {
   int64_t T = 0;
   std::vector<AttnTile> tiles;
   std::vector<int32_t> pos;
-  size_t off_tiles = 0, off_pos = 0, off_D = 0, blob_bytes = 0, total = 0;
+  int64_t max_len = 0;
+  size_t off_tiles = 0, off_pos = 0, off_D = 0, off_rope = 0, blob_bytes = 0, total = 0;
 };
-// tables: [tiles | positions] (uploaded), then D fp32 [T, n_heads]
+// tables: [tiles | positions] (uploaded), then D fp32 [T, n_heads] and the rotary (cos, sin) table [longest sequence, 64]
 int attn_plan(int32_t num_seqs, const int64_t* seq_offsets, int32_t n_heads, bool want_tables, AttnPlan& A) {
   if (num_seqs < 0 || n_heads < 1) return TLORA_EINVAL;
   if (!seq_offsets) return TLORA_ENULL;
@@ -1004,6 +1005,7 @@ int attn_plan(int32_t num_seqs, const int64_t* seq_offsets, int32_t n_heads, boo
     const int64_t len = seq_offsets[s + 1] - seq_offsets[s];
     if (len < 0 || seq_offsets[s + 1] > (int64_t)INT32_MAX) return TLORA_EINVAL;
     n_tiles += (size_t)((len + 127) / 128);
+    A.max_len = std::max(A.max_len, len);
   }
   A.T = seq_offsets[num_seqs];
   if ((int64_t)A.T * n_heads > (int64_t)INT32_MAX) return TLORA_EINVAL;
@@ -1024,6 +1026,7 @@ int attn_plan(int32_t num_seqs, const int64_t* seq_offsets, int32_t n_heads, boo
   A.off_pos = place((size_t)A.T * sizeof(int32_t));
   A.blob_bytes = w;
   A.off_D = place((size_t)A.T * n_heads * sizeof(float));
+  A.off_rope = place((size_t)A.max_len * 64 * 2 * sizeof(float));
   A.total = std::max<size_t>(w, 256);
   return TLORA_OK;
 }
@@ -1067,8 +1070,9 @@ int tlora_rope(void* X, int32_t num_seqs, const int64_t* seq_offsets, int32_t he
   if (rc != TLORA_OK) return rc;
   {
     Timed t(TLORA_K_ROPE, st);
-    launch_rope(static_cast<uint16_t*>(X), reinterpret_cast<const int32_t*>(ws + A.off_pos), A.T, heads, rope_base,
-                inverse != 0, st);
+    launch_rope_table(reinterpret_cast<float*>(ws + A.off_rope), (int)A.max_len, rope_base, st);
+    launch_rope(static_cast<uint16_t*>(X), reinterpret_cast<const int32_t*>(ws + A.off_pos),
+                reinterpret_cast<const float*>(ws + A.off_rope), A.T, heads, inverse != 0, st);
   }
   return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
 }
@@ -1223,8 +1227,10 @@ int tlora_attn_fwd(const tlora_attn_t* p, void* Out, void* workspace, size_t ws_
   const int32_t* pos = reinterpret_cast<const int32_t*>(aw + L.A.off_pos);
   {
     Timed t(TLORA_K_ROPE, st);
-    launch_rope(reinterpret_cast<uint16_t*>(ws + L.off_q), pos, L.T, p->n_heads, p->rope_base, false, st);
-    launch_rope(reinterpret_cast<uint16_t*>(ws + L.off_k), pos, L.T, p->n_kv_heads, p->rope_base, false, st);
+    float* tab = reinterpret_cast<float*>(aw + L.A.off_rope);
+    launch_rope_table(tab, (int)L.A.max_len, p->rope_base, st);
+    launch_rope(reinterpret_cast<uint16_t*>(ws + L.off_q), pos, tab, L.T, p->n_heads, false, st);
+    launch_rope(reinterpret_cast<uint16_t*>(ws + L.off_k), pos, tab, L.T, p->n_kv_heads, false, st);
   }
   {
     Timed t(TLORA_K_ATTN_FWD, st);
@@ -1280,8 +1286,9 @@ int tlora_attn_bwd(const tlora_attn_t* p, const void* dOut, void* dX, void* cons
     }
     {
       Timed t(TLORA_K_ROPE, st);
-      launch_rope(reinterpret_cast<uint16_t*>(ws + L.off_dq), pos, L.T, p->n_heads, p->rope_base, true, st);
-      launch_rope(reinterpret_cast<uint16_t*>(ws + L.off_dk), pos, L.T, p->n_kv_heads, p->rope_base, true, st);
+      const float* tab = reinterpret_cast<const float*>(aw + L.A.off_rope);     // written by tlora_attn_fwd
+      launch_rope(reinterpret_cast<uint16_t*>(ws + L.off_dq), pos, tab, L.T, p->n_heads, true, st);
+      launch_rope(reinterpret_cast<uint16_t*>(ws + L.off_dk), pos, tab, L.T, p->n_kv_heads, true, st);
     }
   }
   rc = tlora_bwd(&L.q, ws + L.off_dq, ws + L.off_dxa, dA[0], dB[0], lf, ws + L.off_ws[0], L.ws_l[0], hip_stream);

@@ -230,19 +230,23 @@ attn_fwd_kernel(const AttnTile* __restrict__ tiles, const uint16_t* __restrict__
   }
 }
 
-// D[t, h] = sum_d dO[t, h, d] * O[t, h, d]   (one wave per (token, head))
+// D[t, h] = sum_d dO[t, h, d] * O[t, h, d]   (16 lanes x 16 bytes per (token, head) row, 16 rows per workgroup)
 __global__ void __launch_bounds__(256) attn_rowdot_kernel(const uint16_t* __restrict__ dO, const uint16_t* __restrict__ O,
                                                           float* __restrict__ D, int64_t n_rows) {
-  const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (r >= n_rows) return;
-  const int lane = threadIdx.x & 63;
-  const uint32_t a = *reinterpret_cast<const uint32_t*>(dO + r * HD + lane * 2);
-  const uint32_t b = *reinterpret_cast<const uint32_t*>(O + r * HD + lane * 2);
-  float s = __builtin_bit_cast(float, a << 16) * __builtin_bit_cast(float, b << 16) +
-            __builtin_bit_cast(float, a & 0xffff0000u) * __builtin_bit_cast(float, b & 0xffff0000u);
+  const int64_t r = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+  const int sub = threadIdx.x & 15;
+  float s = 0.f;
+  if (r < n_rows) {
+    const u32x4 a = *reinterpret_cast<const u32x4*>(dO + r * HD + sub * 8);
+    const u32x4 b = *reinterpret_cast<const u32x4*>(O + r * HD + sub * 8);
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-  if (lane == 0) D[r] = s;
+    for (int e = 0; e < 4; ++e)
+      s += __builtin_bit_cast(float, a[e] << 16) * __builtin_bit_cast(float, b[e] << 16) +
+           __builtin_bit_cast(float, a[e] & 0xffff0000u) * __builtin_bit_cast(float, b[e] & 0xffff0000u);
+  }
+#pragma unroll
+  for (int o = 8; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+  if (sub == 0 && r < n_rows) D[r] = s;
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -461,24 +465,49 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const AttnTile* __res
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Rotary position embedding, in place, on [T, heads * 128] bf16: one wave per (token, head); lane i rotates the
-// pair (i, i + 64) by pos * base^(-i / 64).  inverse = the transposed rotation (the backward of the forward one).
+// Rotary position embedding, in place, on [T, heads * 128] bf16.  A table kernel first writes (cos, sin) of
+// position * base^(-i / 64) for every position up to the longest sequence and i < 64 (fp32); the rotation kernel
+// then only streams: 8 lanes per (token, head) row, each rotating the pairs (i, i + 64) for 8 consecutive i.
+// inverse = the transposed rotation (the backward of the forward one).
 // ---------------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) rope_kernel(uint16_t* __restrict__ x, const int32_t* __restrict__ pos, int heads,
-                                                   int64_t n_rows /* tokens * heads */, float log2_base, int inverse) {
-  const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (r >= n_rows) return;
-  const int lane = threadIdx.x & 63;
-  const int p = pos[r / heads];
-  const float ang = (float)p * exp2f(-log2_base * (float)lane / 64.f);
+__global__ void __launch_bounds__(256) rope_table_kernel(float2* __restrict__ tab, int n /* positions * 64 */,
+                                                         float log2_base) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx >= n) return;
+  const float ang = (float)(idx >> 6) * exp2f(-log2_base * (float)(idx & 63) / 64.f);
   float sn, cs;
   sincosf(ang, &sn, &cs);
-  if (inverse) sn = -sn;
-  uint16_t* row = x + r * HD;
-  const float a = __builtin_bit_cast(float, (uint32_t)row[lane] << 16);
-  const float b = __builtin_bit_cast(float, (uint32_t)row[lane + 64] << 16);
-  row[lane] = (uint16_t)(pack2(a * cs - b * sn, 0.f) & 0xffffu);
-  row[lane + 64] = (uint16_t)(pack2(b * cs + a * sn, 0.f) & 0xffffu);
+  tab[idx] = float2{cs, sn};
+}
+__global__ void __launch_bounds__(256) rope_kernel(uint16_t* __restrict__ x, const int32_t* __restrict__ pos,
+                                                   const float2* __restrict__ tab, int heads,
+                                                   int64_t n_rows /* tokens * heads */, int inverse) {
+  const int64_t r = (int64_t)blockIdx.x * 32 + (threadIdx.x >> 3);
+  if (r >= n_rows) return;
+  const int i0 = (threadIdx.x & 7) * 8;
+  const float2* tr = tab + (int64_t)pos[r / heads] * 64 + i0;
+  uint16_t* row = x + r * HD + i0;
+  const u32x4 lo = *reinterpret_cast<const u32x4*>(row), hi = *reinterpret_cast<const u32x4*>(row + 64);
+  f32x4 cs[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) cs[e] = *reinterpret_cast<const f32x4*>(tr + 2 * e);     // (cos, sin) of two pairs
+  u32x4 olo, ohi;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    float a[2] = {__builtin_bit_cast(float, lo[e] << 16), __builtin_bit_cast(float, lo[e] & 0xffff0000u)};
+    float b[2] = {__builtin_bit_cast(float, hi[e] << 16), __builtin_bit_cast(float, hi[e] & 0xffff0000u)};
+    float ra[2], rb[2];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      const float c = cs[e][2 * k], sn = inverse ? -cs[e][2 * k + 1] : cs[e][2 * k + 1];
+      ra[k] = a[k] * c - b[k] * sn;
+      rb[k] = b[k] * c + a[k] * sn;
+    }
+    olo[e] = pack2(ra[0], ra[1]);
+    ohi[e] = pack2(rb[0], rb[1]);
+  }
+  *reinterpret_cast<u32x4*>(row) = olo;
+  *reinterpret_cast<u32x4*>(row + 64) = ohi;
 }
 
 void launch_attn_fwd(const AttnTile* tiles, int n_tiles, const uint16_t* Q, const uint16_t* K, const uint16_t* V,
@@ -493,17 +522,23 @@ void launch_attn_bwd(const AttnTile* tiles, int n_tiles, const uint16_t* Q, cons
   if (n_tiles == 0) return;
   const float scale = 1.f / sqrtf((float)HD), c = 1.4426950408889634f * scale;
   const int64_t rows = T * Hq;
-  hipLaunchKernelGGL(attn_rowdot_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, dO, O, D, rows);
+  hipLaunchKernelGGL(attn_rowdot_kernel, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, dO, O, D, rows);
   hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3(n_tiles, Hq), dim3(256), 0, st, tiles, Q, K, V, dO, lse, D, dQ, Hq, Hkv, c,
                      scale);
   hipLaunchKernelGGL(attn_bwd_dkv_kernel, dim3(n_tiles, Hkv), dim3(256), 0, st, tiles, n_tiles, Q, K, V, dO, lse, D, dK, dV,
                      Hq, Hkv, c, scale);
 }
-void launch_rope(uint16_t* x, const int32_t* pos, int64_t T, int heads, float base, bool inverse, hipStream_t st) {
+void launch_rope_table(float* table, int positions, float base, hipStream_t st) {
+  const int n = positions * 64;
+  if (n == 0) return;
+  hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, reinterpret_cast<float2*>(table), n,
+                     log2f(base));
+}
+void launch_rope(uint16_t* x, const int32_t* pos, const float* table, int64_t T, int heads, bool inverse, hipStream_t st) {
   const int64_t rows = T * heads;
   if (rows == 0) return;
-  hipLaunchKernelGGL(rope_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, x, pos, heads, rows, log2f(base),
-                     inverse ? 1 : 0);
+  hipLaunchKernelGGL(rope_kernel, dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, st, x, pos,
+                     reinterpret_cast<const float2*>(table), heads, rows, inverse ? 1 : 0);
 }
 
 }  // namespace tlora

@@ -84,7 +84,10 @@ void launch_attn_fwd(const AttnTile* tiles, int n_tiles, const uint16_t* Q, cons
 void launch_attn_bwd(const AttnTile* tiles, int n_tiles, const uint16_t* Q, const uint16_t* K, const uint16_t* V,
                      const uint16_t* O, const uint16_t* dO, const float* lse, float* D, uint16_t* dQ, uint16_t* dK,
                      uint16_t* dV, int64_t T, int Hq, int Hkv, hipStream_t st);
-// In-place rotary embedding of x [T, heads * 128] at positions pos [T]; inverse = the transposed rotation.
-void launch_rope(uint16_t* x, const int32_t* pos, int64_t T, int heads, float base, bool inverse, hipStream_t st);
+// table [positions, 64, 2] fp32 = (cos, sin) of position * base^(-i / 64)
+void launch_rope_table(float* table, int positions, float base, hipStream_t st);
+// In-place rotary embedding of x [T, heads * 128] at positions pos [T] (all < the table's positions);
+// inverse = the transposed rotation.
+void launch_rope(uint16_t* x, const int32_t* pos, const float* table, int64_t T, int heads, bool inverse, hipStream_t st);
 
 }  // namespace tlora
