@@ -311,7 +311,8 @@ def measure_decoder_layer(steps: int, warmup: int):
 
 def measure_scheduler(steps: int, warmup: int):
     """The adapter scheduler over a step-time model measured from this library: the model's points are fwd+bwd times of
-    the gate projection (4096 -> 12288) at seven token counts, its rank term comes from a rank-64 run; twelve jobs
+    the gate projection (4096 -> 12288) at seven token counts, its rank term comes from a rank-64 run, its per-job term from an
+    eight-job run; twelve jobs
     in the paper's ranges (rank 2..16, batch 1..8 sequences of 512 tokens) are grouped, and every group's predicted
     step time is compared with the fused call's measured one, the whole partition with the jobs run alone."""
     import numpy as np
@@ -342,7 +343,9 @@ def measure_scheduler(steps: int, warmup: int):
     ms = [timed([8], [t]) for t in points]
     rho = max(0.0, (timed([64], [16384]) - ms[5]) / (16384.0 * 56.0))
     # the rank term is part of the measured points (rank 8): take it out so that the model adds it back per job
-    model = dict(tokens=[float(t) for t in points], ms=[m - rho * t * 8.0 for m, t in zip(ms, points)], rho=rho)
+    kappa = max(0.0, (timed([8] * 8, [512] * 8) - ms[3]) / 7.0)            # eight jobs against one, same 4096 tokens
+    model = dict(tokens=[float(t) for t in points], ms=[m - rho * t * 8.0 for m, t in zip(ms, points)], rho=rho,
+                 kappa=kappa)
     rng = np.random.default_rng(12)
     jobs = [dict(tokens=int(512 * rng.choice([1, 2, 4, 8])), rank=int(rng.choice([2, 4, 8, 16])), steps=100,
                  max_slowdown=float(rng.choice([2.0, 4.0, 1e300]))) for _ in range(12)]
@@ -359,7 +362,7 @@ def measure_scheduler(steps: int, warmup: int):
         alone_ms += timed([jb["rank"]], [jb["tokens"]])
     _, jct, makespan = sched.simulate(16)
     return {"workload": "12 jobs (rank 2..16, 512..4096 tokens) on the 4096->12288 projection, fwd+bwd",
-            "model": {"tokens": points, "ms": [round(m, 4) for m in ms], "ms_per_token_rank": rho},
+            "model": {"tokens": points, "ms": [round(m, 4) for m in ms], "ms_per_token_rank": rho, "ms_per_job": round(kappa, 5)},
             "groups": rows, "partition_ms_per_step": round(fused_ms, 4), "jobs_alone_ms_per_step": round(alone_ms, 4),
             "speedup_vs_jobs_alone": round(alone_ms / fused_ms, 3),
             "worst_prediction_error": round(max(abs(r["predicted_ms"] / r["measured_ms"] - 1.0) for r in rows), 3),

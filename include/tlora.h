@@ -308,7 +308,7 @@ int tlora_bwd_indexed(const tlora_problem_t* p, const int32_t* row_index, const 
  * (descending), then residual resources (ascending); the first entry seeds a group, the partner with the highest
  * joint throughput is merged in and the union re-inserted, until no partner is beneficial; then the group is final.
  * The paper leaves Throughput, residual and "beneficial" open; here, over a measured step-time model:
- *     step_ms(G)    = curve(sum tokens_j) + ms_per_token_rank * sum tokens_j * rank_j
+ *     step_ms(G)    = curve(sum tokens_j) + ms_per_token_rank * sum tokens_j * rank_j + ms_per_job * (|G| - 1)
  *                     curve: piecewise-linear through (tokens[i], ms[i]) (tokens ascending, n_points >= 2), flat
  *                     below the first point, continued along the last segment above the last
  *     throughput(G) = sum tokens_j / step_ms(G);  residual(G) = 1 - throughput(G) / max_i(tokens[i] / ms[i])
@@ -322,6 +322,7 @@ typedef struct tlora_sched_model_t {
   const double* tokens;        /* HOST [n_points] ascending, > 0 */
   const double* ms;            /* HOST [n_points] > 0 */
   double ms_per_token_rank;    /* >= 0 */
+  double ms_per_job;           /* >= 0: cost of one more job in a fused call */
 } tlora_sched_model_t;
 typedef struct tlora_sched_job_t {
   int64_t tokens;              /* tokens per training step, >= 1 */

@@ -6,9 +6,10 @@ Algorithm 1 keeps a queue of jobs (and already merged groups), sorted by urgency
 joint throughput, merges and re-inserts if there is a beneficial one, and finalizes the seed otherwise.  The paper
 leaves Throughput(.), the residual, the urgency and "beneficial" to the implementation; this build fixes them so:
 
-    step_ms(G)    = curve(sum_j tokens_j) + rho * sum_j tokens_j * rank_j
+    step_ms(G)    = curve(sum_j tokens_j) + rho * sum_j tokens_j * rank_j + kappa * (|G| - 1)
                     curve = piecewise-linear interpolation of measured (tokens, ms) points, flat below the first
-                    point, continued along the last segment above the last point
+                    point, continued along the last segment above the last point; kappa = measured cost of one
+                    more job in a fused call (packing its adapters, its ragged tile edges)
     throughput(G) = sum_j tokens_j / step_ms(G)                                   (tokens per ms)
     residual(G)   = 1 - throughput(G) / peak,   peak = max_i tokens_i / ms_i       (idle share of the device)
     urgency(G)    = max of the members' urgencies
@@ -47,7 +48,7 @@ def step_ms(model, jobs, members):
     for j in members:
         total += jobs[j]["tokens"]
         work += float(jobs[j]["tokens"]) * float(jobs[j]["rank"])
-    return curve(model, total) + model["rho"] * work
+    return curve(model, total) + model["rho"] * work + model.get("kappa", 0.0) * float(len(members) - 1)
 
 
 def tokens_of(jobs, members):

@@ -47,7 +47,7 @@ struct Ctx {
       total += jobs[j].tokens;
       work += (double)jobs[j].tokens * (double)jobs[j].rank;
     }
-    return model.curve(total) + model.m->ms_per_token_rank * work;
+    return model.curve(total) + model.m->ms_per_token_rank * work + model.m->ms_per_job * (double)((int64_t)g.size() - 1);
   }
   double step_ms1(int32_t j) const { return step_ms(Group{j}); }
   double throughput(const Group& g) const { return (double)tokens(g) / step_ms(g); }
@@ -115,7 +115,8 @@ Group next_group(const Ctx& c, const std::vector<int32_t>& active, const std::ve
 
 int check(const tlora_sched_model_t* m, int32_t n_jobs, const tlora_sched_job_t* jobs) {
   if (!m || !m->tokens || !m->ms || (n_jobs > 0 && !jobs)) return TLORA_ENULL;
-  if (m->n_points < 2 || n_jobs < 0 || !(m->ms_per_token_rank >= 0.0)) return TLORA_EINVAL;
+  if (m->n_points < 2 || n_jobs < 0 || !(m->ms_per_token_rank >= 0.0) || !(m->ms_per_job >= 0.0))
+    return TLORA_EINVAL;
   for (int i = 0; i < m->n_points; ++i) {
     if (!(m->tokens[i] > 0.0) || !(m->ms[i] > 0.0)) return TLORA_EINVAL;
     if (i && !(m->tokens[i] > m->tokens[i - 1])) return TLORA_EINVAL;

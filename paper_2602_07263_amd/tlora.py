@@ -71,7 +71,8 @@ class tlora_layer_t(ctypes.Structure):
 
 class tlora_sched_model_t(ctypes.Structure):
     _fields_ = [("n_points", ctypes.c_int32), ("tokens", ctypes.POINTER(ctypes.c_double)),
-                ("ms", ctypes.POINTER(ctypes.c_double)), ("ms_per_token_rank", ctypes.c_double)]
+                ("ms", ctypes.POINTER(ctypes.c_double)), ("ms_per_token_rank", ctypes.c_double),
+                ("ms_per_job", ctypes.c_double)]
 
 
 class tlora_sched_job_t(ctypes.Structure):
@@ -699,13 +700,13 @@ class DecoderLayer:
 
 class Scheduler:
     """Argument marshalling for the host-side adapter scheduler (tlora_sched_*).  model = dict(tokens=[..], ms=[..],
-    rho=ms per token and rank unit); jobs = dicts with tokens, rank and optionally steps, urgency, max_slowdown."""
+    rho=ms per token and rank unit, kappa=ms per additional job); jobs = dicts with tokens, rank and optionally steps, urgency, max_slowdown."""
 
     def __init__(self, model, jobs):
         n = len(model["tokens"])
         self._x = (ctypes.c_double * n)(*[float(v) for v in model["tokens"]])
         self._y = (ctypes.c_double * n)(*[float(v) for v in model["ms"]])
-        self.model = tlora_sched_model_t(n, self._x, self._y, float(model["rho"]))
+        self.model = tlora_sched_model_t(n, self._x, self._y, float(model["rho"]), float(model.get("kappa", 0.0)))
         self.n = len(jobs)
         self.jobs = (tlora_sched_job_t * max(self.n, 1))(*[
             tlora_sched_job_t(int(j["tokens"]), int(j["rank"]), int(j.get("steps", 0)), float(j.get("urgency", 1.0)),

@@ -8,7 +8,7 @@ import pytest
 from oracle import sched_oracle as so
 from paper_2602_07263_amd import tlora
 
-MODEL = dict(tokens=[256.0, 1024.0, 4096.0, 16384.0, 32768.0], ms=[0.31, 0.42, 1.13, 3.94, 7.7], rho=2.5e-7)
+MODEL = dict(tokens=[256.0, 1024.0, 4096.0, 16384.0, 32768.0], ms=[0.31, 0.42, 1.13, 3.94, 7.7], rho=2.5e-7, kappa=0.013)
 
 
 def _jobs(rng, n):

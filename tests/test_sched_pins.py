@@ -22,6 +22,9 @@ def test_curve_closed_forms():
     jobs = [job(100, rank=4), job(200, rank=16)]
     m["rho"] = 0.001
     assert abs(so.step_ms(m, jobs, [0, 1]) - (3.0 + 0.001 * (400 + 3200))) < 1e-15
+    m["kappa"] = 0.25
+    assert abs(so.step_ms(m, jobs, [0, 1]) - (3.0 + 0.001 * (400 + 3200) + 0.25)) < 1e-15
+    assert abs(so.step_ms(m, jobs, [1]) - (2.5 + 0.001 * 3200)) < 1e-15          # a single job pays no per-job extra
     assert so.peak(m) == 100.0                                             # 300 / 3 = 700 / 7 = 100 > 100 / 2
 
 
