@@ -108,3 +108,44 @@ def test_attention_rejects_bad_arguments():
     # head size other than 128, and query heads not a multiple of key/value heads
     assert L.tlora_attention_fwd(None, None, None, None, None, 1, seq, 4, 2, 64, None, 0, None) != 0
     assert L.tlora_attention_fwd(None, None, None, None, None, 1, seq, 3, 2, 128, None, 0, None) != 0
+
+
+def test_attention_at_bench_shape_sampled_sequences():
+    """The decoder-layer leg's attention shape (32 query / 8 key-value heads, 41 sequences of 2048 tokens): three
+    sampled (sequence, key/value head) groups, each compared in full (all 2048 positions, the group's four query
+    heads) with the oracle, which is run on that group's slices alone."""
+    import torch
+    from paper_2602_07263_amd import tlora
+    Hq, Hkv, n, S = 32, 8, 2048, 41
+    G = Hq // Hkv
+    T = n * S
+    seq = _offsets([n] * S)
+    g = torch.Generator(device="cuda"); g.manual_seed(21)
+    rn = lambda h: torch.randn(T, h * HD, device="cuda", generator=g).to(torch.bfloat16)
+    Q, K, V, dO = rn(Hq), rn(Hkv), rn(Hkv), rn(Hq)
+    O, dQ, dK, dV = torch.empty_like(Q), torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    lse = torch.empty(T, Hq, dtype=torch.float32, device="cuda")
+    att = tlora.Attention(seq, Hq, Hkv, "cuda")
+    att.fwd(Q, K, V, O, lse)
+    att.bwd(Q, K, V, O, dO, lse, dQ, dK, dV)
+    torch.cuda.synchronize()
+    for t in (O, dQ, dK, dV):                      # nothing left unwritten anywhere
+        assert bool(torch.isfinite(t.float()).all())
+    worst = {}
+    for s, hk in [(0, 0), (17, 3), (40, 7)]:
+        rows = slice(s * n, (s + 1) * n)
+        qc, kc = slice(hk * G * HD, (hk + 1) * G * HD), slice(hk * HD, (hk + 1) * HD)
+        f = lambda t, c: t[rows, c].double().cpu().numpy()
+        q, k, v, do = f(Q, qc), f(K, kc), f(V, kc), f(dO, qc)
+        O_r, _ = ao.attention(q, k, v, [0, n], G, 1, HD)
+        lse_r = ao.attention_lse2(q, k, [0, n], G, 1, HD)
+        dQ_r, dK_r, dV_r = ao.attention_backward(q, k, v, do, [0, n], G, 1, HD)
+        res = {"O": pu.worst_ratio(f(O, qc), O_r, pu.BF16_TOL),
+               "lse": pu.worst_ratio(lse[rows, hk * G:(hk + 1) * G].double().cpu().numpy(), lse_r, 1e-4),
+               "dQ": pu.worst_ratio(f(dQ, qc), dQ_r, pu.BF16_TOL),
+               "dK": pu.worst_ratio(f(dK, kc), dK_r, pu.BF16_TOL),
+               "dV": pu.worst_ratio(f(dV, kc), dV_r, pu.BF16_TOL)}
+        for name, r in res.items():
+            worst[name] = max(worst.get(name, 0.0), r)
+    print({k_: round(v_, 3) for k_, v_ in worst.items()})
+    assert all(v_ <= 1.0 for v_ in worst.values()), worst
