@@ -46,21 +46,50 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& a, int first) {
 // sw(r) = ((r & 3) << 2) | ((r >> 2) & 3).  16 consecutive rows read at one logical chunk hit 16 distinct bank
 // groups, and the 4 rows x 64 bytes of a transposing read hit 4 distinct 64-byte groups.
 __device__ __forceinline__ int tile_off(int r, int c) { return r * ROWB + ((c ^ (((r & 3) << 2) | ((r >> 2) & 3))) << 4); }
-// operand fragment "rows of the tile": rows rb .. rb+31, k-slice s (head-dim values 16 s .. 16 s + 15)
-__device__ __forceinline__ bf16x8 frag_rows(const uint8_t* tile, int rb, int s, int lane) {
-  return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(tile + tile_off(rb + (lane & 31), 2 * s + (lane >> 5))));
+// Per-lane byte offsets of the operand fragments inside a tile, computed once per kernel: everything that changes
+// afterwards (tile buffer, 32-row block, 16-row slice) is a compile-time multiple of the row pitch on top, which the
+// LDS instructions carry in their immediate offset -- the loops spend no vector instructions on addresses.
+struct FragPat {
+  int row[8];       // "rows of the tile" fragment, k-slice s: row lane % 32, chunk 2 s + lane / 32
+  int col_lo[4];    // "columns of the tile" fragment, column block db: rows 4 h + j / 4 (h = lane / 32, j = lane % 16)
+  int col_hi[4];    //                                                  ... and those rows + 8
+};
+__device__ __forceinline__ FragPat make_frag_pat(int lane) {
+  FragPat P;
+  const int lr = lane & 31, hl = lane >> 5, j = lane & 15;
+#pragma unroll
+  for (int s = 0; s < 8; ++s) P.row[s] = tile_off(lr, 2 * s + hl);
+  const int half16 = (lane >> 4) & 1;
+#pragma unroll
+  for (int db = 0; db < 4; ++db) {
+    const int col = db * 32 + half16 * 16 + (j & 3) * 4;
+    const int r0 = 4 * hl + (j >> 2);
+    P.col_lo[db] = tile_off(r0, col >> 3) + (col & 7) * 2;
+    P.col_hi[db] = tile_off(r0 + 8, col >> 3) + (col & 7) * 2;
+  }
+  // opaque to the optimiser from here on: kept in registers instead of being recomputed inside the loops
+#pragma unroll
+  for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(P.row[s]));
+#pragma unroll
+  for (int db = 0; db < 4; ++db) { asm volatile("" : "+v"(P.col_lo[db]));  asm volatile("" : "+v"(P.col_hi[db])); }
+  return P;
 }
-// operand fragment "columns of the tile": columns 32 cb .. 32 cb + 31 as operand rows, k = tile rows
-// r16 + {4h .. 4h+3, 8 + 4h .. 8 + 4h + 3} (h = lane / 32), through the transposing LDS read
-__device__ __forceinline__ bf16x8 frag_cols(const uint8_t* tile, int cb, int r16, int lane) {
-  const int j = lane & 15, h = lane >> 5;
-  const int col = cb * 32 + ((lane >> 4) & 1) * 16 + (j & 3) * 4;
-  const int c = col >> 3, inner = (col & 7) * 2;
-  const int r0 = r16 + 4 * h + (j >> 2);
-  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, tile + tile_off(r0, c) + inner));
-  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, tile + tile_off(r0 + 8, c) + inner));
+// operand fragment "rows of the tile": rows rb .. rb + 31 (rb a multiple of 32), k-slice s (head-dim values 16 s ..).
+// The swizzle of row rb + r equals that of row r for rb a multiple of 16, so rb only adds rb row pitches.
+__device__ __forceinline__ bf16x8 frag_rows(const uint8_t* tile, int rb, int s, const FragPat& P) {
+  return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(tile + rb * ROWB + P.row[s]));
+}
+// operand fragment "columns of the tile": columns 32 db .. 32 db + 31 as operand rows, k = tile rows
+// r16 + {4h .. 4h+3, 8 + 4h .. 8 + 4h + 3} (h = lane / 32, r16 a multiple of 16), through the transposing LDS read
+__device__ __forceinline__ bf16x8 frag_cols(const uint8_t* tile, int db, int r16, const FragPat& P) {
+  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, tile + r16 * ROWB + P.col_lo[db]));
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, tile + r16 * ROWB + P.col_hi[db]));
   return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
+template <int N>
+struct IntC {
+  static constexpr int value = N;
+};
 // Asynchronous 16-byte-per-lane global->LDS load issued as raw instructions: lane l's 16 bytes land at LDS byte
 // address lds_base + 16 l (lds_base wave-uniform, carried in M0); the global address is a wave-uniform 64-bit base
 // plus an unsigned 32-bit byte offset per lane.  The compiler does not track these loads: the kernels wait
@@ -157,21 +186,23 @@ attn_fwd_kernel(const AttnTile* __restrict__ tiles, const uint16_t* __restrict__
     tile_dma<4>(uniform_ptr(Kh + (int64_t)kvbase * ks), kv_row_bytes, 16 * wave, nkv - 1 - kvbase, kt_lds + buf, lane);
     tile_dma<4>(uniform_ptr(Vh + (int64_t)kvbase * ks), kv_row_bytes, 16 * wave, nkv - 1 - kvbase, vt_lds + buf, lane);
   };
+  const FragPat P = make_frag_pat(lane);
   issue(0);
-  for (int it = 0; it < ntiles; ++it) {
+  auto tile_step = [&](auto bufc, int it) {
+    constexpr int buf = decltype(bufc)::value;
     wait_all_and_sync();                                              // tile `it` is in LDS; the other buffer is free
     if (it + 1 < ntiles) issue(it + 1);
     const int kvbase = it * 64;
     if (active && kvbase <= qmax) {                                   // wave-uniform: something at or below the diagonal
-      const uint8_t* kb = kt[it & 1];
-      const uint8_t* vb = vt[it & 1];
+      const uint8_t* kb = kt[buf];
+      const uint8_t* vb = vt[buf];
       f32x16 sacc[2];
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) sacc[j][e] = 0.f;
 #pragma unroll
-        for (int s = 0; s < 8; ++s) sacc[j] = mfma32(frag_rows(kb, 32 * j, s, lane), qf[s], sacc[j]);
+        for (int s = 0; s < 8; ++s) sacc[j] = mfma32(frag_rows(kb, 32 * j, s, P), qf[s], sacc[j]);
       }
       if (kvbase + 63 > qmin) {                                       // the tile reaches past some query of the wave
 #pragma unroll
@@ -211,9 +242,13 @@ attn_fwd_kernel(const AttnTile* __restrict__ tiles, const uint16_t* __restrict__
         for (int s2 = 0; s2 < 2; ++s2) {
           const bf16x8 pf = pack8(sacc[j], 8 * s2);
 #pragma unroll
-          for (int db = 0; db < 4; ++db) oacc[db] = mfma32(frag_cols(vb, db, 32 * j + 16 * s2, lane), pf, oacc[db]);
+          for (int db = 0; db < 4; ++db) oacc[db] = mfma32(frag_cols(vb, db, 32 * j + 16 * s2, P), pf, oacc[db]);
         }
     }
+  };
+  for (int it = 0; it < ntiles; it += 2) {                           // two steps per trip: the buffer is a constant
+    tile_step(IntC<0>{}, it);
+    if (it + 1 < ntiles) tile_step(IntC<1>{}, it + 1);
   }
   if (qvalid) {
     const float l = lsum + __shfl_xor(lsum, 32, 64);
@@ -290,14 +325,16 @@ attn_bwd_dq_kernel(const AttnTile* __restrict__ tiles, const uint16_t* __restric
     tile_dma<4>(uniform_ptr(Kh + (int64_t)kvbase * ks), kv_row_bytes, 16 * wave, nkv - 1 - kvbase, kt_lds + buf, lane);
     tile_dma<4>(uniform_ptr(Vh + (int64_t)kvbase * ks), kv_row_bytes, 16 * wave, nkv - 1 - kvbase, vt_lds + buf, lane);
   };
+  const FragPat P = make_frag_pat(lane);
   issue(0);
-  for (int it = 0; it < ntiles; ++it) {
+  auto tile_step = [&](auto bufc, int it) {
+    constexpr int buf = decltype(bufc)::value;
     wait_all_and_sync();
     if (it + 1 < ntiles) issue(it + 1);
     const int kvbase = it * 64;
     if (active && kvbase <= qmax) {
-      const uint8_t* kb = kt[it & 1];
-      const uint8_t* vb = vt[it & 1];
+      const uint8_t* kb = kt[buf];
+      const uint8_t* vb = vt[buf];
       const bool diag = kvbase + 63 > qmin;
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
@@ -306,8 +343,8 @@ attn_bwd_dq_kernel(const AttnTile* __restrict__ tiles, const uint16_t* __restric
         for (int e = 0; e < 16; ++e) { sacc[e] = 0.f;  dp[e] = 0.f; }
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
-          sacc = mfma32(frag_rows(kb, 32 * j, s, lane), qf[s], sacc);
-          dp = mfma32(frag_rows(vb, 32 * j, s, lane), dof[s], dp);
+          sacc = mfma32(frag_rows(kb, 32 * j, s, P), qf[s], sacc);
+          dp = mfma32(frag_rows(vb, 32 * j, s, P), dof[s], dp);
         }
         if (diag) {
 #pragma unroll
@@ -320,10 +357,14 @@ attn_bwd_dq_kernel(const AttnTile* __restrict__ tiles, const uint16_t* __restric
         for (int s2 = 0; s2 < 2; ++s2) {
           const bf16x8 dsf = pack8(sacc, 8 * s2);
 #pragma unroll
-          for (int db = 0; db < 4; ++db) dq[db] = mfma32(frag_cols(kb, db, 32 * j + 16 * s2, lane), dsf, dq[db]);
+          for (int db = 0; db < 4; ++db) dq[db] = mfma32(frag_cols(kb, db, 32 * j + 16 * s2, P), dsf, dq[db]);
         }
       }
     }
+  };
+  for (int it = 0; it < ntiles; it += 2) {
+    tile_step(IntC<0>{}, it);
+    if (it + 1 < ntiles) tile_step(IntC<1>{}, it + 1);
   }
   if (qvalid) {
     uint16_t* orow = dQ + qrow * qs + h * HD;
@@ -393,16 +434,17 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const AttnTile* __res
     dma4s(off, uniform_ptr(lse + sbase), ls_lds + (uint32_t)stage * QS * 4);
     dma4s(off, uniform_ptr(D + sbase), ds_lds + (uint32_t)stage * QS * 4);
   };
+  const FragPat P = make_frag_pat(lane);
   if (nsteps > 0) issue(0);
   if (nsteps > 1) issue(1);
-  for (int st = 0; st < nsteps; ++st) {
+  auto q_step = [&](auto stagec, int st) {
+    constexpr int stage = decltype(stagec)::value;                   // = st % NS
     // everything but the loads of step st + 1 has landed (vmcnt in bits 3:0 and 15:14, the other counters 0)
     if (st + 1 < nsteps) __builtin_amdgcn_s_waitcnt(kLoads & 15);
     else                 __builtin_amdgcn_s_waitcnt(0);
     __builtin_amdgcn_s_barrier();
     if (st + 2 < nsteps) issue(st + 2);
     const int q0s = q_first + (st % nq) * QS;
-    const int stage = st % NS;
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
       const int q0 = q0s + 32 * half;
@@ -414,8 +456,8 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const AttnTile* __res
         for (int e = 0; e < 16; ++e) { sacc[e] = 0.f;  dp[e] = 0.f; }
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
-          sacc = mfma32(frag_rows(qb, 32 * half, s, lane), kf[s], sacc);
-          dp = mfma32(frag_rows(dob, 32 * half, s, lane), vf[s], dp);
+          sacc = mfma32(frag_rows(qb, 32 * half, s, P), kf[s], sacc);
+          dp = mfma32(frag_rows(dob, 32 * half, s, P), vf[s], dp);
         }
         if (q0 < kmax || q0 + 31 >= t.seq_len) {                     // some query before a key of the wave, or padding
 #pragma unroll
@@ -441,12 +483,17 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const AttnTile* __res
           const bf16x8 pf = pack8(pm, 8 * s2), dsf = pack8(sacc, 8 * s2);
 #pragma unroll
           for (int db = 0; db < 4; ++db) {
-            dv[db] = mfma32(frag_cols(dob, db, 32 * half + 16 * s2, lane), pf, dv[db]);
-            dk[db] = mfma32(frag_cols(qb, db, 32 * half + 16 * s2, lane), dsf, dk[db]);
+            dv[db] = mfma32(frag_cols(dob, db, 32 * half + 16 * s2, P), pf, dv[db]);
+            dk[db] = mfma32(frag_cols(qb, db, 32 * half + 16 * s2, P), dsf, dk[db]);
           }
         }
       }
     }
+  };
+  for (int st = 0; st < nsteps; st += NS) {                          // NS steps per trip: the stage is a constant
+    q_step(IntC<0>{}, st);
+    if (st + 1 < nsteps) q_step(IntC<1>{}, st + 1);
+    if (st + 2 < nsteps) q_step(IntC<2>{}, st + 2);
   }
   if (kvalid) {
     uint16_t* krow_o = dK + krow * ks + hk * HD;
