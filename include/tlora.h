@@ -82,12 +82,14 @@ typedef struct {
 size_t tlora_workspace_bytes(const tlora_problem_t* p);
 
 /* Forward (Sec. 3.3).  Y: DEVICE [T, d_out], overwritten.  The workspace afterwards holds the
- * intermediates S_j = X_j.A_j, which a following tlora_bwd on the same problem, workspace and
- * stream may reuse (TLORA_BWD_REUSE_S). */
+ * intermediates S_j = X_j.A_j and the packed bf16 copies of the adapters, which a following
+ * tlora_bwd on the same problem (same A_j, B_j values), workspace and stream may reuse
+ * (TLORA_BWD_REUSE_S). */
 int tlora_fwd(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_bytes, void* hip_stream);
 
 /* flags for tlora_bwd */
-#define TLORA_BWD_REUSE_S 1   /* the workspace still holds S_j from tlora_fwd of this same problem */
+#define TLORA_BWD_REUSE_S 1   /* the workspace still holds S_j and the packed adapters from tlora_fwd of this same
+                                 problem; X, A_j, B_j have not changed since */
 #define TLORA_BWD_ACCUMULATE 4 /* dA_j += ..., dB_j += ... instead of overwriting them (gradient accumulation over the
                                  nano-batches or micro-batches of one step); dX is always overwritten */
 #define TLORA_BWD_REUSE_WT 2  /* the workspace still holds the transposed copy of W that an earlier tlora_bwd with

@@ -628,7 +628,8 @@ int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* d
 
   {
     Timed t(TLORA_K_PACK, st);
-    launch_pack_adapters(jobs, pl.J, pl.d_in, pl.d_out, pl.max_rpad, pl.r_total, atp, ap, bp, st);
+    // with TLORA_BWD_REUSE_S the forward's packed copies of the (unchanged) adapters are still in the workspace
+    if (!reuse_S) launch_pack_adapters(jobs, pl.J, pl.d_in, pl.d_out, pl.max_rpad, pl.r_total, atp, ap, bp, st);
     if (pl.T > 0) {
       launch_zero_fill(dSx, 2 * (size_t)pl.sx_elems, st);
       if (redo_S) launch_zero_fill(Sx, 2 * (size_t)pl.sx_elems, st);

@@ -65,3 +65,27 @@ def test_decoder_layer_matches_oracle():
     print({k: round(v, 3) for k, v in res.items()})
     bad = {k: v for k, v in res.items() if not v <= 1.0}
     assert not bad, f"worst error / tolerance ratios {res}"
+
+
+def test_decoder_layer_without_tokens_gives_zero_gradients():
+    import torch
+    from paper_2602_07263_amd import tlora
+    d, dff, Hq, Hkv = 256, 384, 2, 1
+    ranks = [4, 8]
+    g = torch.Generator(device="cuda"); g.manual_seed(0)
+    rn = lambda *sh: torch.randn(*sh, device="cuda", generator=g).to(torch.bfloat16)
+    shapes = dict(q=(d, Hq * HD), k=(d, Hkv * HD), v=(d, Hkv * HD), o=(Hq * HD, d), gate=(d, dff), up=(d, dff), down=(dff, d))
+    tl = {n: (rn(i, o), [rn(i, r) for r in ranks], [rn(r, o) for r in ranks]) for n, (i, o) in shapes.items()}
+    X = torch.empty((0, d), dtype=torch.bfloat16, device="cuda")
+    gamma = torch.ones(d, dtype=torch.bfloat16, device="cuda")
+    layer = tlora.DecoderLayer(d, dff, Hq, Hkv, 10000.0, ranks, [0, 0, 0], [1.0, 2.0], [0], X, gamma, gamma, 1e-5, tl)
+    grads = layer.new_grads()
+    for n in grads:
+        for t in grads[n][0] + grads[n][1]:
+            t.fill_(float("nan"))
+    layer.fwd(X)
+    layer.bwd(X, X, grads)
+    torch.cuda.synchronize()
+    for n in grads:
+        for t in grads[n][0] + grads[n][1]:
+            assert float(t.abs().max()) == 0.0, n
