@@ -37,6 +37,8 @@ def parse_args():
     ap.add_argument("--no-loop-baseline", action="store_true")
     ap.add_argument("--no-secondary", action="store_true", help="skip the extra 4096x4096 (config 1) measurement")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with HIP events")
+    ap.add_argument("--leg", choices=["mlp_block", "indexed", "decoder_layer", "scheduler", "attention"], default=None,
+                    help="run only this additional measurement and print its JSON (for profiling one leg)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (outside the timed region) so that "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled against a known size")
@@ -315,6 +317,38 @@ def measure_decoder_layer(steps: int, warmup: int):
             "kernel_ms_per_step": {k: round(t[0] / steps, 4) for k, t in prof.items() if t[1]}}
 
 
+def measure_attention(steps: int, warmup: int):
+    """The attention primitives alone at the decoder-layer leg's head shape (32 query / 8 key-value heads of 128) on
+    32 768 tokens cut into sequences of 512, 2048 and 4096 tokens; causal flops: 4 x pairs x 128 forward, 10 x pairs x
+    128 backward."""
+    import torch
+    from paper_2602_07263_amd import tlora
+    Hq, Hkv, hd, T = 32, 8, 128, 32768
+    g = torch.Generator(device="cuda"); g.manual_seed(0)
+    rn = lambda h: torch.randn(T, h * hd, device="cuda", generator=g).to(torch.bfloat16)
+    Q, K, V, dO = rn(Hq), rn(Hkv), rn(Hkv), rn(Hq)
+    O, dQ, dK, dV = torch.empty_like(Q), torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    lse = torch.empty(T, Hq, device="cuda")
+    rows = []
+    for n in (512, 2048, 4096):
+        att = tlora.Attention(list(range(0, T + 1, n)), Hq, Hkv, "cuda")
+
+        def step(_i):
+            att.fwd(Q, K, V, O, lse)
+            att.bwd(Q, K, V, O, dO, lse, dQ, dK, dV)
+        for i in range(warmup):
+            step(i)
+        tlora.tlora_profile(True)
+        time_steps(step, steps, 0)
+        pr = tlora.tlora_profile_read()
+        tlora.tlora_profile(False)
+        pairs = (T // n) * Hq * n * (n + 1) / 2
+        f, b = pr["attn_fwd"][0] / steps, pr["attn_bwd"][0] / steps
+        rows.append({"seq_len": n, "fwd_ms": round(f, 4), "bwd_ms": round(b, 4),
+                     "fwd_tflops": round(4 * pairs * hd / f / 1e9, 1), "bwd_tflops": round(10 * pairs * hd / b / 1e9, 1)})
+    return {"workload": "causal grouped-query attention, 32/8 heads of 128, 32768 tokens", "by_sequence_length": rows}
+
+
 def measure_scheduler(steps: int, warmup: int):
     """The adapter scheduler over a step-time model measured from this library: the model's points are fwd+bwd times of
     the gate projection (4096 -> 12288) at seven token counts, its rank term comes from a rank-64 run, its per-job term from an
@@ -432,6 +466,11 @@ def main():
     tlora.lib()
     torch.cuda.set_device(0)
 
+    if args.leg:
+        legs = {"mlp_block": measure_mlp_block, "indexed": measure_indexed, "decoder_layer": measure_decoder_layer,
+                "scheduler": measure_scheduler, "attention": measure_attention}
+        print(json.dumps({"leg": args.leg, "result": legs[args.leg](max(3, args.steps // 4), 1)}))
+        return
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")       # 1 GiB read + 1 GiB written
         dst = torch.empty_like(src)
@@ -487,6 +526,7 @@ def main():
         out["also_decoder_layer"] = measure_decoder_layer(max(3, args.steps // 4), 1)
         torch.cuda.empty_cache()
         out["also_scheduler"] = measure_scheduler(max(5, args.steps // 2), 2)
+        out["also_attention"] = measure_attention(max(3, args.steps // 4), 1)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config)
     print(json.dumps(out))
