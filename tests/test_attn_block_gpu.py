@@ -90,3 +90,30 @@ def test_attn_block_rejects_fp32_and_mismatched_sequences():
     blk = tlora.AttnBlock(d, Hq, Hkv, 10000.0, [4], off, [1.0], [0, 64], up(X), up(gamma), 1e-5, tl)
     blk.prob.dtype = tlora.TLORA_F32
     assert tlora.lib().tlora_attn_workspace_bytes(ctypes.byref(blk.prob)) == 0
+
+
+def test_attn_block_gradient_accumulation():
+    """TLORA_BWD_ACCUMULATE adds to the adapter gradients: a second backward with the flag doubles them (dX is
+    overwritten, so it stays the same)."""
+    import torch
+    from paper_2602_07263_amd import tlora
+    d, Hq, Hkv = 256, 2, 1
+    ranks, tokens = [8, 3], [130, 70]
+    X, gamma, layers, off, dOut = _make(d, Hq, Hkv, ranks, tokens, seed=9)
+    up = lambda a: torch.from_numpy(a).to(device="cuda", dtype=torch.bfloat16).contiguous()
+    tl = {n: (up(W), [up(a) for a in A], [up(b) for b in B]) for n, (W, A, B) in layers.items()}
+    blk = tlora.AttnBlock(d, Hq, Hkv, 10000.0, ranks, off, [1.0, 2.0], [0, 130, 200], up(X), up(gamma), 1e-5, tl)
+    Out = torch.empty((200, d), dtype=torch.bfloat16, device="cuda")
+    dX1, dX2 = torch.empty_like(Out), torch.empty_like(Out)
+    grads = blk.new_grads()
+    blk.fwd(Out)
+    blk.bwd(up(dOut), dX1, grads)
+    torch.cuda.synchronize()
+    once = {n: ([a.clone() for a in grads[n][0]], [b.clone() for b in grads[n][1]]) for n in grads}
+    blk.bwd(up(dOut), dX2, grads, flags=tlora.TLORA_BWD_ACCUMULATE)
+    torch.cuda.synchronize()
+    assert torch.equal(dX1.view(torch.int16), dX2.view(torch.int16))
+    for n in grads:
+        for k in (0, 1):
+            for a, b in zip(once[n][k], grads[n][k]):
+                assert torch.equal(b, 2 * a), n
