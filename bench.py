@@ -24,6 +24,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 BF16_MFMA_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
+HBM_PEAK_GBPS = 8000.0              # MI355X HBM3E peak
 HBM_PEAK_GBS = 8000.0
 
 
@@ -172,6 +173,23 @@ def gemm_roofline(wl, prof, steps):
             "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / BF16_MFMA_PEAK_TFLOPS, 4),
             "avg_launch_ms": round(avg_ms, 4), "launches": n, "flops_per_launch": flops_per_launch,
             "traffic": load_traffic()}
+
+
+def rank_bound_rooflines(wl, prof, steps):
+    """HBM rooflines of the rank-bound kernels.  Algorithmic bytes per step: the shrink launches stream X (forward)
+    and dY (backward) once each, 2 T (d_in + d_out) bytes per projection; the dA / dB launches stream both again."""
+    T = float(wl.total_tokens)
+    bytes_step = sum(2.0 * T * (p.d_in + p.d_out) for p in wl.projections)
+    out = []
+    for name, kernel in (("shrink", "shrink_stream_kernel"), ("rank_grad", "rank_grad_kernel")):
+        ms, n = prof[name]
+        if n == 0 or ms <= 0:
+            continue
+        gbps = bytes_step / (ms / steps * 1e-3) / 1e9
+        out.append({"bound": "hbm", "kernel": kernel, "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                    "frac": round(gbps / HBM_PEAK_GBPS, 4), "ms_per_step": round(ms / steps, 4),
+                    "bytes_per_step": bytes_step})
+    return out
 
 
 def load_traffic():
@@ -498,6 +516,7 @@ def main():
         out["speedup_vs_per_job_loop"] = round(main_res["loop_ms"] / main_res["ms"], 3)
     if main_res["prof"]:
         out["roofline"] = gemm_roofline(wl, main_res["prof"], args.steps)
+        out["rooflines_rank_bound"] = rank_bound_rooflines(wl, main_res["prof"], args.steps)
         if main_res["clock"] and min(main_res["clock"]) > 0:
             ghz = sum(main_res["clock"]) / 2
             out["roofline"]["sustained_shader_clock_ghz"] = round(ghz, 3)
