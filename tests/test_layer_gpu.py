@@ -89,3 +89,75 @@ def test_decoder_layer_without_tokens_gives_zero_gradients():
     for n in grads:
         for t in grads[n][0] + grads[n][1]:
             assert float(t.abs().max()) == 0.0, n
+
+
+def test_decoder_layer_training_steps_follow_the_oracle():
+    """Four steps of forward, backward and AdamW on all 7 x J adapter pairs of one decoder layer (regression onto a
+    fixed target): the loss falls, and its trajectory matches the same loop run with the oracles in float64 (with the
+    bf16 storage points of the GPU path)."""
+    import torch
+    from oracle import adamw_oracle as adw
+    from paper_2602_07263_amd import tlora
+    d, dff, Hq, Hkv = 256, 384, 2, 1
+    ranks, tokens, scales = [8, 4], [96, 64], [2.0, 1.0]
+    seq = np.array([0, 96, 130, 160], dtype=np.int64)
+    eps, base, lr, steps = 1e-5, 10000.0, 2e-3, 4
+    rng = np.random.default_rng(31)
+    f = lambda a: wk.round_to_bf16(np.asarray(a, dtype=np.float32))
+    T = sum(tokens)
+    off = np.concatenate([[0], np.cumsum(tokens)]).astype(np.int64)
+    shapes = dict(q=(d, Hq * HD), k=(d, Hkv * HD), v=(d, Hkv * HD), o=(Hq * HD, d), gate=(d, dff), up=(d, dff), down=(dff, d))
+    names = list(shapes)
+    W = {n: f(rng.normal(size=s) / np.sqrt(s[0])) for n, s in shapes.items()}
+    A0 = {n: [rng.uniform(-1, 1, size=(s[0], r)).astype(np.float32) / np.float32(np.sqrt(s[0])) for r in ranks] for n, s in shapes.items()}
+    B0 = {n: [(0.05 * rng.normal(size=(r, s[1]))).astype(np.float32) for r in ranks] for n, s in shapes.items()}
+    X, target = f(rng.normal(size=(T, d))), f(rng.normal(size=(T, d)))
+    gam = f(np.ones(d))
+    store = lambda a: wk.round_to_bf16(np.asarray(a, dtype=np.float32)).astype(np.float64)
+
+    # ---- oracle loop (fp64 masters; the layer reads their bf16 roundings) ----
+    mA = {n: [a.astype(np.float64) for a in A0[n]] for n in names}
+    mB = {n: [b.astype(np.float64) for b in B0[n]] for n in names}
+    st = {n: [[np.zeros_like(a), np.zeros_like(a), np.zeros_like(b), np.zeros_like(b)] for a, b in zip(mA[n], mB[n])] for n in names}
+    loss_r = []
+    for t in range(1, steps + 1):
+        layers = {n: (W[n], [store(a) for a in mA[n]], [store(b) for b in mB[n]]) for n in names}
+        attn = (gam, eps, {n: layers[n] for n in ("q", "k", "v", "o")})
+        mlp = (gam, eps, {n: layers[n] for n in ("gate", "up", "down")})
+        args = (attn, mlp, scales, off, seq, Hq, Hkv, HD, base)
+        out, _ = ly.forward(X, *args, store)
+        diff = store(out) - target
+        loss_r.append(0.5 * float(np.sum(diff * diff)))
+        _, g = ly.backward(X, *args, store(diff), store)
+        for n in names:
+            for j in range(len(ranks)):
+                mA[n][j], st[n][j][0], st[n][j][1] = adw.adamw_step(mA[n][j], g[n][0][j], st[n][j][0], st[n][j][1], t, lr)
+                mB[n][j], st[n][j][2], st[n][j][3] = adw.adamw_step(mB[n][j], g[n][1][j], st[n][j][2], st[n][j][3], t, lr)
+
+    # ---- GPU loop ----
+    up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(device="cuda", dtype=torch.bfloat16).contiguous()
+    master = {n: ([torch.from_numpy(a.copy()).cuda() for a in A0[n]], [torch.from_numpy(b.copy()).cuda() for b in B0[n]]) for n in names}
+    tl = {n: (up(W[n]), [m_.to(torch.bfloat16) for m_ in master[n][0]], [m_.to(torch.bfloat16) for m_ in master[n][1]]) for n in names}
+    tX, tT = up(X), up(target)
+    layer = tlora.DecoderLayer(d, dff, Hq, Hkv, base, ranks, off, scales, seq, tX, up(gam), up(gam), eps, tl)
+    grads = layer.new_grads()
+    params = [p_ for n in names for p_ in tl[n][1] + tl[n][2]]
+    masters = [p_ for n in names for p_ in master[n][0] + master[n][1]]
+    gl = [p_ for n in names for p_ in grads[n][0] + grads[n][1]]
+    ms = [torch.zeros_like(p_) for p_ in masters]
+    vs = [torch.zeros_like(p_) for p_ in masters]
+    ows = torch.empty(tlora.tlora_adamw_workspace_bytes(len(params)), dtype=torch.uint8, device="cuda")
+    Out, dX = torch.empty_like(tX), torch.empty_like(tX)
+    loss_g = []
+    for t in range(1, steps + 1):
+        layer.fwd(Out)
+        diff = (Out.float() - tT.float())
+        loss_g.append(0.5 * float((diff.double() ** 2).sum()))
+        layer.bwd(diff.to(torch.bfloat16), dX, grads)
+        tens = [dict(param=p_.data_ptr(), master=w_.data_ptr(), grad=g_.data_ptr(), m=a_.data_ptr(), v=b_.data_ptr(),
+                     n=p_.numel(), lr=lr, step=t) for p_, w_, g_, a_, b_ in zip(params, masters, gl, ms, vs)]
+        tlora.tlora_adamw_step(tens, tlora.TLORA_BF16, ows.data_ptr(), ows.numel(), int(torch.cuda.current_stream().cuda_stream))
+    torch.cuda.synchronize()
+    print("loss oracle", [round(x, 2) for x in loss_r], "gpu", [round(x, 2) for x in loss_g])
+    assert all(b < a for a, b in zip(loss_g[:-1], loss_g[1:])), loss_g
+    assert all(abs(a - b) <= 1e-2 * b for a, b in zip(loss_g, loss_r)), (loss_g, loss_r)
