@@ -145,49 +145,93 @@ __device__ __forceinline__ bf16x8 frag16_kn(const uint8_t* tile, int nb, int ks,
 // blockIdx.y == num_jobs zero-fills the 32 trailing columns / rows, which the last tile's K-extension
 // may read (against zero activations) when its rank range is rounded up to the K-step.
 // ---------------------------------------------------------------------------------------------------
+// Every thread assembles 8 consecutive output elements and stores them as one 16-byte chunk (d_in, d_out, rpad,
+// roff and R are multiples of 8, so every chunk is aligned); A_j is read element by element (its rows are r_j
+// elements long, any alignment), B_j in 16-byte chunks when its base is aligned.
 __global__ void __launch_bounds__(256) pack_adapters_kernel(const JobDev* __restrict__ jobs, int num_jobs, int d_in,
                                                             int d_out, int r_total, uint16_t* __restrict__ atp,
                                                             uint16_t* __restrict__ a_all,
                                                             uint16_t* __restrict__ b_all) {
-  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  const int64_t first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int stride = (int)(gridDim.x * blockDim.x);
+  const int first = (int)(blockIdx.x * blockDim.x + threadIdx.x);
   const int ra = r_total + 32;
+  const int kout8 = d_out / 8;
+  const u32x4 zero = {0, 0, 0, 0};
   if ((int)blockIdx.y == num_jobs) {
-    for (int64_t i = first; i < (int64_t)32 * d_in; i += stride) {
-      a_all[(i >> 5) * ra + r_total + (i & 31)] = 0;
-      atp[(int64_t)r_total * d_in + i] = 0;
-    }
-    for (int64_t i = first; i < (int64_t)32 * d_out; i += stride) b_all[(int64_t)r_total * d_out + i] = 0;
+    for (int i = first; i < 4 * d_in; i += stride)
+      *reinterpret_cast<u32x4*>(a_all + (int64_t)(i >> 2) * ra + r_total + (i & 3) * 8) = zero;
+    for (int i = first; i < 4 * d_in; i += stride) *reinterpret_cast<u32x4*>(atp + (int64_t)r_total * d_in + (int64_t)i * 8) = zero;
+    for (int i = first; i < 4 * d_out; i += stride) *reinterpret_cast<u32x4*>(b_all + (int64_t)r_total * d_out + (int64_t)i * 8) = zero;
     return;
   }
   const JobDev jb = jobs[blockIdx.y];
   if (jb.rpad == 0) return;
   const uint16_t* A = static_cast<const uint16_t*>(jb.A);
   const uint16_t* B = static_cast<const uint16_t*>(jb.B);
-  const int64_t na = (int64_t)jb.rpad * d_in;
-  const int64_t nb = (int64_t)jb.rpad * d_out;
-  for (int64_t i = first; i < na; i += stride) {
-    {  // A_j^T [rpad, d_in]
-      const int p = (int)(i / d_in), k = (int)(i % d_in);
-      atp[jb.atp_off + i] = p < jb.rank ? A[(int64_t)k * jb.rank + p] : (uint16_t)0;
+  const int rank = jb.rank;
+  // A_j is read once, in tiles of 64 k-rows x 64 rank columns, row by row (contiguous elements), into LDS; both
+  // packed layouts are written from there: a_all chunks along the rank, A_j^T chunks along k.
+  __shared__ uint16_t tile[64][66];
+  const int tk = (d_in + 63) / 64, tp = (jb.rpad + 63) / 64;
+  for (int t = blockIdx.x; t < tk * tp; t += gridDim.x) {
+    const int k_base = (t / tp) * 64, p_base = (t % tp) * 64;
+#pragma unroll
+    for (int h = 0; h < 16; ++h) {
+      const int kk = (threadIdx.x >> 6) + h * 4, pp = threadIdx.x & 63;
+      const int k = k_base + kk, pcol = p_base + pp;
+      tile[kk][pp] = (k < d_in && pcol < rank) ? A[(int64_t)k * rank + pcol] : (uint16_t)0;
     }
-    {  // A_j into its columns of a_all
-      const int k = (int)(i / jb.rpad), p = (int)(i % jb.rpad);
-      a_all[(int64_t)k * ra + jb.roff + p] = p < jb.rank ? A[(int64_t)k * jb.rank + p] : (uint16_t)0;
+    __syncthreads();
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int c = threadIdx.x + h * 256;                       // 512 chunks of 8 per layout
+      {   // a_all: row k, rank columns p0 .. p0 + 7
+        const int kk = c >> 3, p0 = (c & 7) * 8;
+        if (k_base + kk < d_in && p_base + p0 < jb.rpad) {
+          uint32_t v[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] = tile[kk][p0 + e];
+          *reinterpret_cast<u32x4*>(a_all + (int64_t)(k_base + kk) * ra + jb.roff + p_base + p0) =
+              u32x4{v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16)};
+        }
+      }
+      {   // A_j^T: rank row p, k0 .. k0 + 7
+        const int pp = c >> 3, k0 = (c & 7) * 8;
+        if (p_base + pp < jb.rpad && k_base + k0 < d_in) {
+          uint32_t v[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] = tile[k0 + e][pp];
+          *reinterpret_cast<u32x4*>(atp + jb.atp_off + (int64_t)(p_base + pp) * d_in + k_base + k0) =
+              u32x4{v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16)};
+        }
+      }
     }
+    __syncthreads();
   }
+  // B_j into its rows of b_all
   uint16_t* bdst = b_all + (int64_t)jb.roff * d_out;
-  for (int64_t i = first; i < nb; i += stride) {
-    const int p = (int)(i / d_out);
-    bdst[i] = p < jb.rank ? B[i] : (uint16_t)0;
+  const bool b_aligned = (reinterpret_cast<uintptr_t>(B) & 15) == 0;
+  for (int i = first; i < jb.rpad * kout8; i += stride) {
+    const int p = i / kout8, c0 = (i - p * kout8) * 8;
+    u32x4 v = zero;
+    if (p < rank) {
+      const uint16_t* src = B + (int64_t)p * d_out + c0;
+      if (b_aligned) {
+        v = *reinterpret_cast<const u32x4*>(src);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (uint32_t)src[2 * e] | ((uint32_t)src[2 * e + 1] << 16);
+      }
+    }
+    *reinterpret_cast<u32x4*>(bdst + (int64_t)p * d_out + c0) = v;
   }
 }
 
 void launch_pack_adapters(const JobDev* jobs, int num_jobs, int d_in, int d_out, int max_rpad, int r_total,
                           uint16_t* atp, uint16_t* a_all, uint16_t* b_all, hipStream_t st) {
   if (max_rpad == 0) return;
-  const int64_t n = (int64_t)max_rpad * (d_in > d_out ? d_in : d_out);
-  int bx = (int)((n + 256 * 8 - 1) / (256 * 8));
+  const int64_t n = (int64_t)max_rpad * (d_in > d_out ? d_in : d_out) / 8;     // 16-byte chunks of the largest layout
+  int bx = (int)((n + 256 * 4 - 1) / (256 * 4));
   if (bx > 512) bx = 512;
   if (bx < 1) bx = 1;
   hipLaunchKernelGGL(pack_adapters_kernel, dim3(bx, num_jobs + 1), dim3(256), 0, st, jobs, num_jobs, d_in, d_out,
