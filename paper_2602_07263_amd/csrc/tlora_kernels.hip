@@ -1142,7 +1142,11 @@ void launch_rank_grad(const JobDev* jobs, const GradUnit* units, int num_units, 
 }
 
 // Sum the partial tiles of one output tile in unit order, scale, and store (dB_j row-major [r, D];
-// dA_j is the transpose of the computed tile: [D, r]).  One workgroup = 4 rank rows x 256 columns of a group.
+// dA_j is the transpose of the computed tile: [D, r]).  One thread per column; a workgroup takes the slabs of 4 rank
+// rows blockIdx.y, blockIdx.y + kReduceSplit, ... of its group's 256 columns (a grid over all 32 possible slabs
+// would consist mostly of workgroups that find their slab beyond the job's rank).  The partial tiles are read row
+// by row (coalesced across the threads); dB rows are stored the same way, dA as 16 bytes per thread and slab.
+constexpr int kReduceSplit = 8;
 __global__ void __launch_bounds__(256) grad_reduce_kernel(const JobDev* __restrict__ jobs,
                                                           const GradGroup* __restrict__ groups,
                                                           const float* __restrict__ partial, int D, int out_is_dA,
@@ -1152,23 +1156,34 @@ __global__ void __launch_bounds__(256) grad_reduce_kernel(const JobDev* __restri
   const int c = g.cb * kGradCols + threadIdx.x;
   const int tile_rows = g.mb * kGradRanks;                 // live rows of this tile
   const int pb_rows = kGradMaxBlocks * kGradRanks;         // rank rows per rank block
-  const int pl0 = blockIdx.y * 4;
-  if (c >= D || pl0 >= tile_rows || g.pb * pb_rows + pl0 >= jb.rank) return;
+  const int live = min(tile_rows, jb.rank - g.pb * pb_rows);   // rows of the tile that exist in the job
+  if (c >= D) return;
   const int64_t tile_elems = (int64_t)tile_rows * kGradCols;
-  const float* src = partial + g.part_off + (int64_t)pl0 * kGradCols + threadIdx.x;
-  float s[4] = {0.f, 0.f, 0.f, 0.f};
-  for (int k = 0; k < g.nunits; ++k) {          // fixed order: bit-reproducible
-#pragma unroll
-    for (int i = 0; i < 4; ++i) s[i] += src[k * tile_elems + i * kGradCols];
-  }
   float* dst = static_cast<float*>(out_is_dA ? jb.dA : jb.dB);
+  const bool vec = out_is_dA && (jb.rank & 3) == 0 && (reinterpret_cast<uintptr_t>(dst) & 15) == 0;
+  for (int pl0 = blockIdx.y * 4; pl0 < live; pl0 += 4 * kReduceSplit) {
+    const float* src = partial + g.part_off + (int64_t)pl0 * kGradCols + threadIdx.x;
+    float s[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int k = 0; k < g.nunits; ++k) {          // fixed order: bit-reproducible
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int p = g.pb * pb_rows + pl0 + i;
-    if (p < jb.rank) {
-      float* const d = out_is_dA ? dst + (int64_t)c * jb.rank + p : dst + (int64_t)p * D + c;
-      const float v = s[i] * jb.scale;
-      *d = accumulate ? *d + v : v;
+      for (int i = 0; i < 4; ++i) s[i] += src[k * tile_elems + i * kGradCols];
+    }
+    const int p0 = g.pb * pb_rows + pl0;
+    if (vec) {                                    // rank % 4 == 0: the slab's 4 rows all exist
+      f32x4 v = {s[0] * jb.scale, s[1] * jb.scale, s[2] * jb.scale, s[3] * jb.scale};
+      f32x4* const q = reinterpret_cast<f32x4*>(dst + (int64_t)c * jb.rank + p0);
+      if (accumulate) { const f32x4 o = *q;  v = f32x4{o[0] + v[0], o[1] + v[1], o[2] + v[2], o[3] + v[3]}; }
+      *q = v;
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int p = p0 + i;
+        if (p < jb.rank) {
+          float* const d = out_is_dA ? dst + (int64_t)c * jb.rank + p : dst + (int64_t)p * D + c;
+          const float v = s[i] * jb.scale;
+          *d = accumulate ? *d + v : v;
+        }
+      }
     }
   }
 }
@@ -1176,8 +1191,8 @@ __global__ void __launch_bounds__(256) grad_reduce_kernel(const JobDev* __restri
 void launch_grad_reduce(const JobDev* jobs, const GradGroup* groups, int num_groups, const float* partial, int D,
                         bool out_is_dA, bool accumulate, hipStream_t st) {
   if (num_groups == 0) return;
-  hipLaunchKernelGGL(grad_reduce_kernel, dim3(num_groups, kGradMaxBlocks * kGradRanks / 4), dim3(256), 0, st, jobs, groups, partial,
-                     D, out_is_dA ? 1 : 0, accumulate ? 1 : 0);
+  hipLaunchKernelGGL(grad_reduce_kernel, dim3(num_groups, kReduceSplit), dim3(256), 0, st, jobs, groups, partial, D,
+                     out_is_dA ? 1 : 0, accumulate ? 1 : 0);
 }
 
 // ---------------------------------------------------------------------------------------------------
