@@ -1,5 +1,7 @@
 // gfx950 kernels of the attention half of a decoder layer: rotary position embedding and causal grouped-query
 // attention (forward, and the backward as two deterministic kernels), bf16 with fp32 accumulation, head size 128.
+// (Sec. 3.2 runs the fused jobs on one frozen backbone; Sec. 4.1's backbones are 8B-class decoders with exactly this
+// attention.  The paper gives no kernel for it: these are the standard definitions.)
 //
 // All three attention kernels work on "transposed" score blocks S^T[kv, q] (or S[q, kv] in the dK/dV kernel) so
 // that the 32 x 32 x 16 MFMA leaves every lane with 16 scores of ONE query (key) column: softmax statistics are
