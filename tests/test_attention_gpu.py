@@ -40,10 +40,11 @@ def test_rope_matches_oracle(lens, heads):
 # sequence, single tokens, one sequence of many tiles; group sizes 1, 2 and 4
 CASES = [([1, 130, 0, 64, 257, 31, 128], 4, 2),
          ([33, 1, 1, 200], 2, 2),
-         ([1500, 7], 8, 2)]
+         ([1500, 7], 8, 2),
+         ([5000], 1, 1)]
 
 
-@pytest.mark.parametrize("case", CASES, ids=["ragged_g2", "small_g1", "long_g4"])
+@pytest.mark.parametrize("case", CASES, ids=["ragged_g2", "small_g1", "long_g4", "one_long_sequence"])
 def test_attention_fwd_bwd_match_oracle(case):
     import torch
     from paper_2602_07263_amd import tlora
