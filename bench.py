@@ -38,7 +38,7 @@ def parse_args():
     ap.add_argument("--no-loop-baseline", action="store_true")
     ap.add_argument("--no-secondary", action="store_true", help="skip the extra 4096x4096 (config 1) measurement")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with HIP events")
-    ap.add_argument("--leg", choices=["mlp_block", "indexed", "decoder_layer", "scheduler", "attention"], default=None,
+    ap.add_argument("--leg", choices=["mlp_block", "indexed", "decoder_layer", "scheduler", "attention", "nano"], default=None,
                     help="run only this additional measurement and print its JSON (for profiling one leg)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (outside the timed region) so that "
@@ -367,6 +367,42 @@ def measure_attention(steps: int, warmup: int):
     return {"workload": "causal grouped-query attention, 32/8 heads of 128, 32768 tokens", "by_sequence_length": rows}
 
 
+def measure_nano(steps: int, warmup: int):
+    """Nano-batches of cfg2's gate projection (granule = one 512-token sequence): fwd+bwd step time at fixed N, and
+    the paper's AIMD controller run in closed loop on the measured step times, starting from N = 16."""
+    import torch
+    from paper_2602_07263_amd import tlora, workloads as wk
+    wl = wk.config(2)
+    pr = wl.projections[0]
+    T = wl.total_tokens
+    g = torch.Generator(device="cuda"); g.manual_seed(3)
+    bf = torch.bfloat16
+    X = torch.randn(T, pr.d_in, device="cuda", generator=g).to(bf)
+    dY = torch.randn(T, pr.d_out, device="cuda", generator=g).to(bf)
+    W = (torch.randn(pr.d_in, pr.d_out, device="cuda", generator=g) * 0.02).to(bf)
+    A = [((torch.rand(pr.d_in, r, device="cuda", generator=g) * 2 - 1) / pr.d_in ** 0.5).to(bf) for r in wl.ranks]
+    B = [(torch.randn(r, pr.d_out, device="cuda", generator=g) * 0.01).to(bf) for r in wl.ranks]
+    lp = tlora.LayerProblem("bf16", pr.d_in, pr.d_out, wl.ranks, wl.offsets, wl.scales, X, W, A, B)
+    Y, dX, dA, dB = lp.new_outputs()
+    granule = 512
+
+    def run(n):
+        def step(_i):
+            lp.fwd_nano(n, granule, Y)
+            lp.bwd_nano(n, granule, dY, dX, dA, dB)
+        return time_steps(step, steps, warmup)
+    fixed = {str(n): round(run(n), 4) for n in (1, 2, 4, 8, 16)}
+    ctl = tlora.tlora_aimd_init(16, n_max=T // granule)
+    trace, n = [], 16
+    for _ in range(8):
+        ms = run(n)
+        trace.append([n, round(ms, 4)])
+        n = tlora.tlora_aimd_update(ctl, ms)
+    return {"workload": "cfg2 gate 4096->12288, 31744 tokens, nano-batches of whole 512-token sequences, fwd+bwd",
+            "ms_per_step_by_n": fixed, "aimd_trace_n_ms": trace,
+            "note": "one GPU has no communication to overlap: more nano-batches only add launches, the controller walks N down"}
+
+
 def measure_scheduler(steps: int, warmup: int):
     """The adapter scheduler over a step-time model measured from this library: the model's points are fwd+bwd times of
     the gate projection (4096 -> 12288) at seven token counts, its rank term comes from a rank-64 run, its per-job term from an
@@ -486,7 +522,7 @@ def main():
 
     if args.leg:
         legs = {"mlp_block": measure_mlp_block, "indexed": measure_indexed, "decoder_layer": measure_decoder_layer,
-                "scheduler": measure_scheduler, "attention": measure_attention}
+                "scheduler": measure_scheduler, "attention": measure_attention, "nano": measure_nano}
         print(json.dumps({"leg": args.leg, "result": legs[args.leg](max(3, args.steps // 4), 1)}))
         return
     if args.copy_calibration:
@@ -546,6 +582,7 @@ def main():
         torch.cuda.empty_cache()
         out["also_scheduler"] = measure_scheduler(max(5, args.steps // 2), 2)
         out["also_attention"] = measure_attention(max(3, args.steps // 4), 1)
+        out["also_nano"] = measure_nano(max(3, args.steps // 4), 1)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config)
     print(json.dumps(out))

@@ -455,11 +455,23 @@ class LayerProblem:
                   None if dB is None else [b.data_ptr() if b.numel() else 0 for b in dB],
                   (TLORA_BWD_REUSE_S if reuse_S else 0) | flags, self.ws.data_ptr(), self.ws_bytes, self._stream())
 
+    def _nano_ws(self, n_nano: int, granule: int) -> None:
+        """Grow the workspace to what this partition needs (its tiles start at other rows than the whole batch's, so a
+        tile may hold more jobs and its K-extension operand may be wider)."""
+        need = tlora_nano_workspace_bytes(self.prob, n_nano, granule)
+        if need == 0:
+            raise TloraError("tlora_nano_workspace_bytes: invalid problem or partition")
+        if need > self.ws_bytes:
+            self.ws = self.torch.empty(need, dtype=self.torch.uint8, device=self.X.device)
+            self.ws_bytes = need
+
     def fwd_nano(self, n_nano: int, granule: int, Y) -> None:
-        """Forward over n_nano nano-batches (the workspace of the whole batch is large enough for any of them)."""
+        """Forward over n_nano nano-batches."""
+        self._nano_ws(n_nano, granule)
         tlora_fwd_nano(self.prob, n_nano, granule, Y.data_ptr(), self.ws.data_ptr(), self.ws_bytes, self._stream())
 
     def bwd_nano(self, n_nano: int, granule: int, dY, dX, dA, dB, flags: int = 0) -> None:
+        self._nano_ws(n_nano, granule)
         tlora_bwd_nano(self.prob, n_nano, granule, dY.data_ptr(), dX.data_ptr() if dX is not None else 0,
                        None if dA is None else [a.data_ptr() if a.numel() else 0 for a in dA],
                        None if dB is None else [b.data_ptr() if b.numel() else 0 for b in dB],
