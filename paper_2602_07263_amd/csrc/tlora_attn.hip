@@ -141,6 +141,15 @@ __device__ __forceinline__ void load_row_frags(const uint16_t* row, int lane, bf
     f[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(row + 16 * s + 8 * (lane >> 5)));
 }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+// x of this lane and x of lane ^ 32, in unspecified order: one v_permlane32_swap (the upper half of the first operand
+// trades places with the lower half of the second) instead of a round trip through the LDS crossbar.  Both callers
+// combine the two symmetrically (max, sum).
+__device__ __forceinline__ void with_partner32(float x, float& a, float& b) {
+  const unsigned u = __builtin_bit_cast(unsigned, x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  a = __builtin_bit_cast(float, (unsigned)r[0]);
+  b = __builtin_bit_cast(float, (unsigned)r[1]);
+}
 // key (query) index inside a 32-block that accumulator element i of lanes with lane / 32 = hl stands for
 __device__ __forceinline__ int acc_row(int i, int hl) { return 8 * (i >> 2) + 4 * hl + (i & 3); }
 
@@ -218,7 +227,11 @@ attn_fwd_kernel(const AttnTile* __restrict__ tiles, const uint16_t* __restrict__
       for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[j][i]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      {
+        float a, b;
+        with_partner32(mx, a, b);
+        mx = fmaxf(a, b);
+      }
       const float mnew = fmaxf(m, mx);                                // finite: key 0 is visible to every query
       if (__any(mnew != m)) {
         const float alpha = fast_exp2((m - mnew) * c);                // 0 for m = -inf
@@ -253,7 +266,9 @@ attn_fwd_kernel(const AttnTile* __restrict__ tiles, const uint16_t* __restrict__
     if (it + 1 < ntiles) tile_step(IntC<1>{}, it + 1);
   }
   if (qvalid) {
-    const float l = lsum + __shfl_xor(lsum, 32, 64);
+    float la, lb;
+    with_partner32(lsum, la, lb);
+    const float l = la + lb;
     const float inv = 1.f / l;
     uint16_t* orow = O + (int64_t)(t.seq_start + qpos) * qs + h * HD;
 #pragma unroll
