@@ -125,13 +125,13 @@ __device__ __forceinline__ void wait_all_and_sync() {
 // depends on i and the lane only.
 template <int LOADS>
 __device__ __forceinline__ void tile_dma(const char* sbase, uint32_t row_bytes, int row0, int last_row, uint32_t tile_lds,
-                                         int lane) {
+                                         int lane, int grow0 = 0 /* tile row r holds global row grow0 + r */) {
   const int lr = lane >> 4, slot = lane & 15;
 #pragma unroll
   for (int i = 0; i < LOADS; ++i) {
     const int r = row0 + 4 * i + lr;
     const int c = slot ^ ((lr << 2) | (((row0 >> 2) + i) & 3));
-    dma16s((uint32_t)min(r, last_row) * row_bytes + (uint32_t)c * 16u, sbase, tile_lds + (uint32_t)(row0 + 4 * i) * ROWB);
+    dma16s((uint32_t)min(grow0 + r, last_row) * row_bytes + (uint32_t)c * 16u, sbase, tile_lds + (uint32_t)(row0 + 4 * i) * ROWB);
   }
 }
 // the 8 k-slices of one token row as a "column" operand: lane l -> row (given), head-dim values 16 s + 8 (l / 32) ..
@@ -178,7 +178,6 @@ attn_fwd_kernel(const AttnTile* __restrict__ tiles, const uint16_t* __restrict__
   const bool qvalid = q0w + (lane & 31) < t.seq_len;
   const int64_t qs = (int64_t)Hq * HD, ks = (int64_t)Hkv * HD;
   bf16x8 qf[8];
-  load_row_frags(Q + (int64_t)(t.seq_start + qpos) * qs + h * HD, lane, qf);
   const uint16_t* Kh = K + (int64_t)t.seq_start * ks + hk * HD;
   const uint16_t* Vh = V + (int64_t)t.seq_start * ks + hk * HD;
   const uint32_t kv_row_bytes = (uint32_t)ks * 2u;
@@ -198,7 +197,21 @@ attn_fwd_kernel(const AttnTile* __restrict__ tiles, const uint16_t* __restrict__
     tile_dma<4>(uniform_ptr(Vh + (int64_t)kvbase * ks), kv_row_bytes, 16 * wave, nkv - 1 - kvbase, vt_lds + buf, lane);
   };
   const FragPat P = make_frag_pat(lane);
-  issue(0);
+  {
+    // The 128 query rows come in like a key tile, through the second buffers (rows 0-63 in the key buffer, 64-127
+    // in the value buffer), together with the first key / value tile; each wave then takes its 32 rows' fragments
+    // into registers and the buffers are free again before the second key / value tile is requested.
+    const char* const qbase = uniform_ptr(Q + (int64_t)(t.seq_start + t.t0) * qs + h * HD);
+    const uint32_t q_row_bytes = (uint32_t)qs * 2u;
+    const int last_q = t.seq_len - 1 - t.t0;
+    tile_dma<4>(qbase, q_row_bytes, 16 * wave, last_q, kt_lds + 64 * ROWB, lane);
+    tile_dma<4>(qbase, q_row_bytes, 16 * wave, last_q, vt_lds + 64 * ROWB, lane, 64);
+    issue(0);
+    wait_all_and_sync();
+    const uint8_t* const qtile = wave < 2 ? kt[1] : vt[1];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) qf[s] = frag_rows(qtile, 32 * (wave & 1), s, P);
+  }
   auto tile_step = [&](auto bufc, int it) {
     constexpr int buf = decltype(bufc)::value;
     wait_all_and_sync();                                              // tile `it` is in LDS; the other buffer is free
