@@ -15,6 +15,7 @@ TLORA_F32, TLORA_BF16 = 0, 1
 TLORA_BWD_REUSE_S = 1
 TLORA_BWD_REUSE_WT = 2
 TLORA_BWD_ACCUMULATE = 4
+TLORA_OK, TLORA_EINVAL, TLORA_ENULL, TLORA_EDTYPE, TLORA_EWORKSPACE, TLORA_EARCH, TLORA_EHIP, TLORA_EALIGN = 0, -1, -2, -3, -4, -5, -6, -7
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("TLORA_LIB") or os.path.join(_HERE, "libtlora.so")

@@ -132,3 +132,69 @@ def test_header_is_plain_c():
                 f.write('#include "%s"\nint main(void) { tlora_problem_t p; (void)p; return sizeof(tlora_aimd_t) > 0 ? 0 : 1; }\n' % hdr)
             r = subprocess.run([cc, std, "-Wall", "-Werror", "-pedantic", "-fsyntax-only", src], capture_output=True, text=True)
             assert r.returncode == 0, r.stderr
+
+
+def _attn_struct(ranks, tokens, seq, d_model=256, n_heads=4, n_kv=2, head_dim=128, dtype=tlora.TLORA_BF16):
+    J = len(ranks)
+    off = np.concatenate([[0], np.cumsum(tokens)]).astype(np.int64)
+    keep = [(ctypes.c_int32 * J)(*ranks), (ctypes.c_int64 * (J + 1))(*[int(o) for o in off]), (ctypes.c_float * J)(*[1.0] * J),
+            (ctypes.c_int64 * len(seq))(*seq), (ctypes.c_void_p * J)(*[0x3000] * J)]
+    p = tlora.tlora_attn_t(dtype, J, d_model, n_heads, n_kv, head_dim, 10000.0, 1e-5, keep[0], keep[1], keep[2],
+                           len(seq) - 1, keep[3], 0x1000, 0x2000, 0x5000, 0x6000, 0x7000, 0x8000, *([keep[4]] * 8))
+    return p, keep
+
+
+def test_attention_arguments_are_checked_on_the_host():
+    """Workspace sizing and argument validation of the attention entry points touch no device."""
+    L = tlora.lib()
+    seq = (ctypes.c_int64 * 3)(0, 100, 300)
+    small = L.tlora_attention_workspace_bytes(2, seq, 4)
+    assert small > 0 and small % 256 == 0
+    # grows with tokens x heads (the fp32 row statistics of the backward) and with the longest sequence (rotary table)
+    seq2 = (ctypes.c_int64 * 3)(0, 1000, 3000)
+    assert L.tlora_attention_workspace_bytes(2, seq2, 4) > small
+    assert L.tlora_attention_workspace_bytes(2, seq, 0) == 0                      # no heads
+    assert L.tlora_attention_workspace_bytes(2, (ctypes.c_int64 * 3)(0, 300, 100), 4) == 0   # offsets go down
+    assert L.tlora_attention_workspace_bytes(2, (ctypes.c_int64 * 3)(1, 100, 300), 4) == 0   # do not start at 0
+    ws = ctypes.c_void_p(0x10000)
+    args = lambda hq, hkv, hd: (ctypes.c_void_p(0x1000), ctypes.c_void_p(0x2000), ctypes.c_void_p(0x3000), ctypes.c_void_p(0x4000),
+                                ctypes.c_void_p(0x5000), 2, seq, hq, hkv, hd, ws, ctypes.c_size_t(1 << 40), None)
+    assert L.tlora_attention_fwd(*args(4, 2, 64)) == tlora.TLORA_EINVAL            # head size
+    assert L.tlora_attention_fwd(*args(3, 2, 128)) == tlora.TLORA_EINVAL           # heads not a multiple
+    a = list(args(4, 2, 128)); a[11] = ctypes.c_size_t(16)
+    assert L.tlora_attention_fwd(*a) == tlora.TLORA_EWORKSPACE
+    a = list(args(4, 2, 128)); a[0] = None
+    assert L.tlora_attention_fwd(*a) == tlora.TLORA_ENULL
+    a = list(args(4, 2, 128)); a[1] = ctypes.c_void_p(0x2008)
+    assert L.tlora_attention_fwd(*a) == tlora.TLORA_EALIGN
+    assert L.tlora_rope(ctypes.c_void_p(0x1000), 2, seq, 4, 128, ctypes.c_float(0.5), 0, ws, ctypes.c_size_t(1 << 40), None) \
+        == tlora.TLORA_EINVAL                                                       # rotary base must exceed 1
+
+
+def test_block_and_layer_structs_are_checked_on_the_host():
+    L = tlora.lib()
+    p, keep = _attn_struct([8, 4], [96, 64], [0, 96, 160])
+    need = L.tlora_attn_workspace_bytes(ctypes.byref(p))
+    assert need > 0
+    bad, _k = _attn_struct([8, 4], [96, 64], [0, 96, 150])                          # sequences cover 150 of 160 tokens
+    assert L.tlora_attn_workspace_bytes(ctypes.byref(bad)) == 0
+    bad, _k = _attn_struct([8, 4], [96, 64], [0, 96, 160], dtype=tlora.TLORA_F32)    # bf16 only
+    assert L.tlora_attn_workspace_bytes(ctypes.byref(bad)) == 0
+    bad, _k = _attn_struct([8, 4], [96, 64], [0, 96, 160], n_heads=4, n_kv=3)
+    assert L.tlora_attn_workspace_bytes(ctypes.byref(bad)) == 0
+    assert L.tlora_attn_fwd(ctypes.byref(p), ctypes.c_void_p(0x9000), ctypes.c_void_p(0x10000), ctypes.c_size_t(need - 1), None) \
+        == tlora.TLORA_EWORKSPACE
+    # a layer needs both halves on the same jobs
+    J = 2
+    mlp = tlora.tlora_mlp_t(tlora.TLORA_BF16, J, 256, 512, keep[0], keep[1], keep[2], None, 0x2000, 1e-5, 0x5000, 0x6000, 0x7000,
+                            *([keep[4]] * 6))
+    layer = tlora.tlora_layer_t(p, mlp)
+    total = L.tlora_layer_workspace_bytes(ctypes.byref(layer))
+    assert total > need
+    other = (ctypes.c_int32 * J)(8, 16)                                              # ranks differ between the halves
+    mlp2 = tlora.tlora_mlp_t(tlora.TLORA_BF16, J, 256, 512, other, keep[1], keep[2], None, 0x2000, 1e-5, 0x5000, 0x6000, 0x7000,
+                             *([keep[4]] * 6))
+    assert L.tlora_layer_workspace_bytes(ctypes.byref(tlora.tlora_layer_t(p, mlp2))) == 0
+    mlp3 = tlora.tlora_mlp_t(tlora.TLORA_BF16, J, 128, 512, keep[0], keep[1], keep[2], None, 0x2000, 1e-5, 0x5000, 0x6000, 0x7000,
+                             *([keep[4]] * 6))                                       # d_model differs
+    assert L.tlora_layer_workspace_bytes(ctypes.byref(tlora.tlora_layer_t(p, mlp3))) == 0
