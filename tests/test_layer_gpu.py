@@ -161,3 +161,50 @@ def test_decoder_layer_training_steps_follow_the_oracle():
     print("loss oracle", [round(x, 2) for x in loss_r], "gpu", [round(x, 2) for x in loss_g])
     assert all(b < a for a, b in zip(loss_g[:-1], loss_g[1:])), loss_g
     assert all(abs(a - b) <= 1e-2 * b for a, b in zip(loss_g, loss_r)), (loss_g, loss_r)
+
+
+def test_fused_decoder_layer_equals_each_job_alone():
+    """Sec. 3.2: the shared super-model is functionally equivalent to training each job independently.  A layer run
+    on two jobs together gives, for each job, exactly the outputs, input gradients and adapter gradients of that job
+    run alone (same kernels, same order of every sum), bit for bit."""
+    import torch
+    from paper_2602_07263_amd import tlora
+    d, dff, Hq, Hkv = 256, 384, 4, 2
+    ranks, tokens, scales = [8, 20], [256, 300], [2.0, 0.5]        # job 0 ends on a row-tile boundary of the GEMM
+    seqs = [[0, 100, 256], [0, 300]]                               # per job, relative to its first token
+    g = torch.Generator(device="cuda"); g.manual_seed(5)
+    bf = torch.bfloat16
+    rn = lambda *sh, std=1.0: (torch.randn(*sh, device="cuda", generator=g) * std).to(bf)
+    shapes = dict(q=(d, Hq * HD), k=(d, Hkv * HD), v=(d, Hkv * HD), o=(Hq * HD, d), gate=(d, dff), up=(d, dff), down=(dff, d))
+    W = {n: rn(i, o, std=i ** -0.5) for n, (i, o) in shapes.items()}
+    A = {n: [rn(i, r, std=i ** -0.5) for r in ranks] for n, (i, o) in shapes.items()}
+    B = {n: [rn(r, o, std=0.05) for r in ranks] for n, (i, o) in shapes.items()}
+    T = sum(tokens)
+    X, dOut = rn(T, d), rn(T, d)
+    gam = torch.ones(d, device="cuda", dtype=bf)
+
+    def run(jobs, rows):
+        off = [0]
+        seq = [0]
+        for j in jobs:
+            seq += [off[-1] + s for s in seqs[j][1:]]
+            off.append(off[-1] + tokens[j])
+        tl = {n: (W[n], [A[n][j] for j in jobs], [B[n][j] for j in jobs]) for n in shapes}
+        Xs, dOs = X[rows].contiguous(), dOut[rows].contiguous()
+        layer = tlora.DecoderLayer(d, dff, Hq, Hkv, 10000.0, [ranks[j] for j in jobs], off, [scales[j] for j in jobs], seq,
+                                   Xs, gam, gam, 1e-5, tl)
+        Out, dX, grads = torch.empty_like(Xs), torch.empty_like(Xs), layer.new_grads()
+        layer.fwd(Out)
+        layer.bwd(dOs, dX, grads)
+        torch.cuda.synchronize()
+        return Out, dX, grads
+    Out_f, dX_f, g_f = run([0, 1], slice(0, T))
+    lo = 0
+    for j in (0, 1):
+        rows = slice(lo, lo + tokens[j])
+        Out_s, dX_s, g_s = run([j], rows)
+        assert torch.equal(Out_f[rows].view(torch.int16), Out_s.view(torch.int16)), f"Out of job {j}"
+        assert torch.equal(dX_f[rows].view(torch.int16), dX_s.view(torch.int16)), f"dX of job {j}"
+        for n in shapes:
+            assert torch.equal(g_f[n][0][j], g_s[n][0][0]) and torch.equal(g_f[n][1][j], g_s[n][1][0]), (n, j)
+        lo += tokens[j]
