@@ -208,3 +208,59 @@ def test_fused_decoder_layer_equals_each_job_alone():
         for n in shapes:
             assert torch.equal(g_f[n][0][j], g_s[n][0][0]) and torch.equal(g_f[n][1][j], g_s[n][1][0]), (n, j)
         lo += tokens[j]
+
+
+def test_decoder_layer_at_bench_shape_sampled_jobs():
+    """The decoder-layer leg's full shape (cfg3: 16 jobs, 83 968 tokens in sequences of 2048, d_model 4096, 32 / 8 heads,
+    d_ff 12288), launched as bench.py launches it.  Jobs whose batch is a single sequence are independent of every
+    other row of the batch, so the oracle can run them alone: their rows of Out and dX and their complete dA_j / dB_j
+    of all seven projections are compared with the fused run."""
+    import torch
+    from paper_2602_07263_amd import tlora
+    wl = wk.config(3)
+    d, dff, Hq, Hkv, n = 4096, 12288, 32, 8, 2048
+    T = wl.total_tokens
+    g = torch.Generator(device="cuda"); g.manual_seed(0)
+    bf = torch.bfloat16
+    rn = lambda *shape, std=1.0: (torch.randn(*shape, device="cuda", generator=g) * std).to(bf)
+    shapes = dict(q=(d, Hq * HD), k=(d, Hkv * HD), v=(d, Hkv * HD), o=(Hq * HD, d), gate=(d, dff), up=(d, dff), down=(dff, d))
+    layers = {name: (rn(i, o, std=i ** -0.5), [((torch.rand(i, r, device="cuda", generator=g) * 2 - 1) / i ** 0.5).to(bf)
+                                                for r in wl.ranks], [rn(r, o, std=0.01) for r in wl.ranks])
+              for name, (i, o) in shapes.items()}
+    X, dOut = rn(T, d), rn(T, d)
+    gamma = torch.ones(d, device="cuda", dtype=bf)
+    base, eps = 500000.0, 1e-5
+    layer = tlora.DecoderLayer(d, dff, Hq, Hkv, base, wl.ranks, wl.offsets, wl.scales, list(range(0, T + 1, n)), X, gamma,
+                               gamma, eps, layers)
+    Out, dX, grads = torch.empty_like(X), torch.empty_like(X), layer.new_grads()
+    layer.fwd(Out)
+    layer.bwd(dOut, dX, grads)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(Out.float()).all()) and bool(torch.isfinite(dX.float()).all())
+    store = lambda a: wk.round_to_bf16(np.asarray(a, dtype=np.float32)).astype(np.float64)
+    tol = 2 * pu.BF16_TOL                           # two blocks chained (see test_decoder_layer_matches_oracle)
+
+    def ratio(got, ref):
+        got = np.asarray(got, dtype=np.float64)
+        assert np.all(np.isfinite(got))
+        m = max(1.0, float(np.sqrt(np.mean(ref * ref))))
+        return float(np.max(np.abs(got - ref) / (tol * (m + np.abs(ref)))))
+    f64 = lambda t: t.double().cpu().numpy()
+    worst = {}
+    singles = [j for j, t in enumerate(wl.tokens) if t == n]
+    for j in singles[-1:]:                           # the single-sequence job of the highest rank (64)
+        rows = slice(wl.offsets[j], wl.offsets[j + 1])
+        lay = {name: (f64(W), [f64(A[j])], [f64(B[j])]) for name, (W, A, B) in layers.items()}
+        attn = (f64(gamma), eps, {k_: lay[k_] for k_ in ("q", "k", "v", "o")})
+        mlp = (f64(gamma), eps, {k_: lay[k_] for k_ in ("gate", "up", "down")})
+        args = (attn, mlp, [wl.scales[j]], [0, n], [0, n], Hq, Hkv, HD, base)
+        out_r, _ = ly.forward(f64(X[rows]), *args, store)
+        dX_r, g_r = ly.backward(f64(X[rows]), *args, f64(dOut[rows]), store)
+        res = {"Out": ratio(f64(Out[rows]), out_r), "dX": ratio(f64(dX[rows]), dX_r)}
+        for name in shapes:
+            res["dA_" + name] = ratio(grads[name][0][j].cpu().numpy(), g_r[name][0][0])
+            res["dB_" + name] = ratio(grads[name][1][j].cpu().numpy(), g_r[name][1][0])
+        for k_, v_ in res.items():
+            worst[k_] = max(worst.get(k_, 0.0), v_)
+    print({k_: round(v_, 3) for k_, v_ in worst.items()})
+    assert all(v_ <= 1.0 for v_ in worst.values()), worst
