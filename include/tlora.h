@@ -363,7 +363,7 @@ int tlora_plan_dump(const tlora_problem_t* p, int32_t* rpad, int64_t* soff, int3
                     int32_t* tile_job_last, int64_t* n_tiles);
 
 /* Tuning knobs (process-wide, for experiments and for the tiling-independence tests).
- *   "shrink_rows"  : token rows per work unit of the shrink kernels        (64 | 128)
+ *   "shrink_rows"  : token rows per work unit of the shrink kernels        (0 = chosen per problem (default) | 32 | 64 | 128)
  *   "shrink_stages": LDS stages of the streaming shrink kernel             (4 | 8)
  *   "dx_transposed_w": 1 (default): dX runs against a transposed copy of W kept in the workspace | 0: against W
  *                    as it lies in memory (no copy, slower weight stream)

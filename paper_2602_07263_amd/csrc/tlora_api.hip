@@ -17,7 +17,7 @@ namespace tlora {
 namespace {
 
 struct Options {
-  int shrink_rows = 128;
+  int shrink_rows = 0;          // 0 = chosen per problem (32 | 64 | 128), else forced
   int shrink_stages = 4;
   int grad_tokens = 256;
   int dx_transposed_w = 1;
@@ -33,6 +33,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 struct Plan {
   int J = 0, T = 0, d_in = 0, d_out = 0, dtype = 0;
   int max_rpad = 0;
+  int shrink_rows = 128;                                // token rows per unit of the streaming shrink kernel
   std::vector<JobDev> jobs;
   std::vector<TileDev> tile_jobs;
   std::vector<ShrinkUnit> shrink_units;                 // generic kernel: 64 rows x 64 rank columns
@@ -177,6 +178,20 @@ int build_plan(const tlora_problem_t* p, Plan& pl) {
     }
   }
   if (pl.dtype == TLORA_BF16) {
+    // Rows per unit of the streaming shrink: 128 when that still gives enough workgroups for the 256 CUs, else 64, else
+    // 32 (a small batch would otherwise stream its activations through a few dozen CUs).  The 32-row kernel exists for
+    // K-steps of 64 only, and the units serve both the forward (K = d_in) and the backward (K = d_out) shrink.
+    {
+      auto count = [&](int rows) {
+        int64_t n = 0;
+        for (const JobDev& jb : pl.jobs)
+          if (jb.rpad > 0) n += (int64_t)((jb.row1 - jb.row0 + rows - 1) / rows) * ((jb.rpad + 127) / 128);
+        return n;
+      };
+      const bool can32 = pl.d_in % 64 == 0 && pl.d_out % 64 == 0;
+      if (g_opt.shrink_rows != 0) pl.shrink_rows = (g_opt.shrink_rows == 32 && !can32) ? 64 : g_opt.shrink_rows;
+      else pl.shrink_rows = count(128) >= 192 ? 128 : (count(64) >= 192 || !can32) ? 64 : 32;
+    }
     for (int j = 0; j < pl.J; ++j) {
       const JobDev& jb = pl.jobs[j];
       if (jb.rpad == 0) continue;
@@ -188,10 +203,10 @@ int build_plan(const tlora_problem_t* p, Plan& pl) {
           pl.shrink_units.push_back(u);
         }
       const int npb2 = (jb.rpad + 127) / 128;
-      for (int t0 = jb.row0; t0 < jb.row1; t0 += g_opt.shrink_rows)
+      for (int t0 = jb.row0; t0 < jb.row1; t0 += pl.shrink_rows)
         for (int pb = 0; pb < npb2; ++pb) {
           ShrinkUnit u;
-          u.job = j;  u.t0 = t0;  u.nrows = std::min(g_opt.shrink_rows, jb.row1 - t0);  u.pb = pb;
+          u.job = j;  u.t0 = t0;  u.nrows = std::min(pl.shrink_rows, jb.row1 - t0);  u.pb = pb;
           pl.stream_units.push_back(u);
         }
     }
@@ -351,7 +366,7 @@ void run_shrink(const Plan& pl, const uint8_t* tb, const JobDev* jobs, const Til
                 const uint16_t* packed, bool packed_is_atp, uint16_t* hi, uint16_t* lo, uint16_t* Sx, hipStream_t st) {
   if (K % 32 == 0)
     launch_shrink_stream(jobs, tiles, reinterpret_cast<const ShrinkUnit*>(tb + pl.tb_stream),
-                         (int)pl.stream_units.size(), g_opt.shrink_rows, g_opt.shrink_stages, act, K, packed, packed_is_atp,
+                         (int)pl.stream_units.size(), pl.shrink_rows, g_opt.shrink_stages, act, K, packed, packed_is_atp,
                          hi, lo, Sx, st);
   else
     launch_shrink(jobs, tiles, reinterpret_cast<const ShrinkUnit*>(tb + pl.tb_shrink), (int)pl.shrink_units.size(), 64,
@@ -1541,7 +1556,7 @@ int tlora_set_option(const char* name, int64_t value) {
   if (!name) return TLORA_ENULL;
   const std::string n(name);
   if (n == "shrink_rows") {
-    if (value != 64 && value != 128) return TLORA_EINVAL;
+    if (value != 0 && value != 32 && value != 64 && value != 128) return TLORA_EINVAL;
     g_opt.shrink_rows = (int)value;
     return TLORA_OK;
   }

@@ -588,6 +588,8 @@ void launch_shrink_stream(const JobDev* jobs, const TileDev* tiles, const Shrink
     if (wide)             TLORA_SHRINK_LAUNCH(128, 4, 64);
     else if (stages >= 8) TLORA_SHRINK_LAUNCH(128, 8, 32);
     else                  TLORA_SHRINK_LAUNCH(128, 4, 32);
+  } else if (shrink_rows == 32 && K % 64 == 0) {      // the planner asks for 32 rows only when K % 64 == 0
+    TLORA_SHRINK_LAUNCH(32, 4, 64);
   } else {
     if (wide)             TLORA_SHRINK_LAUNCH(64, 4, 64);
     else if (stages >= 8) TLORA_SHRINK_LAUNCH(64, 8, 32);

@@ -100,12 +100,14 @@ def test_full_size_configs_sampled(cfg, proj):
     _assert_ok(pu.compare(p, Y, dX, dA, dB, rows=rows), f"cfg{cfg}/{wl.projections[proj].name}")
 
 
-DEFAULT_OPTIONS = {"dx_transposed_w": 1, "shrink_rows": 128, "shrink_stages": 4, "grad_tokens": 256}
+DEFAULT_OPTIONS = {"dx_transposed_w": 1, "shrink_rows": 0, "shrink_stages": 4, "grad_tokens": 256}
 TILINGS = [
     {"dx_transposed_w": 0},
     {"shrink_rows": 64, "shrink_stages": 8},
     {"grad_tokens": 64},
     {"grad_tokens": 2048, "shrink_rows": 64},
+    {"shrink_rows": 32},
+    {"shrink_rows": 128},
 ]
 
 
