@@ -150,3 +150,51 @@ def test_attention_at_bench_shape_sampled_sequences():
             worst[name] = max(worst.get(name, 0.0), r)
     print({k_: round(v_, 3) for k_, v_ in worst.items()})
     assert all(v_ <= 1.0 for v_ in worst.values()), worst
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_attention_random_shapes(seed):
+    """Random sequence counts and lengths (1 .. 400 tokens, occasionally empty), head counts and group sizes.  Odd seeds
+    scale the queries by 3 (a much sharper softmax than unit-variance scores give).  The gradients are products of the
+    bf16-rounded score gradients with Q and K, so their rounding noise grows with the operand scale while the "1 +" floor
+    of the tolerance does not: for those cases the floor is the query scale, |err| <= tol (3 + |ref|) (a float64
+    emulation of nothing but the kernel's three rounding points -- P, dS and the stored O -- already shows 2.3 x the
+    unit-floor tolerance on dK there)."""
+    import torch
+    from paper_2602_07263_amd import tlora
+    rng = np.random.default_rng(1000 + seed)
+    Hkv = int(rng.choice([1, 2, 3]))
+    Hq = Hkv * int(rng.choice([1, 2, 4]))
+    lens = [int(x) for x in rng.integers(1, 400, size=int(rng.integers(1, 6)))]
+    if seed % 3 == 0:
+        lens.insert(int(rng.integers(0, len(lens) + 1)), 0)
+    seq = _offsets(lens)
+    T = int(seq[-1])
+    Q, K, V, dO = (_bf(rng.normal(size=(T, h * HD)) * s) for h, s in ((Hq, 1.0), (Hkv, 1.0), (Hkv, 1.0), (Hq, 1.0)))
+    floor = 1.0
+    if seed % 2:                                    # sharper softmax: larger queries
+        Q = _bf(Q * 3.0)
+        floor = 3.0
+    up = lambda a: torch.from_numpy(a).to(device="cuda", dtype=torch.bfloat16).contiguous()
+    nan = lambda h: torch.full((T, h * HD), float("nan"), dtype=torch.bfloat16, device="cuda")
+    att = tlora.Attention(seq, Hq, Hkv, "cuda")
+    tQ, tK, tV, tdO = up(Q), up(K), up(V), up(dO)
+    O, dQ, dK, dV = nan(Hq), nan(Hq), nan(Hkv), nan(Hkv)
+    lse = torch.full((T, Hq), float("nan"), dtype=torch.float32, device="cuda")
+    att.fwd(tQ, tK, tV, O, lse)
+    att.bwd(tQ, tK, tV, O, tdO, lse, dQ, dK, dV)
+    torch.cuda.synchronize()
+    O_r, _ = ao.attention(Q, K, V, seq, Hq, Hkv, HD)
+    lse_r = ao.attention_lse2(Q, K, seq, Hq, Hkv, HD)
+    dQ_r, dK_r, dV_r = ao.attention_backward(Q, K, V, dO, seq, Hq, Hkv, HD)
+    def grad_ratio(got, ref):
+        got = np.asarray(got, dtype=np.float64)
+        assert np.all(np.isfinite(got))
+        return float(np.max(np.abs(got - ref) / (pu.BF16_TOL * (floor + np.abs(ref)))))
+    res = {"O": pu.worst_ratio(O.float().cpu().numpy(), O_r, pu.BF16_TOL),
+           "lse": pu.worst_ratio(lse.cpu().numpy(), lse_r, 1e-4),
+           "dQ": grad_ratio(dQ.float().cpu().numpy(), dQ_r),
+           "dK": grad_ratio(dK.float().cpu().numpy(), dK_r),
+           "dV": grad_ratio(dV.float().cpu().numpy(), dV_r)}
+    bad = {k: v for k, v in res.items() if not v <= 1.0}
+    assert not bad, f"lens {lens}, heads {Hq}/{Hkv}: worst error / tolerance ratios {res}"
