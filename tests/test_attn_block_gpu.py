@@ -11,6 +11,11 @@ from tests import parity_util as pu
 
 pytestmark = pytest.mark.gpu
 HD = 128
+# Every path through the block crosses two fused layers (q / k / v, then o), each with the layer's error budget, and an
+# attention between them whose matrix units take bf16 probabilities and score gradients: the budgets add.  (Measured:
+# the worst ratio against one budget lies between 0.7 and 1.2 over the shapes below; a float64 run of the oracle
+# against itself with the stored tensors disturbed by a few fp32 ulps -- rounding flips alone -- gives 0.1 to 0.8.)
+BLOCK_TOL = 2 * pu.BF16_TOL
 
 
 def _make(d, Hq, Hkv, ranks, tokens, seed):
@@ -55,7 +60,7 @@ def test_attn_block_matches_oracle():
     args = (gamma, eps, layers, scales, off, seq, Hq, Hkv, HD, base)
     out_r, _ = ao.block_forward(X, *args, store)
     dX_r, g_r = ao.block_backward(X, *args, dOut, store)
-    tol = pu.BF16_TOL
+    tol = BLOCK_TOL
 
     def ratio(got, ref):
         # |err| <= tol (m + |ref|), m = max(1, rms(ref)): the adapter gradients are token sums of products of tensors
@@ -117,3 +122,50 @@ def test_attn_block_gradient_accumulation():
         for k in (0, 1):
             for a, b in zip(once[n][k], grads[n][k]):
                 assert torch.equal(b, 2 * a), n
+
+
+@pytest.mark.parametrize("cfg", [(128, 2, 2, [1, 130], [129, 260], [0, 129, 130, 389]),
+                                 (384, 3, 1, [5, 0, 16], [64, 200, 7], [0, 64, 164, 264, 271]),
+                                 (512, 8, 2, [32], [515], [0, 515])],
+                         ids=["odd_ranks", "mqa_rank0_job", "one_job_long_seq"])
+def test_attn_block_other_shapes(cfg):
+    """Other model widths, head groupings (multi-head, multi-query, grouped), odd ranks (1, 130: two rank blocks),
+    a job without adapter, sequences that end off the tile edges."""
+    import torch
+    from paper_2602_07263_amd import tlora
+    d, Hq, Hkv, ranks, tokens, seq = cfg
+    scales = [1.5] * len(ranks)
+    eps, base = 1e-5, 10000.0
+    X, gamma, layers, off, dOut = _make(d, Hq, Hkv, ranks, tokens, seed=17)
+    up = lambda a: torch.from_numpy(a).to(device="cuda", dtype=torch.bfloat16).contiguous()
+    tl = {n: (up(W), [up(a) for a in A], [up(b) for b in B]) for n, (W, A, B) in layers.items()}
+    blk = tlora.AttnBlock(d, Hq, Hkv, base, ranks, off, scales, seq, up(X), up(gamma), eps, tl)
+    Out = torch.full((sum(tokens), d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    dX = torch.full_like(Out, float("nan"))
+    grads = blk.new_grads()
+    for n in grads:
+        for t in grads[n][0] + grads[n][1]:
+            t.fill_(float("nan"))
+    blk.fwd(Out)
+    blk.bwd(up(dOut), dX, grads)
+    torch.cuda.synchronize()
+    store = lambda a: wk.round_to_bf16(a.astype(np.float32)).astype(np.float64)
+    args = (gamma, eps, layers, scales, off, np.asarray(seq, dtype=np.int64), Hq, Hkv, HD, base)
+    out_r, _ = ao.block_forward(X, *args, store)
+    dX_r, g_r = ao.block_backward(X, *args, dOut, store)
+    tol = BLOCK_TOL
+
+    def ratio(got, ref):
+        if ref.size == 0:
+            return 0.0
+        got = np.asarray(got, dtype=np.float64)
+        assert np.all(np.isfinite(got))
+        m = max(1.0, float(np.sqrt(np.mean(ref * ref))))
+        return float(np.max(np.abs(got - ref) / (tol * (m + np.abs(ref)))))
+    res = {"Out": pu.worst_ratio(Out.float().cpu().numpy(), out_r, tol), "dX": pu.worst_ratio(dX.float().cpu().numpy(), dX_r, tol)}
+    for n in grads:
+        res["dA_" + n] = max([ratio(a.cpu().numpy(), r) for a, r in zip(grads[n][0], g_r[n][0])] + [0.0])
+        res["dB_" + n] = max([ratio(b.cpu().numpy(), r) for b, r in zip(grads[n][1], g_r[n][1])] + [0.0])
+    print({k: round(v, 3) for k, v in res.items()})
+    bad = {k: v for k, v in res.items() if not v <= 1.0}
+    assert not bad, f"worst error / tolerance ratios {res}"
