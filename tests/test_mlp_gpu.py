@@ -30,10 +30,13 @@ def _make(dtype, d, dff, ranks, tokens, scales, seed):
 
 
 CASES = [("bf16", 256, 640, [8, 0, 24, 3], [300, 0, 513, 70], [2.0, 1.0, 0.5, 4.0]),
-         ("f32", 64, 96, [4, 7], [50, 81], [2.0, 1.0])]
+         ("f32", 64, 96, [4, 7], [50, 81], [2.0, 1.0]),
+         ("bf16", 128, 384, [1, 130], [129, 260], [1.5, 1.5]),
+         ("bf16", 512, 1024, [32], [515], [1.0]),
+         ("bf16", 384, 200, [5, 0, 16], [64, 200, 7], [1.0, 1.0, 3.0])]
 
 
-@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+@pytest.mark.parametrize("case", CASES, ids=["bf16", "f32", "bf16_odd_ranks", "bf16_one_job", "bf16_narrow_ff"])
 def test_mlp_block_matches_oracle(case):
     import torch
     from paper_2602_07263_amd import tlora
@@ -55,7 +58,9 @@ def test_mlp_block_matches_oracle(case):
     store = (lambda a: wk.round_to_bf16(a.astype(np.float32)).astype(np.float64)) if dtype == "bf16" else (lambda a: a)
     out_r, _ = mo.forward(X, gamma, 1e-5, layers, scales, off, store)
     dX_r, g_r = mo.backward(X, gamma, 1e-5, layers, scales, off, dOut, store)
-    tol = pu.BF16_TOL if dtype == "bf16" else 2e-5      # fp32: three chained fp32 layers and two fp32 glue stages
+    # bf16: every path crosses two fused layers (gate / up, then down), each with the layer's budget: the budgets add
+    # (measured against one budget: 0.25 - 1.0 over the shapes above).  fp32: chained fp32 layers and glue stages.
+    tol = 2 * pu.BF16_TOL if dtype == "bf16" else 2e-5
 
     def ratio(got, ref):
         # |err| <= tol (m + |ref|) with m = max(1, rms(ref)).  Out and dX have rms ~ 1, so this is the layer's bound.
