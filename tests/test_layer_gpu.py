@@ -12,12 +12,17 @@ pytestmark = pytest.mark.gpu
 HD = 128
 
 
-def test_decoder_layer_matches_oracle():
+LAYER_CASES = [(256, 640, 4, 2, [8, 0, 24, 3], [300, 0, 513, 70], [2.0, 1.0, 0.5, 4.0], [0, 100, 300, 301, 600, 813, 883]),
+               (128, 384, 2, 2, [1, 130], [129, 260], [1.5, 1.5], [0, 129, 130, 389]),
+               (512, 1024, 8, 2, [32], [515], [1.0], [0, 515])]
+
+
+@pytest.mark.parametrize("case", LAYER_CASES, ids=["four_jobs", "odd_ranks", "one_job_long_seq"])
+def test_decoder_layer_matches_oracle(case):
     import torch
     from paper_2602_07263_amd import tlora
-    d, dff, Hq, Hkv = 256, 640, 4, 2
-    ranks, tokens, scales = [8, 0, 24, 3], [300, 0, 513, 70], [2.0, 1.0, 0.5, 4.0]
-    seq = np.array([0, 100, 300, 301, 600, 813, 883], dtype=np.int64)
+    d, dff, Hq, Hkv, ranks, tokens, scales, seq = case
+    seq = np.array(seq, dtype=np.int64)
     eps, base = 1e-5, 10000.0
     rng = np.random.default_rng(8)
     f = lambda a: wk.round_to_bf16(np.asarray(a, dtype=np.float32))
