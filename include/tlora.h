@@ -56,7 +56,8 @@ typedef enum {
   TLORA_EWORKSPACE = -4,  /* workspace NULL, misaligned or smaller than tlora_workspace_bytes()           */
   TLORA_EARCH = -5,       /* the current device is not gfx950                                             */
   TLORA_EHIP = -6,        /* a HIP runtime call failed                                                    */
-  TLORA_EALIGN = -7       /* X / W / Y / dY / dX not 16-byte aligned                                      */
+  TLORA_EALIGN = -7,      /* X / W / Y / dY / dX not 16-byte aligned                                      */
+  TLORA_ESCRATCH = -8     /* tlora_fwd_noalloc: the problem needs more than the static scratch holds      */
 } tlora_status_t;
 
 /* Problem statement of one fused layer call (Sec. 3.2 / 3.3: shared frozen backbone, per-job adapters
@@ -86,6 +87,23 @@ size_t tlora_workspace_bytes(const tlora_problem_t* p);
  * tlora_bwd on the same problem (same A_j, B_j values), workspace and stream may reuse
  * (TLORA_BWD_REUSE_S). */
 int tlora_fwd(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_bytes, void* hip_stream);
+
+/* tlora_fwd for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and results as tlora_fwd
+ * (bit-identical Y), but the forward's intermediates (plan tables, S_j, the packed adapters) live in a device array
+ * of TLORA_NOALLOC_SCRATCH_BYTES that is part of the library image; every GPU the library runs on holds it until the
+ * process ends.  The call allocates nothing -- no hipMalloc / hipFree / hipHostMalloc, no event or stream creation,
+ * no allocating library routine -- and records no copy or memset: the plan tables travel as kernel arguments and
+ * everything that must start at zero is cleared by store kernels on `hip_stream`.
+ *   Limits: the forward-only workspace of the problem (about 4 sum_j T_j r_j + 2 * 256 ceil(T / 256) * (padded
+ *   ranks met per 256-row tile) + 6 (sum_j r_j + 32) (d_in + d_out) bytes + tables) must fit in
+ *   TLORA_NOALLOC_SCRATCH_BYTES and its plan tables in 224 KB; otherwise TLORA_ESCRATCH, and nothing is launched.
+ *   The scratch keeps the last call's contents and is shared by every call on that GPU: calls that overlap on one
+ *   GPU (two streams, two host threads) race; order them on one stream.  There is no matching backward: S_j
+ *   does not outlive the next call (tlora_bwd without TLORA_BWD_REUSE_S recomputes it in its own workspace).
+ *   The address of the array on the current device is looked up on the first call on that device. */
+#define TLORA_NOALLOC_SCRATCH_BYTES (16u << 20)
+int tlora_fwd_noalloc(const tlora_problem_t* p, void* Y, void* hip_stream);
 
 /* flags for tlora_bwd */
 #define TLORA_BWD_REUSE_S 1   /* the workspace still holds S_j and the packed adapters from tlora_fwd of this same

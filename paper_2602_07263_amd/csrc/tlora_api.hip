@@ -13,8 +13,32 @@
 #include "tlora_internal.h"
 #include "tlora_kernels.h"
 
+// Device memory of tlora_fwd_noalloc: the forward's workspace for callers that cannot allocate.  Every GPU the
+// library runs on holds its own copy of this array at its own address until the process ends.  In host code the
+// name is only a handle for hipGetSymbolAddress: the address that kernels and fills get is the per-device pointer
+// looked up below, never the name.
+static __device__ __align__(256) unsigned char scratch[TLORA_NOALLOC_SCRATCH_BYTES];
+
 namespace tlora {
 namespace {
+
+constexpr int kMaxDevices = 64;
+constexpr size_t kNoAllocMaxTableBytes = 64 * 3584;   // plan tables of tlora_fwd_noalloc: at most 64 argument chunks
+uint8_t* g_scratch_ptr[kMaxDevices] = {};   // per device: address of `scratch` on that device (0 = not looked up yet)
+
+// Address of the static scratch array on the current device (looked up once per device, with that device current).
+int scratch_of_current_device(uint8_t** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return TLORA_EHIP;
+  if (dev < 0 || dev >= kMaxDevices) return TLORA_EINVAL;
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return TLORA_EHIP;
+    g_scratch_ptr[dev] = static_cast<uint8_t*>(ptr);
+  }
+  *out = g_scratch_ptr[dev];
+  return TLORA_OK;
+}
 
 struct Options {
   int shrink_rows = 0;          // 0 = chosen per problem (32 | 64 | 128), else forced
@@ -131,7 +155,8 @@ void build_grad_units(const Plan& pl, int D, std::vector<GradUnit>& units, std::
   });
 }
 
-int build_plan(const tlora_problem_t* p, Plan& pl) {
+// fwd_only: tables and workspace of the forward alone (no transposed W, no dS, no dA / dB units or partial tiles)
+int build_plan(const tlora_problem_t* p, Plan& pl, bool fwd_only = false) {
   const int rc = validate(p);
   if (rc != TLORA_OK) return rc;
   pl.J = p->num_jobs;  pl.T = (int)p->offsets[p->num_jobs];  pl.d_in = p->d_in;  pl.d_out = p->d_out;
@@ -210,8 +235,10 @@ int build_plan(const tlora_problem_t* p, Plan& pl) {
           pl.stream_units.push_back(u);
         }
     }
-    build_grad_units(pl, pl.d_out, pl.gradB_units, pl.gradB_groups, pl.gradB_partial);
-    build_grad_units(pl, pl.d_in, pl.gradA_units, pl.gradA_groups, pl.gradA_partial);
+    if (!fwd_only) {
+      build_grad_units(pl, pl.d_out, pl.gradB_units, pl.gradB_groups, pl.gradB_partial);
+      build_grad_units(pl, pl.d_in, pl.gradA_units, pl.gradA_groups, pl.gradA_partial);
+    }
   }
 
   // table blob
@@ -247,26 +274,28 @@ int build_plan(const tlora_problem_t* p, Plan& pl) {
   auto wplace = [&](size_t bytes) { const size_t at = w;  w = align_up(w + bytes, 256);  return at; };
   // the transposed W first: its place depends on nothing but d_in x d_out, so a copy made by one call is found
   // by later calls on other token batches (nano-batches) that share the workspace
-  if (pl.dtype == TLORA_BF16) pl.off_wt = wplace(2 * (size_t)pl.d_in * (size_t)pl.d_out);
+  if (pl.dtype == TLORA_BF16 && !fwd_only) pl.off_wt = wplace(2 * (size_t)pl.d_in * (size_t)pl.d_out);
   pl.off_tables = wplace(pl.tables_bytes);
   pl.off_clock = wplace(64);
   if (pl.dtype == TLORA_F32) {
     pl.off_S = wplace(sizeof(float) * (size_t)pl.s_elems);
-    pl.off_dS = wplace(sizeof(float) * (size_t)pl.s_elems);
+    if (!fwd_only) pl.off_dS = wplace(sizeof(float) * (size_t)pl.s_elems);
   }
   if (pl.dtype == TLORA_BF16) {
     pl.off_Shi = wplace(2 * (size_t)pl.s_elems);
     pl.off_Slo = wplace(2 * (size_t)pl.s_elems);
-    pl.off_dShi = wplace(2 * (size_t)pl.s_elems);
-    pl.off_dSlo = wplace(2 * (size_t)pl.s_elems);
+    if (!fwd_only) {
+      pl.off_dShi = wplace(2 * (size_t)pl.s_elems);
+      pl.off_dSlo = wplace(2 * (size_t)pl.s_elems);
+    }
     // + 256: a 64-wide K-step over a last 32-wide slice reads (and ignores) 64 bytes past each operand row
     pl.off_Sx = wplace(2 * (size_t)pl.sx_elems + 256);
-    pl.off_dSx = wplace(2 * (size_t)pl.sx_elems + 256);
+    if (!fwd_only) pl.off_dSx = wplace(2 * (size_t)pl.sx_elems + 256);
     pl.off_atp = wplace(2 * ((size_t)pl.atp_elems + 32 * (size_t)pl.d_in));
 
     pl.off_ap = wplace(2 * (size_t)pl.d_in * (size_t)(pl.r_total + 32));
     pl.off_bp = wplace(2 * (size_t)pl.d_out * (size_t)(pl.r_total + 32));
-    pl.off_partial = wplace(sizeof(float) * (size_t)std::max(pl.gradB_partial, pl.gradA_partial));
+    if (!fwd_only) pl.off_partial = wplace(sizeof(float) * (size_t)std::max(pl.gradB_partial, pl.gradA_partial));
   }
   pl.total = std::max<size_t>(w, 256);
   return TLORA_OK;
@@ -334,7 +363,7 @@ struct Timed {
   hipStream_t st;
   Pending p{};
   bool on;
-  Timed(int cls, hipStream_t s) : st(s), on(g_prof_on) {
+  Timed(int cls, hipStream_t s, bool enable = true) : st(s), on(g_prof_on && enable) {
     if (!on) return;
     p.cls = cls;  p.a = prof_event();  p.b = prof_event();
     if (!p.a || !p.b) { on = false; return; }
@@ -424,6 +453,7 @@ F32Unit f32_unit(const float* A, int64_t a_rs, int64_t a_cs, const float* B, int
 struct F32Launch {
   size_t units_at[2], tiles_at[2];
   int ntiles[2];
+  size_t end;               // the blob is used up to here
 };
 int f32_place(const Plan& pl, std::vector<uint8_t>& blob, std::vector<F32Unit> units[2], std::vector<F32Tile> tiles[2],
               F32Launch& L) {
@@ -437,6 +467,7 @@ int f32_place(const Plan& pl, std::vector<uint8_t>& blob, std::vector<F32Unit> u
     L.ntiles[i] = (int)tiles[i].size();
   }
   if (o > pl.tb_f32 + pl.f32_reserved) return TLORA_EWORKSPACE;
+  L.end = o;
   for (int i = 0; i < 2; ++i) {
     put(blob, L.units_at[i], units[i]);
     put(blob, L.tiles_at[i], tiles[i]);
@@ -444,13 +475,15 @@ int f32_place(const Plan& pl, std::vector<uint8_t>& blob, std::vector<F32Unit> u
   return TLORA_OK;
 }
 
-int common_checks(const tlora_problem_t* p, Plan& pl, void* ws, size_t ws_bytes) {
-  int rc = build_plan(p, pl);
+// static_scratch: the "workspace" is the library's static scratch array and only the forward will run
+int common_checks(const tlora_problem_t* p, Plan& pl, void* ws, size_t ws_bytes, bool static_scratch = false) {
+  int rc = build_plan(p, pl, static_scratch);
   if (rc != TLORA_OK) return rc;
   if ((pl.T > 0 && !p->X) || !p->W || !p->A || !p->B) return TLORA_ENULL;
   for (int j = 0; j < pl.J; ++j)
     if (pl.jobs[j].rank > 0 && (!p->A[j] || !p->B[j])) return TLORA_ENULL;
   if (misaligned16(p->X) || misaligned16(p->W)) return TLORA_EALIGN;
+  if (static_scratch && ws_bytes < pl.total) return TLORA_ESCRATCH;
   if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255) || ws_bytes < pl.total) return TLORA_EWORKSPACE;
   for (int j = 0; j < pl.J; ++j) {
     pl.jobs[j].A = p->A[j];
@@ -473,10 +506,17 @@ size_t tlora_workspace_bytes(const tlora_problem_t* p) {
   return pl.total;
 }
 
-int tlora_fwd(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_bytes, void* hip_stream) {
-  std::lock_guard<std::recursive_mutex> lk(g_mu);
+}  // extern "C"
+
+namespace tlora {
+namespace {
+// The forward's launch sequence.  no_alloc: the workspace is the static device scratch (`workspace` = its address on
+// the current device, `ws_bytes` = its size); the plan and the workspace layout are the forward's alone, the tables
+// reach the device as kernel arguments (no staging buffer, no copy node), and nothing is timed: no HIP object is
+// created and no memory of any kind is allocated on this path.
+int fwd_impl(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_bytes, void* hip_stream, bool no_alloc) {
   Plan pl;
-  int rc = common_checks(p, pl, workspace, ws_bytes);
+  int rc = common_checks(p, pl, workspace, ws_bytes, no_alloc);
   if (rc != TLORA_OK) return rc;
   if (pl.T > 0 && !Y) return TLORA_ENULL;
   if (misaligned16(Y)) return TLORA_EALIGN;
@@ -488,6 +528,13 @@ int tlora_fwd(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_byte
   uint8_t* tb = ws + pl.off_tables;
   std::vector<uint8_t> blob = make_blob(pl);
   const JobDev* jobs = reinterpret_cast<const JobDev*>(tb + pl.tb_jobs);
+  const bool timed = g_prof_on && !no_alloc;
+  auto upload = [&](size_t used) {
+    if (!no_alloc) return upload_tables(blob, tb, st);
+    if (used > kNoAllocMaxTableBytes) return (int)TLORA_ESCRATCH;
+    launch_table_write(blob.data(), used, tb, st);
+    return (int)TLORA_OK;
+  };
 
   if (pl.dtype == TLORA_F32) {
     float* S = reinterpret_cast<float*>(ws + pl.off_S);
@@ -512,17 +559,17 @@ int tlora_fwd(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_byte
     F32Launch L;
     rc = f32_place(pl, blob, units, tiles, L);
     if (rc != TLORA_OK) return rc;
-    rc = upload_tables(blob, tb, st);
+    rc = upload(L.end);
     if (rc != TLORA_OK) return rc;
     for (int i = 0; i < 2; ++i) {
-      Timed t(TLORA_K_F32, st);
+      Timed t(TLORA_K_F32, st, timed);
       launch_f32_units(reinterpret_cast<const F32Unit*>(tb + L.units_at[i]),
                        reinterpret_cast<const F32Tile*>(tb + L.tiles_at[i]), L.ntiles[i], st);
     }
     return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
   }
 
-  rc = upload_tables(blob, tb, st);
+  rc = upload(pl.tables_bytes);
   if (rc != TLORA_OK) return rc;
   uint16_t* Sx = reinterpret_cast<uint16_t*>(ws + pl.off_Sx);
   uint16_t* atp = reinterpret_cast<uint16_t*>(ws + pl.off_atp);
@@ -530,21 +577,38 @@ int tlora_fwd(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_byte
   uint16_t* bp = reinterpret_cast<uint16_t*>(ws + pl.off_bp);
   const TileDev* tiles = reinterpret_cast<const TileDev*>(tb + pl.tb_tiles);
   {
-    Timed t(TLORA_K_PACK, st);
+    Timed t(TLORA_K_PACK, st, timed);
     launch_pack_adapters(jobs, pl.J, pl.d_in, pl.d_out, pl.max_rpad, pl.r_total, atp, ap, bp, st);
     launch_zero_fill(Sx, 2 * (size_t)pl.sx_elems, st);
   }
   {
-    Timed t(TLORA_K_SHRINK, st);
+    Timed t(TLORA_K_SHRINK, st, timed);
     run_shrink(pl, tb, jobs, tiles, static_cast<const uint16_t*>(p->X), pl.d_in, atp, true,
                reinterpret_cast<uint16_t*>(ws + pl.off_Shi), reinterpret_cast<uint16_t*>(ws + pl.off_Slo), Sx, st);
   }
-  if (g_prof_on) launch_zero_fill(ws + pl.off_clock, 16, st);
-  Timed tg(TLORA_K_GEMM_FWD, st);
+  if (timed) launch_zero_fill(ws + pl.off_clock, 16, st);
+  Timed tg(TLORA_K_GEMM_FWD, st, timed);
   launch_seg_gemm(true, tiles, static_cast<const uint16_t*>(p->X), static_cast<const uint16_t*>(p->W), Sx, bp,
-                  pl.r_total, static_cast<uint16_t*>(Y), g_out_index, pl.T, pl.d_in, pl.d_out,
-                  g_prof_on ? (g_clock_slot[0] = reinterpret_cast<unsigned long long*>(ws + pl.off_clock)) : nullptr, st);
+                  pl.r_total, static_cast<uint16_t*>(Y), no_alloc ? nullptr : g_out_index, pl.T, pl.d_in, pl.d_out,
+                  timed ? (g_clock_slot[0] = reinterpret_cast<unsigned long long*>(ws + pl.off_clock)) : nullptr, st);
   return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+}
+}  // namespace
+}  // namespace tlora
+
+extern "C" {
+
+int tlora_fwd(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_bytes, void* hip_stream) {
+  std::lock_guard<std::recursive_mutex> lk(g_mu);
+  return fwd_impl(p, Y, workspace, ws_bytes, hip_stream, false);
+}
+
+int tlora_fwd_noalloc(const tlora_problem_t* p, void* Y, void* hip_stream) {
+  std::lock_guard<std::recursive_mutex> lk(g_mu);
+  uint8_t* ws = nullptr;
+  const int rc = scratch_of_current_device(&ws);
+  if (rc != TLORA_OK) return rc;
+  return fwd_impl(p, Y, ws, TLORA_NOALLOC_SCRATCH_BYTES, hip_stream, true);
 }
 
 int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* dA, void* const* dB, int flags,
@@ -1588,6 +1652,7 @@ const char* tlora_strerror(int status) {
     case TLORA_EARCH: return "the current device is not gfx950";
     case TLORA_EHIP: return "a HIP runtime call failed";
     case TLORA_EALIGN: return "X, W, Y, dY or dX is not 16-byte aligned";
+    case TLORA_ESCRATCH: return "problem too large for the static scratch of tlora_fwd_noalloc";
     default: return "unknown status";
   }
 }

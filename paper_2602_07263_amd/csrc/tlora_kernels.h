@@ -20,6 +20,10 @@ void launch_transpose_bf16(const uint16_t* in, uint16_t* out, int rows, int cols
 // Zero `bytes` (multiple of 16) of device memory with a plain store kernel.
 void launch_zero_fill(void* ptr, size_t bytes, hipStream_t st);
 
+// Copy `bytes` of HOST memory to device memory `dst` (4-byte aligned, room for bytes rounded up to 4) by value,
+// through the arguments of small store kernels: no staging buffer, no copy node, nothing allocated.
+void launch_table_write(const void* host_src, size_t bytes, void* dst, hipStream_t st);
+
 // out_j[t, p] = sum_k act[t, k] * P_j[p, k]   (P_j = A_j^T packed, or B_j packed)
 // writes the result as bf16 hi + lo planes (packed ragged layout, each job's rows zero padded to a multiple of
 // 32) and bf16 `scale_j * S` into the per-tile K-extension matrices `Sx`.

@@ -8,6 +8,7 @@
 // features of one token and stores them with one 8- or 16-byte access.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <string.h>
 
 #include <algorithm>
 
@@ -282,6 +283,30 @@ void launch_zero_fill(void* ptr, size_t bytes, hipStream_t st) {
   size_t blocks = (n16 + 255) / 256;
   if (blocks > 2048) blocks = 2048;
   hipLaunchKernelGGL(zero_fill_kernel, dim3((unsigned)blocks), dim3(256), 0, st, static_cast<u32x4*>(ptr), n16);
+}
+
+// Host tables -> device memory through kernel arguments: a launch carries up to kArgChunkWords 32-bit words by
+// value and its threads store them.  No staging buffer and no copy: usable where nothing may be allocated, and
+// under stream capture (the words are part of the recorded launch).
+constexpr int kArgChunkWords = 896;            // 3584 bytes: below the 4 KB of a launch's argument block
+struct ArgChunk {
+  uint32_t w[kArgChunkWords];
+};
+__global__ void __launch_bounds__(256) table_write_kernel(uint32_t* __restrict__ dst, const ArgChunk c, int n) {
+  for (int i = threadIdx.x; i < n; i += 256) dst[i] = c.w[i];
+}
+
+void launch_table_write(const void* host_src, size_t bytes, void* dst, hipStream_t st) {
+  const size_t words = (bytes + 3) / 4;        // the destination is padded to 256 bytes by the planner
+  const uint8_t* src = static_cast<const uint8_t*>(host_src);
+  for (size_t w0 = 0; w0 < words; w0 += kArgChunkWords) {
+    ArgChunk c;
+    const size_t n = std::min<size_t>(kArgChunkWords, words - w0);
+    const size_t nbytes = std::min<size_t>(n * 4, bytes - w0 * 4);
+    memset(&c, 0, sizeof(c));
+    memcpy(c.w, src + w0 * 4, nbytes);
+    hipLaunchKernelGGL(table_write_kernel, dim3(1), dim3(256), 0, st, static_cast<uint32_t*>(dst) + w0, c, (int)n);
+  }
 }
 
 // ---------------------------------------------------------------------------------------------------

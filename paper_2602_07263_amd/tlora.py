@@ -16,6 +16,8 @@ TLORA_BWD_REUSE_S = 1
 TLORA_BWD_REUSE_WT = 2
 TLORA_BWD_ACCUMULATE = 4
 TLORA_OK, TLORA_EINVAL, TLORA_ENULL, TLORA_EDTYPE, TLORA_EWORKSPACE, TLORA_EARCH, TLORA_EHIP, TLORA_EALIGN = 0, -1, -2, -3, -4, -5, -6, -7
+TLORA_ESCRATCH = -8
+TLORA_NOALLOC_SCRATCH_BYTES = 16 << 20
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("TLORA_LIB") or os.path.join(_HERE, "libtlora.so")
@@ -88,7 +90,7 @@ class tlora_adamw_tensor_t(ctypes.Structure):
                 ("weight_decay", ctypes.c_float), ("step", ctypes.c_int32)]
 
 
-EXPORTS = ["tlora_workspace_bytes", "tlora_fwd", "tlora_bwd", "tlora_adamw_workspace_bytes", "tlora_adamw_step",
+EXPORTS = ["tlora_workspace_bytes", "tlora_fwd", "tlora_fwd_noalloc", "tlora_bwd", "tlora_adamw_workspace_bytes", "tlora_adamw_step",
            "tlora_mlp_workspace_bytes", "tlora_mlp_fwd", "tlora_mlp_bwd",
            "tlora_attention_workspace_bytes", "tlora_rope", "tlora_attention_fwd", "tlora_attention_bwd",
            "tlora_attn_workspace_bytes", "tlora_attn_fwd", "tlora_attn_bwd",
@@ -117,6 +119,8 @@ def lib() -> ctypes.CDLL:
     L.tlora_workspace_bytes.argtypes = [P]
     L.tlora_fwd.restype = ctypes.c_int
     L.tlora_fwd.argtypes = [P, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    L.tlora_fwd_noalloc.restype = ctypes.c_int
+    L.tlora_fwd_noalloc.argtypes = [P, ctypes.c_void_p, ctypes.c_void_p]
     L.tlora_bwd.restype = ctypes.c_int
     L.tlora_bwd.argtypes = [P, ctypes.c_void_p, ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p),
                             ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t,
@@ -272,6 +276,11 @@ def tlora_workspace_bytes(prob: tlora_problem_t) -> int:
 def tlora_fwd(prob: tlora_problem_t, Y_ptr: int, ws_ptr: int, ws_bytes: int, stream: int = 0) -> None:
     _check(lib().tlora_fwd(ctypes.byref(prob), ctypes.c_void_p(Y_ptr), ctypes.c_void_p(ws_ptr),
                            ctypes.c_size_t(ws_bytes), ctypes.c_void_p(stream)), "tlora_fwd")
+
+
+def tlora_fwd_noalloc(prob: tlora_problem_t, Y_ptr: int, stream: int = 0) -> None:
+    _check(lib().tlora_fwd_noalloc(ctypes.byref(prob), ctypes.c_void_p(Y_ptr), ctypes.c_void_p(stream)),
+           "tlora_fwd_noalloc")
 
 
 def tlora_bwd(prob: tlora_problem_t, dY_ptr: int, dX_ptr: int, dA_ptrs: Optional[Sequence[int]],
