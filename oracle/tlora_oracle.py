@@ -122,18 +122,6 @@ def padded_rank(r: int, granule: int = 8) -> int:
     return (int(r) + granule - 1) // granule * granule
 
 
-def packed_offsets(ranks: Sequence[int], offsets: Sequence[int], granule: int = 8, row_granule: int = 32) -> List[int]:
-    """Element offset of job j's block in the packed ragged intermediate:
-    sum_{i<j} ceil(T_i / row_granule) * row_granule * rpad_i  (each job's rows are padded to the token step)."""
-    out, acc = [], 0
-    for j, r in enumerate(ranks):
-        out.append(acc)
-        rows = int(offsets[j + 1]) - int(offsets[j])
-        acc += (rows + row_granule - 1) // row_granule * row_granule * padded_rank(r, granule)
-    out.append(acc)
-    return out
-
-
 def row_tiles(offsets: Sequence[int], tile_rows: int) -> List[Tuple[int, int, int, int]]:
     """Uniform row tiles over the concatenated batch: (row0, rows, first_job, last_job), where
     first/last are the first and last jobs with at least one row inside the tile."""

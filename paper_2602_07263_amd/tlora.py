@@ -106,13 +106,15 @@ KERNEL_CLASSES = ["pack", "shrink", "gemm_fwd", "gemm_bwd", "rank_grad", "grad_r
 
 
 def lib() -> ctypes.CDLL:
-    """Load libtlora.so (building it first only if it has never been built)."""
+    """Load libtlora.so; it is built first if it is missing or older than one of its sources (an explicit
+    TLORA_LIB path is taken as it is)."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(LIB_PATH):
+    if not os.environ.get("TLORA_LIB"):
         from . import build as _build
-        _build.build()
+        if _build.is_stale():
+            _build.build()
     L = ctypes.CDLL(LIB_PATH)
     P = ctypes.POINTER(tlora_problem_t)
     L.tlora_workspace_bytes.restype = ctypes.c_size_t

@@ -1,6 +1,7 @@
 """Host-side checks that need no GPU: the C-ABI library loads and exports what include/tlora.h
 declares, rejects bad arguments before touching the device, and its integer bookkeeping (padded
-ranks, packed offsets, row tiles) is bit-identical to the oracle's independently written version."""
+ranks, row tiles with their first / last job) is bit-identical to the oracle's independently written
+version; the private layout of the intermediates is checked for validity, not against the oracle."""
 import ctypes
 import os
 import re
@@ -73,6 +74,20 @@ def test_invalid_problems_are_rejected_on_the_host():
         tlora.tlora_set_option("shrink_rows", 100)
 
 
+def _check_packed_layout(prob, plan, ranks, off):
+    """Where job j's block of the intermediates lies in the workspace is the library's own choice (the paper fixes
+    no layout), so it is not compared with the oracle: it only has to be a valid layout -- blocks in job order that
+    do not overlap, each with room for the job's T_j x rpad_j elements, starting on 16-byte boundaries (two-byte
+    elements), and all of it inside the workspace the library asks for."""
+    soff = plan["soff"]
+    assert soff[0] == 0 and len(soff) == len(ranks) + 1
+    for j, r in enumerate(ranks):
+        need = (int(off[j + 1]) - int(off[j])) * orc.padded_rank(r)
+        assert soff[j + 1] - soff[j] >= need, f"job {j}: block too small"
+        assert (soff[j] * 2) % 16 == 0
+    assert 4 * 2 * soff[-1] <= tlora.tlora_workspace_bytes(prob)      # S and dS, hi and lo planes
+
+
 @pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4])
 def test_plan_bookkeeping_is_bit_exact(cfg):
     wl = wk.config(cfg)
@@ -82,8 +97,8 @@ def test_plan_bookkeeping_is_bit_exact(cfg):
                                          0x1000, 0x2000, [0x3000] * wl.num_jobs, [0x4000] * wl.num_jobs)
         plan = tlora.tlora_plan_dump(prob)
         assert plan["rpad"] == [orc.padded_rank(r) for r in wl.ranks]
-        assert plan["soff"] == orc.packed_offsets(wl.ranks, off)
         assert plan["tiles"] == orc.row_tiles(off, plan["tile_rows"])
+        _check_packed_layout(prob, plan, wl.ranks, off)
 
 
 def test_plan_handles_empty_segments_and_rank_zero():
@@ -92,7 +107,7 @@ def test_plan_handles_empty_segments_and_rank_zero():
     off = np.concatenate([[0], np.cumsum(tokens)])
     plan = tlora.tlora_plan_dump(prob)
     assert plan["rpad"] == [8, 0, 16, 8]
-    assert plan["soff"] == orc.packed_offsets(ranks, off) == [0, 0, 0, 0, 256]
+    _check_packed_layout(prob, plan, ranks, off)
     assert plan["tiles"] == orc.row_tiles(off, plan["tile_rows"])
     # all-empty batch: no tiles
     prob0, _k = _problem([4, 4], [0, 0])

@@ -231,8 +231,6 @@ def test_rank_zero_job_is_backbone_only():
 # -- integer bookkeeping --------------------------------------------------------------------------------
 def test_bookkeeping_closed_forms():
     assert [orc.padded_rank(r) for r in (0, 1, 3, 8, 9, 48, 256)] == [0, 8, 8, 8, 16, 48, 256]
-    assert orc.packed_offsets([4, 8, 0, 3], [0, 10, 10, 15, 20]) == [0, 256, 256, 256, 512]
-    assert orc.packed_offsets([4, 8], [0, 64, 100], row_granule=1) == [0, 512, 800]
     tiles = orc.row_tiles([0, 3, 3, 300, 520], 256)
     assert tiles == [(0, 256, 0, 2), (256, 256, 2, 3), (512, 8, 3, 3)]
 
