@@ -76,3 +76,41 @@ def compare(p, Y, dX, dA, dB, rows=None, tol=None):
         out["frob"] = max([frob_rel(Y[sel], Yr), frob_rel(dX[sel], dXr)] +
                           [frob_rel(a, r) for a, r in zip(dA, dAr)] + [frob_rel(b, r) for b, r in zip(dB, dBr)]) / tol
     return out
+
+
+def rms_floor_ratio(got, ref, tol: float) -> float:
+    """Worst |err| / (tol (m + |ref|)) with m = max(1, rms(ref)): for gradients that are long token sums of products
+    of tensors a block stores in bf16 between its kernels, one-ulp flips of those reach a sum as noise relative to
+    the sum's typical size (its rms), also on entries that happen to be near zero."""
+    if ref.size == 0:
+        return 0.0
+    got = np.asarray(got, dtype=np.float64)
+    assert np.all(np.isfinite(got)), "non-finite values in GPU output"
+    m = max(1.0, float(np.sqrt(np.mean(ref * ref))))
+    return float(np.max(np.abs(got - ref) / (tol * (m + np.abs(ref)))))
+
+
+def bf16_store(a):
+    """Storage hook of the block oracles: round a float64 tensor to bf16 (RNE) and widen it again."""
+    from paper_2602_07263_amd import workloads as wk
+    return wk.round_to_bf16(np.asarray(a, dtype=np.float32)).astype(np.float64)
+
+
+def block_report(label, Out, dX, grads, oracle, tol: float, stored_hook, rms_floor_on_acts: bool = False):
+    """Compare a block's GPU results (torch tensors) with its fp64 oracle twice: against the oracle that rounds the
+    tensors the block keeps in memory (`stored_hook`; this is the comparison that is asserted) and against the
+    plain oracle that rounds nothing (printed, so the share of the error that the storage points explain is on
+    record).  `oracle(store)` returns (Out, dX, {name: (dA list, dB list)}).  Returns the asserted ratios."""
+    got_out, got_dX = Out.float().cpu().numpy(), dX.float().cpu().numpy()
+    got_g = {n: ([a.cpu().numpy() for a in grads[n][0]], [b.cpu().numpy() for b in grads[n][1]]) for n in grads}
+    act = rms_floor_ratio if rms_floor_on_acts else worst_ratio
+    out = {}
+    for kind, hook in (("rounding oracle", stored_hook), ("plain oracle", lambda a: a)):
+        out_r, dX_r, g_r = oracle(hook)
+        res = {"Out": act(got_out, out_r, tol), "dX": act(got_dX, dX_r, tol)}
+        for n in got_g:
+            res["dA_" + n] = max([rms_floor_ratio(a, r, tol) for a, r in zip(got_g[n][0], g_r[n][0])] + [0.0])
+            res["dB_" + n] = max([rms_floor_ratio(b, r, tol) for b, r in zip(got_g[n][1], g_r[n][1])] + [0.0])
+        print(f"{label} vs {kind}: worst error / tolerance", {k: round(v, 3) for k, v in res.items()}, flush=True)
+        out[kind] = res
+    return out["rounding oracle"]

@@ -13,8 +13,10 @@ pytestmark = pytest.mark.gpu
 HD = 128
 # Every path through the block crosses two fused layers (q / k / v, then o), each with the layer's error budget, and an
 # attention between them whose matrix units take bf16 probabilities and score gradients: the budgets add.  (Measured:
-# the worst ratio against one budget lies between 0.7 and 1.2 over the shapes below; a float64 run of the oracle
-# against itself with the stored tensors disturbed by a few fp32 ulps -- rounding flips alone -- gives 0.1 to 0.8.)
+# the worst ratio against one budget lies between 0.7 and 1.2 over the shapes below; the float64 run of the oracle
+# against itself with the stored tensors disturbed by a few fp32 ulps -- rounding flips alone -- in
+# tests/test_tolerance_derivations.py gives 0.1 to 0.8 of one budget.)  Adapter gradients are held to
+# tol (max(1, rms(ref)) + |ref|), see parity_util.rms_floor_ratio.
 BLOCK_TOL = 2 * pu.BF16_TOL
 
 
@@ -56,28 +58,13 @@ def test_attn_block_matches_oracle():
     blk.fwd(Out)
     blk.bwd(up(dOut), dX, grads)
     torch.cuda.synchronize()
-    store = lambda a: wk.round_to_bf16(a.astype(np.float32)).astype(np.float64)
     args = (gamma, eps, layers, scales, off, seq, Hq, Hkv, HD, base)
-    out_r, _ = ao.block_forward(X, *args, store)
-    dX_r, g_r = ao.block_backward(X, *args, dOut, store)
-    tol = BLOCK_TOL
 
-    def ratio(got, ref):
-        # |err| <= tol (m + |ref|), m = max(1, rms(ref)): the adapter gradients are token sums of products of tensors
-        # the block stores in bf16 between its kernels; one-ulp flips of those reach a sum as noise relative to the
-        # sum's typical size (its rms), also on entries that happen to be near zero.
-        if ref.size == 0:
-            return 0.0
-        got = np.asarray(got, dtype=np.float64)
-        assert np.all(np.isfinite(got))
-        m = max(1.0, float(np.sqrt(np.mean(ref * ref))))
-        return float(np.max(np.abs(got - ref) / (tol * (m + np.abs(ref)))))
-    res = {"Out": pu.worst_ratio(Out.float().cpu().numpy(), out_r, tol),
-           "dX": pu.worst_ratio(dX.float().cpu().numpy(), dX_r, tol)}
-    for n in grads:
-        res["dA_" + n] = max([ratio(a.cpu().numpy(), r) for a, r in zip(grads[n][0], g_r[n][0])] + [0.0])
-        res["dB_" + n] = max([ratio(b.cpu().numpy(), r) for b, r in zip(grads[n][1], g_r[n][1])] + [0.0])
-    print({k: round(v, 3) for k, v in res.items()})
+    def oracle(store):
+        out_r, _ = ao.block_forward(X, *args, store)
+        dX_r, g_r = ao.block_backward(X, *args, dOut, store)
+        return out_r, dX_r, g_r
+    res = pu.block_report("attention block", Out, dX, grads, oracle, BLOCK_TOL, pu.bf16_store)
     bad = {k: v for k, v in res.items() if not v <= 1.0}
     assert not bad, f"worst error / tolerance ratios {res}"
 
@@ -149,23 +136,12 @@ def test_attn_block_other_shapes(cfg):
     blk.fwd(Out)
     blk.bwd(up(dOut), dX, grads)
     torch.cuda.synchronize()
-    store = lambda a: wk.round_to_bf16(a.astype(np.float32)).astype(np.float64)
     args = (gamma, eps, layers, scales, off, np.asarray(seq, dtype=np.int64), Hq, Hkv, HD, base)
-    out_r, _ = ao.block_forward(X, *args, store)
-    dX_r, g_r = ao.block_backward(X, *args, dOut, store)
-    tol = BLOCK_TOL
 
-    def ratio(got, ref):
-        if ref.size == 0:
-            return 0.0
-        got = np.asarray(got, dtype=np.float64)
-        assert np.all(np.isfinite(got))
-        m = max(1.0, float(np.sqrt(np.mean(ref * ref))))
-        return float(np.max(np.abs(got - ref) / (tol * (m + np.abs(ref)))))
-    res = {"Out": pu.worst_ratio(Out.float().cpu().numpy(), out_r, tol), "dX": pu.worst_ratio(dX.float().cpu().numpy(), dX_r, tol)}
-    for n in grads:
-        res["dA_" + n] = max([ratio(a.cpu().numpy(), r) for a, r in zip(grads[n][0], g_r[n][0])] + [0.0])
-        res["dB_" + n] = max([ratio(b.cpu().numpy(), r) for b, r in zip(grads[n][1], g_r[n][1])] + [0.0])
-    print({k: round(v, 3) for k, v in res.items()})
+    def oracle(store):
+        out_r, _ = ao.block_forward(X, *args, store)
+        dX_r, g_r = ao.block_backward(X, *args, dOut, store)
+        return out_r, dX_r, g_r
+    res = pu.block_report("attention block", Out, dX, grads, oracle, BLOCK_TOL, pu.bf16_store)
     bad = {k: v for k, v in res.items() if not v <= 1.0}
     assert not bad, f"worst error / tolerance ratios {res}"

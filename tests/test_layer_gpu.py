@@ -45,29 +45,16 @@ def test_decoder_layer_matches_oracle(case):
     layer.fwd(Out)
     layer.bwd(up(dOut), dX, grads)
     torch.cuda.synchronize()
-    store = lambda a: wk.round_to_bf16(a.astype(np.float32)).astype(np.float64)
     attn = (g_attn, eps, {n: layers[n] for n in ("q", "k", "v", "o")})
     mlp = (g_mlp, eps, {n: layers[n] for n in ("gate", "up", "down")})
     args = (attn, mlp, scales, off, seq, Hq, Hkv, HD, base)
-    out_r, _ = ly.forward(X, *args, store)
-    dX_r, g_r = ly.backward(X, *args, dOut, store)
-    # two blocks chained: each block's error budget (see the block tests) adds
-    tol = 2 * pu.BF16_TOL
 
-    def ratio(got, ref):
-        # |err| <= tol (m + |ref|), m = max(1, rms(ref)): gradients that are long sums of products of bf16-stored
-        # tensors carry one-ulp flips of those as noise relative to the sum's typical size
-        if ref.size == 0:
-            return 0.0
-        got = np.asarray(got, dtype=np.float64)
-        assert np.all(np.isfinite(got))
-        m = max(1.0, float(np.sqrt(np.mean(ref * ref))))
-        return float(np.max(np.abs(got - ref) / (tol * (m + np.abs(ref)))))
-    res = {"Out": ratio(Out.float().cpu().numpy(), out_r), "dX": ratio(dX.float().cpu().numpy(), dX_r)}
-    for n in grads:
-        res["dA_" + n] = max([ratio(a.cpu().numpy(), r) for a, r in zip(grads[n][0], g_r[n][0])] + [0.0])
-        res["dB_" + n] = max([ratio(b.cpu().numpy(), r) for b, r in zip(grads[n][1], g_r[n][1])] + [0.0])
-    print({k: round(v, 3) for k, v in res.items()})
+    def oracle(store):
+        out_r, _ = ly.forward(X, *args, store)
+        dX_r, g_r = ly.backward(X, *args, dOut, store)
+        return out_r, dX_r, g_r
+    # two blocks chained: each block's error budget (see the block tests) adds
+    res = pu.block_report("decoder layer", Out, dX, grads, oracle, 2 * pu.BF16_TOL, pu.bf16_store, rms_floor_on_acts=True)
     bad = {k: v for k, v in res.items() if not v <= 1.0}
     assert not bad, f"worst error / tolerance ratios {res}"
 

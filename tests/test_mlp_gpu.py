@@ -55,30 +55,15 @@ def test_mlp_block_matches_oracle(case):
     blk.fwd(Out)
     blk.bwd(up(dOut), dX, grads)
     torch.cuda.synchronize()
-    store = (lambda a: wk.round_to_bf16(a.astype(np.float32)).astype(np.float64)) if dtype == "bf16" else (lambda a: a)
-    out_r, _ = mo.forward(X, gamma, 1e-5, layers, scales, off, store)
-    dX_r, g_r = mo.backward(X, gamma, 1e-5, layers, scales, off, dOut, store)
     # bf16: every path crosses two fused layers (gate / up, then down), each with the layer's budget: the budgets add
     # (measured against one budget: 0.25 - 1.0 over the shapes above).  fp32: chained fp32 layers and glue stages.
+    # Out and dX have rms ~ 1 and are held to tol (1 + |ref|); the adapter gradients to tol (max(1, rms) + |ref|).
     tol = 2 * pu.BF16_TOL if dtype == "bf16" else 2e-5
 
-    def ratio(got, ref):
-        # |err| <= tol (m + |ref|) with m = max(1, rms(ref)).  Out and dX have rms ~ 1, so this is the layer's bound.
-        # The adapter gradients are token sums of products of tensors the block stores in bf16 between its
-        # kernels: a GEMM output such as G differs from the oracle's by one bf16 ulp wherever the bf16 adapter
-        # operand moved it across a rounding boundary, which reaches a length-N sum as noise of about 2^-9 of the
-        # sum's typical size (its rms), also on the entries that happen to be near zero.
-        if ref.size == 0:
-            return 0.0
-        got = np.asarray(got, dtype=np.float64)
-        assert np.all(np.isfinite(got))
-        m = max(1.0, float(np.sqrt(np.mean(ref * ref))))
-        return float(np.max(np.abs(got - ref) / (tol * (m + np.abs(ref)))))
-    res = {"Out": pu.worst_ratio(Out.float().cpu().numpy(), out_r, tol),
-           "dX": pu.worst_ratio(dX.float().cpu().numpy(), dX_r, tol)}
-    for n in grads:
-        res["dA_" + n] = max([ratio(a.cpu().numpy(), r) for a, r in zip(grads[n][0], g_r[n][0])] + [0.0])
-        res["dB_" + n] = max([ratio(b.cpu().numpy(), r) for b, r in zip(grads[n][1], g_r[n][1])] + [0.0])
-    print({k: round(v, 3) for k, v in res.items()})
+    def oracle(store):
+        out_r, _ = mo.forward(X, gamma, 1e-5, layers, scales, off, store)
+        dX_r, g_r = mo.backward(X, gamma, 1e-5, layers, scales, off, dOut, store)
+        return out_r, dX_r, g_r
+    res = pu.block_report(f"MLP block {dtype}", Out, dX, grads, oracle, tol, pu.bf16_store if dtype == "bf16" else (lambda a: a))
     bad = {k: v for k, v in res.items() if not v <= 1.0}
     assert not bad, f"{dtype}: worst error / tolerance ratios {res}"

@@ -91,12 +91,20 @@ def test_run_to_run_determinism():
         assert np.array_equal(x, y)
 
 
-@pytest.mark.parametrize("cfg,proj", [(2, 0), (2, 2), (3, 1), (3, 6), (4, 0), (4, 1)])
+# every (configuration, projection) pair of the three large bf16 workloads, at full size, in the launch configuration
+# the benchmark times (default options, backward reusing the forward's S): cfg2's gate / up / down, cfg3's q / k / v / o /
+# gate / up / down, cfg4's up / down.  dA_j / dB_j are compared in full; Y / dX on every segment edge, every tile
+# edge, whole short segments and 256 random rows per job.
+FULL_SIZE = [(2, 0), (2, 1), (2, 2), (3, 0), (3, 1), (3, 2), (3, 3), (3, 4), (3, 5), (3, 6), (4, 0), (4, 1)]
+
+
+@pytest.mark.parametrize("cfg,proj", FULL_SIZE, ids=[f"cfg{c}-{wk.config(c).projections[q].name}" for c, q in FULL_SIZE])
 def test_full_size_configs_sampled(cfg, proj):
     wl = wk.config(cfg)
+    print(f"full size cfg{cfg} projection {wl.projections[proj].name}", flush=True)
     p = wk.generate(wl, proj)
     Y, dX, dA, dB, lp = pu.run_gpu(p)
-    rows = pu.sample_rows(p.offsets, 256, np.random.default_rng(cfg * 10 + proj))
+    rows = pu.sample_rows(p.offsets, 256, np.random.default_rng(cfg * 10 + proj), per_job=256)
     _assert_ok(pu.compare(p, Y, dX, dA, dB, rows=rows), f"cfg{cfg}/{wl.projections[proj].name}")
 
 

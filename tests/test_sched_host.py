@@ -40,6 +40,16 @@ def test_simulation_matches_oracle(seed):
     assert jct == jct_r and now == now_r
 
 
+def test_native_simulation_reproduces_the_hand_worked_trace():
+    import json
+    import os
+    with open(os.path.join(os.path.dirname(__file__), "golden", "sched_three_job_trace.json")) as f:
+        g = json.load(f)
+    trace, jct, now = tlora.Scheduler(g["model"], g["jobs"]).simulate(g["horizon"])
+    assert [[grp, n] for grp, n in trace] == g["trace"]
+    assert np.allclose(jct, g["jct_ms"], rtol=1e-12, atol=0.0) and abs(now - g["makespan_ms"]) <= 1e-12 * now
+
+
 def test_scheduler_rejects_bad_arguments():
     L = tlora.lib()
     s = tlora.Scheduler(MODEL, [dict(tokens=100, rank=4)])

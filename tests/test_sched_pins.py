@@ -1,6 +1,8 @@
 """Pins of the scheduler oracle (Sec. 3.4, Algorithm 1 Phase 1): a hand-worked example, exhaustive search over the
 partners on small queues, closed-form cases of the step-time model, and invariants of the result."""
 import itertools
+import json
+import os
 
 import numpy as np
 
@@ -106,3 +108,18 @@ def test_simulation_accounts_for_every_step():
     assert done == [jb["steps"] for jb in jobs] and abs(t - now) < 1e-9 and max(jct) == now
     # grouping cannot lose against running the jobs one after another, alone (a merge must beat time sharing)
     assert now <= sum(jb["steps"] * so.step_ms(model, jobs, [j]) for j, jb in enumerate(jobs)) * (1 + 1e-12)
+
+
+def _golden_trace():
+    with open(os.path.join(os.path.dirname(__file__), "golden", "sched_three_job_trace.json")) as f:
+        return json.load(f)
+
+
+def test_simulation_reproduces_the_hand_worked_three_job_trace():
+    """Pins the outer loop including its urgency update: in round 4 of the hand-worked run the job that has made less
+    progress relative to its standalone speed must go first; other plausible urgency formulas order that round the
+    other way (see the file's derivation)."""
+    g = _golden_trace()
+    trace, jct, now = so.simulate(g["model"], g["jobs"], g["horizon"])
+    assert [[grp, n] for grp, n in trace] == g["trace"]
+    assert np.allclose(jct, g["jct_ms"], rtol=1e-12, atol=0.0) and abs(now - g["makespan_ms"]) <= 1e-12 * now
