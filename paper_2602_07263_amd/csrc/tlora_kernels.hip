@@ -443,28 +443,38 @@ constexpr int waitcnt_vm_lgkm0(int vm) { return (vm & 15) | ((vm >> 4) << 14) | 
 // ---------------------------------------------------------------------------------------------------
 // PCOLS: rank columns staged per step.  A unit whose job has at most 32 padded rank columns stages a 32-column
 // adapter tile and spends the LDS it saves on more stages: the kernel is bound by the bytes of X in flight.
-template <int ROWS, int NS, int KS, int PCOLS>
+// WAVES: 4, or 8 for the 128-row units.  A CU runs one workgroup (the stages fill its LDS), so with four waves every
+// SIMD has a single wave whose LDS reads, MFMAs and waits follow one another; for a 128-column unit that serial
+// chain (20 KB of fragment reads and 16 MFMAs per wave and step) is as long as the step's share of the memory
+// stream, and since a launch is one round of units its slowest units set its duration.  Eight waves (4 row blocks
+// x 2 column halves) put two waves on every SIMD, so one's fragment reads overlap the other's MFMAs, and halve the
+// loads each wave issues.  For a 32-column unit waves 4-7 only help to load.
+template <int ROWS, int NS, int KS, int PCOLS, int WAVES>
 __device__ __forceinline__ void shrink_stream_body(uint8_t* lds, const ShrinkUnit u, const JobDev jb,
                                                    const TileDev* __restrict__ tiles,
                                                    const uint16_t* __restrict__ act, int K,
                                                    const uint16_t* __restrict__ packed, int packed_is_atp,
                                                    uint16_t* __restrict__ Shi, uint16_t* __restrict__ Slo,
                                                    uint16_t* __restrict__ Sx) {
+  constexpr int CW = PCOLS == 32 ? 4 : WAVES;      // waves that multiply
   constexpr int WM = PCOLS == 32 ? 4 : ROWS / 32;  // waves along token rows
-  constexpr int WN = 4 / WM;                       // waves along rank columns
+  constexpr int WN = CW / WM;                      // waves along rank columns
   static_assert(WM * 32 == ROWS || PCOLS != 32, "a 32-column unit needs 128 token rows for its four waves");
   constexpr int PW = PCOLS / WN, NPB = PW / 32;    // rank columns (and 32-wide blocks) per wave
+  static_assert(WN >= 1 && PW % 32 == 0 && NPB >= 1, "wave layout");
   constexpr int RB = KS * 2;                       // bytes per tile row: 64 (K-steps of 32) or 128 (of 64)
   constexpr int CPR = RB / 16;                     // 16-byte chunks per tile row
   constexpr int A_BYTES = ROWS * RB, P_BYTES = PCOLS * RB, STAGE = A_BYTES + P_BYTES;
-  constexpr int A_LD = A_BYTES / 1024 / 4, P_LD = P_BYTES / 1024 / 4;   // loads per wave per step
+  constexpr int A_TOT = A_BYTES / 1024, P_TOT = P_BYTES / 1024;            // 1 KB wave-loads per tile
+  constexpr int A_LD = A_TOT / WAVES, P_LD = (P_TOT + WAVES - 1) / WAVES;   // loads per wave per step
   static_assert(kGemmBM == 256, "the row -> GEMM tile lookup below shifts by 8");
   static_assert(NS * STAGE <= 160 * 1024, "LDS of a CU");
-  static_assert(P_LD >= 1, "at least one adapter load per wave and step");
+  static_assert(A_LD >= 1 && A_LD * WAVES == A_TOT && P_LD >= 1, "every wave issues the same number of loads per step");
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, so LDS bases stay in SGPRs
-  const int wm = wave % WM, wn = wave / WM;
+  const bool multiplies = wave < CW;
+  const int wm = wave % WM, wn = (wave / WM) % WN;
   const int p0 = u.pb * PCOLS;
   const int pvalid = min(PCOLS, jb.rpad - p0);     // > 0 by construction
   const uint16_t* P = packed + (packed_is_atp ? jb.atp_off : (int64_t)jb.roff * K) + (int64_t)p0 * K;
@@ -481,6 +491,9 @@ __device__ __forceinline__ void shrink_stream_body(uint8_t* lds, const ShrinkUni
   // (they only feed outputs that are not stored, or that are stored as zeros)
   const uint16_t* asrc[A_LD];
   const uint16_t* psrc[P_LD];
+  int pslot[P_LD];         // which 1 KB piece of the adapter tile this wave's load i fills (when the tile has fewer
+                           // pieces than there are waves, the upper waves repeat the lower waves' loads: same bytes
+                           // to the same place, and every wave keeps the same number of loads in flight)
   bool plive[P_LD];        // adapter-tile lanes beyond rpad fetch nothing (the stale slots only feed unused rank
                            // columns); lane 0 always fetches so every wave issues the same number of loads
 #pragma unroll
@@ -491,7 +504,8 @@ __device__ __forceinline__ void shrink_stream_body(uint8_t* lds, const ShrinkUni
   }
 #pragma unroll
   for (int i = 0; i < P_LD; ++i) {
-    const int q = (wave * P_LD + i) * 64 + lane, r = q / CPR;
+    pslot[i] = (wave * P_LD + i) % P_TOT;
+    const int q = pslot[i] * 64 + lane, r = q / CPR;
     const int c = KS == 32 ? (q & 3) ^ ((r >> 2) & 3) : (q & 7) ^ ((r >> 1) & 7);
     psrc[i] = P + (int64_t)min(r, pvalid - 1) * K + c * 8;
     plive[i] = r < pvalid || lane == 0;
@@ -505,7 +519,7 @@ __device__ __forceinline__ void shrink_stream_body(uint8_t* lds, const ShrinkUni
     for (int i = 0; i < A_LD; ++i) dma16(asrc[i] + st * KS, base + (wave * A_LD + i) * 1024);
 #pragma unroll
     for (int i = 0; i < P_LD; ++i)
-      if (plive[i]) dma16(psrc[i] + st * KS, base + A_BYTES + (wave * P_LD + i) * 1024);
+      if (plive[i]) dma16(psrc[i] + st * KS, base + A_BYTES + __builtin_amdgcn_readfirstlane(pslot[i]) * 1024);
     ++f_step;
   };
   for (int i = 0; i < NS - 1; ++i) issue();
@@ -514,69 +528,90 @@ __device__ __forceinline__ void shrink_stream_body(uint8_t* lds, const ShrinkUni
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NS - 2) * (A_LD + P_LD)));
     __builtin_amdgcn_s_barrier();
     issue();                                       // into the stage read in step kt - 1
-    const uint8_t* S = lds + (kt % NS) * STAGE;
-    // all fragments of the step first, then the MFMAs: with one wave per SIMD a read -> wait -> MFMA chain per
-    // k-slice would pay the LDS latency KS / 16 times per step
-    bf16x8 xf[KS / 16], pf[KS / 16][NPB];
+    if (multiplies) {
+      const uint8_t* S = lds + (kt % NS) * STAGE;
+      // all fragments of the step first, then the MFMAs: a read -> wait -> MFMA chain per k-slice would pay the LDS
+      // latency KS / 16 times per step
+      bf16x8 xf[KS / 16], pf[KS / 16][NPB];
 #pragma unroll
-    for (int kk = 0; kk < KS / 16; ++kk) {
-      xf[kk] = KS == 32 ? frag_row32(S, wm * 32, kk, lane) : frag_row_tile(S, wm * 32, kk, lane);
+      for (int kk = 0; kk < KS / 16; ++kk) {
+        xf[kk] = KS == 32 ? frag_row32(S, wm * 32, kk, lane) : frag_row_tile(S, wm * 32, kk, lane);
+#pragma unroll
+        for (int i = 0; i < NPB; ++i)
+          pf[kk][i] = KS == 32 ? frag_row32(S + A_BYTES, wn * PW + i * 32, kk, lane)
+                               : frag_row_tile(S + A_BYTES, wn * PW + i * 32, kk, lane);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int kk = 0; kk < KS / 16; ++kk)
+#pragma unroll
+        for (int i = 0; i < NPB; ++i) acc[i] = mfma32(pf[kk][i], xf[kk], acc[i]);
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));   // drain: the stages are reused below
+  __syncthreads();
+
+  // Outputs: bf16 hi + lo planes (hi = bf16(x), lo = bf16(x - hi); pad rows of the job's last unit written as zeros)
+  // and bf16 scale_j * x into the row's slot of its GEMM tile's K-extension operand.  A lane holds 4 rank columns of
+  // one token row per accumulator group, so storing from the registers would be 8-byte pieces 2 * rpad bytes apart;
+  // instead each of the three tensors goes through LDS ([ROWS][PCOLS] bf16, row pitch padded by 8 bytes so the 32 rows
+  // a store instruction touches fall into distinct banks) and leaves as 16 bytes per lane along the rows -- in the
+  // packed layout the unit's rows follow one another, so a 128-column unit writes one contiguous 32 KB block per plane.
+  constexpr int OPITCH = PCOLS * 2 + 8;
+  static_assert(ROWS * OPITCH <= NS * STAGE, "the output tile fits in the stages");
+  const int jrows_padded = (jb.row1 - jb.row0 + kGradStep - 1) / kGradStep * kGradStep;
+  const bool last_unit = u.t0 + u.nrows == jb.row1;
+#pragma unroll
+  for (int which = 0; which < 3; ++which) {            // 0: hi plane, 1: lo plane, 2: scaled operand of the GEMM
+    if (multiplies) {
+      const int r = wm * 32 + (lane & 31);
+      const bool live = r < u.nrows;
 #pragma unroll
       for (int i = 0; i < NPB; ++i)
-        pf[kk][i] = KS == 32 ? frag_row32(S + A_BYTES, wn * PW + i * 32, kk, lane)
-                             : frag_row_tile(S + A_BYTES, wn * PW + i * 32, kk, lane);
-    }
-    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int kk = 0; kk < KS / 16; ++kk)
-#pragma unroll
-      for (int i = 0; i < NPB; ++i) acc[i] = mfma32(pf[kk][i], xf[kk], acc[i]);
-  }
-  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));   // drain before the workgroup's LDS is released
-
-  // Outputs as in shrink_kernel: bf16 hi + lo planes (pad rows of the job's last unit written as zeros) and
-  // bf16 scale_j * x into the row's slot of its GEMM tile's K-extension operand.
-  const int r = wm * 32 + (lane & 31);
-  const int jrow = u.t0 - jb.row0 + r;
-  const bool last_unit = u.t0 + u.nrows == jb.row1;
-  const int jrows_padded = (jb.row1 - jb.row0 + kGradStep - 1) / kGradStep * kGradStep;
-  if (r < u.nrows || (last_unit && jrow < jrows_padded)) {
-    const bool live = r < u.nrows;
-    const int t = u.t0 + r;
-    const int64_t rowbase = jb.soff + (int64_t)jrow * jb.rpad;
-    const TileDev td = tiles[min(t, jb.row1 - 1) >> 8];
-    uint16_t* const xrow = Sx + td.aoff + (int64_t)(t & 255) * td.kext + (jb.roff - td.roff_first);
-#pragma unroll
-    for (int i = 0; i < NPB; ++i)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int p = p0 + wn * PW + i * 32 + g * 8 + (lane >> 5) * 4;
-        if (p < jb.rpad) {
+        for (int g = 0; g < 4; ++g) {
+          const int pl = wn * PW + i * 32 + g * 8 + (lane >> 5) * 4;
           float v[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = live ? acc[i][g * 4 + e] : 0.f;
-          float lo[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) lo[e] = v[e] - (float)(__bf16)v[e];
-          *reinterpret_cast<u32x2*>(Shi + rowbase + p) = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
-          *reinterpret_cast<u32x2*>(Slo + rowbase + p) = u32x2{pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3])};
-          if (live) {
-            u32x2 b = {pack_bf16x2(jb.scale * v[0], jb.scale * v[1]), pack_bf16x2(jb.scale * v[2], jb.scale * v[3])};
-            *reinterpret_cast<u32x2*>(xrow + p) = b;
+          for (int e = 0; e < 4; ++e) {
+            const float x = live ? acc[i][g * 4 + e] : 0.f;
+            v[e] = which == 0 ? x : which == 1 ? x - (float)(__bf16)x : jb.scale * x;
           }
+          *reinterpret_cast<u32x2*>(lds + r * OPITCH + pl * 2) = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+        }
+    }
+    __syncthreads();
+    constexpr int CPT = PCOLS / 8;                      // 16-byte chunks per tile row
+    for (int q = tid; q < ROWS * CPT; q += WAVES * 64) {
+      const int r = q / CPT, c = q % CPT;
+      const int p = p0 + c * 8;
+      const int jrow = u.t0 - jb.row0 + r;
+      const bool live = r < u.nrows;
+      if (p < jb.rpad && (live || (which < 2 && last_unit && jrow < jrows_padded))) {
+        const u32x2 a = *reinterpret_cast<const u32x2*>(lds + r * OPITCH + c * 16);
+        const u32x2 b = *reinterpret_cast<const u32x2*>(lds + r * OPITCH + c * 16 + 8);
+        const u32x4 v = {a[0], a[1], b[0], b[1]};
+        if (which < 2) {
+          *reinterpret_cast<u32x4*>((which == 0 ? Shi : Slo) + jb.soff + (int64_t)jrow * jb.rpad + p) = v;
+        } else {
+          const int t = u.t0 + r;
+          const TileDev td = tiles[t >> 8];
+          *reinterpret_cast<u32x4*>(Sx + td.aoff + (int64_t)(t & 255) * td.kext + (jb.roff - td.roff_first) + p) = v;
         }
       }
+    }
+    if (which < 2) __syncthreads();
   }
 }
 
-template <int ROWS, int NS, int KS>
-__global__ void __launch_bounds__(256) shrink_stream_kernel(const JobDev* __restrict__ jobs,
-                                                            const TileDev* __restrict__ tiles,
-                                                            const ShrinkUnit* __restrict__ units,
-                                                            const uint16_t* __restrict__ act, int K,
-                                                            const uint16_t* __restrict__ packed, int packed_is_atp,
-                                                            uint16_t* __restrict__ Shi, uint16_t* __restrict__ Slo,
-                                                            uint16_t* __restrict__ Sx) {
+template <int ROWS, int NS, int KS, int WAVES>
+__global__ void __launch_bounds__(WAVES * 64) shrink_stream_kernel(const JobDev* __restrict__ jobs,
+                                                                   const TileDev* __restrict__ tiles,
+                                                                   const ShrinkUnit* __restrict__ units,
+                                                                   const uint16_t* __restrict__ act, int K,
+                                                                   const uint16_t* __restrict__ packed, int packed_is_atp,
+                                                                   uint16_t* __restrict__ Shi, uint16_t* __restrict__ Slo,
+                                                                   uint16_t* __restrict__ Sx) {
   // NS stages of (ROWS + 128) rows, or -- 128-row units of low-rank jobs, K-steps of 64 -- 8 stages of 128 + 32 rows
   constexpr int LOW = ROWS == 128 && KS == 64;
   constexpr int BYTES = LOW ? 8 * (128 + 32) * 128 : NS * (ROWS + 128) * KS * 2;
@@ -585,9 +620,9 @@ __global__ void __launch_bounds__(256) shrink_stream_kernel(const JobDev* __rest
   const ShrinkUnit u = units[blockIdx.x];
   const JobDev jb = jobs[u.job];
   if (LOW && jb.rpad <= 32)
-    shrink_stream_body<128, 8, 64, 32>(lds, u, jb, tiles, act, K, packed, packed_is_atp, Shi, Slo, Sx);
+    shrink_stream_body<128, 8, 64, 32, WAVES>(lds, u, jb, tiles, act, K, packed, packed_is_atp, Shi, Slo, Sx);
   else
-    shrink_stream_body<ROWS, NS_HIGH, KS, 128>(lds, u, jb, tiles, act, K, packed, packed_is_atp, Shi, Slo, Sx);
+    shrink_stream_body<ROWS, NS_HIGH, KS, 128, WAVES>(lds, u, jb, tiles, act, K, packed, packed_is_atp, Shi, Slo, Sx);
 }
 
 void launch_shrink(const JobDev* jobs, const TileDev* tiles, const ShrinkUnit* units, int num_units, int shrink_rows,
@@ -605,20 +640,20 @@ void launch_shrink_stream(const JobDev* jobs, const TileDev* tiles, const Shrink
                           bool packed_is_atp, uint16_t* S_hi, uint16_t* S_lo, uint16_t* Sx, hipStream_t st) {
   if (num_units == 0) return;
   const int atp = packed_is_atp ? 1 : 0;
-#define TLORA_SHRINK_LAUNCH(R, N, KS)                                                                                  \
-  hipLaunchKernelGGL((shrink_stream_kernel<R, N, KS>), dim3(num_units), dim3(256), 0, st, jobs, tiles, units, act, K,  \
-                     packed, atp, S_hi, S_lo, Sx)
+#define TLORA_SHRINK_LAUNCH(R, N, KS, WV)                                                                              \
+  hipLaunchKernelGGL((shrink_stream_kernel<R, N, KS, WV>), dim3(num_units), dim3(WV * 64), 0, st, jobs, tiles, units,  \
+                     act, K, packed, atp, S_hi, S_lo, Sx)
   const bool wide = K % 64 == 0 && stages < 8;      // K-steps of 64: half as many barriers per byte
   if (shrink_rows == 128) {
-    if (wide)             TLORA_SHRINK_LAUNCH(128, 4, 64);
-    else if (stages >= 8) TLORA_SHRINK_LAUNCH(128, 8, 32);
-    else                  TLORA_SHRINK_LAUNCH(128, 4, 32);
+    if (wide)             TLORA_SHRINK_LAUNCH(128, 4, 64, 8);
+    else if (stages >= 8) TLORA_SHRINK_LAUNCH(128, 8, 32, 8);
+    else                  TLORA_SHRINK_LAUNCH(128, 4, 32, 8);
   } else if (shrink_rows == 32 && K % 64 == 0) {      // the planner asks for 32 rows only when K % 64 == 0
-    TLORA_SHRINK_LAUNCH(32, 4, 64);
+    TLORA_SHRINK_LAUNCH(32, 4, 64, 4);
   } else {
-    if (wide)             TLORA_SHRINK_LAUNCH(64, 4, 64);
-    else if (stages >= 8) TLORA_SHRINK_LAUNCH(64, 8, 32);
-    else                  TLORA_SHRINK_LAUNCH(64, 4, 32);
+    if (wide)             TLORA_SHRINK_LAUNCH(64, 4, 64, 4);
+    else if (stages >= 8) TLORA_SHRINK_LAUNCH(64, 8, 32, 4);
+    else                  TLORA_SHRINK_LAUNCH(64, 4, 32, 4);
   }
 #undef TLORA_SHRINK_LAUNCH
 }
@@ -1002,9 +1037,9 @@ void launch_seg_gemm(bool w_is_kn, const TileDev* tiles, const uint16_t* act, co
 //   dB_j: U = S_j, V = dY;   dA_j^T: U = dS_j, V = X.   U comes as two bf16 planes hi + lo (two MFMAs keep ~16
 //   mantissa bits of the fp32 intermediate), packed [T_j padded to 32, rpad_j] with zero pad rows.
 // The contraction runs over tokens, the row index of both operands, so both are staged in LDS as they lie
-// in memory (token-major) and read through the transposing LDS read.  One workgroup (4 waves) owns
-// kGradCols = 256 feature columns x 32*MB rank rows for a chunk of tokens; each wave takes 64 columns, so V
-// is read once for all rank rows.  Per step of 32 tokens a stage holds the V tile (32 x 256, 16 KB) and
+// in memory (token-major) and read through the transposing LDS read.  One workgroup (8 waves) owns
+// kGradCols = 256 feature columns x 32*MB rank rows for a chunk of tokens, so V is read from memory once for all
+// rank rows; a wave takes 64 columns and every other rank block.  Per step of 32 tokens a stage holds the V tile (32 x 256, 16 KB) and
 // the two U tiles (32 x 32*MB); four stages are filled by asynchronous global->LDS loads three steps
 // ahead.  V rows beyond the chunk are clamped to its last row: they meet the zero pad rows of U.
 // ---------------------------------------------------------------------------------------------------
@@ -1022,7 +1057,12 @@ __device__ __forceinline__ bf16x8 frag_tr_u(const uint8_t* plane, int pitch, int
   return __builtin_bit_cast(bf16x8, v);
 }
 
-__global__ void __launch_bounds__(256) rank_grad_kernel(const JobDev* __restrict__ jobs,
+// Eight waves: wave w owns the 64 feature columns of group (w % 4) and the rank blocks (w / 4), (w / 4) + 2 of the
+// unit's up to four.  A CU runs one workgroup (the stages fill most of its LDS); with two waves per SIMD the fragment
+// reads of one overlap the MFMAs of the other, and a 128-rank unit's 32 MFMAs and 20 KB of reads per step are split
+// over two waves (with four waves such a unit took about twice as long per byte as a low-rank one, and the slowest
+// units of the one-round launch set its duration).
+__global__ void __launch_bounds__(512) rank_grad_kernel(const JobDev* __restrict__ jobs,
                                                         const GradUnit* __restrict__ units,
                                                         const uint16_t* __restrict__ Uhi,
                                                         const uint16_t* __restrict__ Ulo,
@@ -1037,7 +1077,12 @@ __global__ void __launch_bounds__(256) rank_grad_kernel(const JobDev* __restrict
   constexpr int SW_MASK = 3;
   constexpr int UPLANE = kGradStep * UPITCH;                // 2 KB * MB
   constexpr int VTILE = kGradStep * kGradCols * 2;          // 16 KB
-  constexpr int LOADS = 4 + MB;                             // asynchronous loads per wave per step
+  constexpr int WAVES = 8;
+  constexpr int V_LD = VTILE / 1024 / WAVES;                // 2 loads per wave: V tile
+  constexpr int U_LD = 2 * UPLANE / 1024 / WAVES;           // 2 loads per wave: hi and lo planes of U
+  constexpr int LOADS = V_LD + U_LD;                        // asynchronous loads per wave per step
+  constexpr int MW = MB / 2;                                // rank blocks per wave
+  static_assert(V_LD * WAVES * 1024 == VTILE && U_LD * WAVES * 1024 == 2 * UPLANE && MB == 4, "load split over the waves");
   __shared__ __attribute__((aligned(1024))) uint8_t g0[VTILE];
   __shared__ __attribute__((aligned(1024))) uint8_t g1[VTILE];
   __shared__ __attribute__((aligned(1024))) uint8_t g2[VTILE];
@@ -1049,37 +1094,39 @@ __global__ void __launch_bounds__(256) rank_grad_kernel(const JobDev* __restrict
 
   const GradUnit u = units[blockIdx.x];
   const JobDev jb = jobs[u.job];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int cg = wave & 3, rh = wave >> 2;                  // column group, rank half
   const int col0 = u.cb * kGradCols;
   const int pbase = u.pb * RP;
   const int nsteps = (u.t1 - u.t0 + kGradStep - 1) / kGradStep;
 
-  f32x16 acc[MB][2];
+  f32x16 acc[MW][2];
 #pragma unroll
-  for (int m = 0; m < MB; ++m)
+  for (int m = 0; m < MW; ++m)
 #pragma unroll
     for (int n = 0; n < 2; ++n)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[m][n][e] = 0.f;
 
   // V tile [32 tokens][512 B], same swizzle as the GEMM's weight tile: lane -> (token k, chunk c)
-  int vk[4], vcol[4];
+  int vk[V_LD], vcol[V_LD];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int p = (wave * 4 + i) * 64 + lane;
+  for (int i = 0; i < V_LD; ++i) {
+    const int p = (wave * V_LD + i) * 64 + lane;
     vk[i] = p >> 5;
     const int c = (p & 31) ^ ((vk[i] & 3) << 2);
     vcol[i] = min(col0 + c * 8, D - 8);               // columns beyond D are clamped; their results are not stored
   }
-  // U tiles: hi plane then lo plane, 2 * MB KB each = 2 * MB wave-loads; wave w issues load q = w * MB + i of the
+  // U tiles: hi plane then lo plane, 2 * MB KB each = 2 * MB wave-loads; wave w issues loads q = w * U_LD + i of the
   // 4 * MB.  Lanes whose rank chunk lies beyond rpad fetch nothing: the stale slots only feed rank rows >= rpad
   // of the tile, which are never stored.
-  const uint16_t* usrc[MB];
-  int udst[MB];
-  bool ulive[MB];
+  const uint16_t* usrc[U_LD];
+  int udst[U_LD];
+  bool ulive[U_LD];
 #pragma unroll
-  for (int i = 0; i < MB; ++i) {
-    const int q = wave * MB + i;                      // 0 .. 4 MB - 1
+  for (int i = 0; i < U_LD; ++i) {
+    const int q = wave * U_LD + i;                    // 0 .. 4 MB - 1
     const int plane = q / (2 * MB), within = q % (2 * MB);
     const int slot = within * 64 + lane;              // 16-byte slot inside the plane
     const int k = slot / (RP / 8), cphys = slot % (RP / 8);
@@ -1092,14 +1139,14 @@ __global__ void __launch_bounds__(256) rank_grad_kernel(const JobDev* __restrict
   int f_step = 0;                                     // next step to fetch
   auto issue = [&](uint8_t* S, uint8_t* H) {
     const int st = min(f_step, nsteps - 1);           // trailing issues re-load the last step (uniform load count)
-    const uint32_t sbase = lds_addr(S + wave * 4096), hbase = lds_addr(H);
+    const uint32_t sbase = lds_addr(S + wave * (V_LD * 1024)), hbase = lds_addr(H);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < V_LD; ++i) {
       const int t = min(u.t0 + st * kGradStep + vk[i], u.t1 - 1);
       dma16(V + (int64_t)t * D + vcol[i], sbase + i * 1024);
     }
 #pragma unroll
-    for (int i = 0; i < MB; ++i)
+    for (int i = 0; i < U_LD; ++i)
       if (ulive[i]) dma16(usrc[i] + (int64_t)st * kGradStep * jb.rpad, hbase + __builtin_amdgcn_readfirstlane(udst[i]));
     ++f_step;
   };
@@ -1108,16 +1155,17 @@ __global__ void __launch_bounds__(256) rank_grad_kernel(const JobDev* __restrict
     for (int kk = 0; kk < 2; ++kk) {
       bf16x8 vf[2];
 #pragma unroll
-      for (int n = 0; n < 2; ++n) vf[n] = frag_kn_tile(S, wave * 64 + n * 32, kk, lane);
+      for (int n = 0; n < 2; ++n) vf[n] = frag_kn_tile(S, cg * 64 + n * 32, kk, lane);
 #pragma unroll
-      for (int m = 0; m < MB; ++m) {
+      for (int i = 0; i < MW; ++i) {
+        const int m = rh + 2 * i;
         if (m < u.mb) {
           const bf16x8 hi = frag_tr_u(H, UPITCH, SW_SHIFT, SW_MASK, m * 32, kk, lane);
           const bf16x8 lo = frag_tr_u(H + UPLANE, UPITCH, SW_SHIFT, SW_MASK, m * 32, kk, lane);
 #pragma unroll
           for (int n = 0; n < 2; ++n) {
-            acc[m][n] = mfma32(hi, vf[n], acc[m][n]);
-            acc[m][n] = mfma32(lo, vf[n], acc[m][n]);
+            acc[i][n] = mfma32(hi, vf[n], acc[i][n]);
+            acc[i][n] = mfma32(lo, vf[n], acc[i][n]);
           }
         }
       }
@@ -1125,10 +1173,9 @@ __global__ void __launch_bounds__(256) rank_grad_kernel(const JobDev* __restrict
   };
   auto landed = [&]() {
     // loads complete in order: all but those of the two youngest steps have landed
-    __builtin_amdgcn_s_waitcnt(0x4070);                     // vmcnt(16) lgkmcnt(0)
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LOADS));
     __builtin_amdgcn_s_barrier();
   };
-  static_assert(2 * LOADS == 16, "wait count above");
   if (nsteps > 0) {
     issue(g0, h0);
     issue(g1, h1);
@@ -1149,14 +1196,15 @@ __global__ void __launch_bounds__(256) rank_grad_kernel(const JobDev* __restrict
   // partial tile [32 * u.mb][256]: lane holds column (lane % 32) of its n-block and 16 rank rows per m-block
   float* out = partial + u.part_off;
 #pragma unroll
-  for (int m = 0; m < MB; ++m) {
+  for (int i = 0; i < MW; ++i) {
+    const int m = rh + 2 * i;
     if (m < u.mb) {
 #pragma unroll
       for (int n = 0; n < 2; ++n)
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
           const int pl = m * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-          out[pl * kGradCols + wave * 64 + n * 32 + (lane & 31)] = acc[m][n][e];
+          out[pl * kGradCols + cg * 64 + n * 32 + (lane & 31)] = acc[i][n][e];
         }
     }
   }
@@ -1165,7 +1213,7 @@ __global__ void __launch_bounds__(256) rank_grad_kernel(const JobDev* __restrict
 void launch_rank_grad(const JobDev* jobs, const GradUnit* units, int num_units, const uint16_t* U_hi,
                       const uint16_t* U_lo, const uint16_t* V, int D, float* partial, hipStream_t st) {
   if (num_units == 0) return;
-  hipLaunchKernelGGL(rank_grad_kernel, dim3(num_units), dim3(256), 0, st, jobs, units, U_hi, U_lo, V, D, partial);
+  hipLaunchKernelGGL(rank_grad_kernel, dim3(num_units), dim3(512), 0, st, jobs, units, U_hi, U_lo, V, D, partial);
 }
 
 // Sum the partial tiles of one output tile in unit order, scale, and store (dB_j row-major [r, D];

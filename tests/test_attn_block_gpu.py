@@ -1,7 +1,7 @@
 """GPU parity of the attention block (RMSNorm -> q / k / v fused multi-LoRA projections -> rotary embedding -> causal
-grouped-query attention -> o projection -> residual) against the fp64 oracle on the same seeded bf16 inputs.  The
-oracle rounds the tensors the block keeps in memory between its kernels at the same points (its arithmetic stays
-fp64)."""
+grouped-query attention -> o projection -> residual) against the fp64 oracle on the same seeded bf16 inputs.  The results must hold the
+tolerance against the plain fp64 oracle and against the oracle that rounds the tensors the block keeps in memory
+between its kernels."""
 import numpy as np
 import pytest
 

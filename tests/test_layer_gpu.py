@@ -1,6 +1,6 @@
 """GPU parity of one whole decoder layer (attention half, then MLP half; seven fused multi-LoRA projections) against
-the fp64 oracle on the same seeded bf16 inputs; the oracle rounds the tensors the layer keeps in memory between its
-kernels at the same points."""
+the fp64 oracle on the same seeded bf16 inputs; the results must hold the tolerance against the plain fp64 oracle
+and against the oracle that rounds the tensors the layer keeps in memory between its kernels."""
 import numpy as np
 import pytest
 

@@ -1,6 +1,6 @@
 """GPU parity of the MLP block (RMSNorm -> gate / up -> gated SiLU -> down -> residual over fused multi-LoRA
-projections) against the fp64 oracle on the same seeded inputs.  For bf16 the oracle rounds the tensors the block
-keeps in memory between its kernels at the same points (its arithmetic stays fp64)."""
+projections) against the fp64 oracle on the same seeded inputs.  The results must hold the tolerance against the plain fp64
+oracle and against the oracle that rounds the tensors the block keeps in memory between its kernels."""
 import numpy as np
 import pytest
 
