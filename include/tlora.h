@@ -17,7 +17,9 @@
  *   - HOST pointers: the problem struct, ranks, offsets, scales and the arrays of per-job
  *     pointers.  DEVICE pointers: X, W, every A_j / B_j, Y, dY, dX, every dA_j / dB_j and the
  *     workspace.  The caller owns every buffer; the library allocates no device memory, keeps no
- *     pointer after a call returns and never writes W, X, A_j, B_j or dY.
+ *     pointer after a call returns (one exception: while tlora_profile is enabled it remembers where in the
+ *     last call's workspace the GEMM's clock probe lies, for tlora_profile_clock) and never writes W, X, A_j,
+ *     B_j or dY.
  *   - dtype TLORA_BF16: X, W, A_j, B_j, Y, dY, dX hold bf16; accumulation is fp32; Y / dX are rounded
  *     to nearest-even once on store.  dtype TLORA_F32: those tensors hold fp32.  dA_j, dB_j are fp32
  *     for both dtypes.  Gradients are overwritten, not accumulated.
@@ -30,8 +32,11 @@
  *   - Calls are asynchronous on `hip_stream` (a hipStream_t; NULL = the default stream).  Host
  *     arrays may be reused as soon as the call returns.  Two calls that share a workspace must be
  *     ordered on one stream.
- *   - Every entry point returns a tlora_status_t (0 = ok, negative = error).  On error nothing has
- *     been launched.  The results are independent of the internal tiling and are bit-identical from
+ *   - Every entry point returns a tlora_status_t (0 = ok, negative = error).  tlora_fwd, tlora_fwd_noalloc and
+ *     tlora_bwd validate everything before their first launch: on an argument error nothing has been launched.
+ *     The composite entry points (nano-batched, token-indexed, MLP / attention block, decoder layer) check their
+ *     own arguments first but run their sub-calls one after the other: if a later sub-call fails (a HIP error,
+ *     an invalid per-projection pointer) the kernels of the earlier ones are already queued.  The results are independent of the internal tiling and are bit-identical from
  *     run to run (no floating-point atomics).
  */
 #ifndef TLORA_H
@@ -386,12 +391,18 @@ int tlora_plan_dump(const tlora_problem_t* p, int32_t* rpad, int64_t* soff, int3
  *   "dx_transposed_w": 1 (default): dX runs against a transposed copy of W kept in the workspace | 0: against W
  *                    as it lies in memory (no copy, slower weight stream)
  *   "grad_tokens"  : minimum tokens per work unit of the dA / dB kernels   (multiple of 64)
+ *   "plan_cache"   : 1 (default): the integer plan of a problem (tiles, work units, workspace layout) is kept, keyed
+ *                    by the contents of (dtype, d_in, d_out, ranks, offsets), and reused by later calls with the same
+ *                    values -- scales and pointers are taken from every call afresh | 0: rebuilt on every call.
+ *                    Setting it (to either value) empties the cache.
  * Returns TLORA_EINVAL for an unknown name or an illegal value. */
 int tlora_set_option(const char* name, int64_t value);
 
 /* Per-kernel timing, the runtime signal a nano-batch controller feeds on (Algorithm 1, Phase 3:
  * Monitor_Speed).  While enabled, every kernel launch of tlora_fwd / tlora_bwd is bracketed by a
  * pair of HIP events on the call's stream.  tlora_profile(1) enables and clears the totals,
+ * tlora_profile(2) does the same for the two segmented-GEMM classes only (an event pair costs a few
+ * microseconds of stream time, which adds up over the ~15 short launches of a forward + backward),
  * tlora_profile(0) disables.  tlora_profile_read waits for the recorded events, adds them to the
  * totals and returns, for one kernel class, the summed milliseconds and the number of launches
  * (either output may be NULL).  Returns TLORA_EINVAL for an unknown class. */

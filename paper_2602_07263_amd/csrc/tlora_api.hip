@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <list>
 #include <mutex>
 #include <string>
 #include <vector>
@@ -45,6 +46,7 @@ struct Options {
   int shrink_stages = 4;
   int grad_tokens = 256;
   int dx_transposed_w = 1;
+  int plan_cache = 1;           // reuse plans of problems seen before (keyed by their contents)
 };
 Options g_opt;
 // set (under g_mu) by the token-indexed entry points around their inner call: the GEMMs then scatter their output rows
@@ -341,6 +343,7 @@ struct Pending {
   hipEvent_t a, b;
 };
 bool g_prof_on = false;
+bool g_prof_gemm_only = false;   // mode 2: only the two segmented-GEMM classes are bracketed
 std::vector<Pending> g_pending;
 std::vector<hipEvent_t> g_event_pool;
 double g_prof_ms[TLORA_K_COUNT] = {};
@@ -363,7 +366,8 @@ struct Timed {
   hipStream_t st;
   Pending p{};
   bool on;
-  Timed(int cls, hipStream_t s, bool enable = true) : st(s), on(g_prof_on && enable) {
+  Timed(int cls, hipStream_t s, bool enable = true)
+      : st(s), on(g_prof_on && enable && (!g_prof_gemm_only || cls == TLORA_K_GEMM_FWD || cls == TLORA_K_GEMM_BWD)) {
     if (!on) return;
     p.cls = cls;  p.a = prof_event();  p.b = prof_event();
     if (!p.a || !p.b) { on = false; return; }
@@ -433,6 +437,62 @@ std::vector<uint8_t> make_blob(const Plan& pl) {
   return blob;
 }
 
+// ---- plan cache ---------------------------------------------------------------------------------------------
+// A plan depends only on (dtype, d_in, d_out, ranks, offsets), the forward-only flag and the tiling options; the
+// per-call values (scales, adapter and gradient pointers) live in the job table alone, which every call patches into
+// its copy of the cached table blob.  Training loops call with the same few problems step after step, so building
+// the plan (vectors, unit sorting) and assembling the blob are paid once per distinct problem.  Entries are kept in
+// most-recently-used order; everything here runs under g_mu.
+struct PlanEntry {
+  std::vector<int64_t> key;
+  Plan pl;
+  std::vector<uint8_t> blob;     // tables with a job table whose per-call fields are zero
+};
+constexpr size_t kPlanCacheEntries = 128;
+std::list<PlanEntry> g_plans;
+PlanEntry g_plan_uncached;       // the plan of the current call when the cache is switched off
+
+void plan_key(const tlora_problem_t* p, bool fwd_only, std::vector<int64_t>& key) {
+  key.clear();
+  key.reserve(10 + 2 * (size_t)p->num_jobs);
+  key.push_back(p->dtype);  key.push_back(p->num_jobs);  key.push_back(p->d_in);  key.push_back(p->d_out);
+  key.push_back(fwd_only ? 1 : 0);
+  key.push_back(g_opt.shrink_rows);  key.push_back(g_opt.grad_tokens);
+  for (int j = 0; j < p->num_jobs; ++j) key.push_back(p->ranks[j]);
+  for (int j = 0; j <= p->num_jobs; ++j) key.push_back(p->offsets[j]);
+}
+
+// The plan of a problem: from the cache, or built and inserted.
+int get_plan(const tlora_problem_t* p, bool fwd_only, const PlanEntry** out) {
+  const int rc = validate(p);
+  if (rc != TLORA_OK) return rc;
+  if (!g_opt.plan_cache) {
+    g_plan_uncached = PlanEntry();
+    const int rb = build_plan(p, g_plan_uncached.pl, fwd_only);
+    if (rb != TLORA_OK) return rb;
+    g_plan_uncached.blob = make_blob(g_plan_uncached.pl);
+    *out = &g_plan_uncached;
+    return TLORA_OK;
+  }
+  static std::vector<int64_t> key;
+  plan_key(p, fwd_only, key);
+  for (auto it = g_plans.begin(); it != g_plans.end(); ++it)
+    if (it->key == key) {
+      if (it != g_plans.begin()) g_plans.splice(g_plans.begin(), g_plans, it);
+      *out = &g_plans.front();
+      return TLORA_OK;
+    }
+  PlanEntry e;
+  const int rb = build_plan(p, e.pl, fwd_only);
+  if (rb != TLORA_OK) return rb;
+  e.key = key;
+  e.blob = make_blob(e.pl);
+  g_plans.push_front(std::move(e));
+  if (g_plans.size() > kPlanCacheEntries) g_plans.pop_back();
+  *out = &g_plans.front();
+  return TLORA_OK;
+}
+
 // fp32 path: append the tiles of one product
 void f32_add(std::vector<F32Unit>& units, std::vector<F32Tile>& tiles, const F32Unit& u) {
   if (u.M <= 0 || u.N <= 0) return;
@@ -475,19 +535,24 @@ int f32_place(const Plan& pl, std::vector<uint8_t>& blob, std::vector<F32Unit> u
   return TLORA_OK;
 }
 
-// static_scratch: the "workspace" is the library's static scratch array and only the forward will run
-int common_checks(const tlora_problem_t* p, Plan& pl, void* ws, size_t ws_bytes, bool static_scratch = false) {
-  int rc = build_plan(p, pl, static_scratch);
+// static_scratch: the "workspace" is the library's static scratch array and only the forward will run.
+// Gives the (cached) plan and this call's job table: the plan's with the caller's scales and adapter pointers.
+int common_checks(const tlora_problem_t* p, const PlanEntry** entry, std::vector<JobDev>& hjobs, void* ws, size_t ws_bytes,
+                  bool static_scratch = false) {
+  int rc = get_plan(p, static_scratch, entry);
   if (rc != TLORA_OK) return rc;
+  const Plan& pl = (*entry)->pl;
   if ((pl.T > 0 && !p->X) || !p->W || !p->A || !p->B) return TLORA_ENULL;
   for (int j = 0; j < pl.J; ++j)
     if (pl.jobs[j].rank > 0 && (!p->A[j] || !p->B[j])) return TLORA_ENULL;
   if (misaligned16(p->X) || misaligned16(p->W)) return TLORA_EALIGN;
   if (static_scratch && ws_bytes < pl.total) return TLORA_ESCRATCH;
   if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255) || ws_bytes < pl.total) return TLORA_EWORKSPACE;
+  hjobs = pl.jobs;
   for (int j = 0; j < pl.J; ++j) {
-    pl.jobs[j].A = p->A[j];
-    pl.jobs[j].B = p->B[j];
+    hjobs[j].scale = p->scales[j];
+    hjobs[j].A = p->A[j];
+    hjobs[j].B = p->B[j];
   }
   return TLORA_OK;
 }
@@ -501,9 +566,9 @@ extern "C" {
 
 size_t tlora_workspace_bytes(const tlora_problem_t* p) {
   std::lock_guard<std::recursive_mutex> lk(g_mu);
-  Plan pl;
-  if (build_plan(p, pl) != TLORA_OK) return 0;
-  return pl.total;
+  const PlanEntry* e = nullptr;
+  if (get_plan(p, false, &e) != TLORA_OK) return 0;
+  return e->pl.total;
 }
 
 }  // extern "C"
@@ -515,9 +580,11 @@ namespace {
 // reach the device as kernel arguments (no staging buffer, no copy node), and nothing is timed: no HIP object is
 // created and no memory of any kind is allocated on this path.
 int fwd_impl(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_bytes, void* hip_stream, bool no_alloc) {
-  Plan pl;
-  int rc = common_checks(p, pl, workspace, ws_bytes, no_alloc);
+  const PlanEntry* entry = nullptr;
+  std::vector<JobDev> hjobs;
+  int rc = common_checks(p, &entry, hjobs, workspace, ws_bytes, no_alloc);
   if (rc != TLORA_OK) return rc;
+  const Plan& pl = entry->pl;
   if (pl.T > 0 && !Y) return TLORA_ENULL;
   if (misaligned16(Y)) return TLORA_EALIGN;
   rc = check_arch();
@@ -526,7 +593,8 @@ int fwd_impl(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_bytes
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   uint8_t* ws = static_cast<uint8_t*>(workspace);
   uint8_t* tb = ws + pl.off_tables;
-  std::vector<uint8_t> blob = make_blob(pl);
+  std::vector<uint8_t> blob = entry->blob;          // the cached tables, with this call's job table
+  put(blob, pl.tb_jobs, hjobs);
   const JobDev* jobs = reinterpret_cast<const JobDev*>(tb + pl.tb_jobs);
   const bool timed = g_prof_on && !no_alloc;
   auto upload = [&](size_t used) {
@@ -545,7 +613,7 @@ int fwd_impl(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_bytes
     std::vector<F32Tile> tiles[2];
     f32_add(units[0], tiles[0], f32_unit(X, pl.d_in, 1, W, pl.d_out, 1, Yf, pl.d_out, pl.T, pl.d_out, pl.d_in, 1.f, false));
     for (int j = 0; j < pl.J; ++j) {
-      const JobDev& jb = pl.jobs[j];
+      const JobDev& jb = hjobs[j];
       const int Tj = jb.row1 - jb.row0;
       if (jb.rank == 0 || Tj == 0) continue;
       const float* Xj = X + (int64_t)jb.row0 * pl.d_in;
@@ -614,9 +682,11 @@ int tlora_fwd_noalloc(const tlora_problem_t* p, void* Y, void* hip_stream) {
 int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* dA, void* const* dB, int flags,
               void* workspace, size_t ws_bytes, void* hip_stream) {
   std::lock_guard<std::recursive_mutex> lk(g_mu);
-  Plan pl;
-  int rc = common_checks(p, pl, workspace, ws_bytes);
+  const PlanEntry* entry = nullptr;
+  std::vector<JobDev> hjobs;
+  int rc = common_checks(p, &entry, hjobs, workspace, ws_bytes);
   if (rc != TLORA_OK) return rc;
+  const Plan& pl = entry->pl;
   if (pl.T > 0 && !dY) return TLORA_ENULL;
   if ((dA == nullptr) != (dB == nullptr)) return TLORA_ENULL;
   if (misaligned16(dY) || (dX && misaligned16(dX))) return TLORA_EALIGN;
@@ -624,8 +694,8 @@ int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* d
   if (want_grads)
     for (int j = 0; j < pl.J; ++j) {
       if (pl.jobs[j].rank > 0 && (!dA[j] || !dB[j])) return TLORA_ENULL;
-      pl.jobs[j].dA = dA[j];
-      pl.jobs[j].dB = dB[j];
+      hjobs[j].dA = dA[j];
+      hjobs[j].dB = dB[j];
     }
   if (flags & ~(TLORA_BWD_REUSE_S | TLORA_BWD_REUSE_WT | TLORA_BWD_ACCUMULATE)) return TLORA_EINVAL;
   const bool accumulate = (flags & TLORA_BWD_ACCUMULATE) != 0;
@@ -635,7 +705,8 @@ int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* d
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   uint8_t* ws = static_cast<uint8_t*>(workspace);
   uint8_t* tb = ws + pl.off_tables;
-  std::vector<uint8_t> blob = make_blob(pl);
+  std::vector<uint8_t> blob = entry->blob;          // the cached tables, with this call's job table
+  put(blob, pl.tb_jobs, hjobs);
   const JobDev* jobs = reinterpret_cast<const JobDev*>(tb + pl.tb_jobs);
 
   if (pl.dtype == TLORA_F32) {
@@ -650,7 +721,7 @@ int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* d
     if (dXf)   // dX = dY . W^T : B(k = o, n = i) = W[i, o]
       f32_add(units[0], tiles[0], f32_unit(dYf, pl.d_out, 1, W, 1, pl.d_out, dXf, pl.d_in, pl.T, pl.d_in, pl.d_out, 1.f, false));
     for (int j = 0; j < pl.J; ++j) {
-      const JobDev& jb = pl.jobs[j];
+      const JobDev& jb = hjobs[j];
       const int Tj = jb.row1 - jb.row0;
       if (jb.rank == 0) continue;
       const float* Aj = static_cast<const float*>(jb.A);
@@ -1552,9 +1623,10 @@ int tlora_bwd_indexed(const tlora_problem_t* p, const int32_t* row_index, const 
 int tlora_plan_dump(const tlora_problem_t* p, int32_t* rpad, int64_t* soff, int32_t* tile_rows, int64_t* tile_row0,
                     int32_t* tile_nrows, int32_t* tile_job_first, int32_t* tile_job_last, int64_t* n_tiles) {
   std::lock_guard<std::recursive_mutex> lk(g_mu);
-  Plan pl;
-  const int rc = build_plan(p, pl);
+  const PlanEntry* e = nullptr;
+  const int rc = get_plan(p, false, &e);
   if (rc != TLORA_OK) return rc;
+  const Plan& pl = e->pl;
   for (int j = 0; j < pl.J; ++j) {
     if (rpad) rpad[j] = pl.jobs[j].rpad;
     if (soff) soff[j] = pl.jobs[j].soff;
@@ -1581,7 +1653,9 @@ int tlora_plan_dump(const tlora_problem_t* p, int32_t* rpad, int64_t* soff, int3
 int tlora_profile(int enable) {
   std::lock_guard<std::recursive_mutex> lk(g_mu);
   const int rc = prof_drain();
+  if (enable < 0 || enable > 2) return TLORA_EINVAL;
   g_prof_on = enable != 0;
+  g_prof_gemm_only = enable == 2;
   if (g_prof_on) g_clock_slot[0] = g_clock_slot[1] = nullptr;
   if (g_prof_on)
     for (int i = 0; i < TLORA_K_COUNT; ++i) {
@@ -1632,6 +1706,12 @@ int tlora_set_option(const char* name, int64_t value) {
   if (n == "dx_transposed_w") {
     if (value != 0 && value != 1) return TLORA_EINVAL;
     g_opt.dx_transposed_w = (int)value;
+    return TLORA_OK;
+  }
+  if (n == "plan_cache") {
+    if (value != 0 && value != 1) return TLORA_EINVAL;
+    g_opt.plan_cache = (int)value;
+    g_plans.clear();
     return TLORA_OK;
   }
   if (n == "grad_tokens") {

@@ -234,8 +234,9 @@ def tlora_set_option(name: str, value: int) -> None:
     _check(lib().tlora_set_option(name.encode(), int(value)), f"tlora_set_option({name})")
 
 
-def tlora_profile(enable: bool) -> None:
-    _check(lib().tlora_profile(1 if enable else 0), "tlora_profile")
+def tlora_profile(enable) -> None:
+    """False / 0: off; True / 1: bracket every kernel launch with events; 2: only the segmented GEMMs."""
+    _check(lib().tlora_profile(int(enable)), "tlora_profile")
 
 
 def tlora_profile_read() -> dict:

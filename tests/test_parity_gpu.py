@@ -82,6 +82,23 @@ def test_zero_B_gives_backbone_only_and_jobs_do_not_leak():
     _assert_ok(pu.compare(p3, Y3, dX3, dA3, dB3), "B=0")
 
 
+def test_cached_plan_takes_scales_and_pointers_from_every_call():
+    """Two problems with the same sizes, ranks and offsets share one cached plan; their scales, activations and
+    adapters differ (other tensors at other addresses): each must match its own oracle, with the cache on and off."""
+    from paper_2602_07263_amd import tlora
+    shape = ("bf16", 256, 384, [8, 40, 3], [300, 129, 260])
+    a = wk.generate(wk.custom("cache_a", *shape, [2.0, 0.5, 1.0]), seed=31)
+    b = wk.generate(wk.custom("cache_b", *shape, [0.25, 3.0, 4.0]), seed=32)
+    try:
+        for cache in (1, 0, 1):
+            tlora.tlora_set_option("plan_cache", cache)
+            for p in (a, b, a):
+                Y, dX, dA, dB, _ = pu.run_gpu(p)
+                _assert_ok(pu.compare(p, Y, dX, dA, dB), f"{p.name if hasattr(p, 'name') else 'problem'} cache={cache}")
+    finally:
+        tlora.tlora_set_option("plan_cache", 1)
+
+
 def test_run_to_run_determinism():
     p = wk.generate(wk.custom("det", "bf16", 512, 768, [8, 64, 33], [700, 1300, 129]), seed=2)
     a = pu.run_gpu(p)
