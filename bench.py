@@ -35,6 +35,18 @@ def device_peak():
     pr = torch.cuda.get_device_properties(0)
     cus = int(pr.multi_processor_count)
     khz = getattr(pr, "clock_rate", None)
+    if not khz:
+        # the runtime's device listing states the maximum engine clock of every agent; take the GPU agent's
+        try:
+            import re
+            import subprocess
+            txt = subprocess.run(["/opt/rocm/bin/rocminfo"], capture_output=True, text=True, timeout=30).stdout
+            gpu = txt[txt.index("gfx950"):] if "gfx950" in txt else ""
+            m = re.search(r"Max Clock Freq\. \(MHz\):\s*(\d+)", gpu)
+            if m:
+                khz = int(m.group(1)) * 1000
+        except Exception:
+            khz = None
     out = {"published_tflops": BF16_MFMA_PEAK_TFLOPS, "compute_units": cus, "flop_per_clk_per_cu": MFMA_FLOP_PER_CLK_PER_CU,
            "formula": "compute_units x clock_ghz x 4096 flop/clk/CU"}
     if khz:

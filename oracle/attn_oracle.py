@@ -78,9 +78,9 @@ def attention(Q, K, V, seq_offsets, n_heads, n_kv, hd):
     return O, probs
 
 
-def attention_lse2(Q, K, seq_offsets, n_heads, n_kv, hd):
-    """Base-2 logarithm of the softmax denominators: lse2[t, h] = log2(sum over visible keys of exp(S[t, key])), the
-    statistic the GPU forward hands to its backward."""
+def attention_lse(Q, K, seq_offsets, n_heads, n_kv, hd):
+    """Log-sum-exp of every query's visible scores: lse[t, h] = log(sum over keys <= t of exp(S[t, key])), S = q.k /
+    sqrt(hd) -- the logarithm of the softmax denominator (natural logarithm, the textbook statistic)."""
     Q, K = np.asarray(Q, dtype=np.float64), np.asarray(K, dtype=np.float64)
     out = np.zeros((Q.shape[0], n_heads))
     g = n_heads // n_kv
@@ -90,7 +90,7 @@ def attention_lse2(Q, K, seq_offsets, n_heads, n_kv, hd):
             S = Q[a:b, h * hd:(h + 1) * hd] @ K[a:b, (h // g) * hd:(h // g + 1) * hd].T / np.sqrt(hd)
             for t in range(b - a):
                 row = S[t, :t + 1]
-                out[a + t, h] = (row.max() + np.log(np.sum(np.exp(row - row.max())))) / np.log(2.0)
+                out[a + t, h] = row.max() + np.log(np.sum(np.exp(row - row.max())))
     return out
 
 

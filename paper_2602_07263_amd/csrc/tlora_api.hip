@@ -49,8 +49,6 @@ struct Options {
   int plan_cache = 1;           // reuse plans of problems seen before (keyed by their contents)
 };
 Options g_opt;
-// set (under g_mu) by the token-indexed entry points around their inner call: the GEMMs then scatter their output rows
-const int32_t* g_out_index = nullptr;
 std::recursive_mutex g_mu;   // the nano-batch entry points call tlora_fwd / tlora_bwd under it
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -579,7 +577,9 @@ namespace {
 // the current device, `ws_bytes` = its size); the plan and the workspace layout are the forward's alone, the tables
 // reach the device as kernel arguments (no staging buffer, no copy node), and nothing is timed: no HIP object is
 // created and no memory of any kind is allocated on this path.
-int fwd_impl(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_bytes, void* hip_stream, bool no_alloc) {
+// out_index: null, or the output row of every (sorted) token row -- the GEMM then scatters its rows (token-indexed calls).
+int fwd_impl(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_bytes, void* hip_stream, bool no_alloc,
+             const int32_t* out_index = nullptr) {
   const PlanEntry* entry = nullptr;
   std::vector<JobDev> hjobs;
   int rc = common_checks(p, &entry, hjobs, workspace, ws_bytes, no_alloc);
@@ -657,7 +657,7 @@ int fwd_impl(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_bytes
   if (timed) launch_zero_fill(ws + pl.off_clock, 16, st);
   Timed tg(TLORA_K_GEMM_FWD, st, timed);
   launch_seg_gemm(true, tiles, static_cast<const uint16_t*>(p->X), static_cast<const uint16_t*>(p->W), Sx, bp,
-                  pl.r_total, static_cast<uint16_t*>(Y), no_alloc ? nullptr : g_out_index, pl.T, pl.d_in, pl.d_out,
+                  pl.r_total, static_cast<uint16_t*>(Y), out_index, pl.T, pl.d_in, pl.d_out,
                   timed ? (g_clock_slot[0] = reinterpret_cast<unsigned long long*>(ws + pl.off_clock)) : nullptr, st);
   return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
 }
@@ -679,9 +679,13 @@ int tlora_fwd_noalloc(const tlora_problem_t* p, void* Y, void* hip_stream) {
   return fwd_impl(p, Y, ws, TLORA_NOALLOC_SCRATCH_BYTES, hip_stream, true);
 }
 
-int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* dA, void* const* dB, int flags,
-              void* workspace, size_t ws_bytes, void* hip_stream) {
-  std::lock_guard<std::recursive_mutex> lk(g_mu);
+}  // extern "C"
+
+namespace tlora {
+namespace {
+// The backward's launch sequence (out_index as in fwd_impl: dX rows are scattered).
+int bwd_impl(const tlora_problem_t* p, const void* dY, void* dX, void* const* dA, void* const* dB, int flags,
+             void* workspace, size_t ws_bytes, void* hip_stream, const int32_t* out_index) {
   const PlanEntry* entry = nullptr;
   std::vector<JobDev> hjobs;
   int rc = common_checks(p, &entry, hjobs, workspace, ws_bytes);
@@ -807,7 +811,7 @@ int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* d
       if (g_prof_on) launch_zero_fill(ws + pl.off_clock + 16, 16, st);
       Timed t(TLORA_K_GEMM_BWD, st);
       launch_seg_gemm(wt, tiles, dYb, wt ? Wt : static_cast<const uint16_t*>(p->W), dSx, wt ? atp : ap, pl.r_total,
-                      static_cast<uint16_t*>(dX), g_out_index, pl.T, pl.d_out, pl.d_in,
+                      static_cast<uint16_t*>(dX), out_index, pl.T, pl.d_out, pl.d_in,
                       g_prof_on ? (g_clock_slot[1] = reinterpret_cast<unsigned long long*>(ws + pl.off_clock) + 2) : nullptr,
                       st);
     }
@@ -835,6 +839,17 @@ int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* d
     }
   }
   return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+}
+
+}  // namespace
+}  // namespace tlora
+
+extern "C" {
+
+int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* dA, void* const* dB, int flags,
+              void* workspace, size_t ws_bytes, void* hip_stream) {
+  std::lock_guard<std::recursive_mutex> lk(g_mu);
+  return bwd_impl(p, dY, dX, dA, dB, flags, workspace, ws_bytes, hip_stream, nullptr);
 }
 
 // ---- adaptive nano-batching (Sec. 3.3) --------------------------------------------------------------------
@@ -1546,10 +1561,6 @@ int indexed_layout(const tlora_problem_t* p, IndexedLayout& L) {
   L.total = align_up(L.off_dx + (p->dtype == TLORA_F32 ? (size_t)L.T * p->d_in * L.elt : 0), 256);
   return TLORA_OK;
 }
-struct OutIndexScope {        // the inner call's GEMM scatters its rows while this is alive
-  explicit OutIndexScope(const int32_t* idx) { g_out_index = idx; }
-  ~OutIndexScope() { g_out_index = nullptr; }
-};
 }  // namespace
 
 size_t tlora_indexed_workspace_bytes(const tlora_problem_t* p) {
@@ -1577,10 +1588,7 @@ int tlora_fwd_indexed(const tlora_problem_t* p, const int32_t* row_index, void* 
   }
   tlora_problem_t q = *p;
   q.X = ws + L.off_x;
-  if (p->dtype == TLORA_BF16) {
-    OutIndexScope scope(row_index);
-    return tlora_fwd(&q, Y, workspace, L.inner, hip_stream);
-  }
+  if (p->dtype == TLORA_BF16) return fwd_impl(&q, Y, workspace, L.inner, hip_stream, false, row_index);
   rc = tlora_fwd(&q, ws + L.off_y, workspace, L.inner, hip_stream);
   if (rc != TLORA_OK) return rc;
   Timed t(TLORA_K_PERMUTE, st);
@@ -1609,10 +1617,8 @@ int tlora_bwd_indexed(const tlora_problem_t* p, const int32_t* row_index, const 
   }
   tlora_problem_t q = *p;
   q.X = ws + L.off_x;
-  if (p->dtype == TLORA_BF16 || !dX) {
-    OutIndexScope scope(row_index);
-    return tlora_bwd(&q, ws + L.off_y, dX, dA, dB, flags, workspace, L.inner, hip_stream);
-  }
+  if (p->dtype == TLORA_BF16 || !dX)
+    return bwd_impl(&q, ws + L.off_y, dX, dA, dB, flags, workspace, L.inner, hip_stream, row_index);
   rc = tlora_bwd(&q, ws + L.off_y, ws + L.off_dx, dA, dB, flags, workspace, L.inner, hip_stream);
   if (rc != TLORA_OK) return rc;
   Timed t(TLORA_K_PERMUTE, st);

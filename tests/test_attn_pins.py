@@ -35,21 +35,21 @@ def test_attention_closed_forms():
     np.testing.assert_allclose(O0[:, :8], np.cumsum(V[:, :8], axis=0) / np.arange(1, 7)[:, None], rtol=1e-13)
 
 
-def test_lse2_matches_library_logsumexp_and_probabilities():
+def test_lse_matches_library_logsumexp_and_probabilities():
     from scipy.special import logsumexp
     rng = np.random.default_rng(2)
     seq, Hq, Hkv, hd = [0, 3, 3, 9], 4, 2, 8
     Q, K, V = rng.normal(size=(9, Hq * hd)), rng.normal(size=(9, Hkv * hd)), rng.normal(size=(9, Hkv * hd))
-    lse2 = ao.attention_lse2(Q, K, seq, Hq, Hkv, hd)
+    lse = ao.attention_lse(Q, K, seq, Hq, Hkv, hd)
     _, probs = ao.attention(Q, K, V, seq, Hq, Hkv, hd)
     for s, (a, b) in enumerate(zip(seq[:-1], seq[1:])):
         for h in range(Hq):
             for t in range(a, b):
                 scores = np.array([Q[t, h * hd:(h + 1) * hd] @ K[u, (h // 2) * hd:(h // 2 + 1) * hd] for u in range(a, t + 1)])
                 scores /= np.sqrt(hd)
-                assert abs(lse2[t, h] - logsumexp(scores) / np.log(2.0)) < 1e-12
+                assert abs(lse[t, h] - logsumexp(scores)) < 1e-12
                 # exp(score - lse) reproduces the probabilities of the attention oracle
-                np.testing.assert_allclose(np.exp(scores - lse2[t, h] * np.log(2.0)), probs[(s, h)][t - a, :t - a + 1],
+                np.testing.assert_allclose(np.exp(scores - lse[t, h]), probs[(s, h)][t - a, :t - a + 1],
                                            rtol=1e-12)
 
 
