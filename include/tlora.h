@@ -390,7 +390,10 @@ int tlora_plan_dump(const tlora_problem_t* p, int32_t* rpad, int64_t* soff, int3
  *   "shrink_stages": LDS stages of the streaming shrink kernel             (4 | 8)
  *   "dx_transposed_w": 1 (default): dX runs against a transposed copy of W kept in the workspace | 0: against W
  *                    as it lies in memory (no copy, slower weight stream)
- *   "grad_tokens"  : minimum tokens per work unit of the dA / dB kernels   (multiple of 64)
+ *   "grad_tokens"  : minimum tokens per work unit of the dA / dB kernels   (multiple of 64, at most 4096)
+ *   "indexed_direct": 1 (default): bf16 token-indexed calls read the batch rows through the index list inside the
+ *                    kernels' loads (while T * max(d_in, d_out) * 2 bytes stays below 4 GiB) | 0: always gather the
+ *                    activations into the workspace first
  *   "plan_cache"   : 1 (default): the integer plan of a problem (tiles, work units, workspace layout) is kept, keyed
  *                    by the contents of (dtype, d_in, d_out, ranks, offsets), and reused by later calls with the same
  *                    values -- scales and pointers are taken from every call afresh | 0: rebuilt on every call.

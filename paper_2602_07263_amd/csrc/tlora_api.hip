@@ -47,6 +47,7 @@ struct Options {
   int grad_tokens = 256;
   int dx_transposed_w = 1;
   int plan_cache = 1;           // reuse plans of problems seen before (keyed by their contents)
+  int indexed_direct = 1;       // token-indexed bf16 calls fetch rows through the index inside the kernels' loads
 };
 Options g_opt;
 std::recursive_mutex g_mu;   // the nano-batch entry points call tlora_fwd / tlora_bwd under it
@@ -109,7 +110,8 @@ void build_grad_units(const Plan& pl, int D, std::vector<GradUnit>& units, std::
   };
   auto chunk_of = [&](int live, double shrink) {
     int chunk = std::max(g_opt.grad_tokens, (int)(32 * kGradRanks * live * shrink));
-    return (chunk + kGradStep - 1) / kGradStep * kGradStep;
+    chunk = (chunk + kGradStep - 1) / kGradStep * kGradStep;
+    return std::min(chunk, kGradMaxTokens);          // the kernel stages at most that many row indices per unit
   };
   auto count_units = [&](double shrink) {
     int64_t n = 0;
@@ -394,14 +396,15 @@ int prof_drain() {
 
 // S_j = X_j.A_j (or dS_j = dY_j.B_j^T): streaming kernel when the contraction length allows, else generic
 void run_shrink(const Plan& pl, const uint8_t* tb, const JobDev* jobs, const TileDev* tiles, const uint16_t* act, int K,
-                const uint16_t* packed, bool packed_is_atp, uint16_t* hi, uint16_t* lo, uint16_t* Sx, hipStream_t st) {
+                const uint16_t* packed, bool packed_is_atp, uint16_t* hi, uint16_t* lo, uint16_t* Sx,
+                const int32_t* row_index, hipStream_t st) {
   if (K % 32 == 0)
     launch_shrink_stream(jobs, tiles, reinterpret_cast<const ShrinkUnit*>(tb + pl.tb_stream),
                          (int)pl.stream_units.size(), pl.shrink_rows, g_opt.shrink_stages, act, K, packed, packed_is_atp,
-                         hi, lo, Sx, st);
+                         hi, lo, Sx, row_index, st);
   else
     launch_shrink(jobs, tiles, reinterpret_cast<const ShrinkUnit*>(tb + pl.tb_shrink), (int)pl.shrink_units.size(), 64,
-                  act, K, packed, packed_is_atp, hi, lo, Sx, st);
+                  act, K, packed, packed_is_atp, hi, lo, Sx, row_index, st);
 }
 
 int check_arch() {
@@ -577,9 +580,11 @@ namespace {
 // the current device, `ws_bytes` = its size); the plan and the workspace layout are the forward's alone, the tables
 // reach the device as kernel arguments (no staging buffer, no copy node), and nothing is timed: no HIP object is
 // created and no memory of any kind is allocated on this path.
-// out_index: null, or the output row of every (sorted) token row -- the GEMM then scatters its rows (token-indexed calls).
+// Token-indexed calls (bf16): out_index = the batch row of every token row of the job-sorted order -- the GEMM scatters
+// its output rows there; in_index = the same list when X is the batch in its own order, fetched through the list
+// inside the kernels' loads (null: X already lies in job-sorted order).
 int fwd_impl(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_bytes, void* hip_stream, bool no_alloc,
-             const int32_t* out_index = nullptr) {
+             const int32_t* out_index = nullptr, const int32_t* in_index = nullptr) {
   const PlanEntry* entry = nullptr;
   std::vector<JobDev> hjobs;
   int rc = common_checks(p, &entry, hjobs, workspace, ws_bytes, no_alloc);
@@ -652,12 +657,12 @@ int fwd_impl(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_bytes
   {
     Timed t(TLORA_K_SHRINK, st, timed);
     run_shrink(pl, tb, jobs, tiles, static_cast<const uint16_t*>(p->X), pl.d_in, atp, true,
-               reinterpret_cast<uint16_t*>(ws + pl.off_Shi), reinterpret_cast<uint16_t*>(ws + pl.off_Slo), Sx, st);
+               reinterpret_cast<uint16_t*>(ws + pl.off_Shi), reinterpret_cast<uint16_t*>(ws + pl.off_Slo), Sx, in_index, st);
   }
   if (timed) launch_zero_fill(ws + pl.off_clock, 16, st);
   Timed tg(TLORA_K_GEMM_FWD, st, timed);
   launch_seg_gemm(true, tiles, static_cast<const uint16_t*>(p->X), static_cast<const uint16_t*>(p->W), Sx, bp,
-                  pl.r_total, static_cast<uint16_t*>(Y), out_index, pl.T, pl.d_in, pl.d_out,
+                  pl.r_total, static_cast<uint16_t*>(Y), out_index, in_index, pl.T, pl.d_in, pl.d_out,
                   timed ? (g_clock_slot[0] = reinterpret_cast<unsigned long long*>(ws + pl.off_clock)) : nullptr, st);
   return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
 }
@@ -683,9 +688,10 @@ int tlora_fwd_noalloc(const tlora_problem_t* p, void* Y, void* hip_stream) {
 
 namespace tlora {
 namespace {
-// The backward's launch sequence (out_index as in fwd_impl: dX rows are scattered).
+// The backward's launch sequence (out_index / in_index as in fwd_impl: dX rows are scattered; X and dY are fetched
+// through the list).
 int bwd_impl(const tlora_problem_t* p, const void* dY, void* dX, void* const* dA, void* const* dB, int flags,
-             void* workspace, size_t ws_bytes, void* hip_stream, const int32_t* out_index) {
+             void* workspace, size_t ws_bytes, void* hip_stream, const int32_t* out_index, const int32_t* in_index) {
   const PlanEntry* entry = nullptr;
   std::vector<JobDev> hjobs;
   int rc = common_checks(p, &entry, hjobs, workspace, ws_bytes);
@@ -792,11 +798,11 @@ int bwd_impl(const tlora_problem_t* p, const void* dY, void* dX, void* const* dA
   if (pl.T > 0) {
     if (redo_S) {
       Timed t(TLORA_K_SHRINK, st);
-      run_shrink(pl, tb, jobs, tiles, Xb, pl.d_in, atp, true, Shi, Slo, Sx, st);
+      run_shrink(pl, tb, jobs, tiles, Xb, pl.d_in, atp, true, Shi, Slo, Sx, in_index, st);
     }
     {
       Timed t(TLORA_K_SHRINK, st);
-      run_shrink(pl, tb, jobs, tiles, dYb, pl.d_out, bp, false, dShi, dSlo, dSx, st);
+      run_shrink(pl, tb, jobs, tiles, dYb, pl.d_out, bp, false, dShi, dSlo, dSx, in_index, st);
     }
     if (dX) {
       // dX = dY . W^T contracts over W's contiguous dimension.  Against a transposed copy of W the weight tiles
@@ -811,7 +817,7 @@ int bwd_impl(const tlora_problem_t* p, const void* dY, void* dX, void* const* dA
       if (g_prof_on) launch_zero_fill(ws + pl.off_clock + 16, 16, st);
       Timed t(TLORA_K_GEMM_BWD, st);
       launch_seg_gemm(wt, tiles, dYb, wt ? Wt : static_cast<const uint16_t*>(p->W), dSx, wt ? atp : ap, pl.r_total,
-                      static_cast<uint16_t*>(dX), out_index, pl.T, pl.d_out, pl.d_in,
+                      static_cast<uint16_t*>(dX), out_index, in_index, pl.T, pl.d_out, pl.d_in,
                       g_prof_on ? (g_clock_slot[1] = reinterpret_cast<unsigned long long*>(ws + pl.off_clock) + 2) : nullptr,
                       st);
     }
@@ -820,7 +826,7 @@ int bwd_impl(const tlora_problem_t* p, const void* dY, void* dX, void* const* dA
     {
       Timed t(TLORA_K_RANK_GRAD, st);
       launch_rank_grad(jobs, reinterpret_cast<const GradUnit*>(tb + pl.tb_gBu), (int)pl.gradB_units.size(), Shi, Slo,
-                       dYb, pl.d_out, partial, st);
+                       dYb, pl.d_out, partial, in_index, st);
     }
     {
       Timed t(TLORA_K_GRAD_REDUCE, st);
@@ -830,7 +836,7 @@ int bwd_impl(const tlora_problem_t* p, const void* dY, void* dX, void* const* dA
     {
       Timed t(TLORA_K_RANK_GRAD, st);
       launch_rank_grad(jobs, reinterpret_cast<const GradUnit*>(tb + pl.tb_gAu), (int)pl.gradA_units.size(), dShi, dSlo,
-                       Xb, pl.d_in, partial, st);
+                       Xb, pl.d_in, partial, in_index, st);
     }
     {
       Timed t(TLORA_K_GRAD_REDUCE, st);
@@ -849,7 +855,7 @@ extern "C" {
 int tlora_bwd(const tlora_problem_t* p, const void* dY, void* dX, void* const* dA, void* const* dB, int flags,
               void* workspace, size_t ws_bytes, void* hip_stream) {
   std::lock_guard<std::recursive_mutex> lk(g_mu);
-  return bwd_impl(p, dY, dX, dA, dB, flags, workspace, ws_bytes, hip_stream, nullptr);
+  return bwd_impl(p, dY, dX, dA, dB, flags, workspace, ws_bytes, hip_stream, nullptr, nullptr);
 }
 
 // ---- adaptive nano-batching (Sec. 3.3) --------------------------------------------------------------------
@@ -1547,6 +1553,10 @@ struct IndexedLayout {
   size_t inner = 0, off_x = 0, off_y = 0, off_dx = 0, total = 0, elt = 2;
   int64_t T = 0;
 };
+// The kernels that fetch rows through the index list keep 32-bit byte offsets from the tensor's base.
+inline bool direct_index_ok(int64_t T, int64_t width) {
+  return g_opt.indexed_direct != 0 && T * width * 2 < ((int64_t)1 << 32);
+}
 int indexed_layout(const tlora_problem_t* p, IndexedLayout& L) {
   const int rc = validate(p);
   if (rc != TLORA_OK) return rc;
@@ -1582,12 +1592,23 @@ int tlora_fwd_indexed(const tlora_problem_t* p, const int32_t* row_index, void* 
   if (L.T == 0) return TLORA_OK;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   uint8_t* ws = static_cast<uint8_t*>(workspace);
+  // bf16: the kernels fetch the activation rows through the list inside their loads and the GEMM scatters its output
+  // rows, so the batch is read and written exactly as often as in a contiguous call (the in-kernel row offsets are 32
+  // bits: larger activations take the gathered copy below)
+  if (p->dtype == TLORA_BF16 && direct_index_ok(L.T, p->d_in))
+    return fwd_impl(p, Y, workspace, L.inner, hip_stream, false, row_index, row_index);
+  tlora_problem_t q = *p;
+  q.X = ws + L.off_x;
+  {   // validate everything the inner call will check before the gather is queued
+    const PlanEntry* e = nullptr;
+    std::vector<JobDev> hj;
+    rc = common_checks(&q, &e, hj, workspace, L.inner);
+    if (rc != TLORA_OK) return rc;
+  }
   {
     Timed t(TLORA_K_PERMUTE, st);
     launch_permute_rows(p->X, ws + L.off_x, row_index, L.T, (int64_t)p->d_in * L.elt, false, st);
   }
-  tlora_problem_t q = *p;
-  q.X = ws + L.off_x;
   if (p->dtype == TLORA_BF16) return fwd_impl(&q, Y, workspace, L.inner, hip_stream, false, row_index);
   rc = tlora_fwd(&q, ws + L.off_y, workspace, L.inner, hip_stream);
   if (rc != TLORA_OK) return rc;
@@ -1609,16 +1630,29 @@ int tlora_bwd_indexed(const tlora_problem_t* p, const int32_t* row_index, const 
   if (rc != TLORA_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   uint8_t* ws = static_cast<uint8_t*>(workspace);
+  if (p->dtype == TLORA_BF16 && direct_index_ok(L.T, std::max(p->d_in, p->d_out)))
+    return bwd_impl(p, dY, dX, dA, dB, flags, workspace, L.inner, hip_stream, row_index, row_index);
+  tlora_problem_t q = *p;
+  q.X = ws + L.off_x;
+  {   // validate what the inner call will check before the gathers are queued
+    const PlanEntry* e = nullptr;
+    std::vector<JobDev> hj;
+    rc = common_checks(&q, &e, hj, workspace, L.inner);
+    if (rc != TLORA_OK) return rc;
+    if ((dA == nullptr) != (dB == nullptr)) return TLORA_ENULL;
+    if (dA)
+      for (int j = 0; j < p->num_jobs; ++j)
+        if (p->ranks[j] > 0 && (!dA[j] || !dB[j])) return TLORA_ENULL;
+    if (flags & ~(TLORA_BWD_REUSE_S | TLORA_BWD_REUSE_WT | TLORA_BWD_ACCUMULATE)) return TLORA_EINVAL;
+  }
   if (L.T > 0) {
     Timed t(TLORA_K_PERMUTE, st);
     // the sorted activations are gathered again: the region may have been reused since the forward
     launch_permute_rows(p->X, ws + L.off_x, row_index, L.T, (int64_t)p->d_in * L.elt, false, st);
     launch_permute_rows(dY, ws + L.off_y, row_index, L.T, (int64_t)p->d_out * L.elt, false, st);
   }
-  tlora_problem_t q = *p;
-  q.X = ws + L.off_x;
   if (p->dtype == TLORA_BF16 || !dX)
-    return bwd_impl(&q, ws + L.off_y, dX, dA, dB, flags, workspace, L.inner, hip_stream, row_index);
+    return bwd_impl(&q, ws + L.off_y, dX, dA, dB, flags, workspace, L.inner, hip_stream, row_index, nullptr);
   rc = tlora_bwd(&q, ws + L.off_y, ws + L.off_dx, dA, dB, flags, workspace, L.inner, hip_stream);
   if (rc != TLORA_OK) return rc;
   Timed t(TLORA_K_PERMUTE, st);
@@ -1714,6 +1748,11 @@ int tlora_set_option(const char* name, int64_t value) {
     g_opt.dx_transposed_w = (int)value;
     return TLORA_OK;
   }
+  if (n == "indexed_direct") {
+    if (value != 0 && value != 1) return TLORA_EINVAL;
+    g_opt.indexed_direct = (int)value;
+    return TLORA_OK;
+  }
   if (n == "plan_cache") {
     if (value != 0 && value != 1) return TLORA_EINVAL;
     g_opt.plan_cache = (int)value;
@@ -1721,7 +1760,7 @@ int tlora_set_option(const char* name, int64_t value) {
     return TLORA_OK;
   }
   if (n == "grad_tokens") {
-    if (value < 64 || value % 64 || value > (1 << 20)) return TLORA_EINVAL;
+    if (value < 64 || value % 64 || value > kGradMaxTokens) return TLORA_EINVAL;
     g_opt.grad_tokens = (int)value;
     return TLORA_OK;
   }

@@ -15,6 +15,7 @@ constexpr int kGradCols = 256;      // feature columns per dA/dB work unit (4 wa
 constexpr int kGradRanks = 32;      // rank rows per MFMA block of the dA/dB kernel
 constexpr int kGradMaxBlocks = 4;   // rank blocks of 32 per dA/dB work unit (128 rank rows)
 constexpr int kGradStep = 32;       // tokens per pipeline step of the dA/dB kernel
+constexpr int kGradMaxTokens = 4096;  // most tokens of one dA/dB work unit (32 per live rank row of a full 128-row block)
 
 // One job's view of the problem (Sec. 3.2: one adapter branch per job on the shared backbone).
 struct JobDev {

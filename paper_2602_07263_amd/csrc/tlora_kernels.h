@@ -25,30 +25,35 @@ void launch_zero_fill(void* ptr, size_t bytes, hipStream_t st);
 void launch_table_write(const void* host_src, size_t bytes, void* dst, hipStream_t st);
 
 // out_j[t, p] = sum_k act[t, k] * P_j[p, k]   (P_j = A_j^T packed, or B_j packed)
+// row_index (null = identity): the row of `act` that holds token row t of the job-sorted order (token-indexed calls).
 // writes the result as bf16 hi + lo planes (packed ragged layout, each job's rows zero padded to a multiple of
 // 32) and bf16 `scale_j * S` into the per-tile K-extension matrices `Sx`.
 // packed_is_atp: P_j = atp + atp_off_j (row stride K);  otherwise P_j = b_all + roff_j * K.
 void launch_shrink(const JobDev* jobs, const TileDev* tiles, const ShrinkUnit* units, int num_units,
                    int shrink_rows, const uint16_t* act, int K, const uint16_t* packed, bool packed_is_atp,
-                   uint16_t* S_hi, uint16_t* S_lo, uint16_t* Sx, hipStream_t st);
+                   uint16_t* S_hi, uint16_t* S_lo, uint16_t* Sx, const int32_t* row_index, hipStream_t st);
 // Same result for K % 32 == 0 with streaming units (shrink_rows = 64 | 128 token rows x 128 rank columns).
 void launch_shrink_stream(const JobDev* jobs, const TileDev* tiles, const ShrinkUnit* units, int num_units,
                           int shrink_rows, int stages, const uint16_t* act, int K, const uint16_t* packed,
-                          bool packed_is_atp, uint16_t* S_hi, uint16_t* S_lo, uint16_t* Sx, hipStream_t st);
+                          bool packed_is_atp, uint16_t* S_hi, uint16_t* S_lo, uint16_t* Sx, const int32_t* row_index,
+                          hipStream_t st);
 
 // out[t, n] = sum_k act[t, k] * Wop[k, n] + sum_p Sx_tile[t, p] * Eop[roff_first + p, n]
 //   w_is_kn = true : W is [K, N] row-major (forward,  Eop = b_all [R + 32, N])
 //   w_is_kn = false: W is [N, K] row-major (backward, Eop = a_all^T, stored [N, R + 32])
 void launch_seg_gemm(bool w_is_kn, const TileDev* tiles, const uint16_t* act, const uint16_t* W,
                      const uint16_t* Sx, const uint16_t* packed, int r_total, uint16_t* out,
-                     const int32_t* out_index /* null, or the output row of every row (scatter) */, int T, int K, int N,
+                     const int32_t* out_index /* null, or the output row of every row (scatter) */,
+                     const int32_t* in_index /* null, or the row of `act` behind every row (gather; needs T * K * 2 < 4 GiB) */,
+                     int T, int K, int N,
                      unsigned long long* clk /* null, or 2 zeroed words: every 64th workgroup adds the shader
                                                 cycles and 100 MHz ticks of its K-loop */,
                      hipStream_t st);
 
 // partial[u] = sum_{t in unit u} U_j[t, p] * V[t, c]   then   G_j = scale_j * sum_u partial[u]
 void launch_rank_grad(const JobDev* jobs, const GradUnit* units, int num_units, const uint16_t* U_hi,
-                      const uint16_t* U_lo, const uint16_t* V, int D, float* partial, hipStream_t st);
+                      const uint16_t* U_lo, const uint16_t* V, int D, float* partial,
+                      const int32_t* row_index /* null, or the row of V behind every token row */, hipStream_t st);
 // accumulate: G_j += ... instead of G_j = ...
 void launch_grad_reduce(const JobDev* jobs, const GradGroup* groups, int num_groups, const float* partial, int D,
                         bool out_is_dA, bool accumulate, hipStream_t st);

@@ -320,7 +320,7 @@ __global__ void __launch_bounds__(256) shrink_kernel(const JobDev* __restrict__ 
                                                      const uint16_t* __restrict__ act, int K,
                                                      const uint16_t* __restrict__ packed, int packed_is_atp,
                                                      uint16_t* __restrict__ Shi, uint16_t* __restrict__ Slo,
-                                                     uint16_t* __restrict__ Sx) {
+                                                     uint16_t* __restrict__ Sx, const int32_t* __restrict__ row_index) {
   constexpr int WM = ROWS / 32;          // waves along token rows
   constexpr int WN = 4 / WM;             // waves along rank columns
   constexpr int PW = kShrinkCols / WN;   // rank columns per wave
@@ -340,7 +340,6 @@ __global__ void __launch_bounds__(256) shrink_kernel(const JobDev* __restrict__ 
   const int p0 = u.pb * kShrinkCols;                     // first padded rank column of this unit
   const int pvalid = min(kShrinkCols, jb.rpad - p0);     // > 0 by construction
   const uint16_t* P = packed + (packed_is_atp ? jb.atp_off : (int64_t)jb.roff * K) + (int64_t)p0 * K;
-  const uint16_t* Arow = act + (int64_t)u.t0 * K;
 
   f32x16 acc[NPB];
 #pragma unroll
@@ -348,13 +347,20 @@ __global__ void __launch_bounds__(256) shrink_kernel(const JobDev* __restrict__ 
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
 
+  // the activation rows this thread fetches (row_index: the batch row that holds token row t of the job-sorted order)
+  const uint16_t* arow[A_CH];
+#pragma unroll
+  for (int i = 0; i < A_CH; ++i) {
+    const int t = u.t0 + min((tid + i * 256) >> 3, u.nrows - 1);
+    arow[i] = act + (int64_t)(row_index ? row_index[t] : t) * K;
+  }
   u32x4 areg[A_CH], preg[P_CH];
   auto load_tiles = [&](int k0) {
 #pragma unroll
     for (int i = 0; i < A_CH; ++i) {
       const int id = tid + i * 256, r = id >> 3, c = id & 7;
       const bool ok = r < u.nrows && k0 + c * 8 < K;
-      areg[i] = ok ? ldg16(Arow + (int64_t)r * K + k0 + c * 8) : u32x4{0, 0, 0, 0};
+      areg[i] = ok ? ldg16(arow[i] + k0 + c * 8) : u32x4{0, 0, 0, 0};
     }
 #pragma unroll
     for (int i = 0; i < P_CH; ++i) {
@@ -455,7 +461,7 @@ __device__ __forceinline__ void shrink_stream_body(uint8_t* lds, const ShrinkUni
                                                    const uint16_t* __restrict__ act, int K,
                                                    const uint16_t* __restrict__ packed, int packed_is_atp,
                                                    uint16_t* __restrict__ Shi, uint16_t* __restrict__ Slo,
-                                                   uint16_t* __restrict__ Sx) {
+                                                   uint16_t* __restrict__ Sx, const int32_t* __restrict__ row_index) {
   constexpr int CW = PCOLS == 32 ? 4 : WAVES;      // waves that multiply
   constexpr int WM = PCOLS == 32 ? 4 : ROWS / 32;  // waves along token rows
   constexpr int WN = CW / WM;                      // waves along rank columns
@@ -478,7 +484,6 @@ __device__ __forceinline__ void shrink_stream_body(uint8_t* lds, const ShrinkUni
   const int p0 = u.pb * PCOLS;
   const int pvalid = min(PCOLS, jb.rpad - p0);     // > 0 by construction
   const uint16_t* P = packed + (packed_is_atp ? jb.atp_off : (int64_t)jb.roff * K) + (int64_t)p0 * K;
-  const uint16_t* Arow = act + (int64_t)u.t0 * K;
   const int nsteps = K / KS;
 
   f32x16 acc[NPB];
@@ -500,7 +505,8 @@ __device__ __forceinline__ void shrink_stream_body(uint8_t* lds, const ShrinkUni
   for (int i = 0; i < A_LD; ++i) {
     const int q = (wave * A_LD + i) * 64 + lane, r = q / CPR;
     const int c = KS == 32 ? (q & 3) ^ ((r >> 2) & 3) : (q & 7) ^ ((r >> 1) & 7);
-    asrc[i] = Arow + (int64_t)min(r, u.nrows - 1) * K + c * 8;
+    const int t = u.t0 + min(r, u.nrows - 1);      // token row of the job-sorted order; row_index: where it lies
+    asrc[i] = act + (int64_t)(row_index ? row_index[t] : t) * K + c * 8;
   }
 #pragma unroll
   for (int i = 0; i < P_LD; ++i) {
@@ -611,7 +617,8 @@ __global__ void __launch_bounds__(WAVES * 64) shrink_stream_kernel(const JobDev*
                                                                    const uint16_t* __restrict__ act, int K,
                                                                    const uint16_t* __restrict__ packed, int packed_is_atp,
                                                                    uint16_t* __restrict__ Shi, uint16_t* __restrict__ Slo,
-                                                                   uint16_t* __restrict__ Sx) {
+                                                                   uint16_t* __restrict__ Sx,
+                                                                   const int32_t* __restrict__ row_index) {
   // NS stages of (ROWS + 128) rows, or -- 128-row units of low-rank jobs, K-steps of 64 -- 8 stages of 128 + 32 rows
   constexpr int LOW = ROWS == 128 && KS == 64;
   constexpr int BYTES = LOW ? 8 * (128 + 32) * 128 : NS * (ROWS + 128) * KS * 2;
@@ -620,29 +627,31 @@ __global__ void __launch_bounds__(WAVES * 64) shrink_stream_kernel(const JobDev*
   const ShrinkUnit u = units[blockIdx.x];
   const JobDev jb = jobs[u.job];
   if (LOW && jb.rpad <= 32)
-    shrink_stream_body<128, 8, 64, 32, WAVES>(lds, u, jb, tiles, act, K, packed, packed_is_atp, Shi, Slo, Sx);
+    shrink_stream_body<128, 8, 64, 32, WAVES>(lds, u, jb, tiles, act, K, packed, packed_is_atp, Shi, Slo, Sx, row_index);
   else
-    shrink_stream_body<ROWS, NS_HIGH, KS, 128, WAVES>(lds, u, jb, tiles, act, K, packed, packed_is_atp, Shi, Slo, Sx);
+    shrink_stream_body<ROWS, NS_HIGH, KS, 128, WAVES>(lds, u, jb, tiles, act, K, packed, packed_is_atp, Shi, Slo, Sx,
+                                                      row_index);
 }
 
 void launch_shrink(const JobDev* jobs, const TileDev* tiles, const ShrinkUnit* units, int num_units, int shrink_rows,
                    const uint16_t* act, int K, const uint16_t* packed, bool packed_is_atp, uint16_t* S_hi,
-                   uint16_t* S_lo, uint16_t* Sx, hipStream_t st) {
+                   uint16_t* S_lo, uint16_t* Sx, const int32_t* row_index, hipStream_t st) {
   if (num_units == 0) return;
   // generic kernel: units of 64 rows x 64 rank columns
   hipLaunchKernelGGL(shrink_kernel<64>, dim3(num_units), dim3(256), 0, st, jobs, tiles, units, act, K, packed,
-                     packed_is_atp ? 1 : 0, S_hi, S_lo, Sx);
+                     packed_is_atp ? 1 : 0, S_hi, S_lo, Sx, row_index);
   (void)shrink_rows;
 }
 
 void launch_shrink_stream(const JobDev* jobs, const TileDev* tiles, const ShrinkUnit* units, int num_units,
                           int shrink_rows, int stages, const uint16_t* act, int K, const uint16_t* packed,
-                          bool packed_is_atp, uint16_t* S_hi, uint16_t* S_lo, uint16_t* Sx, hipStream_t st) {
+                          bool packed_is_atp, uint16_t* S_hi, uint16_t* S_lo, uint16_t* Sx, const int32_t* row_index,
+                          hipStream_t st) {
   if (num_units == 0) return;
   const int atp = packed_is_atp ? 1 : 0;
 #define TLORA_SHRINK_LAUNCH(R, N, KS, WV)                                                                              \
   hipLaunchKernelGGL((shrink_stream_kernel<R, N, KS, WV>), dim3(num_units), dim3(WV * 64), 0, st, jobs, tiles, units,  \
-                     act, K, packed, atp, S_hi, S_lo, Sx)
+                     act, K, packed, atp, S_hi, S_lo, Sx, row_index)
   const bool wide = K % 64 == 0 && stages < 8;      // K-steps of 64: half as many barriers per byte
   if (shrink_rows == 128) {
     if (wide)             TLORA_SHRINK_LAUNCH(128, 4, 64, 8);
@@ -687,11 +696,15 @@ struct GemmParams {
   int tiles_m, tiles_n;
   unsigned long long* clk;  // optional: every 64th workgroup adds {cycles, 100 MHz ticks} of its K-loop (pre-zeroed)
   const int32_t* out_index; // optional: output row of tile row t (scatter); null = t itself
+  const int32_t* in_index;  // INDEXED instantiations: batch row that holds activation row t (gather inside the loads)
 };
 
 // KTAIL: the instantiation for K % 32 != 0 carries the extra predicated step; keeping it out of the common one
 // keeps its register pressure away from every tile.
-template <bool KN, bool KTAIL>
+// INDEXED: the activation rows are fetched through P.in_index (token-indexed calls: the batch stays in its own order).
+// A lane then keeps one byte offset per row it loads (four) instead of two offsets plus scalar row strides; offsets are
+// 32 bits, so the launcher takes this instantiation only while T * K * 2 stays below 4 GiB.
+template <bool KN, bool KTAIL, bool INDEXED>
 __global__ void __launch_bounds__(512) seg_gemm_kernel(GemmParams P) {
   constexpr int NT = 512;                            // threads: 8 waves
   constexpr int NFB = 4;                             // 16-wide feature blocks per wave (64 columns)
@@ -772,7 +785,7 @@ __global__ void __launch_bounds__(512) seg_gemm_kernel(GemmParams P) {
     const int lr = wave * 32 + (lane >> 3);                   // row / column of the tile for i = 0 (i adds 8)
     const int coff = ((lane & 3) ^ (lane >> 4)) * 16;         // byte offset of the lane's chunk inside its 32-k half
     const int h0 = (lane >> 2) & 1;                           // which half, for even i (odd i: the other one)
-    const char* const a_base = uniform_ptr(reinterpret_cast<const char*>(P.act + (int64_t)row0 * P.K));
+    const char* const a_base = uniform_ptr(reinterpret_cast<const char*>(INDEXED ? P.act : P.act + (int64_t)row0 * P.K));
     const char* const x_base = uniform_ptr(reinterpret_cast<const char*>(P.Sx + td.aoff) - (int64_t)nfull * 64);
     const char* const w_base = uniform_ptr(reinterpret_cast<const char*>(KN ? P.W + col0 : P.W + (int64_t)col0 * P.K));
     const char* const e_base = uniform_ptr(
@@ -786,18 +799,30 @@ __global__ void __launch_bounds__(512) seg_gemm_kernel(GemmParams P) {
 #pragma unroll
     for (int par = 0; par < 2; ++par) {
       k_off[par] = (uint32_t)lr * (uint32_t)(P.K * 2) + coff + (h0 ^ par) * 64;       // rows of K elements: act, NT weight
-      x_off[par] = (uint32_t)lr * (uint32_t)(td.kext * 2) + coff + (h0 ^ par) * 64;   // rows of the adapter operand
+      x_off[par] = INDEXED ? 0u : (uint32_t)lr * (uint32_t)(td.kext * 2) + coff + (h0 ^ par) * 64;   // rows of the adapter operand
       const int kl = wave * 8 + par * 2 + (lane >> 5);                                // forward weight: k-row of i = par
       const int c = (lane & 31) ^ ((kl & 3) << 2) ^ (((kl >> 3) & 1) << 1);
       kn_off[par] = KN ? (uint32_t)(kl & 31) * (uint32_t)(P.N * 2) + c * 16 : 0u;
     }
+    // INDEXED: byte offset (from P.act) of the batch row behind each of the lane's four tile rows, chunk and half
+    // included; rows beyond the problem edge repeat the last valid one
+    uint32_t g_off[INDEXED ? 4 : 1];
+    if (INDEXED) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        g_off[i] = (uint32_t)P.in_index[row0 + min(lr + i * 8, rows_valid - 1)] * (uint32_t)(P.K * 2) + coff + (h0 ^ (i & 1)) * 64;
+    }
     auto issue_act = [&](int slot, int tq) {                  // activation tile holding steps tq, tq + 1 (tq >= 0)
       const uint32_t dst = lds0 + slot * SLOT + wave * 4096;
-      if (interior_m && tq + 1 < nfull) {
+      if (INDEXED && tq + 1 < nfull) {
+        const char* const sb = a_base + (int64_t)tq * 64;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) dma16s(g_off[i], sb, dst + i * 1024);
+      } else if (!INDEXED && interior_m && tq + 1 < nfull) {
         const char* const sb = a_base + (int64_t)tq * 64;
 #pragma unroll
         for (int i = 0; i < 4; ++i) dma16s(k_off[i & 1], uniform_ptr(sb + (int64_t)i * 16 * P.K), dst + i * 1024);
-      } else if (tq >= nfull && tq + 1 < ntot) {
+      } else if (!INDEXED && tq >= nfull && tq + 1 < ntot) {   // (INDEXED keeps no offsets for these few steps: general path)
         const char* const sb = x_base + (int64_t)tq * 64;
 #pragma unroll
         for (int i = 0; i < 4; ++i) dma16s(x_off[i & 1], uniform_ptr(sb + (int64_t)i * 16 * td.kext), dst + i * 1024);
@@ -810,7 +835,8 @@ __global__ void __launch_bounds__(512) seg_gemm_kernel(GemmParams P) {
           const int t = min(max(tq + (h0 ^ (i & 1)), 0), ntot - 1);
           const bool ext = t >= nfull;
           const uint32_t off = (ext ? (uint32_t)r * (uint32_t)(td.kext * 2)
-                                    : (uint32_t)min(r, rows_valid - 1) * (uint32_t)(P.K * 2)) + t * 64 + coff;
+                                : INDEXED ? g_off[i] - coff - (h0 ^ (i & 1)) * 64
+                                          : (uint32_t)min(r, rows_valid - 1) * (uint32_t)(P.K * 2)) + t * 64 + coff;
           dma16((ext ? x_base : a_base) + off, dst + i * 1024);
         }
       }
@@ -952,7 +978,8 @@ __global__ void __launch_bounds__(512) seg_gemm_kernel(GemmParams P) {
     for (int i = 0; i < TCH; ++i) {
       const int id = tid + i * NT, r = id >> 2, c = id & 3;
       const bool ok = r < rows_valid && c * 8 < kvalid;
-      areg[i] = ok ? ldg16(P.act + (int64_t)(row0 + r) * P.K + k0 + c * 8) : u32x4{0, 0, 0, 0};
+      const int64_t arow = INDEXED ? (int64_t)P.in_index[row0 + min(r, rows_valid - 1)] : (int64_t)(row0 + r);
+      areg[i] = ok ? ldg16(P.act + arow * P.K + k0 + c * 8) : u32x4{0, 0, 0, 0};
       if (KN) {
         const int k = id >> 5, cc = id & 31;
         const bool okb = k < kvalid && col0 + cc * 8 < P.N;
@@ -1014,11 +1041,12 @@ __global__ void __launch_bounds__(512) seg_gemm_kernel(GemmParams P) {
 }
 
 void launch_seg_gemm(bool w_is_kn, const TileDev* tiles, const uint16_t* act, const uint16_t* W, const uint16_t* Sx,
-                     const uint16_t* packed, int r_total, uint16_t* out, const int32_t* out_index, int T, int K, int N,
-                     unsigned long long* clk, hipStream_t st) {
+                     const uint16_t* packed, int r_total, uint16_t* out, const int32_t* out_index,
+                     const int32_t* in_index, int T, int K, int N, unsigned long long* clk, hipStream_t st) {
   GemmParams P;
   P.clk = clk;
   P.out_index = out_index;
+  P.in_index = in_index;
   P.tiles = tiles;  P.act = act;  P.W = W;  P.Sx = Sx;  P.packed = packed;  P.out = out;
   P.T = T;  P.K = K;  P.N = N;  P.ra = r_total + 32;
   P.tiles_m = (T + kGemmBM - 1) / kGemmBM;
@@ -1026,9 +1054,15 @@ void launch_seg_gemm(bool w_is_kn, const TileDev* tiles, const uint16_t* act, co
   const int nb = P.tiles_m * P.tiles_n;
   if (nb == 0) return;
   const bool tail = K % kGemmBK != 0;
-#define TLORA_GEMM_LAUNCH(KN, TAIL) hipLaunchKernelGGL((seg_gemm_kernel<KN, TAIL>), dim3(nb), dim3(512), 0, st, P)
-  if (w_is_kn) { if (tail) TLORA_GEMM_LAUNCH(true, true);  else TLORA_GEMM_LAUNCH(true, false); }
-  else         { if (tail) TLORA_GEMM_LAUNCH(false, true); else TLORA_GEMM_LAUNCH(false, false); }
+#define TLORA_GEMM_LAUNCH(KN, TAIL, IDX) \
+  hipLaunchKernelGGL((seg_gemm_kernel<KN, TAIL, IDX>), dim3(nb), dim3(512), 0, st, P)
+  if (in_index) {
+    if (w_is_kn) { if (tail) TLORA_GEMM_LAUNCH(true, true, true);  else TLORA_GEMM_LAUNCH(true, false, true); }
+    else         { if (tail) TLORA_GEMM_LAUNCH(false, true, true); else TLORA_GEMM_LAUNCH(false, false, true); }
+  } else {
+    if (w_is_kn) { if (tail) TLORA_GEMM_LAUNCH(true, true, false);  else TLORA_GEMM_LAUNCH(true, false, false); }
+    else         { if (tail) TLORA_GEMM_LAUNCH(false, true, false); else TLORA_GEMM_LAUNCH(false, false, false); }
+  }
 #undef TLORA_GEMM_LAUNCH
 }
 
@@ -1062,12 +1096,17 @@ __device__ __forceinline__ bf16x8 frag_tr_u(const uint8_t* plane, int pitch, int
 // reads of one overlap the MFMAs of the other, and a 128-rank unit's 32 MFMAs and 20 KB of reads per step are split
 // over two waves (with four waves such a unit took about twice as long per byte as a low-rank one, and the slowest
 // units of the one-round launch set its duration).
+// INDEXED: the rows of V are fetched through row_index (token-indexed calls).  A separate instantiation, so that the
+// plain one carries no trace of it: even a branch around a memory load inside the load loop would make the compiler
+// wait, where the paths merge, for every asynchronous load in flight.
+template <bool INDEXED>
 __global__ void __launch_bounds__(512) rank_grad_kernel(const JobDev* __restrict__ jobs,
                                                         const GradUnit* __restrict__ units,
                                                         const uint16_t* __restrict__ Uhi,
                                                         const uint16_t* __restrict__ Ulo,
                                                         const uint16_t* __restrict__ V, int D,
-                                                        float* __restrict__ partial) {
+                                                        float* __restrict__ partial,
+                                                        const int32_t* __restrict__ row_index) {
   constexpr int MB = kGradMaxBlocks;                        // the U tile always has room for 4 blocks of 32 ranks;
   constexpr int RP = kGradRanks * MB;                       // a unit multiplies only its u.mb live ones
   constexpr int UPITCH = 2 * RP;                            // 256 bytes per token row of a U tile
@@ -1091,6 +1130,9 @@ __global__ void __launch_bounds__(512) rank_grad_kernel(const JobDev* __restrict
   __shared__ __attribute__((aligned(1024))) uint8_t h1[2 * UPLANE];
   __shared__ __attribute__((aligned(1024))) uint8_t h2[2 * UPLANE];
   __shared__ __attribute__((aligned(1024))) uint8_t h3[2 * UPLANE];
+  // token-indexed calls: where in the batch each token row of the unit lies (row_index of the unit's chunk, staged
+  // once so that the load loop never waits for an index from memory; a unit has at most kGradMaxTokens tokens)
+  __shared__ int32_t srow[INDEXED ? kGradMaxTokens : 1];
 
   const GradUnit u = units[blockIdx.x];
   const JobDev jb = jobs[u.job];
@@ -1136,13 +1178,18 @@ __global__ void __launch_bounds__(512) rank_grad_kernel(const JobDev* __restrict
     usrc[i] = (plane ? Ulo : Uhi) + jb.soff + (int64_t)(u.t0 - jb.row0 + k) * jb.rpad + p;
     udst[i] = plane * UPLANE + within * 1024;
   }
+  if (INDEXED) {
+    for (int i = tid; i < min(u.t1 - u.t0, kGradMaxTokens); i += WAVES * 64) srow[i] = row_index[u.t0 + i];
+    __syncthreads();
+  }
   int f_step = 0;                                     // next step to fetch
   auto issue = [&](uint8_t* S, uint8_t* H) {
     const int st = min(f_step, nsteps - 1);           // trailing issues re-load the last step (uniform load count)
     const uint32_t sbase = lds_addr(S + wave * (V_LD * 1024)), hbase = lds_addr(H);
 #pragma unroll
     for (int i = 0; i < V_LD; ++i) {
-      const int t = min(u.t0 + st * kGradStep + vk[i], u.t1 - 1);
+      int t = min(u.t0 + st * kGradStep + vk[i], u.t1 - 1);
+      if (INDEXED) t = srow[min(t - u.t0, kGradMaxTokens - 1)];
       dma16(V + (int64_t)t * D + vcol[i], sbase + i * 1024);
     }
 #pragma unroll
@@ -1211,9 +1258,15 @@ __global__ void __launch_bounds__(512) rank_grad_kernel(const JobDev* __restrict
 }
 
 void launch_rank_grad(const JobDev* jobs, const GradUnit* units, int num_units, const uint16_t* U_hi,
-                      const uint16_t* U_lo, const uint16_t* V, int D, float* partial, hipStream_t st) {
+                      const uint16_t* U_lo, const uint16_t* V, int D, float* partial, const int32_t* row_index,
+                      hipStream_t st) {
   if (num_units == 0) return;
-  hipLaunchKernelGGL(rank_grad_kernel, dim3(num_units), dim3(512), 0, st, jobs, units, U_hi, U_lo, V, D, partial);
+  if (row_index)
+    hipLaunchKernelGGL(rank_grad_kernel<true>, dim3(num_units), dim3(512), 0, st, jobs, units, U_hi, U_lo, V, D, partial,
+                       row_index);
+  else
+    hipLaunchKernelGGL(rank_grad_kernel<false>, dim3(num_units), dim3(512), 0, st, jobs, units, U_hi, U_lo, V, D,
+                       partial, row_index);
 }
 
 // Sum the partial tiles of one output tile in unit order, scale, and store (dB_j row-major [r, D];

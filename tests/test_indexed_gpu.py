@@ -10,13 +10,31 @@ from tests import parity_util as pu
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+# dtype, d_in, d_out, path: "direct" = rows fetched through the index inside the kernels' loads (bf16 only),
+# "gathered" = activations copied into job-sorted order first.  320 -> 264 has a contraction tail in the backward
+# (264 = 8 * 32 + 8) and takes the generic shrink kernel there; 512 -> 768 runs the streaming kernels on both sides.
+VARIANTS = [("bf16", 320, 264, "direct"), ("bf16", 320, 264, "gathered"), ("bf16", 512, 768, "direct"),
+            ("f32", 96, 72, "gathered")]
+
+
+@pytest.mark.parametrize("variant", VARIANTS, ids=["-".join(map(str, v)) for v in VARIANTS])
 @pytest.mark.parametrize("shuffle", ["random", "interleaved_sequences", "identity"])
-def test_indexed_layer_matches_oracle(dtype, shuffle):
+@pytest.mark.parametrize("reuse_S", [True, False])
+def test_indexed_layer_matches_oracle(variant, shuffle, reuse_S):
+    from paper_2602_07263_amd import tlora
+    dtype, d_in, d_out, path = variant
+    tlora.tlora_set_option("indexed_direct", 1 if path == "direct" else 0)
+    try:
+        _run_indexed(dtype, d_in, d_out, shuffle, reuse_S)
+    finally:
+        tlora.tlora_set_option("indexed_direct", 1)
+
+
+def _run_indexed(dtype, d_in, d_out, shuffle, reuse_S):
     import torch
     from paper_2602_07263_amd import tlora
     ranks, tokens, scales = [8, 0, 24, 3, 64], [300, 40, 513, 70, 256], [2.0, 1.0, 0.5, 4.0, 2.0]
-    d_in, d_out = (320, 264) if dtype == "bf16" else (96, 72)
+    print(f"indexed {dtype} {d_in}->{d_out} {shuffle} reuse_S={reuse_S}", flush=True)
     p = wk.generate(wk.custom("idx", dtype, d_in, d_out, ranks, tokens, scales), seed=13)
     T = int(p.offsets[-1])
     rng = np.random.default_rng(2)
@@ -51,7 +69,7 @@ def test_indexed_layer_matches_oracle(dtype, shuffle):
     tlora.tlora_fwd_indexed(lp.prob, it.data_ptr(), Y.data_ptr(), ws.data_ptr(), ws_bytes, st)
     tlora.tlora_bwd_indexed(lp.prob, it.data_ptr(), dYt.data_ptr(), dX.data_ptr(),
                             [a.data_ptr() if a.numel() else 0 for a in dA], [b.data_ptr() if b.numel() else 0 for b in dB],
-                            tlora.TLORA_BWD_REUSE_S, ws.data_ptr(), ws_bytes, st)
+                            tlora.TLORA_BWD_REUSE_S if reuse_S else 0, ws.data_ptr(), ws_bytes, st)
     torch.cuda.synchronize()
     Yr, dXr, dAr, dBr = io.forward_backward(X, p.W, p.A, p.B, scales, p.offsets, idx, dY)
     tol = pu.BF16_TOL if dtype == "bf16" else pu.F32_TOL
