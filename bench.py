@@ -28,30 +28,35 @@ HBM_PEAK_GBPS = 8000.0              # MI355X published HBM3E peak
 MFMA_FLOP_PER_CLK_PER_CU = 4096     # dense bf16: 4 SIMDs x one 16x16x32 MFMA (16384 flop) per 16 cycles
 
 
+ENGINE_CLOCK_MHZ = None     # maximum engine clock of the GPU agent as the runtime's device listing states it
+
+
+def read_engine_clock():
+    """Parse `rocminfo` (run as a child process before this process touches the GPU) for the gfx950 agent's maximum
+    engine clock in MHz; None if that fails."""
+    import re
+    import subprocess
+    try:
+        txt = subprocess.run(["/opt/rocm/bin/rocminfo"], capture_output=True, text=True, timeout=60).stdout
+        gpu = txt[txt.index("gfx950"):]
+        m = re.search(r"Max Clock Freq\. \(MHz\):\s*(\d+)", gpu)
+        return int(m.group(1)) if m else None
+    except Exception:
+        return None
+
+
 def device_peak():
     """The bf16 MFMA peak as the device itself describes it: compute units x clock x 4096 flop / clock / CU.  Printed
     beside the published 2.5 PFLOP/s that the fractions use."""
     import torch
     pr = torch.cuda.get_device_properties(0)
     cus = int(pr.multi_processor_count)
-    khz = getattr(pr, "clock_rate", None)
-    if not khz:
-        # the runtime's device listing states the maximum engine clock of every agent; take the GPU agent's
-        try:
-            import re
-            import subprocess
-            txt = subprocess.run(["/opt/rocm/bin/rocminfo"], capture_output=True, text=True, timeout=30).stdout
-            gpu = txt[txt.index("gfx950"):] if "gfx950" in txt else ""
-            m = re.search(r"Max Clock Freq\. \(MHz\):\s*(\d+)", gpu)
-            if m:
-                khz = int(m.group(1)) * 1000
-        except Exception:
-            khz = None
     out = {"published_tflops": BF16_MFMA_PEAK_TFLOPS, "compute_units": cus, "flop_per_clk_per_cu": MFMA_FLOP_PER_CLK_PER_CU,
            "formula": "compute_units x clock_ghz x 4096 flop/clk/CU"}
-    if khz:
-        ghz = float(khz) / 1e6
+    if ENGINE_CLOCK_MHZ:
+        ghz = ENGINE_CLOCK_MHZ / 1e3
         out["clock_ghz"] = round(ghz, 3)
+        out["clock_source"] = "rocminfo, Max Clock Freq. of the gfx950 agent"
         out["derived_tflops"] = round(cus * ghz * MFMA_FLOP_PER_CLK_PER_CU / 1e3, 1)
     return out
 
@@ -80,6 +85,8 @@ def parse_args():
     ap.add_argument("--oracle-full", action="store_true",
                     help="time the CPU oracle on every projection and every token of the workload (minutes to tens of minutes)")
     ap.add_argument("--no-extra-configs", action="store_true", help="skip the cfg1 / cfg3 / cfg4 measurements")
+    ap.add_argument("--no-rocminfo", action="store_true",
+                    help="do not start `rocminfo` as a child process to read the engine clock (use under profilers)")
     ap.add_argument("--leg", choices=["mlp_block", "indexed", "decoder_layer", "scheduler", "attention", "nano"], default=None,
                     help="run only this additional measurement and print its JSON (for profiling one leg)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -658,6 +665,11 @@ def main():
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
+    global ENGINE_CLOCK_MHZ
+    # a child process, started before anything here initialises the GPU; never under a profiler, whose preloaded
+    # library has initialised the GPU before this program starts
+    profiled = any(k.startswith(("ROCPROF", "ROCP_")) for k in os.environ) or "rocprof" in os.environ.get("LD_PRELOAD", "")
+    ENGINE_CLOCK_MHZ = None if (args.no_rocminfo or profiled) else read_engine_clock()
     import torch
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
