@@ -213,3 +213,31 @@ def test_block_and_layer_structs_are_checked_on_the_host():
     mlp3 = tlora.tlora_mlp_t(tlora.TLORA_BF16, J, 128, 512, keep[0], keep[1], keep[2], None, 0x2000, 1e-5, 0x5000, 0x6000, 0x7000,
                              *([keep[4]] * 6))                                       # d_model differs
     assert L.tlora_layer_workspace_bytes(ctypes.byref(tlora.tlora_layer_t(p, mlp3))) == 0
+
+
+def test_plan_cache_returns_the_same_plan_as_a_fresh_build():
+    """Plans are cached by the contents of (dtype, sizes, ranks, offsets) and the tiling options: the cached plan, the
+    plan after 200 other problems have pushed it out, and the plan with the cache switched off must be identical, and
+    a tiling option that changes the plan must not be answered from an entry built under another value."""
+    rng = np.random.default_rng(5)
+    ref_prob, _k = _problem([8, 40, 3, 130], [300, 129, 260, 513], d_in=256, d_out=384)
+    first = tlora.tlora_plan_dump(ref_prob)
+    ws_first = tlora.tlora_workspace_bytes(ref_prob)
+    assert tlora.tlora_plan_dump(ref_prob) == first                      # served from the cache
+    for _ in range(200):                                                  # more distinct problems than the cache holds
+        J = int(rng.integers(1, 6))
+        q, _kq = _problem([int(r) for r in rng.integers(0, 70, J)], [int(t) for t in rng.integers(0, 600, J)])
+        tlora.tlora_plan_dump(q)
+    assert tlora.tlora_plan_dump(ref_prob) == first and tlora.tlora_workspace_bytes(ref_prob) == ws_first
+    try:
+        tlora.tlora_set_option("plan_cache", 0)
+        assert tlora.tlora_plan_dump(ref_prob) == first and tlora.tlora_workspace_bytes(ref_prob) == ws_first
+        tlora.tlora_set_option("plan_cache", 1)
+        tlora.tlora_set_option("grad_tokens", 64)                         # shorter dA / dB chunks: more partial tiles
+        ws_small_chunks = tlora.tlora_workspace_bytes(ref_prob)
+        tlora.tlora_set_option("grad_tokens", 256)
+        assert tlora.tlora_workspace_bytes(ref_prob) == ws_first
+        assert ws_small_chunks >= ws_first
+    finally:
+        tlora.tlora_set_option("plan_cache", 1)
+        tlora.tlora_set_option("grad_tokens", 256)

@@ -133,6 +133,7 @@ TILINGS = [
     {"grad_tokens": 2048, "shrink_rows": 64},
     {"shrink_rows": 32},
     {"shrink_rows": 128},
+    {"shrink_rows": 128, "shrink_stages": 8},
 ]
 
 
@@ -149,6 +150,23 @@ def test_results_do_not_depend_on_the_tiling(opts):
             tlora.tlora_set_option(k, v)
         Y, dX, dA, dB, _ = pu.run_gpu(p, reuse_S=False)
         _assert_ok(pu.compare(p, Y, dX, dA, dB), f"tiling {opts}")
+    finally:
+        for k, v in DEFAULT_OPTIONS.items():
+            tlora.tlora_set_option(k, v)
+
+
+@pytest.mark.parametrize("opts", [{"shrink_rows": 128}, {"shrink_rows": 128, "shrink_stages": 8}, {"shrink_rows": 64}],
+                         ids=["rows128", "rows128-stages8", "rows64"])
+def test_streaming_shrink_with_k_steps_of_32(opts):
+    """Contraction lengths that are multiples of 32 but not of 64 (96 forward, 160 backward) take the streaming
+    shrink's 32-wide K-steps, also in its 128-row, eight-wave form."""
+    from paper_2602_07263_amd import tlora
+    p = wk.generate(wk.custom("k32", "bf16", 96, 160, [3, 40, 130, 8], [300, 129, 260, 513], [2.0, 0.5, 1.0, 3.0]), seed=41)
+    try:
+        for k, v in opts.items():
+            tlora.tlora_set_option(k, v)
+        Y, dX, dA, dB, _ = pu.run_gpu(p, reuse_S=False)
+        _assert_ok(pu.compare(p, Y, dX, dA, dB), f"K-steps of 32, {opts}")
     finally:
         for k, v in DEFAULT_OPTIONS.items():
             tlora.tlora_set_option(k, v)
