@@ -385,6 +385,16 @@ int tlora_plan_dump(const tlora_problem_t* p, int32_t* rpad, int64_t* soff, int3
                     int64_t* tile_row0, int32_t* tile_nrows, int32_t* tile_job_first,
                     int32_t* tile_job_last, int64_t* n_tiles);
 
+/* Host-only self-check of the planner (no GPU work, no cache): builds the plan of `p` afresh -- of the forward alone if
+ * fwd_only != 0 -- and verifies what the kernels rely on: job segments, padded ranks and packed offsets add up; every
+ * row tile's adapter range holds all jobs with a row inside it and fits the packed operands; the shrink work units tile
+ * each job's [tokens x padded ranks] exactly once; every dA / dB work unit lies inside its job, starts on the token
+ * step, owns a partial tile that overlaps no other, and each output tile's partial tiles are consecutive and cover the
+ * job's tokens; all tables fit the table block and all workspace regions are disjoint and inside
+ * tlora_workspace_bytes().  Returns TLORA_OK, the validation error of `p`, or TLORA_EINVAL with the number of the
+ * first failed check in *failed_check (may be NULL; 0 when nothing failed).  Used by the CPU tests on random problems. */
+int tlora_plan_check(const tlora_problem_t* p, int32_t fwd_only, int32_t* failed_check);
+
 /* Tuning knobs (process-wide, for experiments and for the tiling-independence tests).
  *   "shrink_rows"  : token rows per work unit of the shrink kernels        (0 = chosen per problem (default) | 32 | 64 | 128)
  *   "shrink_stages": LDS stages of the streaming shrink kernel             (4 | 8)

@@ -6,8 +6,11 @@
 #include <algorithm>
 #include <cmath>
 #include <list>
+#include <map>
 #include <mutex>
 #include <string>
+#include <tuple>
+#include <utility>
 #include <vector>
 
 #include "../../include/tlora.h"
@@ -1688,6 +1691,171 @@ int tlora_plan_dump(const tlora_problem_t* p, int32_t* rpad, int64_t* soff, int3
     if (tile_job_last) tile_job_last[t] = pl.tile_jobs[t].last;
   }
   return TLORA_OK;
+}
+
+// Host-side consistency check of a freshly built plan: every table entry and every workspace region that a kernel
+// will index lies where the kernels assume.  Numbered checks; returns the number of the first one that fails.
+static int check_plan(const Plan& pl, bool fwd_only) {
+  const bool bf16 = pl.dtype == TLORA_BF16;
+  // 1x: jobs
+  int64_t soff = 0, atp = 0, roff = 0;
+  int row = 0;
+  for (int j = 0; j < pl.J; ++j) {
+    const JobDev& jb = pl.jobs[j];
+    if (jb.row0 != row || jb.row1 < jb.row0) return 10;
+    row = jb.row1;
+    if (jb.rpad < jb.rank || jb.rpad % kRankGranule || jb.rpad - jb.rank >= kRankGranule) return 11;
+    if (jb.soff != soff || jb.atp_off != atp || jb.roff != roff) return 12;
+    soff += (int64_t)((jb.row1 - jb.row0 + kGradStep - 1) / kGradStep * kGradStep) * jb.rpad;
+    atp += (int64_t)jb.rpad * pl.d_in;
+    roff += jb.rpad;
+  }
+  if (row != pl.T || soff != pl.s_elems || atp != pl.atp_elems || roff != pl.r_total) return 13;
+  // 2x: row tiles of the GEMM
+  if ((int64_t)pl.tile_jobs.size() != ((int64_t)pl.T + kGemmBM - 1) / kGemmBM) return 20;
+  int64_t aoff = 0;
+  for (size_t tm = 0; tm < pl.tile_jobs.size(); ++tm) {
+    const TileDev& td = pl.tile_jobs[tm];
+    const int r0 = (int)tm * kGemmBM, r1 = std::min(pl.T, r0 + kGemmBM);
+    if (td.first < 0 || td.last < td.first || td.last >= pl.J) return 21;
+    for (int j = 0; j < pl.J; ++j) {          // every job with a row inside the tile lies in first..last
+      const JobDev& jb = pl.jobs[j];
+      const bool inside = std::max(jb.row0, r0) < std::min(jb.row1, r1);
+      if (inside && (j < td.first || j > td.last)) return 22;
+    }
+    if (td.kext < 0 || td.kext % kGemmBK || td.roff_first != pl.jobs[td.first].roff) return 23;
+    if (pl.jobs[td.last].roff + pl.jobs[td.last].rpad > td.roff_first + td.kext) return 24;
+    if (td.roff_first + td.kext > pl.r_total + 32) return 25;       // the packed adapters carry 32 spare rank rows
+    if (td.aoff != aoff) return 26;
+    aoff += (int64_t)kGemmBM * td.kext;
+  }
+  if (aoff != pl.sx_elems) return 27;
+  if (bf16) {
+    // 3x: shrink work units tile [row0, row1) x [0, rpad) of every job exactly once
+    auto check_shrink = [&](const std::vector<ShrinkUnit>& units, int rows, int cols) -> int {
+      std::vector<int64_t> covered(pl.J, 0);
+      for (const ShrinkUnit& u : units) {
+        if (u.job < 0 || u.job >= pl.J) return 30;
+        const JobDev& jb = pl.jobs[u.job];
+        if (u.nrows < 1 || u.nrows > rows || u.t0 < jb.row0 || u.t0 + u.nrows > jb.row1) return 31;
+        if ((u.t0 - jb.row0) % rows) return 32;
+        if (u.pb < 0 || u.pb * cols >= jb.rpad) return 33;
+        covered[u.job] += (int64_t)u.nrows * std::min(cols, jb.rpad - u.pb * cols);
+      }
+      for (int j = 0; j < pl.J; ++j)
+        if (covered[j] != (int64_t)(pl.jobs[j].row1 - pl.jobs[j].row0) * pl.jobs[j].rpad) return 34;
+      return 0;
+    };
+    if (pl.shrink_rows != 32 && pl.shrink_rows != 64 && pl.shrink_rows != 128) return 35;
+    if (pl.shrink_rows == 32 && (pl.d_in % 64 || pl.d_out % 64)) return 36;
+    if (int rc = check_shrink(pl.shrink_units, 64, kShrinkCols)) return rc;
+    if (int rc = check_shrink(pl.stream_units, pl.shrink_rows, 128)) return rc + 100;
+    // 4x: dA / dB work units and their partial tiles
+    auto check_grad = [&](const std::vector<GradUnit>& units, const std::vector<GradGroup>& groups, int64_t partial,
+                          int D) -> int {
+      const int pb_rows = kGradMaxBlocks * kGradRanks;
+      std::vector<std::pair<int64_t, int64_t>> spans;
+      for (const GradUnit& u : units) {
+        if (u.job < 0 || u.job >= pl.J) return 40;
+        const JobDev& jb = pl.jobs[u.job];
+        if (u.t0 < jb.row0 || u.t1 <= u.t0 || u.t1 > jb.row1 || u.t1 - u.t0 > kGradMaxTokens) return 41;
+        if ((u.t0 - jb.row0) % kGradStep) return 42;                 // the packed S rows are padded to the token step
+        if (u.cb < 0 || u.cb * kGradCols >= D || u.pb < 0 || u.pb * pb_rows >= jb.rpad) return 43;
+        const int mb = std::min(kGradMaxBlocks, (jb.rpad - u.pb * pb_rows + kGradRanks - 1) / kGradRanks);
+        if (u.mb != mb || mb < 1) return 44;
+        const int64_t n = (int64_t)mb * kGradRanks * kGradCols;
+        if (u.part_off < 0 || u.part_off + n > partial) return 45;
+        spans.push_back({u.part_off, n});
+      }
+      std::sort(spans.begin(), spans.end());
+      for (size_t i = 1; i < spans.size(); ++i)
+        if (spans[i - 1].first + spans[i - 1].second > spans[i].first) return 46;
+      // every output tile (job with a rank, column block, rank block) has one group; its partial tiles are the
+      // units of the same (job, cb, pb), consecutive in memory and covering the job's tokens
+      int64_t want_groups = 0;
+      for (const JobDev& jb : pl.jobs)
+        if (jb.rank > 0) want_groups += (int64_t)((jb.rpad + pb_rows - 1) / pb_rows) * ((D + kGradCols - 1) / kGradCols);
+      if ((int64_t)groups.size() != want_groups) return 47;
+      std::map<std::tuple<int, int, int>, std::vector<const GradUnit*>> by_tile;
+      for (const GradUnit& u : units) by_tile[{u.job, u.cb, u.pb}].push_back(&u);
+      for (const GradGroup& g : groups) {
+        if (g.job < 0 || g.job >= pl.J) return 48;
+        const JobDev& jb = pl.jobs[g.job];
+        auto& us = by_tile[{g.job, g.cb, g.pb}];
+        if ((int)us.size() != g.nunits) return 49;
+        std::sort(us.begin(), us.end(), [](const GradUnit* a, const GradUnit* b) { return a->t0 < b->t0; });
+        int t = jb.row0;
+        for (int k = 0; k < g.nunits; ++k) {
+          if (us[k]->t0 != t || us[k]->mb != g.mb) return 50;
+          if (us[k]->part_off != g.part_off + (int64_t)k * g.mb * kGradRanks * kGradCols) return 51;
+          t = us[k]->t1;
+        }
+        if (t != jb.row1) return 52;
+        if (g.nunits == 0 && jb.row1 != jb.row0) return 53;
+      }
+      return 0;
+    };
+    if (!fwd_only) {
+      if (int rc = check_grad(pl.gradB_units, pl.gradB_groups, pl.gradB_partial, pl.d_out)) return rc;
+      if (int rc = check_grad(pl.gradA_units, pl.gradA_groups, pl.gradA_partial, pl.d_in)) return rc + 100;
+    } else if (!pl.gradA_units.empty() || !pl.gradB_units.empty()) {
+      return 54;
+    }
+  }
+  // 6x: tables inside the blob, regions inside the workspace, nothing overlapping
+  {
+    std::vector<std::pair<size_t, size_t>> t = {
+        {pl.tb_jobs, sizeof(JobDev) * pl.jobs.size()},          {pl.tb_tiles, sizeof(TileDev) * pl.tile_jobs.size()},
+        {pl.tb_shrink, sizeof(ShrinkUnit) * pl.shrink_units.size()}, {pl.tb_stream, sizeof(ShrinkUnit) * pl.stream_units.size()},
+        {pl.tb_gBu, sizeof(GradUnit) * pl.gradB_units.size()},  {pl.tb_gBg, sizeof(GradGroup) * pl.gradB_groups.size()},
+        {pl.tb_gAu, sizeof(GradUnit) * pl.gradA_units.size()},  {pl.tb_gAg, sizeof(GradGroup) * pl.gradA_groups.size()}};
+    if (pl.dtype == TLORA_F32) t.push_back({pl.tb_f32, pl.f32_reserved});
+    size_t end = 0;
+    for (auto& r : t) {
+      if (r.first % 256 || r.first < end) return 60;
+      end = r.first + r.second;
+    }
+    if (end > pl.tables_bytes) return 61;
+  }
+  {
+    std::vector<std::pair<size_t, size_t>> w;
+    const size_t se = (size_t)pl.s_elems, sx = 2 * (size_t)pl.sx_elems + 256;
+    if (bf16 && !fwd_only) w.push_back({pl.off_wt, 2 * (size_t)pl.d_in * (size_t)pl.d_out});
+    w.push_back({pl.off_tables, pl.tables_bytes});
+    w.push_back({pl.off_clock, 64});
+    if (!bf16) {
+      w.push_back({pl.off_S, 4 * se});
+      if (!fwd_only) w.push_back({pl.off_dS, 4 * se});
+    } else {
+      w.push_back({pl.off_Shi, 2 * se});
+      w.push_back({pl.off_Slo, 2 * se});
+      if (!fwd_only) { w.push_back({pl.off_dShi, 2 * se});  w.push_back({pl.off_dSlo, 2 * se}); }
+      w.push_back({pl.off_Sx, sx});
+      if (!fwd_only) w.push_back({pl.off_dSx, sx});
+      w.push_back({pl.off_atp, 2 * ((size_t)pl.atp_elems + 32 * (size_t)pl.d_in)});
+      w.push_back({pl.off_ap, 2 * (size_t)pl.d_in * (size_t)(pl.r_total + 32)});
+      w.push_back({pl.off_bp, 2 * (size_t)pl.d_out * (size_t)(pl.r_total + 32)});
+      if (!fwd_only) w.push_back({pl.off_partial, 4 * (size_t)std::max(pl.gradB_partial, pl.gradA_partial)});
+    }
+    size_t end = 0;
+    for (auto& r : w) {
+      if (r.first % 256 || r.first < end) return 62;
+      end = r.first + r.second;
+    }
+    if (end > pl.total) return 63;
+  }
+  return 0;
+}
+
+int tlora_plan_check(const tlora_problem_t* p, int32_t fwd_only, int32_t* failed_check) {
+  std::lock_guard<std::recursive_mutex> lk(g_mu);
+  if (failed_check) *failed_check = 0;
+  Plan pl;
+  const int rc = build_plan(p, pl, fwd_only != 0);
+  if (rc != TLORA_OK) return rc;
+  const int bad = check_plan(pl, fwd_only != 0);
+  if (failed_check) *failed_check = bad;
+  return bad ? TLORA_EINVAL : TLORA_OK;
 }
 
 int tlora_profile(int enable) {

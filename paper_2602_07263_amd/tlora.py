@@ -99,7 +99,7 @@ EXPORTS = ["tlora_workspace_bytes", "tlora_fwd", "tlora_fwd_noalloc", "tlora_bwd
            "tlora_indexed_workspace_bytes", "tlora_fwd_indexed", "tlora_bwd_indexed",
            "tlora_aimd_init", "tlora_aimd_update",
            "tlora_nano_split", "tlora_nano_workspace_bytes", "tlora_fwd_nano", "tlora_bwd_nano",
-           "tlora_plan_dump", "tlora_set_option",
+           "tlora_plan_dump", "tlora_plan_check", "tlora_set_option",
            "tlora_profile", "tlora_profile_read", "tlora_profile_clock", "tlora_strerror", "tlora_version"]
 KERNEL_CLASSES = ["pack", "shrink", "gemm_fwd", "gemm_bwd", "rank_grad", "grad_reduce", "f32", "w_transpose", "optimizer", "glue", "permute",
                   "attn_fwd", "attn_bwd", "rope"]
@@ -201,6 +201,8 @@ def lib() -> ctypes.CDLL:
                                   ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64),
                                   ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32),
                                   ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64)]
+    L.tlora_plan_check.restype = ctypes.c_int
+    L.tlora_plan_check.argtypes = [P, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]
     L.tlora_set_option.restype = ctypes.c_int
     L.tlora_set_option.argtypes = [ctypes.c_char_p, ctypes.c_int64]
     L.tlora_profile.restype = ctypes.c_int
@@ -407,6 +409,13 @@ def tlora_plan_dump(prob: tlora_problem_t) -> dict:
     k = int(n.value)
     return {"rpad": list(rpad), "soff": list(soff), "tile_rows": int(tile_rows.value),
             "tiles": [(int(row0[i]), int(nrows[i]), int(jf[i]), int(jl[i])) for i in range(k)]}
+
+
+def tlora_plan_check(prob: tlora_problem_t, fwd_only: bool = False):
+    """(status, number of the first failed consistency check or 0) for a freshly built plan of `prob`."""
+    bad = ctypes.c_int32(0)
+    rc = lib().tlora_plan_check(ctypes.byref(prob), 1 if fwd_only else 0, ctypes.byref(bad))
+    return int(rc), int(bad.value)
 
 
 # ---- torch-backed convenience holder ---------------------------------------------------------------------

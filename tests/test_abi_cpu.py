@@ -241,3 +241,61 @@ def test_plan_cache_returns_the_same_plan_as_a_fresh_build():
     finally:
         tlora.tlora_set_option("plan_cache", 1)
         tlora.tlora_set_option("grad_tokens", 256)
+
+
+def _random_plan_problem(rng):
+    """Problem shapes of the kinds the workloads have: even and skewed token counts, empty segments, rank 0, ranks up
+    to the maximum, feature sizes that are and are not multiples of 64."""
+    J = int(rng.integers(1, 41))
+    kind = int(rng.integers(0, 4))
+    if kind == 0:
+        tokens = rng.integers(0, 700, J)
+    elif kind == 1:                                                   # heavy tail, many tiny or empty jobs
+        tokens = (rng.pareto(0.8, J) * 20).astype(np.int64) % 20000
+    elif kind == 2:
+        tokens = rng.choice([0, 1, 31, 32, 33, 255, 256, 257, 4095, 4096, 4097], J)
+    else:
+        tokens = rng.integers(0, 3, J)                                # nearly empty batch (sometimes T = 0)
+    rank_set = [0, 1, 3, 8, 16, 33, 64, 96, 127, 128, 129, 256, 384, 513, 1024]
+    ranks = [int(rng.choice(rank_set)) if rng.random() < 0.8 else int(rng.integers(0, 1025)) for _ in range(J)]
+    d_in = int(rng.choice([8, 64, 72, 256, 1000, 4096]))
+    d_out = int(rng.choice([8, 64, 136, 512, 1024, 12288]))
+    dtype = tlora.TLORA_BF16 if rng.random() < 0.85 else tlora.TLORA_F32
+    return _problem(ranks, [int(t) for t in tokens], d_in=d_in, d_out=d_out, dtype=dtype)
+
+
+def test_planner_self_check_on_random_problems():
+    """Every table entry and workspace region the kernels index is verified on the host, for 1500 random problems under
+    every tiling option (unit heights of the shrink, token chunks of the dA / dB reduction), forward-only and full."""
+    rng = np.random.default_rng(20240607)
+    settings = [(0, 256), (32, 64), (64, 1024), (128, 4096), (0, 64)]
+    try:
+        for i in range(1500):
+            rows, chunk = settings[i % len(settings)]
+            tlora.tlora_set_option("shrink_rows", rows)
+            tlora.tlora_set_option("grad_tokens", chunk)
+            prob, _keep = _random_plan_problem(rng)
+            for fwd_only in (False, True):
+                rc, bad = tlora.tlora_plan_check(prob, fwd_only)
+                assert (rc, bad) == (0, 0), (i, fwd_only, rows, chunk, bad, list(prob.ranks[:prob.num_jobs]),
+                                             list(prob.offsets[:prob.num_jobs + 1]), prob.d_in, prob.d_out, prob.dtype)
+    finally:
+        tlora.tlora_set_option("shrink_rows", 0)
+        tlora.tlora_set_option("grad_tokens", 256)
+
+
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4])
+def test_planner_self_check_on_the_five_configurations(cfg):
+    wl = wk.config(cfg)
+    for proj in wl.projections:
+        prob, _keep = tlora.make_problem(tlora.TLORA_F32 if wl.dtype == "f32" else tlora.TLORA_BF16, proj.d_in, proj.d_out,
+                                         wl.ranks, wl.offsets, wl.scales, 0x1000, 0x2000, [0x3000] * wl.num_jobs,
+                                         [0x4000] * wl.num_jobs)
+        for fwd_only in (False, True):
+            assert tlora.tlora_plan_check(prob, fwd_only) == (0, 0)
+
+
+def test_planner_self_check_reports_the_problem_s_own_errors():
+    prob, _keep = _problem([8, 8], [10, 10], d_in=60)                  # d_in not a multiple of 8
+    rc, bad = tlora.tlora_plan_check(prob)
+    assert rc == tlora.TLORA_EINVAL and bad == 0
