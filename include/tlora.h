@@ -318,10 +318,14 @@ int tlora_layer_bwd(const tlora_layer_t* p, const void* dOut, void* dX, void* co
  * output tensor.  Here X, Y, dY, dX are in the batch's own (arbitrary) token order, and row_index (DEVICE int32 [T],
  * a permutation of 0 .. T-1) lists the rows job by job: row_index[offsets[j] .. offsets[j+1]-1] are the rows of job
  * j, in the order in which they enter that job's gradient sums.  Row t of Y / dX belongs to row t of X / dY.
- * The activations are gathered into the workspace by a copy pass (X for the forward; X and dY for the backward)
- * and the bf16 GEMMs scatter their output rows while storing them; the fp32 configuration scatters with a second
- * copy pass.  Same arguments, flags and results as tlora_fwd / tlora_bwd otherwise (TLORA_BWD_REUSE_S included,
- * under the same condition).  The permutation is not checked. */
+ * bf16: the kernels fetch the activation rows through the list inside their loads and the GEMMs scatter their output
+ * rows while storing them, so the batch is read and written as often as in a contiguous call (option
+ * "indexed_direct"; activations of 4 GiB or more are first gathered into the workspace by a copy pass, and so is the
+ * fp32 configuration, which also scatters with a second copy pass).  Same arguments, flags and results as tlora_fwd /
+ * tlora_bwd otherwise (TLORA_BWD_REUSE_S included, under the same condition).
+ * The list is device data and is not checked to be a permutation; the kernels work on a copy of it (in the workspace)
+ * with every entry forced into [0, T-1], so a bad list yields wrong rows -- a row named twice is written by either
+ * of its tokens, a row never named is not written -- but no access outside the tensors. */
 size_t tlora_indexed_workspace_bytes(const tlora_problem_t* p);
 int tlora_fwd_indexed(const tlora_problem_t* p, const int32_t* row_index, void* Y, void* workspace, size_t ws_bytes,
                       void* hip_stream);

@@ -1553,7 +1553,7 @@ int tlora_layer_bwd(const tlora_layer_t* p, const void* dOut, void* dX, void* co
 // ---- general token -> adapter assignment (Sec. 3.3: tokens of an adapter are gathered, results scattered back) ----
 namespace {
 struct IndexedLayout {
-  size_t inner = 0, off_x = 0, off_y = 0, off_dx = 0, total = 0, elt = 2;
+  size_t inner = 0, off_x = 0, off_y = 0, off_dx = 0, off_idx = 0, total = 0, elt = 2;
   int64_t T = 0;
 };
 // The kernels that fetch rows through the index list keep 32-bit byte offsets from the tensor's base.
@@ -1571,7 +1571,23 @@ int indexed_layout(const tlora_problem_t* p, IndexedLayout& L) {
   L.off_y = align_up(L.off_x + (size_t)L.T * p->d_in * L.elt, 256);
   L.off_dx = align_up(L.off_y + (size_t)L.T * p->d_out * L.elt, 256);
   // the fp32 configuration has no scattering epilogue: its sorted dX is staged and scattered by a copy pass
-  L.total = align_up(L.off_dx + (p->dtype == TLORA_F32 ? (size_t)L.T * p->d_in * L.elt : 0), 256);
+  L.off_idx = align_up(L.off_dx + (p->dtype == TLORA_F32 ? (size_t)L.T * p->d_in * L.elt : 0), 256);
+  // the row list as the kernels use it: the caller's, with every entry forced into [0, T)
+  L.total = align_up(L.off_idx + (size_t)L.T * sizeof(int32_t), 256);
+  return TLORA_OK;
+}
+// Everything tlora_fwd / tlora_bwd would reject, checked before the first launch of an indexed call.
+int indexed_checks(const tlora_problem_t* q, void* workspace, size_t inner, bool backward, void* const* dA,
+                   void* const* dB, int flags) {
+  const PlanEntry* e = nullptr;
+  std::vector<JobDev> hj;
+  const int rc = common_checks(q, &e, hj, workspace, inner);
+  if (rc != TLORA_OK || !backward) return rc;
+  if ((dA == nullptr) != (dB == nullptr)) return TLORA_ENULL;
+  if (dA)
+    for (int j = 0; j < q->num_jobs; ++j)
+      if (q->ranks[j] > 0 && (!dA[j] || !dB[j])) return TLORA_ENULL;
+  if (flags & ~(TLORA_BWD_REUSE_S | TLORA_BWD_REUSE_WT | TLORA_BWD_ACCUMULATE)) return TLORA_EINVAL;
   return TLORA_OK;
 }
 }  // namespace
@@ -1595,28 +1611,29 @@ int tlora_fwd_indexed(const tlora_problem_t* p, const int32_t* row_index, void* 
   if (L.T == 0) return TLORA_OK;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   uint8_t* ws = static_cast<uint8_t*>(workspace);
+  int32_t* const index = reinterpret_cast<int32_t*>(ws + L.off_idx);
   // bf16: the kernels fetch the activation rows through the list inside their loads and the GEMM scatters its output
   // rows, so the batch is read and written exactly as often as in a contiguous call (the in-kernel row offsets are 32
   // bits: larger activations take the gathered copy below)
-  if (p->dtype == TLORA_BF16 && direct_index_ok(L.T, p->d_in))
-    return fwd_impl(p, Y, workspace, L.inner, hip_stream, false, row_index, row_index);
+  const bool direct = p->dtype == TLORA_BF16 && direct_index_ok(L.T, p->d_in);
   tlora_problem_t q = *p;
-  q.X = ws + L.off_x;
-  {   // validate everything the inner call will check before the gather is queued
-    const PlanEntry* e = nullptr;
-    std::vector<JobDev> hj;
-    rc = common_checks(&q, &e, hj, workspace, L.inner);
-    if (rc != TLORA_OK) return rc;
-  }
+  if (!direct) q.X = ws + L.off_x;
+  rc = indexed_checks(&q, workspace, L.inner, false, nullptr, nullptr, 0);
+  if (rc != TLORA_OK) return rc;
   {
     Timed t(TLORA_K_PERMUTE, st);
-    launch_permute_rows(p->X, ws + L.off_x, row_index, L.T, (int64_t)p->d_in * L.elt, false, st);
+    launch_clamp_index(row_index, index, L.T, st);
   }
-  if (p->dtype == TLORA_BF16) return fwd_impl(&q, Y, workspace, L.inner, hip_stream, false, row_index);
+  if (direct) return fwd_impl(p, Y, workspace, L.inner, hip_stream, false, index, index);
+  {
+    Timed t(TLORA_K_PERMUTE, st);
+    launch_permute_rows(p->X, ws + L.off_x, index, L.T, (int64_t)p->d_in * L.elt, false, st);
+  }
+  if (p->dtype == TLORA_BF16) return fwd_impl(&q, Y, workspace, L.inner, hip_stream, false, index);
   rc = tlora_fwd(&q, ws + L.off_y, workspace, L.inner, hip_stream);
   if (rc != TLORA_OK) return rc;
   Timed t(TLORA_K_PERMUTE, st);
-  launch_permute_rows(ws + L.off_y, Y, row_index, L.T, (int64_t)p->d_out * L.elt, true, st);
+  launch_permute_rows(ws + L.off_y, Y, index, L.T, (int64_t)p->d_out * L.elt, true, st);
   return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
 }
 
@@ -1633,33 +1650,29 @@ int tlora_bwd_indexed(const tlora_problem_t* p, const int32_t* row_index, const 
   if (rc != TLORA_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   uint8_t* ws = static_cast<uint8_t*>(workspace);
-  if (p->dtype == TLORA_BF16 && direct_index_ok(L.T, std::max(p->d_in, p->d_out)))
-    return bwd_impl(p, dY, dX, dA, dB, flags, workspace, L.inner, hip_stream, row_index, row_index);
+  int32_t* const index = reinterpret_cast<int32_t*>(ws + L.off_idx);
+  const bool direct = p->dtype == TLORA_BF16 && direct_index_ok(L.T, std::max(p->d_in, p->d_out));
   tlora_problem_t q = *p;
-  q.X = ws + L.off_x;
-  {   // validate what the inner call will check before the gathers are queued
-    const PlanEntry* e = nullptr;
-    std::vector<JobDev> hj;
-    rc = common_checks(&q, &e, hj, workspace, L.inner);
-    if (rc != TLORA_OK) return rc;
-    if ((dA == nullptr) != (dB == nullptr)) return TLORA_ENULL;
-    if (dA)
-      for (int j = 0; j < p->num_jobs; ++j)
-        if (p->ranks[j] > 0 && (!dA[j] || !dB[j])) return TLORA_ENULL;
-    if (flags & ~(TLORA_BWD_REUSE_S | TLORA_BWD_REUSE_WT | TLORA_BWD_ACCUMULATE)) return TLORA_EINVAL;
+  if (!direct) q.X = ws + L.off_x;
+  rc = indexed_checks(&q, workspace, L.inner, true, dA, dB, flags);
+  if (rc != TLORA_OK) return rc;
+  if (L.T > 0) {   // made again: the region may have been reused since the forward
+    Timed t(TLORA_K_PERMUTE, st);
+    launch_clamp_index(row_index, index, L.T, st);
   }
+  if (direct) return bwd_impl(p, dY, dX, dA, dB, flags, workspace, L.inner, hip_stream, index, index);
   if (L.T > 0) {
     Timed t(TLORA_K_PERMUTE, st);
     // the sorted activations are gathered again: the region may have been reused since the forward
-    launch_permute_rows(p->X, ws + L.off_x, row_index, L.T, (int64_t)p->d_in * L.elt, false, st);
-    launch_permute_rows(dY, ws + L.off_y, row_index, L.T, (int64_t)p->d_out * L.elt, false, st);
+    launch_permute_rows(p->X, ws + L.off_x, index, L.T, (int64_t)p->d_in * L.elt, false, st);
+    launch_permute_rows(dY, ws + L.off_y, index, L.T, (int64_t)p->d_out * L.elt, false, st);
   }
   if (p->dtype == TLORA_BF16 || !dX)
-    return bwd_impl(&q, ws + L.off_y, dX, dA, dB, flags, workspace, L.inner, hip_stream, row_index, nullptr);
+    return bwd_impl(&q, ws + L.off_y, dX, dA, dB, flags, workspace, L.inner, hip_stream, index, nullptr);
   rc = tlora_bwd(&q, ws + L.off_y, ws + L.off_dx, dA, dB, flags, workspace, L.inner, hip_stream);
   if (rc != TLORA_OK) return rc;
   Timed t(TLORA_K_PERMUTE, st);
-  launch_permute_rows(ws + L.off_dx, dX, row_index, L.T, (int64_t)p->d_in * L.elt, true, st);
+  launch_permute_rows(ws + L.off_dx, dX, index, L.T, (int64_t)p->d_in * L.elt, true, st);
   return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
 }
 

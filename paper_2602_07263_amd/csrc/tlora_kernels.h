@@ -78,6 +78,8 @@ void launch_residual_add(bool bf16, const void* X, const void* D, void* Out, int
 // Row gather (dst[i] = src[index[i]]) / scatter (dst[index[i]] = src[i]); row_bytes a multiple of 16.
 void launch_permute_rows(const void* src, void* dst, const int32_t* index, int64_t rows, int64_t row_bytes, bool scatter,
                          hipStream_t st);
+// Copy of a row list with every entry forced into [0, rows)  (rows < 2^31).
+void launch_clamp_index(const int32_t* src, int32_t* dst, int64_t rows, hipStream_t st);
 
 // ---- attention half (bf16, head size 128) -----------------------------------------------------------------
 constexpr int kAttnHeadDim = 128;

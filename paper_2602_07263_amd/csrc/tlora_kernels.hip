@@ -1616,4 +1616,16 @@ void launch_permute_rows(const void* src, void* dst, const int32_t* index, int64
                      static_cast<const uint8_t*>(src), static_cast<uint8_t*>(dst), index, rows, row_bytes, scatter ? 1 : 0);
 }
 
+// dst[i] = src[i] forced into [0, rows): whatever list the caller passed, the kernels that fetch and scatter rows through
+// the copy stay inside the tensors (a bad list then gives wrong rows, never an access outside them).
+__global__ void __launch_bounds__(256) clamp_index_kernel(const int32_t* __restrict__ src, int32_t* __restrict__ dst,
+                                                          int rows) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < rows) dst[i] = min(max(src[i], 0), rows - 1);
+}
+void launch_clamp_index(const int32_t* src, int32_t* dst, int64_t rows, hipStream_t st) {
+  if (rows <= 0) return;
+  hipLaunchKernelGGL(clamp_index_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st, src, dst, (int)rows);
+}
+
 }  // namespace tlora

@@ -78,3 +78,52 @@ def _run_indexed(dtype, d_in, d_out, shuffle, reuse_S):
            "dB": max([pu.worst_ratio(b.cpu().numpy(), r, tol) for b, r in zip(dB, dBr)] + [0.0])}
     bad = {k: v for k, v in res.items() if not v <= 1.0}
     assert not bad, f"{dtype}/{shuffle}: worst error / tolerance ratios {res}"
+
+
+@pytest.mark.parametrize("variant", [VARIANTS[0], VARIANTS[1], VARIANTS[3]], ids=["bf16-direct", "bf16-gathered", "f32"])
+def test_row_list_entries_out_of_range_are_forced_into_the_batch(variant):
+    """The list is the caller's device data and cannot be checked on the host; the library works on a copy with every
+    entry forced into [0, T), so a bad list gives wrong rows, never an access outside the tensors.  Checked here: a list
+    with entries below 0 and at or beyond T behaves exactly like the list with those entries replaced by 0 / T - 1 --
+    the gradient sums in full, Y and dX on every row that the forced list names once."""
+    import torch
+    from paper_2602_07263_amd import tlora
+    dtype, d_in, d_out, path = variant
+    ranks, tokens, scales = [8, 0, 24, 3, 64], [300, 40, 513, 70, 256], [2.0, 1.0, 0.5, 4.0, 2.0]
+    print(f"indexed, list out of range, {dtype} {d_in}->{d_out} {path}", flush=True)
+    p = wk.generate(wk.custom("idx_bad", dtype, d_in, d_out, ranks, tokens, scales), seed=14)
+    T = int(p.offsets[-1])
+    rng = np.random.default_rng(3)
+    idx = rng.permutation(T).astype(np.int64)
+    bad_at = rng.choice(T, size=9, replace=False)
+    idx[bad_at] = [-1, -7, -2**31, T, T + 1, T + 4096, 2**30, 2**31 - 1, -T]
+    forced = np.clip(idx, 0, T - 1)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    up = lambda a: torch.from_numpy(a).to(device="cuda", dtype=tdt).contiguous()
+    lp = tlora.LayerProblem(dtype, d_in, d_out, ranks, p.offsets, scales, up(p.X), up(p.W), [up(a) for a in p.A],
+                            [up(b) for b in p.B])
+    ws_bytes = tlora.tlora_indexed_workspace_bytes(lp.prob)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    Y, dX, dA, dB = lp.new_outputs()
+    it = torch.from_numpy(idx.astype(np.int32)).cuda()
+    dYt = up(p.dY)
+    st = int(torch.cuda.current_stream().cuda_stream)
+    tlora.tlora_set_option("indexed_direct", 1 if path == "direct" else 0)
+    try:
+        tlora.tlora_fwd_indexed(lp.prob, it.data_ptr(), Y.data_ptr(), ws.data_ptr(), ws_bytes, st)
+        tlora.tlora_bwd_indexed(lp.prob, it.data_ptr(), dYt.data_ptr(), dX.data_ptr(),
+                                [a.data_ptr() if a.numel() else 0 for a in dA],
+                                [b.data_ptr() if b.numel() else 0 for b in dB], 0, ws.data_ptr(), ws_bytes, st)
+        torch.cuda.synchronize()
+    finally:
+        tlora.tlora_set_option("indexed_direct", 1)
+    Yr, dXr, dAr, dBr = io.forward_backward(p.X, p.W, p.A, p.B, scales, p.offsets, forced, p.dY)
+    once = np.flatnonzero(np.bincount(forced, minlength=T) == 1)
+    assert once.size >= T - 20
+    tol = pu.BF16_TOL if dtype == "bf16" else pu.F32_TOL
+    res = {"Y": pu.worst_ratio(Y.float().cpu().numpy()[once], Yr[once], tol),
+           "dX": pu.worst_ratio(dX.float().cpu().numpy()[once], dXr[once], tol),
+           "dA": max([pu.worst_ratio(a.cpu().numpy(), r, tol) for a, r in zip(dA, dAr)] + [0.0]),
+           "dB": max([pu.worst_ratio(b.cpu().numpy(), r, tol) for b, r in zip(dB, dBr)] + [0.0])}
+    bad = {k: v for k, v in res.items() if not v <= 1.0}
+    assert not bad, f"{dtype}/{path}: worst error / tolerance ratios {res}"
