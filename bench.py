@@ -26,6 +26,10 @@ if ROOT not in sys.path:
 BF16_MFMA_PEAK_TFLOPS = 2500.0      # MI355X published dense bf16 MFMA peak (the figure every fraction divides by)
 HBM_PEAK_GBPS = 8000.0              # MI355X published HBM3E peak
 MFMA_FLOP_PER_CLK_PER_CU = 4096     # dense bf16: 4 SIMDs x one 16x16x32 MFMA (16384 flop) per 16 cycles
+# Sustained load before a workload's timed region: the socket reaches its power limit within the first second and the
+# power manager then takes ~2 s to settle the shader clock (1.8 GHz at first, 1.63 - 1.69 GHz settled); steps timed
+# before that run ~1.3 % faster than the steady state.
+WARMUP_SECONDS = 3.0
 
 
 ENGINE_CLOCK_MHZ = None     # maximum engine clock of the GPU agent as the runtime's device listing states it
@@ -77,8 +81,12 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=30,
-                    help="untimed steps before the timed region (default 30 = ~0.45 s of cfg2: about 0.3 s into a sustained "
-                         "load every box of this pool shows one step that takes 5-8 ms longer, once; the warm-up runs past it)")
+                    help="untimed steps before the timed region; the warm-up also lasts at least 3 s of sustained load, "
+                         "until the power manager has settled the shader clock (about 0.3 s into a load every box of "
+                         "this pool also shows one step that takes 5-8 ms longer, once)")
+    ap.add_argument("--warmup-seconds", type=float, default=WARMUP_SECONDS,
+                    help="least duration of each workload's warm-up (default 3 s: the settled clock; profiling runs that "
+                         "only want per-launch counters pass less)")
     ap.add_argument("--config", type=int, default=2, help="workload index (0-based); 2 = 8B-class MLP projections")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-loop-baseline", action="store_true")
@@ -219,9 +227,9 @@ def measure_workload(cfg_index: int, steps: int, warmup: int, profile: bool, loo
         for r in runs:
             r.step(i, reuse_wt=True)
 
-    # warm-up: the requested number of steps and at least half a second of sustained load
+    # warm-up: the requested number of steps and at least WARMUP_SECONDS of sustained load
     t_start, i = time.perf_counter(), 0
-    while i < warmup or time.perf_counter() - t_start < 0.5:
+    while i < warmup or time.perf_counter() - t_start < WARMUP_SECONDS:
         step(i)
         i += 1
         if i % 8 == 0:
@@ -675,7 +683,8 @@ def main():
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
-    global ENGINE_CLOCK_MHZ
+    global ENGINE_CLOCK_MHZ, WARMUP_SECONDS
+    WARMUP_SECONDS = max(0.0, args.warmup_seconds)
     # a child process, started before anything here initialises the GPU; never under a profiler, whose preloaded
     # library has initialised the GPU before this program starts
     profiled = any(k.startswith(("ROCPROF", "ROCP_")) for k in os.environ) or "rocprof" in os.environ.get("LD_PRELOAD", "")
@@ -704,7 +713,7 @@ def main():
     summ = summarize(main_res, args.steps, True)
     out = {
         "metric": "fused multi-LoRA fwd+bwd TFLOP/s (% bf16 MFMA peak); speedup vs per-job loop",
-        "value": summ["value"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": summ["value"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "warmup_seconds": WARMUP_SECONDS,
         "ms_per_step": summ["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name,
