@@ -106,7 +106,8 @@ int tlora_fwd(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_byte
  *   The scratch keeps the last call's contents and is shared by every call on that GPU: calls that overlap on one
  *   GPU (two streams, two host threads) race; order them on one stream.  There is no matching backward: S_j
  *   does not outlive the next call (tlora_bwd without TLORA_BWD_REUSE_S recomputes it in its own workspace).
- *   The address of the array on the current device is looked up on the first call on that device. */
+ *   The address of the array on the current device is looked up (and the device's architecture checked) on the first
+ *   call on that device: a caller that captures the stream makes one call before the capture begins. */
 #define TLORA_NOALLOC_SCRATCH_BYTES (16u << 20)
 int tlora_fwd_noalloc(const tlora_problem_t* p, void* Y, void* hip_stream);
 
