@@ -2,7 +2,8 @@
 is part of the library) against tlora_fwd on a caller-provided workspace: same kernels, so Y must agree bit for
 bit -- on two calls in a row, the second on a smaller problem (the array keeps the first call's contents), in
 both dtypes; the result is also held to the oracle's tolerance.  A problem beyond the array's size is refused
-before anything is launched."""
+before anything is launched.  Last: the call recorded into a captured stream (what the entry point exists for) and
+replayed three times, with eager calls on another problem through the same array in between."""
 import numpy as np
 import pytest
 
@@ -64,3 +65,33 @@ def test_problem_beyond_the_scratch_is_refused():
     assert "scratch" in tlora.tlora_strerror(rc)
     torch.cuda.synchronize()
     assert bool((Y == 7.0).all()), "a refused call must not launch anything"
+
+
+def test_noalloc_forward_replays_from_a_captured_stream():
+    import torch
+    from paper_2602_07263_amd import tlora
+    mk = lambda case, seed: tlora.LayerProblem.from_numpy(wk.generate(wk.custom(case[0], "bf16", *case[1:]), seed=seed))
+    lp, other = mk(FIRST, 31), mk(SECOND, 32)
+    Y_ref, _, _, _ = lp.new_outputs()
+    Y_other, _, _, _ = other.new_outputs()
+    lp.fwd(Y_ref)
+    Y = torch.empty_like(Y_ref)
+    st = lambda: int(torch.cuda.current_stream().cuda_stream)
+    print("noalloc: set-up call before the capture", flush=True)
+    tlora.tlora_fwd_noalloc(lp.prob, Y.data_ptr(), st())
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Y_ref)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    print("noalloc: capture", flush=True)
+    with torch.cuda.graph(graph, stream=side):
+        tlora.tlora_fwd_noalloc(lp.prob, Y.data_ptr(), st())
+    for rep in range(3):
+        Y.fill_(float("nan"))
+        # eager work between the replays: another problem through the same scratch array
+        tlora.tlora_fwd_noalloc(other.prob, Y_other.data_ptr(), st())
+        torch.cuda.synchronize()
+        print(f"noalloc: replay {rep}", flush=True)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Y, Y_ref), f"replay {rep}: {int((Y != Y_ref).sum())} elements differ from the eager call"
