@@ -28,7 +28,11 @@
  *     aligned.
  *   - Legal degenerate inputs: T_j = 0 (dA_j = dB_j = 0), r_j = 0 (rows of that job get the
  *     backbone product only; its A/B/dA/dB pointers are ignored and may be NULL), T = 0 (X, Y, dY, dX
- *     may be NULL; the forward launches nothing, the backward zero-fills dA_j / dB_j).  T must be below 2^31 and r_j at most TLORA_MAX_RANK.
+ *     may be NULL; the forward launches nothing, the backward zero-fills dA_j / dB_j).
+ *   - Limits (TLORA_EINVAL beyond them, before anything is launched): J <= TLORA_MAX_JOBS, T <= TLORA_MAX_TOKENS,
+ *     d_in, d_out <= TLORA_MAX_FEATURES, r_j <= TLORA_MAX_RANK, and a plan of at most 2^22 GEMM tiles
+ *     (ceil(T / 256) * ceil(max(d_in, d_out) / 256)) and 2^22 work units of each kind -- the kernels keep 32-bit
+ *     offsets inside a tile and one workgroup per tile / unit.
  *   - Calls are asynchronous on `hip_stream` (a hipStream_t; NULL = the default stream).  Host
  *     arrays may be reused as soon as the call returns.  Two calls that share a workspace must be
  *     ordered on one stream.
@@ -50,6 +54,9 @@ extern "C" {
 #endif
 
 #define TLORA_MAX_RANK 1024
+#define TLORA_MAX_JOBS 65536
+#define TLORA_MAX_TOKENS (1 << 24)
+#define TLORA_MAX_FEATURES (1 << 20)
 
 typedef enum { TLORA_F32 = 0, TLORA_BF16 = 1 } tlora_dtype_t;
 

@@ -84,17 +84,25 @@ struct Plan {
   size_t f32_reserved = 0;
 };
 
+constexpr int64_t kMaxUnits = (int64_t)1 << 22;   // most GEMM tiles / work units of one kind in a launch
+
 int validate(const tlora_problem_t* p) {
   if (!p) return TLORA_ENULL;
   if (p->dtype != TLORA_F32 && p->dtype != TLORA_BF16) return TLORA_EDTYPE;
   if (p->num_jobs < 1 || p->d_in < 8 || p->d_out < 8 || (p->d_in % 8) || (p->d_out % 8)) return TLORA_EINVAL;
+  if (p->num_jobs > TLORA_MAX_JOBS || p->d_in > TLORA_MAX_FEATURES || p->d_out > TLORA_MAX_FEATURES) return TLORA_EINVAL;
   if (!p->ranks || !p->offsets || !p->scales) return TLORA_ENULL;
   if (p->offsets[0] != 0) return TLORA_EINVAL;
   for (int j = 0; j < p->num_jobs; ++j) {
     if (p->offsets[j + 1] < p->offsets[j]) return TLORA_EINVAL;
     if (p->ranks[j] < 0 || p->ranks[j] > TLORA_MAX_RANK) return TLORA_EINVAL;
   }
-  if (p->offsets[p->num_jobs] >= (int64_t)1 << 31) return TLORA_EINVAL;
+  if (p->offsets[p->num_jobs] > TLORA_MAX_TOKENS) return TLORA_EINVAL;
+  {   // one workgroup per GEMM tile: the grid (and the 32-bit tile index arithmetic) must hold them all
+    const int64_t tiles_m = (p->offsets[p->num_jobs] + kGemmBM - 1) / kGemmBM;
+    const int64_t tiles_n = (std::max(p->d_in, p->d_out) + kGemmBN - 1) / kGemmBN;
+    if (tiles_m * tiles_n > kMaxUnits) return TLORA_EINVAL;
+  }
   return TLORA_OK;
 }
 
@@ -104,7 +112,7 @@ int validate(const tlora_problem_t* p) {
 // bytes that is written and read once more, so the default chunk is 32 * live_rows tokens (partial traffic
 // <= ~12 %).  If that gives too few units to fill the GPU the chunks are shortened (not below `grad_tokens`).
 // Units are issued longest first.
-void build_grad_units(const Plan& pl, int D, std::vector<GradUnit>& units, std::vector<GradGroup>& groups,
+bool build_grad_units(const Plan& pl, int D, std::vector<GradUnit>& units, std::vector<GradGroup>& groups,
                       int64_t& partial_floats) {
   const int ncb = (D + kGradCols - 1) / kGradCols;
   const int pb_rows = kGradMaxBlocks * kGradRanks;
@@ -130,6 +138,7 @@ void build_grad_units(const Plan& pl, int D, std::vector<GradUnit>& units, std::
   double shrink = 1.0;
   const int64_t want = 1024;
   while (shrink > 1.0 / 64 && count_units(shrink) < want) shrink *= 0.5;
+  if (count_units(shrink) > kMaxUnits) return false;      // refused before the tables are built
   partial_floats = 0;
   for (int j = 0; j < pl.J; ++j) {
     const JobDev& jb = pl.jobs[j];
@@ -158,6 +167,7 @@ void build_grad_units(const Plan& pl, int D, std::vector<GradUnit>& units, std::
     const int64_t ca = (int64_t)(a.t1 - a.t0) * (4 + a.mb), cb = (int64_t)(b.t1 - b.t0) * (4 + b.mb);
     return ca > cb;
   });
+  return true;
 }
 
 // fwd_only: tables and workspace of the forward alone (no transposed W, no dS, no dA / dB units or partial tiles)
@@ -218,6 +228,10 @@ int build_plan(const tlora_problem_t* p, Plan& pl, bool fwd_only = false) {
           if (jb.rpad > 0) n += (int64_t)((jb.row1 - jb.row0 + rows - 1) / rows) * ((jb.rpad + 127) / 128);
         return n;
       };
+      int64_t generic = 0;                           // units of the generic kernel: 64 rows x 64 rank columns
+      for (const JobDev& jb : pl.jobs)
+        generic += (int64_t)((jb.row1 - jb.row0 + 63) / 64) * ((jb.rpad + kShrinkCols - 1) / kShrinkCols);
+      if (generic > kMaxUnits || count(32) > kMaxUnits) return TLORA_EINVAL;
       const bool can32 = pl.d_in % 64 == 0 && pl.d_out % 64 == 0;
       if (g_opt.shrink_rows != 0) pl.shrink_rows = (g_opt.shrink_rows == 32 && !can32) ? 64 : g_opt.shrink_rows;
       else pl.shrink_rows = count(128) >= 192 ? 128 : (count(64) >= 192 || !can32) ? 64 : 32;
@@ -241,8 +255,9 @@ int build_plan(const tlora_problem_t* p, Plan& pl, bool fwd_only = false) {
         }
     }
     if (!fwd_only) {
-      build_grad_units(pl, pl.d_out, pl.gradB_units, pl.gradB_groups, pl.gradB_partial);
-      build_grad_units(pl, pl.d_in, pl.gradA_units, pl.gradA_groups, pl.gradA_partial);
+      if (!build_grad_units(pl, pl.d_out, pl.gradB_units, pl.gradB_groups, pl.gradB_partial) ||
+          !build_grad_units(pl, pl.d_in, pl.gradA_units, pl.gradA_groups, pl.gradA_partial))
+        return TLORA_EINVAL;
     }
   }
 

@@ -299,3 +299,25 @@ def test_planner_self_check_reports_the_problem_s_own_errors():
     prob, _keep = _problem([8, 8], [10, 10], d_in=60)                  # d_in not a multiple of 8
     rc, bad = tlora.tlora_plan_check(prob)
     assert rc == tlora.TLORA_EINVAL and bad == 0
+
+
+def test_sizes_beyond_the_stated_limits_are_refused_on_the_host():
+    """No pointer is touched: the fake addresses of _problem are never dereferenced by the planner."""
+    L = tlora.lib()
+
+    def ws(ranks, tokens, **kw):
+        prob, _keep = _problem(ranks, tokens, **kw)
+        return tlora.tlora_workspace_bytes(prob), tlora.tlora_plan_check(prob)[0]
+    at_limit = ws([8], [4096], d_in=1 << 20, d_out=64)
+    assert at_limit[0] > 0 and at_limit[1] == 0                                             # at the limit: fine
+    assert ws([8], [4096], d_in=(1 << 20) + 8, d_out=64) == (0, tlora.TLORA_EINVAL)
+    assert ws([8], [4096], d_in=64, d_out=(1 << 20) + 8) == (0, tlora.TLORA_EINVAL)
+    assert ws([8], [(1 << 24) + 1], d_in=64, d_out=64) == (0, tlora.TLORA_EINVAL)
+    assert ws([8], [1 << 24], d_in=64, d_out=64)[1] == 0                                    # 65536 x 1 tiles
+    assert ws([8], [1 << 24], d_in=64, d_out=1 << 15) == (0, tlora.TLORA_EINVAL)            # 65536 x 128 tiles > 2^22
+    assert ws([8], [1 << 20], d_in=64, d_out=1 << 18)[1] == 0                               # 4096 x 1024 tiles = 2^22
+    assert ws([1025], [10]) == (0, tlora.TLORA_EINVAL)
+    J = 65537
+    prob, _keep = tlora.make_problem(tlora.TLORA_BF16, 64, 64, [1] * J, list(range(J + 1)), [1.0] * J, 0x1000, 0x2000,
+                                     [0x3000] * J, [0x4000] * J)
+    assert tlora.tlora_workspace_bytes(prob) == 0 and tlora.tlora_plan_check(prob)[0] == tlora.TLORA_EINVAL
