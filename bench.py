@@ -271,6 +271,18 @@ def measure_workload(cfg_index: int, steps: int, warmup: int, profile: bool, loo
     return res
 
 
+def measure_cfg0(steps: int):
+    """The fp32 correctness configuration (256 -> 256, two jobs of 64 tokens): its time only, no roofline."""
+    from paper_2602_07263_amd import workloads as wk
+    wl = wk.config(0)
+    run = ProjectionRun.from_numpy(wk.generate(wl, 0), 4)
+    ms = time_steps(run.step, steps, 20)
+    times = sorted(LAST_STEP_TIMES)
+    return {"workload": wl.name, "dtype": "f32", "ms_per_step": round(ms, 4), "ms_per_step_median": round(times[len(times) // 2], 4),
+            "ms_per_step_min": round(times[0], 4), "steps": steps, "flops_per_step": wl.flops(),
+            "note": "correctness configuration: fp32 operands, fp64 running sums, launch-bound; time only"}
+
+
 def summarize(res, steps: int, with_roofline: bool):
     """JSON fields of one measured workload."""
     wl = res["wl"]
@@ -747,6 +759,8 @@ def main():
             out[key] = d
             del r
             torch.cuda.empty_cache()
+    if not args.no_secondary and not args.no_extra_configs and args.config != 0:
+        out["also_cfg0"] = measure_cfg0(max(args.steps, 50))
     if not args.no_secondary:
         out["also_mlp_block"] = measure_mlp_block(max(5, args.steps // 2), 2)
         torch.cuda.empty_cache()
