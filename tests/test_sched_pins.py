@@ -116,9 +116,9 @@ def _golden_trace():
 
 
 def test_simulation_reproduces_the_hand_worked_three_job_trace():
-    """Pins the outer loop including its urgency update: in round 4 of the hand-worked run the job that has made less
-    progress relative to its standalone speed must go first; other plausible urgency formulas order that round the
-    other way (see the file's derivation)."""
+    """Pins the outer loop including its urgency update: in the fourth scheduling step of the hand-worked run the job
+    that has made less progress relative to its standalone speed must go first; other plausible urgency formulas
+    order that step the other way (see the file's derivation)."""
     g = _golden_trace()
     trace, jct, now = so.simulate(g["model"], g["jobs"], g["horizon"])
     assert [[grp, n] for grp, n in trace] == g["trace"]
