@@ -30,7 +30,7 @@
  *     backbone product only; its A/B/dA/dB pointers are ignored and may be NULL), T = 0 (X, Y, dY, dX
  *     may be NULL; the forward launches nothing, the backward zero-fills dA_j / dB_j).
  *   - Limits (TLORA_EINVAL beyond them, before anything is launched): J <= TLORA_MAX_JOBS, T <= TLORA_MAX_TOKENS,
- *     d_in, d_out <= TLORA_MAX_FEATURES, r_j <= TLORA_MAX_RANK, and a plan of at most 2^22 GEMM tiles
+ *     d_in, d_out <= TLORA_MAX_FEATURES, r_j <= TLORA_MAX_RANK, sum_j (r_j padded to 8) <= 2^22, and a plan of at most 2^22 GEMM tiles
  *     (ceil(T / 256) * ceil(max(d_in, d_out) / 256)) and 2^22 work units of each kind -- the kernels keep 32-bit
  *     offsets inside a tile and one workgroup per tile / unit.
  *   - Calls are asynchronous on `hip_stream` (a hipStream_t; NULL = the default stream).  Host
@@ -54,7 +54,7 @@ extern "C" {
 #endif
 
 #define TLORA_MAX_RANK 1024
-#define TLORA_MAX_JOBS 65536
+#define TLORA_MAX_JOBS 32768
 #define TLORA_MAX_TOKENS (1 << 24)
 #define TLORA_MAX_FEATURES (1 << 20)
 

@@ -193,7 +193,7 @@ int build_plan(const tlora_problem_t* p, Plan& pl, bool fwd_only = false) {
     roff += jb.rpad;
     pl.max_rpad = std::max(pl.max_rpad, jb.rpad);
   }
-  if (roff > (int64_t)1 << 24) return TLORA_EINVAL;
+  if (roff > (int64_t)1 << 22) return TLORA_EINVAL;   // rows of the stacked adapter operands: 256 of them span 32-bit byte offsets
   pl.s_elems = soff;  pl.atp_elems = atp;  pl.r_total = (int)roff;
 
   // row tiles of the backbone GEMM (nano-batches of the concatenated batch, Sec. 3.3)

@@ -317,7 +317,11 @@ def test_sizes_beyond_the_stated_limits_are_refused_on_the_host():
     assert ws([8], [1 << 24], d_in=64, d_out=1 << 15) == (0, tlora.TLORA_EINVAL)            # 65536 x 128 tiles > 2^22
     assert ws([8], [1 << 20], d_in=64, d_out=1 << 18)[1] == 0                               # 4096 x 1024 tiles = 2^22
     assert ws([1025], [10]) == (0, tlora.TLORA_EINVAL)
-    J = 65537
+    J = 8192                                                                                # padded ranks sum to 2^23
+    prob, _keep = tlora.make_problem(tlora.TLORA_BF16, 64, 64, [1024] * J, list(range(J + 1)), [1.0] * J, 0x1000, 0x2000,
+                                     [0x3000] * J, [0x4000] * J)
+    assert tlora.tlora_workspace_bytes(prob) == 0 and tlora.tlora_plan_check(prob)[0] == tlora.TLORA_EINVAL
+    J = 32769
     prob, _keep = tlora.make_problem(tlora.TLORA_BF16, 64, 64, [1] * J, list(range(J + 1)), [1.0] * J, 0x1000, 0x2000,
                                      [0x3000] * J, [0x4000] * J)
     assert tlora.tlora_workspace_bytes(prob) == 0 and tlora.tlora_plan_check(prob)[0] == tlora.TLORA_EINVAL

@@ -31,6 +31,10 @@ RAGGED = [
     ("tile_edges", 256, 512, [8, 16, 24], [256, 255, 257], [2.0, 2.0, 2.0]),
     ("rank_256_straddle", 320, 264, [256, 3, 130], [100, 700, 90], [1.5, 2.0, 0.5]),
     ("narrow_features", 8, 8, [2, 5], [40, 300], [2.0, 1.0]),
+    # the largest legal rank (TLORA_MAX_RANK = 1024: eight rank blocks per shrink / dA-dB unit column) next to a rank
+    # that ends inside a block; feature sizes that take the streaming kernels, then sizes that take the generic ones
+    ("rank_max_streaming", 256, 320, [1024, 513], [300, 129], [1.0, 2.0]),
+    ("rank_max_generic", 136, 200, [1024, 8, 513], [70, 33, 260], [0.5, 2.0, 1.5]),
 ]
 
 
