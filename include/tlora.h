@@ -416,6 +416,9 @@ int tlora_plan_check(const tlora_problem_t* p, int32_t fwd_only, int32_t* failed
  *   "indexed_direct": 1 (default): bf16 token-indexed calls read the batch rows through the index list inside the
  *                    kernels' loads (while T * max(d_in, d_out) * 2 bytes stays below 4 GiB) | 0: always gather the
  *                    activations into the workspace first
+ *   "table_copy_kernel": 1 (default): a call's plan tables are moved from the pinned staging buffer into the
+ *                    workspace by a kernel on the caller's stream that reads the host buffer directly | 0: by a
+ *                    host-to-device copy command (the stream's next kernel then waits for the copy engine, ~20 us)
  *   "plan_cache"   : 1 (default): the integer plan of a problem (tiles, work units, workspace layout) is kept, keyed
  *                    by the contents of (dtype, d_in, d_out, ranks, offsets), and reused by later calls with the same
  *                    values -- scales and pointers are taken from every call afresh | 0: rebuilt on every call.
@@ -458,6 +461,9 @@ int tlora_profile_clock(double* ghz_fwd, double* ghz_bwd);
 
 /* Static description of an error code. */
 const char* tlora_strerror(int status);
+/* After a TLORA_EHIP: which HIP error the runtime reported and where in the library's host code ("none" if no call has
+ * failed).  The text lives in a static buffer that the next call overwrites. */
+const char* tlora_last_hip_error(void);
 
 /* Library version string. */
 const char* tlora_version(void);

@@ -1,6 +1,7 @@
 // Host side of the C ABI: argument validation, the nano-batch plan (integer bookkeeping), workspace
 // layout and the launch sequence of the forward and backward passes.
 #include <hip/hip_runtime.h>
+#include <stdio.h>
 #include <string.h>
 
 #include <algorithm>
@@ -27,17 +28,31 @@ namespace tlora {
 namespace {
 
 constexpr int kMaxDevices = 64;
+// What the HIP runtime said when a call last failed (for tlora_last_hip_error): the code and the line of this file.
+int g_hip_err = 0, g_hip_line = 0;
+inline int hip_failed(hipError_t e, int line) {
+  g_hip_err = (int)e;  g_hip_line = line;
+  return TLORA_EHIP;
+}
+// TLORA_OK, or TLORA_EHIP if the runtime reports an error from the launches queued so far
+inline int launches_ok(int line) {
+  const hipError_t e = hipGetLastError();
+  return e == hipSuccess ? TLORA_OK : hip_failed(e, line);
+}
+#define TLORA_HIP(expr) do { const hipError_t e_ = (expr); if (e_ != hipSuccess) return hip_failed(e_, __LINE__); } while (0)
+
 constexpr size_t kNoAllocMaxTableBytes = 64 * 3584;   // plan tables of tlora_fwd_noalloc: at most 64 argument chunks
 uint8_t* g_scratch_ptr[kMaxDevices] = {};   // per device: address of `scratch` on that device (0 = not looked up yet)
 
 // Address of the static scratch array on the current device (looked up once per device, with that device current).
 int scratch_of_current_device(uint8_t** out) {
   int dev = -1;
-  if (hipGetDevice(&dev) != hipSuccess) return TLORA_EHIP;
+  TLORA_HIP(hipGetDevice(&dev));
   if (dev < 0 || dev >= kMaxDevices) return TLORA_EINVAL;
   if (!g_scratch_ptr[dev]) {
     void* ptr = nullptr;
-    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return TLORA_EHIP;
+    TLORA_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return TLORA_EHIP;
     g_scratch_ptr[dev] = static_cast<uint8_t*>(ptr);
   }
   *out = g_scratch_ptr[dev];
@@ -51,6 +66,7 @@ struct Options {
   int dx_transposed_w = 1;
   int plan_cache = 1;           // reuse plans of problems seen before (keyed by their contents)
   int indexed_direct = 1;       // token-indexed bf16 calls fetch rows through the index inside the kernels' loads
+  int table_copy_kernel = 1;    // plan tables reach the workspace through a kernel that reads the pinned staging buffer
 };
 Options g_opt;
 std::recursive_mutex g_mu;   // the nano-batch entry points call tlora_fwd / tlora_bwd under it
@@ -325,6 +341,7 @@ int build_plan(const tlora_problem_t* p, Plan& pl, bool fwd_only = false) {
 // A small ring of pinned host buffers; a slot is reused only after the copy that read it has finished.
 struct Slot {
   void* host = nullptr;
+  void* dev_view = nullptr;   // the same buffer as the device addresses it (null: not mapped, copy commands are used)
   size_t cap = 0;
   hipEvent_t ev = nullptr;
   bool busy = false;
@@ -337,20 +354,29 @@ int upload_tables(const std::vector<uint8_t>& blob, void* dst, hipStream_t st) {
   Slot& s = g_slots[g_next_slot];
   g_next_slot = (g_next_slot + 1) % kSlots;
   if (s.busy) {
-    if (hipEventSynchronize(s.ev) != hipSuccess) return TLORA_EHIP;
+    TLORA_HIP(hipEventSynchronize(s.ev));
     s.busy = false;
   }
   if (s.cap < blob.size()) {
     if (s.host) (void)hipHostFree(s.host);
-    s.host = nullptr;  s.cap = 0;
+    s.host = nullptr;  s.dev_view = nullptr;  s.cap = 0;
     const size_t cap = align_up(blob.size() * 2, 4096);
-    if (hipHostMalloc(&s.host, cap, hipHostMallocDefault) != hipSuccess) return TLORA_EHIP;
+    TLORA_HIP(hipHostMalloc(&s.host, cap, hipHostMallocDefault));
     s.cap = cap;
+    if (hipHostGetDevicePointer(&s.dev_view, s.host, 0) != hipSuccess) {
+      s.dev_view = nullptr;
+      (void)hipGetLastError();
+    }
   }
-  if (!s.ev && hipEventCreateWithFlags(&s.ev, hipEventDisableTiming) != hipSuccess) return TLORA_EHIP;
+  if (!s.ev) TLORA_HIP(hipEventCreateWithFlags(&s.ev, hipEventDisableTiming));
   memcpy(s.host, blob.data(), blob.size());
-  if (hipMemcpyAsync(dst, s.host, blob.size(), hipMemcpyHostToDevice, st) != hipSuccess) return TLORA_EHIP;
-  if (hipEventRecord(s.ev, st) != hipSuccess) return TLORA_EHIP;
+  if (g_opt.table_copy_kernel && s.dev_view && blob.size() % 16 == 0 && (reinterpret_cast<uintptr_t>(dst) & 15) == 0) {
+    launch_table_copy(s.dev_view, dst, blob.size(), st);
+    TLORA_HIP(hipGetLastError());
+  } else {
+    TLORA_HIP(hipMemcpyAsync(dst, s.host, blob.size(), hipMemcpyHostToDevice, st));
+  }
+  TLORA_HIP(hipEventRecord(s.ev, st));
   s.busy = true;
   return TLORA_OK;
 }
@@ -400,9 +426,9 @@ struct Timed {
 
 int prof_drain() {
   for (const Pending& p : g_pending) {
-    if (hipEventSynchronize(p.b) != hipSuccess) return TLORA_EHIP;
+    TLORA_HIP(hipEventSynchronize(p.b));
     float ms = 0.f;
-    if (hipEventElapsedTime(&ms, p.a, p.b) != hipSuccess) return TLORA_EHIP;
+    TLORA_HIP(hipEventElapsedTime(&ms, p.a, p.b));
     g_prof_ms[p.cls] += ms;
     g_prof_n[p.cls] += 1;
     g_event_pool.push_back(p.a);
@@ -429,9 +455,9 @@ int check_arch() {
   static int cached = 1;   // 1 = unknown
   if (cached != 1) return cached;
   int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess) return TLORA_EHIP;
+  TLORA_HIP(hipGetDevice(&dev));
   hipDeviceProp_t prop;
-  if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return TLORA_EHIP;
+  TLORA_HIP(hipGetDeviceProperties(&prop, dev));
   cached = strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? TLORA_OK : TLORA_EARCH;
   return cached;
 }
@@ -657,7 +683,7 @@ int fwd_impl(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_bytes
       launch_f32_units(reinterpret_cast<const F32Unit*>(tb + L.units_at[i]),
                        reinterpret_cast<const F32Tile*>(tb + L.tiles_at[i]), L.ntiles[i], st);
     }
-    return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+    return launches_ok(__LINE__);
   }
 
   rc = upload(pl.tables_bytes);
@@ -682,7 +708,7 @@ int fwd_impl(const tlora_problem_t* p, void* Y, void* workspace, size_t ws_bytes
   launch_seg_gemm(true, tiles, static_cast<const uint16_t*>(p->X), static_cast<const uint16_t*>(p->W), Sx, bp,
                   pl.r_total, static_cast<uint16_t*>(Y), out_index, in_index, pl.T, pl.d_in, pl.d_out,
                   timed ? (g_clock_slot[0] = reinterpret_cast<unsigned long long*>(ws + pl.off_clock)) : nullptr, st);
-  return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+  return launches_ok(__LINE__);
 }
 }  // namespace
 }  // namespace tlora
@@ -784,7 +810,7 @@ int bwd_impl(const tlora_problem_t* p, const void* dY, void* dX, void* const* dA
       launch_f32_units(reinterpret_cast<const F32Unit*>(tb + L.units_at[i]),
                        reinterpret_cast<const F32Tile*>(tb + L.tiles_at[i]), L.ntiles[i], st);
     }
-    return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+    return launches_ok(__LINE__);
   }
 
   rc = upload_tables(blob, tb, st);
@@ -862,7 +888,7 @@ int bwd_impl(const tlora_problem_t* p, const void* dY, void* dX, void* const* dA
                          pl.d_in, true, accumulate, st);
     }
   }
-  return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+  return launches_ok(__LINE__);
 }
 
 }  // namespace
@@ -1043,7 +1069,7 @@ int tlora_adamw_step(const tlora_adamw_tensor_t* tensors, int32_t count, int32_t
     Timed t(TLORA_K_OPT, st);
     launch_adamw(static_cast<const AdamwDev*>(workspace), count, max_n, st);
   }
-  return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+  return launches_ok(__LINE__);
 }
 
 // ---- MLP block: RMSNorm -> gate / up (fused multi-LoRA) -> silu(G) * U -> down (fused multi-LoRA) -> + X -------
@@ -1134,7 +1160,7 @@ int tlora_mlp_fwd(const tlora_mlp_t* p, void* Out, void* workspace, size_t ws_by
     Timed t(TLORA_K_GLUE, st);
     launch_residual_add(bf, p->X, ws + L.off_d, Out, L.T * p->d_model, st);
   }
-  return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+  return launches_ok(__LINE__);
 }
 
 int tlora_mlp_bwd(const tlora_mlp_t* p, const void* dOut, void* dX, void* const* dA_gate, void* const* dB_gate,
@@ -1173,7 +1199,7 @@ int tlora_mlp_bwd(const tlora_mlp_t* p, const void* dOut, void* dX, void* const*
     launch_rmsnorm_bwd(bf, p->X, p->gamma, reinterpret_cast<const float*>(ws + L.off_rstd), ws + L.off_dxa,
                        ws + L.off_dxb, nullptr, dOut, (int)L.T, p->d_model, dX, st);
   }
-  return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+  return launches_ok(__LINE__);
 }
 
 // ---- attention half: rotary embedding, causal grouped-query attention, and the block around them ----------
@@ -1264,7 +1290,7 @@ int tlora_rope(void* X, int32_t num_seqs, const int64_t* seq_offsets, int32_t he
     launch_rope(static_cast<uint16_t*>(X), reinterpret_cast<const int32_t*>(ws + A.off_pos),
                 reinterpret_cast<const float*>(ws + A.off_rope), A.T, heads, inverse != 0, st);
   }
-  return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+  return launches_ok(__LINE__);
 }
 
 int tlora_attention_fwd(const void* Q, const void* K, const void* V, void* O, float* lse, int32_t num_seqs,
@@ -1291,7 +1317,7 @@ int tlora_attention_fwd(const void* Q, const void* K, const void* V, void* O, fl
                     static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), lse,
                     n_heads, n_kv_heads, st);
   }
-  return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+  return launches_ok(__LINE__);
 }
 
 int tlora_attention_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* lse,
@@ -1322,7 +1348,7 @@ int tlora_attention_bwd(const void* Q, const void* K, const void* V, const void*
                     static_cast<uint16_t*>(dQ), static_cast<uint16_t*>(dK), static_cast<uint16_t*>(dV), A.T, n_heads,
                     n_kv_heads, st);
   }
-  return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+  return launches_ok(__LINE__);
 }
 
 namespace {
@@ -1436,7 +1462,7 @@ int tlora_attn_fwd(const tlora_attn_t* p, void* Out, void* workspace, size_t ws_
     Timed t(TLORA_K_GLUE, st);
     launch_residual_add(true, p->X, ws + L.off_d, Out, L.T * p->d_model, st);
   }
-  return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+  return launches_ok(__LINE__);
 }
 
 int tlora_attn_bwd(const tlora_attn_t* p, const void* dOut, void* dX, void* const* const* dA, void* const* const* dB,
@@ -1490,7 +1516,7 @@ int tlora_attn_bwd(const tlora_attn_t* p, const void* dOut, void* dX, void* cons
     launch_rmsnorm_bwd(true, p->X, p->gamma, reinterpret_cast<const float*>(ws + L.off_rstd), ws + L.off_dxa,
                        ws + L.off_dxb, ws + L.off_dxc, dOut, (int)L.T, p->d_model, dX, st);
   }
-  return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+  return launches_ok(__LINE__);
 }
 
 // ---- one decoder layer: attention block, then MLP block -----------------------------------------------------
@@ -1649,7 +1675,7 @@ int tlora_fwd_indexed(const tlora_problem_t* p, const int32_t* row_index, void* 
   if (rc != TLORA_OK) return rc;
   Timed t(TLORA_K_PERMUTE, st);
   launch_permute_rows(ws + L.off_y, Y, index, L.T, (int64_t)p->d_out * L.elt, true, st);
-  return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+  return launches_ok(__LINE__);
 }
 
 int tlora_bwd_indexed(const tlora_problem_t* p, const int32_t* row_index, const void* dY, void* dX, void* const* dA,
@@ -1688,7 +1714,7 @@ int tlora_bwd_indexed(const tlora_problem_t* p, const int32_t* row_index, const 
   if (rc != TLORA_OK) return rc;
   Timed t(TLORA_K_PERMUTE, st);
   launch_permute_rows(ws + L.off_dx, dX, index, L.T, (int64_t)p->d_in * L.elt, true, st);
-  return hipGetLastError() == hipSuccess ? TLORA_OK : TLORA_EHIP;
+  return launches_ok(__LINE__);
 }
 
 int tlora_plan_dump(const tlora_problem_t* p, int32_t* rpad, int64_t* soff, int32_t* tile_rows, int64_t* tile_row0,
@@ -1919,7 +1945,7 @@ int tlora_profile_clock(double* ghz_fwd, double* ghz_bwd) {
     *out[i] = 0.0;
     if (!g_clock_slot[i]) continue;
     unsigned long long h[2] = {0, 0};
-    if (hipMemcpy(h, g_clock_slot[i], sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) return TLORA_EHIP;
+    TLORA_HIP(hipMemcpy(h, g_clock_slot[i], sizeof(h), hipMemcpyDeviceToHost));
     if (h[1] > 0) *out[i] = (double)h[0] / ((double)h[1] * 10.0);     // cycles per 10 ns tick -> GHz
   }
   return TLORA_OK;
@@ -1949,6 +1975,11 @@ int tlora_set_option(const char* name, int64_t value) {
     g_opt.indexed_direct = (int)value;
     return TLORA_OK;
   }
+  if (n == "table_copy_kernel") {
+    if (value != 0 && value != 1) return TLORA_EINVAL;
+    g_opt.table_copy_kernel = (int)value;
+    return TLORA_OK;
+  }
   if (n == "plan_cache") {
     if (value != 0 && value != 1) return TLORA_EINVAL;
     g_opt.plan_cache = (int)value;
@@ -1961,6 +1992,15 @@ int tlora_set_option(const char* name, int64_t value) {
     return TLORA_OK;
   }
   return TLORA_EINVAL;
+}
+
+const char* tlora_last_hip_error(void) {
+  std::lock_guard<std::recursive_mutex> lk(g_mu);
+  static char text[160];
+  if (g_hip_err == 0) return "none";
+  snprintf(text, sizeof(text), "%s (%d) at line %d of tlora_api.hip", hipGetErrorName((hipError_t)g_hip_err), g_hip_err,
+           g_hip_line);
+  return text;
 }
 
 const char* tlora_strerror(int status) {

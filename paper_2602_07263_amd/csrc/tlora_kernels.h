@@ -23,6 +23,8 @@ void launch_zero_fill(void* ptr, size_t bytes, hipStream_t st);
 // Copy `bytes` of HOST memory to device memory `dst` (4-byte aligned, room for bytes rounded up to 4) by value,
 // through the arguments of small store kernels: no staging buffer, no copy node, nothing allocated.
 void launch_table_write(const void* host_src, size_t bytes, void* dst, hipStream_t st);
+// Copy `bytes` (a multiple of 16) from pinned host memory, given by its device address, to device memory.
+void launch_table_copy(const void* src_device_view, void* dst, size_t bytes, hipStream_t st);
 
 // out_j[t, p] = sum_k act[t, k] * P_j[p, k]   (P_j = A_j^T packed, or B_j packed)
 // row_index (null = identity): the row of `act` that holds token row t of the job-sorted order (token-indexed calls).

@@ -309,6 +309,22 @@ void launch_table_write(const void* host_src, size_t bytes, void* dst, hipStream
   }
 }
 
+// Plan tables from a pinned staging buffer (host memory, read through its device address) into the workspace, as an
+// ordinary kernel on the caller's stream: a host-to-device copy command makes the stream's next kernel wait for the
+// copy engine's signal (~20 us of idle stream per call), a kernel in the same queue does not.
+__global__ void __launch_bounds__(256) table_copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst,
+                                                         size_t n16) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+void launch_table_copy(const void* src_device_view, void* dst, size_t bytes, hipStream_t st) {
+  const size_t n16 = bytes / 16;                 // the caller passes a multiple of 16 bytes
+  if (n16 == 0) return;
+  const unsigned blocks = (unsigned)std::min<size_t>((n16 + 255) / 256, 256);
+  hipLaunchKernelGGL(table_copy_kernel, dim3(blocks), dim3(256), 0, st, static_cast<const u32x4*>(src_device_view),
+                     static_cast<u32x4*>(dst), n16);
+}
+
 // ---------------------------------------------------------------------------------------------------
 // Shrink:  out_j[t, p] = sum_k act[t, k] * P_j[p, k]      (Sec. 3.3: the compact |X_j| x r_j intermediate)
 // One workgroup = ROWS token rows of one job x 64 padded rank columns; 4 waves.

@@ -100,7 +100,8 @@ EXPORTS = ["tlora_workspace_bytes", "tlora_fwd", "tlora_fwd_noalloc", "tlora_bwd
            "tlora_aimd_init", "tlora_aimd_update",
            "tlora_nano_split", "tlora_nano_workspace_bytes", "tlora_fwd_nano", "tlora_bwd_nano",
            "tlora_plan_dump", "tlora_plan_check", "tlora_set_option",
-           "tlora_profile", "tlora_profile_read", "tlora_profile_clock", "tlora_strerror", "tlora_version"]
+           "tlora_profile", "tlora_profile_read", "tlora_profile_clock", "tlora_strerror", "tlora_last_hip_error",
+           "tlora_version"]
 KERNEL_CLASSES = ["pack", "shrink", "gemm_fwd", "gemm_bwd", "rank_grad", "grad_reduce", "f32", "w_transpose", "optimizer", "glue", "permute",
                   "attn_fwd", "attn_bwd", "rope"]
 
@@ -111,6 +112,13 @@ def lib() -> ctypes.CDLL:
     global _lib
     if _lib is not None:
         return _lib
+    # One HIP runtime per process: PyTorch ships its own copy of libamdhip64 and loads it by path, so if this library
+    # (linked against the system's copy) came first the process would hold two runtimes, and the second one finds
+    # no device.  With torch loaded first the dynamic loader hands this library the copy that is already there.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     if not os.environ.get("TLORA_LIB"):
         from . import build as _build
         if _build.is_stale():
@@ -213,6 +221,8 @@ def lib() -> ctypes.CDLL:
     L.tlora_profile_clock.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
     L.tlora_strerror.restype = ctypes.c_char_p
     L.tlora_strerror.argtypes = [ctypes.c_int]
+    L.tlora_last_hip_error.restype = ctypes.c_char_p
+    L.tlora_last_hip_error.argtypes = []
     L.tlora_version.restype = ctypes.c_char_p
     L.tlora_version.argtypes = []
     _lib = L
@@ -229,7 +239,8 @@ def tlora_version() -> str:
 
 def _check(status: int, what: str) -> None:
     if status != 0:
-        raise TloraError(f"{what} failed: {status} ({tlora_strerror(status)})")
+        detail = f": {lib().tlora_last_hip_error().decode()}" if status == TLORA_EHIP else ""
+        raise TloraError(f"{what} failed: {status} ({tlora_strerror(status)}{detail})")
 
 
 def tlora_set_option(name: str, value: int) -> None:
